@@ -1,0 +1,153 @@
+"""ctypes access to the plain CPU oracle (oracle/halos_oracle.cpp).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg.  The GPU library never imports or calls it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "halos_oracle.cpp")
+_LIB = os.path.join(_HERE, "libhalos_oracle.so")
+
+THETA, MOM, AUX, GPS_THETA, GPS_MOM = 0, 1, 2, 3, 4
+SCALE = 10   # add to the ids above for the running max-magnitude of the same array
+
+FORM_LITERAL = 0       # Delta by snapshot subtraction (Algorithm 1 line 14 as written)
+FORM_ACCUMULATOR = 1   # running sum of applied steps
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ (no fast-math, no contraction; -mfma only makes std::fma one instruction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["g++", "-std=c++17", "-O2", "-mfma", "-ffp-contract=off", "-fno-fast-math",
+               "-fPIC", "-shared", "-Wall", "-o", _LIB, _SRC]
+        subprocess.check_call(cmd)
+    return _LIB
+
+
+class StepInfo(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("sent", ctypes.c_int32), ("accumulated", ctypes.c_int32),
+                ("worker", ctypes.c_int32), ("t", ctypes.c_int64), ("t_last", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        f32, i32, i64, vp = ctypes.c_float, ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
+        lib.ho_create.restype = vp
+        lib.ho_create.argtypes = [i64, i32, i32, i32, f32, f32, f32, f32, f32, f32, f32, vp, vp]
+        lib.ho_destroy.argtypes = [vp]
+        lib.ho_arrive_delta_f32.argtypes = [vp, i32, i32, vp]
+        lib.ho_arrive_delta_bf16.argtypes = [vp, i32, i32, vp]
+        lib.ho_arrive_global.argtypes = [vp, i32]
+        lib.ho_lps_step.argtypes = [vp, i32, ctypes.POINTER(StepInfo)]
+        lib.ho_gps_receive.argtypes = [vp, i32]
+        lib.ho_set_K.argtypes = [vp, i32, i32]
+        lib.ho_set_rules.argtypes = [vp, f32, f32, f32, f32, f32, f32, f32]
+        lib.ho_get.argtypes = [vp, i32, i32, vp]
+        lib.ho_counters.argtypes = [vp, i32] + [vp] * 5
+        lib.ho_bf16_to_f32.restype = f32
+        lib.ho_bf16_to_f32.argtypes = [ctypes.c_uint16]
+        _lib = lib
+    return _lib
+
+
+class OracleError(RuntimeError):
+    pass
+
+
+class HalosOracle:
+    """One GPS and n_lps LPSs over a flat vector of n parameters.
+
+    precision 64 is the reference; precision 32 with form=FORM_ACCUMULATOR
+    performs the same fp32 operations, in the same order, as a one-pass fp32
+    implementation and can be compared bit for bit.
+    """
+
+    def __init__(self, theta0: np.ndarray, n_lps: int, *, eta_l: float, beta_l: float, eta_g: float, beta_g: float,
+                 alpha: float, K: Sequence[int] | int, cg_l: float | None = None, cg_g: float | None = None,
+                 precision: int = 64, form: int = FORM_LITERAL):
+        lib = _load()
+        theta0 = np.ascontiguousarray(theta0, dtype=np.float32)
+        self.n = int(theta0.size)
+        self.n_lps = int(n_lps)
+        f = np.float32
+        if cg_l is None:
+            cg_l = f(1) - f(beta_l)       # the paper's (1 - beta), formed in fp32 like any fp32 caller would
+        if cg_g is None:
+            cg_g = f(1) - f(beta_g)
+        Ks = np.full(n_lps, K, dtype=np.int32) if np.isscalar(K) else np.ascontiguousarray(K, dtype=np.int32)
+        assert Ks.size == n_lps
+        self._lib = lib
+        self._h = lib.ho_create(self.n, n_lps, precision, form, f(eta_l), f(beta_l), f(cg_l), f(eta_g), f(beta_g),
+                                f(cg_g), f(alpha), Ks.ctypes.data, theta0.ctypes.data)
+        if not self._h:
+            raise OracleError("ho_create failed")
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.ho_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def _chk(self, rc, what):
+        if rc != 0:
+            raise OracleError(f"{what}: protocol violation (code {rc})")
+
+    def arrive_delta(self, l: int, worker: int, g: np.ndarray):
+        """g is the pseudo-gradient (start - end model): float32 values, or raw bfloat16 bit patterns as uint16/int16."""
+        g = np.ascontiguousarray(g)
+        assert g.size == self.n
+        if g.dtype == np.float32:
+            rc = self._lib.ho_arrive_delta_f32(self._h, l, worker, g.ctypes.data)
+        elif g.dtype in (np.uint16, np.int16):
+            rc = self._lib.ho_arrive_delta_bf16(self._h, l, worker, g.ctypes.data)
+        else:
+            raise TypeError(g.dtype)
+        self._chk(rc, "arrive_delta")
+
+    def arrive_global(self, l: int):
+        self._chk(self._lib.ho_arrive_global(self._h, l), "arrive_global")
+
+    def lps_step(self, l: int) -> StepInfo:
+        info = StepInfo()
+        self._chk(self._lib.ho_lps_step(self._h, l, ctypes.byref(info)), "lps_step")
+        return info
+
+    def gps_receive(self, l: int):
+        self._chk(self._lib.ho_gps_receive(self._h, l), "gps_receive")
+
+    def set_K(self, l: int, K: int):
+        self._chk(self._lib.ho_set_K(self._h, l, K), "set_K")
+
+    def set_rules(self, *, eta_l, beta_l, cg_l, eta_g, beta_g, cg_g, alpha):
+        f = np.float32
+        self._lib.ho_set_rules(self._h, f(eta_l), f(beta_l), f(cg_l), f(eta_g), f(beta_g), f(cg_g), f(alpha))
+
+    def get(self, what: int, l: int = 0) -> np.ndarray:
+        out = np.empty(self.n, dtype=np.float64)
+        self._chk(self._lib.ho_get(self._h, what, l, out.ctypes.data), "get")
+        return out
+
+    def counters(self, l: int):
+        t, tl, gu = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+        ph, q = ctypes.c_int32(), ctypes.c_int32()
+        self._lib.ho_counters(self._h, l, ctypes.byref(t), ctypes.byref(tl), ctypes.byref(ph), ctypes.byref(q),
+                              ctypes.byref(gu))
+        return {"t": t.value, "t_last": tl.value, "phase": ph.value, "queued": q.value, "gps_updates": gu.value}
+
+
+def bf16_to_f32(bits: int) -> float:
+    return float(_load().ho_bf16_to_f32(bits & 0xFFFF))

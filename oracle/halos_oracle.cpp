@@ -1,0 +1,379 @@
+// HALoS server-side update rules -- plain CPU oracle.
+//
+// TEST INFRASTRUCTURE ONLY.  This file is the slow, single-threaded,
+// obviously-correct statement of what the local parameter servers (LPS) and
+// the global parameter server (GPS) compute.  It exists so that the GPU
+// library can be checked against something written independently from the
+// paper; it shares no code, header, table or helper with that library and
+// nothing in the product path may call it.
+//
+// What it follows (HALoS, arXiv 2506.04531):
+//   * Algorithm 1 "HALoS Update Rules": the GPS block (receive Delta, update,
+//     send the model back), the LPS block (update on every worker delta, send
+//     Delta = theta_t - theta_{t_last} after K updates, merge the returned
+//     global model with weight alpha and reset t_last).
+//   * Sec. 4.1 item 2: worker deltas and returned global models share ONE
+//     queue per LPS and are handled in arrival order.
+//   * Appendix E, first two displays: ModelUpdate is
+//         m  <- beta * m + grad
+//         x  <- x - eta * [ (1 - beta) * grad + beta * m ]
+//     for both tiers.  "grad" is the pseudo-gradient, i.e. the NEGATIVE of the
+//     delta that Algorithm 1 sends (delta = end - start model), so that
+//     beta = 0, eta = 1 adopts the sender's progress:  x <- x + delta.
+//
+// Readings taken where the paper is silent (each is listed in the design
+// document of this repository):
+//   * The coefficient on grad is kept as a parameter cg; the paper's value is
+//     cg = 1 - beta.  cg = 1 gives the textbook Nesterov step.
+//   * theta_{t_last} is the model right AFTER the merge (line 18 sets t_last,
+//     line 19 overwrites theta_t), so updates applied while a Delta is in
+//     flight are never part of any later Delta.
+//   * At most one Delta per LPS is in flight: the send test is
+//     "t - t_last >= K and nothing in flight", which equals the paper's
+//     "t - t_last = K" whenever K only changes at a merge.
+//   * The model the LPS merges is the GPS model right after THAT LPS's Delta
+//     was applied, even if other LPSs update the GPS before it is merged.
+//   * Delta is applied at the GPS unnormalised (no 1/K, no 1/M).
+//
+// Two numerical forms are provided and selected at creation:
+//   form 0 (literal)      keeps the snapshot theta_{t_last} and forms Delta by
+//                         subtraction exactly as Algorithm 1 line 14 writes it;
+//   form 1 (accumulator)  keeps a running sum of the applied steps instead.
+// In exact arithmetic they are the same; in fp64 they agree to ~1e-13.
+// Precision is fp64 (the reference) or fp32 (same operation order as a
+// single-pass fp32 implementation would use; useful as a bit-level check).
+//
+// Pins (tests/test_oracle_pins.py): local-SGD special case, K identical deltas,
+// geometric momentum series, IIR-filter closed form via scipy.signal.lfilter,
+// torch.optim.SGD(nesterov) for cg = 1, the theta - eta (g + beta^2 m_old)
+// identity from the proof, merge endpoints alpha in {0, 1}, geometric
+// contraction of repeated merges, hierarchy collapse to one level, linearity,
+// snapshot == accumulator, bf16 upcast vs torch, protocol counters.
+// Full-size end states (hundreds of events on 70M..1B parameters) have no
+// external reference: they are pinned only through the tiny cases above plus
+// elementwise independence -- otherwise parity unpinned.
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <deque>
+#include <vector>
+
+namespace {
+
+enum ItemKind { ITEM_DELTA = 1, ITEM_GLOBAL = 2 };
+enum Phase {
+    ACCUMULATING = 0,   // no Delta in flight
+    SENT = 1,           // Delta frozen and travelling to the GPS
+    RETURNING = 2,      // GPS has applied it; the global model is travelling back
+    QUEUED = 3          // the global model sits in this LPS's queue
+};
+
+struct StepInfo {       // what one lps_step did (mirrors nothing: its own layout)
+    int32_t kind;       // 0 nothing queued, 1 worker update, 2 global-model merge
+    int32_t sent;       // 1 if this update reached the accumulation count and froze a Delta
+    int32_t accumulated;// 1 if this update counted towards the Delta being accumulated
+    int32_t worker;     // worker whose delta was applied (-1 for a merge)
+    int64_t t;
+    int64_t t_last;
+};
+
+template <class R>
+struct Rule { R eta, beta, cg; };
+
+// ModelUpdate (Appendix E): momentum first, then the step.  Returns the step
+// that was subtracted so that callers can accumulate it.
+template <class R>
+inline R model_update(R &x, R &m, R grad, const Rule<R> &r) {
+    m = std::fma(r.beta, m, grad);                       // m <- beta m + grad
+    R direction = std::fma(r.beta, m, r.cg * grad);      // (1-beta) grad + beta m   (cg = 1-beta)
+    R step = r.eta * direction;
+    x = x - step;
+    return step;
+}
+
+template <class R>
+struct QueueItem {
+    int kind;
+    int worker;
+    std::vector<float> grad;     // pseudo-gradient values (exactly representable in fp32)
+};
+
+template <class R>
+struct Lps {
+    std::vector<R> theta, m;
+    std::vector<R> snap;         // form 0: theta_{t_last}
+    std::vector<R> acc;          // form 1: sum of steps since t_last
+    std::vector<R> frozen;       // G = theta_{t_last} - theta_t at the send (= -Delta)
+    std::vector<R> inbox;        // the global model returned for this LPS
+    std::vector<R> sc_theta, sc_m, sc_aux;   // running max |value| (error scale for fp32 comparisons)
+    std::deque<QueueItem<R>> queue;
+    std::vector<char> worker_queued;
+    int64_t t = 0, t_last = 0;
+    int32_t K = 1;
+    int phase = ACCUMULATING;
+};
+
+template <class R>
+struct Oracle {
+    int64_t n;
+    int form;
+    Rule<R> local, global;
+    R alpha;
+    std::vector<R> Theta, M, sc_Theta, sc_M;
+    int64_t gps_updates = 0;
+    std::vector<Lps<R>> lps;
+
+    static void grow(std::vector<R> &scale, const std::vector<R> &v) {
+        for (size_t j = 0; j < v.size(); ++j) {
+            R a = std::fabs(v[j]);
+            if (a > scale[j]) scale[j] = a;
+        }
+    }
+
+    Oracle(int64_t n_, int n_lps, int form_, Rule<R> loc, Rule<R> glob, R alpha_,
+           const int32_t *K, const float *theta0)
+        : n(n_), form(form_), local(loc), global(glob), alpha(alpha_) {
+        Theta.assign(theta0, theta0 + n);
+        M.assign(n, R(0));
+        sc_Theta.assign(n, R(0)); sc_M.assign(n, R(0));
+        grow(sc_Theta, Theta);
+        lps.resize(n_lps);
+        for (int l = 0; l < n_lps; ++l) {
+            Lps<R> &s = lps[l];
+            s.theta = Theta;                 // Alg. 1 line 6: theta_0 <- Theta_0
+            s.m.assign(n, R(0));
+            s.snap = Theta;
+            s.acc.assign(n, R(0));
+            s.frozen.assign(n, R(0));
+            s.inbox.assign(n, R(0));
+            s.sc_theta.assign(n, R(0)); s.sc_m.assign(n, R(0)); s.sc_aux.assign(n, R(0));
+            grow(s.sc_theta, s.theta);
+            s.K = K[l];
+        }
+    }
+
+    // Alg. 1 line 9: a worker's delta arrives and joins the queue.
+    int arrive_delta(int l, int worker, const float *g) {
+        Lps<R> &s = lps[l];
+        if (worker < 0) return -1;
+        if ((size_t)worker >= s.worker_queued.size()) s.worker_queued.resize(worker + 1, 0);
+        if (s.worker_queued[worker]) return -2;            // one delta per worker at a time
+        s.worker_queued[worker] = 1;
+        QueueItem<R> it;
+        it.kind = ITEM_DELTA; it.worker = worker; it.grad.assign(g, g + n);
+        s.queue.push_back(std::move(it));
+        return 0;
+    }
+
+    // Alg. 1 line 17: the global model sent back by the GPS arrives and joins the same queue.
+    int arrive_global(int l) {
+        Lps<R> &s = lps[l];
+        if (s.phase != RETURNING) return -2;
+        s.phase = QUEUED;
+        QueueItem<R> it; it.kind = ITEM_GLOBAL; it.worker = -1;
+        s.queue.push_back(std::move(it));
+        return 0;
+    }
+
+    // Handle the head of the queue: lines 10-15 for a delta, lines 18-19 for a global model.
+    int lps_step(int l, StepInfo *info) {
+        Lps<R> &s = lps[l];
+        StepInfo out{}; out.worker = -1;
+        if (s.queue.empty()) { out.t = s.t; out.t_last = s.t_last; *info = out; return 0; }
+        QueueItem<R> it = std::move(s.queue.front());
+        s.queue.pop_front();
+        if (it.kind == ITEM_DELTA) {
+            s.t += 1;                                                   // line 10
+            const bool accumulate = (s.phase == ACCUMULATING);
+            for (int64_t j = 0; j < n; ++j) {                           // line 11
+                R step = model_update<R>(s.theta[j], s.m[j], R(it.grad[j]), local);
+                if (form == 1 && accumulate) s.acc[j] = s.acc[j] + step;
+            }
+            grow(s.sc_theta, s.theta); grow(s.sc_m, s.m);
+            if (accumulate) {
+                if (form == 1) grow(s.sc_aux, s.acc);
+                else for (int64_t j = 0; j < n; ++j) {
+                    R a = std::fabs(s.snap[j] - s.theta[j]);
+                    if (a > s.sc_aux[j]) s.sc_aux[j] = a;
+                }
+            }
+            s.worker_queued[it.worker] = 0;
+            out.kind = 1; out.worker = it.worker; out.accumulated = accumulate ? 1 : 0;
+            if (accumulate && s.t - s.t_last >= s.K) {                  // line 13
+                for (int64_t j = 0; j < n; ++j)                         // line 14, sign flipped: G = -Delta
+                    s.frozen[j] = (form == 1) ? s.acc[j] : (s.snap[j] - s.theta[j]);
+                s.phase = SENT;
+                out.sent = 1;
+            }
+        } else {
+            if (s.phase != QUEUED) return -3;
+            s.t_last = s.t;                                             // line 18
+            const R keep = R(1) - alpha;
+            for (int64_t j = 0; j < n; ++j)                             // line 19
+                s.theta[j] = std::fma(alpha, s.inbox[j], keep * s.theta[j]);
+            grow(s.sc_theta, s.theta);
+            s.snap = s.theta;                                           // theta_{t_last}: the post-merge model
+            std::fill(s.acc.begin(), s.acc.end(), R(0));
+            std::fill(s.sc_aux.begin(), s.sc_aux.end(), R(0));
+            s.phase = ACCUMULATING;
+            out.kind = 2;
+        }
+        out.t = s.t; out.t_last = s.t_last;
+        *info = out;
+        return 0;
+    }
+
+    // GPS lines 2-4 for the Delta that LPS l has in flight.
+    int gps_receive(int l) {
+        Lps<R> &s = lps[l];
+        if (s.phase != SENT) return -2;
+        gps_updates += 1;
+        for (int64_t j = 0; j < n; ++j)
+            model_update<R>(Theta[j], M[j], s.frozen[j], global);       // line 3
+        grow(sc_Theta, Theta); grow(sc_M, M);
+        s.inbox = Theta;                                                // line 4: this Theta_i, frozen
+        s.sc_aux = sc_Theta;
+        s.phase = RETURNING;
+        return 0;
+    }
+
+    // The "third buffer" of an LPS as a single-buffer implementation would hold it:
+    // the running accumulation, then the frozen G, then the returned global model.
+    void aux(int l, std::vector<R> &out) const {
+        const Lps<R> &s = lps[l];
+        out.resize(n);
+        if (s.phase == ACCUMULATING) {
+            for (int64_t j = 0; j < n; ++j) out[j] = (form == 1) ? s.acc[j] : (s.snap[j] - s.theta[j]);
+        } else if (s.phase == SENT) {
+            out = s.frozen;
+        } else {
+            out = s.inbox;
+        }
+    }
+};
+
+struct Handle {
+    int precision;
+    Oracle<float> *f = nullptr;
+    Oracle<double> *d = nullptr;
+};
+
+template <class R>
+void copy_out(const std::vector<R> &v, double *out) {
+    for (size_t j = 0; j < v.size(); ++j) out[j] = (double)v[j];
+}
+
+template <class R>
+int get_impl(Oracle<R> *o, int what, int l, double *out) {
+    if (what >= 0 && what <= 2 && (l < 0 || (size_t)l >= o->lps.size())) return -1;
+    switch (what) {
+        case 0: copy_out(o->lps[l].theta, out); return 0;
+        case 1: copy_out(o->lps[l].m, out); return 0;
+        case 2: { std::vector<R> a; o->aux(l, a); copy_out(a, out); return 0; }
+        case 3: copy_out(o->Theta, out); return 0;
+        case 4: copy_out(o->M, out); return 0;
+        case 10: copy_out(o->lps[l].sc_theta, out); return 0;
+        case 11: copy_out(o->lps[l].sc_m, out); return 0;
+        case 12: copy_out(o->lps[l].sc_aux, out); return 0;
+        case 13: copy_out(o->sc_Theta, out); return 0;
+        case 14: copy_out(o->sc_M, out); return 0;
+    }
+    return -1;
+}
+
+inline float bf16_to_f32(uint16_t bits) {       // bfloat16 is the upper half of a binary32
+    uint32_t u = (uint32_t)bits << 16;
+    float f;
+    std::memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+}  // namespace
+
+extern "C" {
+
+void *ho_create(int64_t n, int32_t n_lps, int32_t precision, int32_t form,
+                float eta_l, float beta_l, float cg_l, float eta_g, float beta_g, float cg_g,
+                float alpha, const int32_t *K, const float *theta0) {
+    if (n <= 0 || n_lps <= 0 || (precision != 32 && precision != 64) || (form != 0 && form != 1)) return nullptr;
+    Handle *h = new Handle;
+    h->precision = precision;
+    if (precision == 32)
+        h->f = new Oracle<float>(n, n_lps, form, Rule<float>{eta_l, beta_l, cg_l},
+                                 Rule<float>{eta_g, beta_g, cg_g}, alpha, K, theta0);
+    else
+        h->d = new Oracle<double>(n, n_lps, form, Rule<double>{eta_l, beta_l, cg_l},
+                                  Rule<double>{eta_g, beta_g, cg_g}, (double)alpha, K, theta0);
+    return h;
+}
+
+void ho_destroy(void *p) {
+    Handle *h = (Handle *)p;
+    if (!h) return;
+    delete h->f; delete h->d; delete h;
+}
+
+#define DISPATCH(call) (h->precision == 32 ? h->f->call : h->d->call)
+
+int ho_arrive_delta_f32(void *p, int32_t l, int32_t worker, const float *g) {
+    Handle *h = (Handle *)p;
+    return DISPATCH(arrive_delta(l, worker, g));
+}
+
+int ho_arrive_delta_bf16(void *p, int32_t l, int32_t worker, const uint16_t *g) {
+    Handle *h = (Handle *)p;
+    int64_t n = h->precision == 32 ? h->f->n : h->d->n;
+    std::vector<float> up(n);
+    for (int64_t j = 0; j < n; ++j) up[j] = bf16_to_f32(g[j]);
+    return DISPATCH(arrive_delta(l, worker, up.data()));
+}
+
+int ho_arrive_global(void *p, int32_t l) { Handle *h = (Handle *)p; return DISPATCH(arrive_global(l)); }
+
+int ho_lps_step(void *p, int32_t l, void *info) {
+    Handle *h = (Handle *)p;
+    return DISPATCH(lps_step(l, (StepInfo *)info));
+}
+
+int ho_gps_receive(void *p, int32_t l) { Handle *h = (Handle *)p; return DISPATCH(gps_receive(l)); }
+
+int ho_set_K(void *p, int32_t l, int32_t K) {
+    Handle *h = (Handle *)p;
+    if (K < 1) return -1;
+    if (h->precision == 32) h->f->lps[l].K = K; else h->d->lps[l].K = K;
+    return 0;
+}
+
+int ho_set_rules(void *p, float eta_l, float beta_l, float cg_l, float eta_g, float beta_g, float cg_g, float alpha) {
+    Handle *h = (Handle *)p;
+    if (h->precision == 32) {
+        h->f->local = Rule<float>{eta_l, beta_l, cg_l}; h->f->global = Rule<float>{eta_g, beta_g, cg_g}; h->f->alpha = alpha;
+    } else {
+        h->d->local = Rule<double>{eta_l, beta_l, cg_l}; h->d->global = Rule<double>{eta_g, beta_g, cg_g}; h->d->alpha = alpha;
+    }
+    return 0;
+}
+
+// what: 0 theta_l, 1 m_l, 2 third buffer of l (accumulation / frozen G / returned model),
+//       3 Theta, 4 M;  10..14 the running max-magnitude of the same five arrays.
+int ho_get(void *p, int32_t what, int32_t l, double *out) {
+    Handle *h = (Handle *)p;
+    return h->precision == 32 ? get_impl(h->f, what, l, out) : get_impl(h->d, what, l, out);
+}
+
+int ho_counters(void *p, int32_t l, int64_t *t, int64_t *t_last, int32_t *phase, int32_t *queued, int64_t *gps_updates) {
+    Handle *h = (Handle *)p;
+    if (h->precision == 32) {
+        auto &s = h->f->lps[l]; *t = s.t; *t_last = s.t_last; *phase = s.phase; *queued = (int32_t)s.queue.size();
+        *gps_updates = h->f->gps_updates;
+    } else {
+        auto &s = h->d->lps[l]; *t = s.t; *t_last = s.t_last; *phase = s.phase; *queued = (int32_t)s.queue.size();
+        *gps_updates = h->d->gps_updates;
+    }
+    return 0;
+}
+
+float ho_bf16_to_f32(uint16_t bits) { return bf16_to_f32(bits); }
+
+}  // extern "C"
