@@ -1,0 +1,216 @@
+/*
+ * halos.h -- C ABI of the HALoS server-side update path on one AMD GPU.
+ *
+ * HALoS (arXiv 2506.04531) trains with a two-level parameter-server hierarchy:
+ * local parameter servers (LPS) apply worker deltas with a momentum step and
+ * accumulate them, a global parameter server (GPS) applies the accumulated
+ * updates with its own momentum step, and each LPS merges the returned global
+ * model into its local model (Algorithm 1; update rule in Appendix E).  This
+ * library is that server side, over a list of parameter tensors that all live
+ * in one GPU's memory.  Each call below is one message or one step of
+ * Algorithm 1.
+ *
+ * Conventions
+ *   Pointers     "device" pointers are GPU addresses, "host" pointers are CPU
+ *                addresses.  Pointer ARRAYS (void *const *) are host arrays of
+ *                n_tensors device pointers, one per tensor of the layout.
+ *   Layout       tensor i is a contiguous array of numel[i] elements; every
+ *                non-empty tensor's base address must be 16-byte aligned.
+ *                Server state is fp32.  Worker deltas are fp32 or bfloat16.
+ *   Ownership    all parameter-sized buffers are allocated by the caller and
+ *                only BORROWED: state buffers for the life of the handle, a
+ *                pushed delta until the step that consumes it has finished on
+ *                its stream, a pull destination until that copy has finished.
+ *                The library allocates only small tables and frees them in the
+ *                destroy calls.  It never frees caller memory.
+ *   Streams      `stream` is a hipStream_t (NULL = the default stream).  Device
+ *                work is enqueued there and the call returns; the caller
+ *                synchronises.  All calls that touch the same server's state
+ *                must be issued on streams that are ordered with each other.
+ *   Threads      a handle may be used by one host thread at a time.
+ *   Errors       every call returns a halos_status; on anything but HALOS_OK no
+ *                host or device state has been modified and halos_last_error()
+ *                describes the problem (thread-local string).
+ *   Sign         a "delta" handed to this library is the PSEUDO-GRADIENT
+ *                g = (model the sender started from) - (model it ended with),
+ *                i.e. the negative of Algorithm 1's delta / Delta, so that
+ *                beta = 0, eta = 1 adopts the sender's progress.
+ */
+#ifndef HALOS_H
+#define HALOS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct halos_gps halos_gps;   /* opaque: global parameter server */
+typedef struct halos_lps halos_lps;   /* opaque: local parameter server  */
+
+typedef enum {
+    HALOS_OK = 0,
+    HALOS_EINVAL = 1,   /* bad argument: null/misaligned pointer, bad size, bad hyper-parameter */
+    HALOS_ESTATE = 2,   /* call not allowed in the current protocol state */
+    HALOS_ENOMEM = 3,   /* a small table could not be allocated */
+    HALOS_EHIP = 4      /* the HIP runtime reported an error */
+} halos_status;
+
+typedef enum { HALOS_F32 = 0, HALOS_BF16 = 1 } halos_dtype;
+
+/* Tensor list.  numel is a host array, copied by the create call. */
+typedef struct {
+    int32_t n_tensors;
+    const int64_t *numel;
+} halos_layout;
+
+/* ModelUpdate(x, g, eta, beta) of Algorithm 1, as defined in Appendix E:
+ *     m <- beta * m + g
+ *     x <- x - eta * (cg * g + beta * m)
+ * The paper's rule has cg = 1 - beta; cg = 1 is the textbook Nesterov step. */
+typedef struct {
+    float eta;
+    float beta;
+    float cg;
+} halos_rule;
+
+/* Hyper-parameters of Algorithm 1 (its REQUIRE line). */
+typedef struct {
+    halos_rule local;    /* eta_l, beta_l: used by every LPS                       */
+    halos_rule global;   /* eta_g, beta_g: used by the GPS                         */
+    float alpha;         /* merge weight of the global model, 0 <= alpha <= 1      */
+    int32_t K;           /* local updates accumulated before a Delta is sent, >= 1 */
+    uint32_t flags;      /* reserved, must be 0                                    */
+} halos_hparams;
+
+/* What one halos_lps_step did. */
+typedef struct {
+    int32_t kind;         /* 0 queue was empty, 1 applied a worker delta, 2 merged a global model */
+    int32_t delta_ready;  /* 1 if this update reached the accumulation count: the accumulated
+                             update is now frozen and waits for halos_gps_merge               */
+    int32_t accumulated;  /* 1 if this update was added to the accumulated update             */
+    int32_t worker;       /* worker whose delta was applied, -1 otherwise                     */
+    int64_t t;            /* number of worker updates applied so far (Alg. 1 line 10)         */
+    int64_t t_last;       /* value of t at the last merge (line 18)                           */
+} halos_step_info;
+
+/* Protocol phase of an LPS with respect to its accumulated update. */
+enum {
+    HALOS_PHASE_ACCUMULATING = 0,  /* collecting updates; nothing in flight         */
+    HALOS_PHASE_SENT = 1,          /* frozen update waits for halos_gps_merge       */
+    HALOS_PHASE_RETURNING = 2,     /* GPS applied it; global model not yet arrived  */
+    HALOS_PHASE_QUEUED = 3         /* global model sits in the LPS queue            */
+};
+
+/*
+ * Create the GPS (Algorithm 1, REQUIRE line and GPS block).
+ *   layout   tensor list (copied).  Tensors with numel 0 are allowed and skipped.
+ *   hp       hyper-parameters (copied); hp->global is the GPS rule.
+ *   Theta    device tensors holding the initial model Theta_0 (read and later updated in place).
+ *   M        device tensors for the GPS momentum; zero-filled on `stream` by this call.
+ * Errors: EINVAL (null/misaligned pointers, n_tensors < 1, negative numel, more than 2^32-1 elements
+ * in one tensor, non-finite or out-of-range hyper-parameters), ENOMEM, EHIP.
+ */
+halos_status halos_gps_create(const halos_layout *layout, const halos_hparams *hp,
+                              void *const *Theta, void *const *M, void *stream, halos_gps **out);
+
+/*
+ * Create one LPS attached to `gps` (Algorithm 1 line 6: theta_0 <- Theta_0, t <- 0, t_last <- 0).
+ *   lps_id      caller's label for this server, >= 0 (reported in error strings only)
+ *   n_workers   number of workers that may push to it, >= 1
+ *   theta,m,acc device tensors of the layout.  On `stream` this call copies the GPS's CURRENT model into
+ *               theta and zero-fills m and acc.  `acc` is the server's third buffer: it holds the
+ *               accumulated update G = theta_{t_last} - theta_t while collecting, stays frozen while that
+ *               update is in flight, is overwritten with the returned global model by halos_gps_merge,
+ *               and is zeroed again by the merge step.
+ * The LPS keeps a pointer to the GPS: destroy the LPS first.
+ */
+halos_status halos_lps_create(halos_gps *gps, int32_t lps_id, int32_t n_workers,
+                              void *const *theta, void *const *m, void *const *acc,
+                              void *stream, halos_lps **out);
+
+/*
+ * A worker's delta arrives (Algorithm 1 line 9).  Appends it to the LPS queue (Sec. 4.1 item 2); no device work.
+ *   worker     0 <= worker < n_workers; a worker may have only one delta queued at a time (else ESTATE)
+ *   g          device tensors of the layout holding the pseudo-gradient, dtype fp32 or bf16; borrowed
+ *              until the halos_lps_step that applies it has finished on its stream
+ *   staleness  number of server updates since the worker pulled its start model; carried as metadata
+ *              (HALoS applies no staleness scaling) and readable through halos_lps_get_counters
+ */
+halos_status halos_lps_push_update(halos_lps *lps, int32_t worker, const void *const *g,
+                                   halos_dtype dtype, uint32_t staleness);
+
+/*
+ * The global model sent back by the GPS arrives (Algorithm 1 line 17).  Appends it to the same queue as
+ * the worker deltas; no device work.  ESTATE unless a halos_gps_merge for this LPS has run and its
+ * result has not been delivered yet.
+ */
+halos_status halos_lps_push_global(halos_lps *lps);
+
+/*
+ * Handle the head of the LPS queue, in arrival order (Sec. 4.1 item 2).
+ *   worker delta (lines 10-15): t <- t+1; one fused pass applies ModelUpdate(theta, g, eta_l, beta_l) and,
+ *       unless an accumulated update is in flight, adds the applied step to acc.  If t - t_last has reached
+ *       K and nothing is in flight, acc is frozen as the outgoing update (delta_ready = 1).
+ *   global model (lines 18-19): t_last <- t; theta <- (1-alpha) theta + alpha Theta_i; acc <- 0.
+ * An empty queue is not an error (kind = 0).  `info` may be NULL.
+ */
+halos_status halos_lps_step(halos_lps *lps, void *stream, halos_step_info *info);
+
+/*
+ * The accumulated update of LPS `from` reaches the GPS (Algorithm 1 lines 2-4): one fused pass applies
+ * ModelUpdate(Theta, G, eta_g, beta_g) and writes the new global model Theta_i over `from`'s third buffer,
+ * where it stays frozen until `from` merges it -- later GPS updates do not change it.
+ * ESTATE unless `from` has a frozen update waiting (delta_ready was reported and not yet consumed).
+ */
+halos_status halos_gps_merge(halos_gps *gps, halos_lps *from, void *stream);
+
+/*
+ * Copy a server's current model into caller tensors ("Schedule the worker theta_t", lines 7 and 12; also
+ * usable to read the global model).  server is a halos_lps* (is_gps = 0) or a halos_gps* (is_gps = 1).
+ * dst: device tensors of the layout, fp32.
+ */
+halos_status halos_pull_model(const void *server, int32_t is_gps, void *const *dst, void *stream);
+
+/*
+ * Replace hyper-parameters between events (learning-rate schedules belong to the caller; the theorem of
+ * Sec. 4.2 allows a time-varying rate).  For an LPS: hp->local, hp->alpha and hp->K take effect from the
+ * next step.  For the GPS: hp->global.  Other fields are validated but ignored.
+ */
+halos_status halos_set_hparams(void *server, int32_t is_gps, const halos_hparams *hp);
+
+/* Change only the accumulation count K of one LPS (>= 1), effective from the next step. */
+halos_status halos_lps_set_threshold(halos_lps *lps, int32_t K);
+
+/*
+ * Read the protocol counters of an LPS.  Any out pointer may be NULL.
+ *   t, t_last     as in Algorithm 1
+ *   phase         one of HALOS_PHASE_*
+ *   queued        items waiting in the queue
+ *   max_staleness largest staleness value seen in halos_lps_push_update
+ */
+halos_status halos_lps_get_counters(const halos_lps *lps, int64_t *t, int64_t *t_last, int32_t *phase,
+                                    int32_t *queued, uint32_t *max_staleness);
+
+/* Number of accumulated updates the GPS has applied (the index i of Algorithm 1's GPS loop). */
+halos_status halos_gps_get_counters(const halos_gps *gps, int64_t *updates);
+
+/*
+ * Launch shape for all later kernel launches of the calling process.
+ *   blocks_per_cu  persistent workgroups per compute unit, 1..64 (0 = keep)
+ *   nontemporal    1 = stream state through the caches with non-temporal accesses, 0 = plain, -1 = keep
+ * Returns EINVAL for out-of-range values.
+ */
+halos_status halos_set_launch_config(int32_t blocks_per_cu, int32_t nontemporal);
+
+/* Release the handle's tables.  Caller buffers are untouched.  NULL is ignored. */
+void halos_lps_destroy(halos_lps *lps);
+void halos_gps_destroy(halos_gps *gps);
+
+/* Description of the calling thread's most recent error ("" if none). */
+const char *halos_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HALOS_H */

@@ -1,0 +1,208 @@
+"""ctypes binding of include/halos.h: same names, argument marshalling only.
+
+Tensor arguments are sequences of torch CUDA tensors (one per tensor of the
+layout); the binding passes their data pointers.  `stream` defaults to
+torch's current HIP stream.  Any status other than HALOS_OK raises HalosError
+carrying the status code and the library's message.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+OK, EINVAL, ESTATE, ENOMEM, EHIP = 0, 1, 2, 3, 4
+F32, BF16 = 0, 1
+PHASE_ACCUMULATING, PHASE_SENT, PHASE_RETURNING, PHASE_QUEUED = 0, 1, 2, 3
+
+
+class Rule(ctypes.Structure):
+    _fields_ = [("eta", ctypes.c_float), ("beta", ctypes.c_float), ("cg", ctypes.c_float)]
+
+
+class HParams(ctypes.Structure):
+    _fields_ = [("local", Rule), ("glob", Rule), ("alpha", ctypes.c_float), ("K", ctypes.c_int32),
+                ("flags", ctypes.c_uint32)]
+
+
+class _Layout(ctypes.Structure):
+    _fields_ = [("n_tensors", ctypes.c_int32), ("numel", ctypes.POINTER(ctypes.c_int64))]
+
+
+class StepInfo(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("delta_ready", ctypes.c_int32), ("accumulated", ctypes.c_int32),
+                ("worker", ctypes.c_int32), ("t", ctypes.c_int64), ("t_last", ctypes.c_int64)]
+
+
+class HalosError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"halos status {status}: {message}")
+        self.status = status
+        self.message = message
+
+
+def paper_hparams(eta_l: float, beta_l: float, eta_g: float, beta_g: float, alpha: float, K: int,
+                  cg_l: Optional[float] = None, cg_g: Optional[float] = None) -> HParams:
+    """Hyper-parameter block with the paper's coefficient cg = 1 - beta (formed in fp32) unless given."""
+    f = np.float32
+    hp = HParams()
+    hp.local = Rule(f(eta_l), f(beta_l), f(f(1) - f(beta_l)) if cg_l is None else f(cg_l))
+    hp.glob = Rule(f(eta_g), f(beta_g), f(f(1) - f(beta_g)) if cg_g is None else f(cg_g))
+    hp.alpha = f(alpha)
+    hp.K = int(K)
+    hp.flags = 0
+    return hp
+
+
+_lib = None
+
+
+def load_library():
+    """Load libhalos.so (building it first only if it does not exist)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    from . import LIB_PATH, build
+    if not os.path.exists(LIB_PATH):
+        build()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, u32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32
+    P = ctypes.POINTER
+    sigs = {
+        "halos_gps_create": [P(_Layout), P(HParams), P(vp), P(vp), vp, P(vp)],
+        "halos_lps_create": [vp, i32, i32, P(vp), P(vp), P(vp), vp, P(vp)],
+        "halos_lps_push_update": [vp, i32, P(vp), i32, u32],
+        "halos_lps_push_global": [vp],
+        "halos_lps_step": [vp, vp, P(StepInfo)],
+        "halos_gps_merge": [vp, vp, vp],
+        "halos_pull_model": [vp, i32, P(vp), vp],
+        "halos_set_hparams": [vp, i32, P(HParams)],
+        "halos_lps_set_threshold": [vp, i32],
+        "halos_lps_get_counters": [vp, P(i64), P(i64), P(i32), P(i32), P(u32)],
+        "halos_gps_get_counters": [vp, P(i64)],
+        "halos_set_launch_config": [i32, i32],
+    }
+    for name, args in sigs.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = ctypes.c_int
+    lib.halos_lps_destroy.argtypes = [vp]
+    lib.halos_lps_destroy.restype = None
+    lib.halos_gps_destroy.argtypes = [vp]
+    lib.halos_gps_destroy.restype = None
+    lib.halos_last_error.argtypes = []
+    lib.halos_last_error.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def halos_last_error() -> str:
+    return load_library().halos_last_error().decode()
+
+
+def _check(status: int):
+    if status != OK:
+        raise HalosError(status, halos_last_error())
+
+
+def _ptrs(tensors) -> ctypes.Array:
+    """Host array of device pointers.  Accepts torch tensors or raw integer addresses (None -> NULL)."""
+    if tensors is None or isinstance(tensors, ctypes.Array):
+        return tensors
+    arr = (ctypes.c_void_p * max(1, len(tensors)))()
+    for i, t in enumerate(tensors):
+        if t is None:
+            arr[i] = None
+        elif isinstance(t, int):
+            arr[i] = t
+        else:
+            arr[i] = t.data_ptr() if t.numel() > 0 else None
+    return arr
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def halos_gps_create(numel: Sequence[int], hp: HParams, Theta, M, stream=None) -> int:
+    lib = load_library()
+    n = len(numel)
+    arr = (ctypes.c_int64 * max(1, n))(*[int(x) for x in numel])
+    lay = _Layout(n, arr)
+    out = ctypes.c_void_p()
+    _check(lib.halos_gps_create(ctypes.byref(lay), ctypes.byref(hp), _ptrs(Theta), _ptrs(M), _stream(stream),
+                                ctypes.byref(out)))
+    return out.value
+
+
+def halos_lps_create(gps: int, lps_id: int, n_workers: int, theta, m, acc, stream=None) -> int:
+    lib = load_library()
+    out = ctypes.c_void_p()
+    _check(lib.halos_lps_create(gps, lps_id, n_workers, _ptrs(theta), _ptrs(m), _ptrs(acc), _stream(stream),
+                                ctypes.byref(out)))
+    return out.value
+
+
+def halos_lps_push_update(lps: int, worker: int, g, dtype: int, staleness: int = 0) -> None:
+    _check(load_library().halos_lps_push_update(lps, worker, _ptrs(g), dtype, staleness))
+
+
+def halos_lps_push_global(lps: int) -> None:
+    _check(load_library().halos_lps_push_global(lps))
+
+
+def halos_lps_step(lps: int, stream=None) -> StepInfo:
+    info = StepInfo()
+    _check(load_library().halos_lps_step(lps, _stream(stream), ctypes.byref(info)))
+    return info
+
+
+def halos_gps_merge(gps: int, from_lps: int, stream=None) -> None:
+    _check(load_library().halos_gps_merge(gps, from_lps, _stream(stream)))
+
+
+def halos_pull_model(server: int, is_gps: bool, dst, stream=None) -> None:
+    _check(load_library().halos_pull_model(server, 1 if is_gps else 0, _ptrs(dst), _stream(stream)))
+
+
+def halos_set_hparams(server: int, is_gps: bool, hp: HParams) -> None:
+    _check(load_library().halos_set_hparams(server, 1 if is_gps else 0, ctypes.byref(hp)))
+
+
+def halos_lps_set_threshold(lps: int, K: int) -> None:
+    _check(load_library().halos_lps_set_threshold(lps, K))
+
+
+def halos_lps_get_counters(lps: int) -> dict:
+    t, tl = ctypes.c_int64(), ctypes.c_int64()
+    ph, q, ms = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_uint32()
+    _check(load_library().halos_lps_get_counters(lps, ctypes.byref(t), ctypes.byref(tl), ctypes.byref(ph),
+                                                 ctypes.byref(q), ctypes.byref(ms)))
+    return {"t": t.value, "t_last": tl.value, "phase": ph.value, "queued": q.value, "max_staleness": ms.value}
+
+
+def halos_gps_get_counters(gps: int) -> dict:
+    u = ctypes.c_int64()
+    _check(load_library().halos_gps_get_counters(gps, ctypes.byref(u)))
+    return {"updates": u.value}
+
+
+def halos_set_launch_config(blocks_per_cu: int = 0, nontemporal: int = -1) -> None:
+    _check(load_library().halos_set_launch_config(blocks_per_cu, nontemporal))
+
+
+def halos_lps_destroy(lps: Optional[int]) -> None:
+    if lps:
+        load_library().halos_lps_destroy(lps)
+
+
+def halos_gps_destroy(gps: Optional[int]) -> None:
+    if gps:
+        load_library().halos_gps_destroy(gps)

@@ -1,0 +1,492 @@
+// C ABI of the HALoS server-side update path (see include/halos.h for the contract of every call).
+// This file is host logic only: argument checking, the protocol state machine, the small device
+// tables, and the decision which kernel to launch.  All parameter arithmetic is in kernels.hip.
+#include "../../include/halos.h"
+
+#include <hip/hip_runtime_api.h>
+
+#include <atomic>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "kernels.hpp"
+#include "protocol.hpp"
+
+using namespace halos;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+halos_status fail(halos_status code, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return code;
+}
+
+halos_status fail_hip(hipError_t e, const char *what) {
+    return fail(HALOS_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+std::atomic<int> g_blocks_per_cu{8};
+std::atomic<int> g_nontemporal{1};
+
+constexpr uint32_t GPS_MAGIC = 0x48475053u;   // "HGPS"
+constexpr uint32_t LPS_MAGIC = 0x484c5053u;   // "HLPS"
+
+bool rule_ok(const halos_rule &r) {
+    return std::isfinite(r.eta) && std::isfinite(r.beta) && std::isfinite(r.cg);
+}
+
+halos_status check_hparams(const halos_hparams *hp) {
+    if (!hp) return fail(HALOS_EINVAL, "hparams is NULL");
+    if (!rule_ok(hp->local) || !rule_ok(hp->global)) return fail(HALOS_EINVAL, "non-finite eta/beta/cg");
+    if (!(hp->alpha >= 0.0f && hp->alpha <= 1.0f)) return fail(HALOS_EINVAL, "alpha %g outside [0,1]", (double)hp->alpha);
+    if (hp->K < 1) return fail(HALOS_EINVAL, "K = %d, must be >= 1", hp->K);
+    if (hp->flags != 0) return fail(HALOS_EINVAL, "flags must be 0");
+    return HALOS_OK;
+}
+
+}  // namespace
+
+struct halos_gps {
+    uint32_t magic = GPS_MAGIC;
+    int device = 0;
+    int n_cu = 1;
+    std::vector<int64_t> numel;
+    int64_t total = 0;
+    std::vector<TileRange> ranges;
+    Tile *d_tiles = nullptr;
+    uint32_t n_tiles = 0;
+    void *d_tables = nullptr;          // one allocation: [Theta pointers | M pointers]
+    float **d_Theta = nullptr, **d_M = nullptr;
+    halos_rule rule{};
+    halos_hparams hp{};
+    int64_t updates = 0;
+    int n_lps_attached = 0;
+};
+
+struct PendingDelta {
+    std::vector<const void *> ptrs;
+    halos_dtype dtype = HALOS_F32;
+    uint32_t staleness = 0;
+};
+
+struct halos_lps {
+    uint32_t magic = LPS_MAGIC;
+    halos_gps *gps = nullptr;
+    int32_t id = 0;
+    void *d_tables = nullptr;          // one allocation: [theta | m | acc] pointer tables
+    float **d_theta = nullptr, **d_m = nullptr, **d_acc = nullptr;
+    halos_rule rule{};
+    float alpha = 0.f;
+    LpsProtocol proto;
+    std::vector<PendingDelta> pending;           // per worker: the delta it has queued
+    std::vector<std::vector<const void *>> validated;   // per worker: last pointer set whose ranges were checked
+    std::vector<halos_dtype> validated_dtype;
+    std::vector<const void *> validated_pull;
+    uint32_t max_staleness = 0;
+    halos_lps(int32_t n_workers, int32_t K) : proto(n_workers, K) {}
+};
+
+namespace {
+
+LaunchShape current_shape(const halos_gps *g) {
+    LaunchShape s;
+    s.grid_cap = g_blocks_per_cu.load() * g->n_cu;
+    s.nontemporal = g_nontemporal.load() != 0;
+    return s;
+}
+
+// Each non-empty tensor must be a 16-byte aligned device address with room for numel elements.
+halos_status check_tensors(const halos_gps *g, const void *const *ptrs, size_t elem_bytes, const char *what) {
+    if (!ptrs) return fail(HALOS_EINVAL, "%s: pointer array is NULL", what);
+    for (size_t i = 0; i < g->numel.size(); ++i) {
+        if (g->numel[i] == 0) continue;
+        const void *p = ptrs[i];
+        if (!p) return fail(HALOS_EINVAL, "%s: tensor %zu is NULL", what, i);
+        if ((reinterpret_cast<uintptr_t>(p) & 15u) != 0)
+            return fail(HALOS_EINVAL, "%s: tensor %zu is not 16-byte aligned", what, i);
+        hipPointerAttribute_t attr;
+        hipError_t e = hipPointerGetAttributes(&attr, p);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(HALOS_EINVAL, "%s: tensor %zu is not a device pointer (%s)", what, i, hipGetErrorString(e));
+        }
+        if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged)
+            return fail(HALOS_EINVAL, "%s: tensor %zu is not device memory", what, i);
+        if (attr.type == hipMemoryTypeDevice && attr.device != g->device)
+            return fail(HALOS_EINVAL, "%s: tensor %zu lives on device %d, server on %d", what, i, attr.device, g->device);
+        hipDeviceptr_t base = nullptr;
+        size_t size = 0;
+        e = hipMemGetAddressRange(&base, &size, const_cast<void *>(p));
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(HALOS_EINVAL, "%s: tensor %zu: cannot query its allocation (%s)", what, i, hipGetErrorString(e));
+        }
+        const uintptr_t end = reinterpret_cast<uintptr_t>(p) + (size_t)g->numel[i] * elem_bytes;
+        if (end > reinterpret_cast<uintptr_t>(base) + size)
+            return fail(HALOS_EINVAL, "%s: tensor %zu (%lld elements) runs past the end of its allocation", what, i,
+                        (long long)g->numel[i]);
+    }
+    return HALOS_OK;
+}
+
+halos_status check_device(const halos_gps *g) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    if (dev != g->device) return fail(HALOS_EINVAL, "current device %d differs from the server's device %d", dev, g->device);
+    return HALOS_OK;
+}
+
+void fill_args(PtrArgs &a, const void *const *ptrs, const TileRange &r, size_t n_tensors) {
+    for (int i = 0; i < MAX_ARG_TENSORS; ++i) {
+        const size_t t = (size_t)r.tensor_base + i;
+        a.p[i] = t < n_tensors ? ptrs[t] : nullptr;
+    }
+}
+
+halos_status upload_tables(void **d_out, const std::vector<const void *const *> &host_tabs, size_t n_tensors) {
+    const size_t bytes = host_tabs.size() * n_tensors * sizeof(void *);
+    void *d = nullptr;
+    hipError_t e = hipMalloc(&d, bytes ? bytes : sizeof(void *));
+    if (e != hipSuccess) { (void)hipGetLastError(); return fail(HALOS_ENOMEM, "pointer tables: %s", hipGetErrorString(e)); }
+    std::vector<const void *> flat;
+    flat.reserve(host_tabs.size() * n_tensors);
+    for (const void *const *tab : host_tabs)
+        for (size_t i = 0; i < n_tensors; ++i) flat.push_back(tab[i]);
+    if (bytes) {
+        e = hipMemcpy(d, flat.data(), bytes, hipMemcpyHostToDevice);
+        if (e != hipSuccess) { (void)hipFree(d); return fail_hip(e, "uploading pointer tables"); }
+    }
+    *d_out = d;
+    return HALOS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *halos_last_error(void) { return g_last_error.c_str(); }
+
+halos_status halos_set_launch_config(int32_t blocks_per_cu, int32_t nontemporal) {
+    if (blocks_per_cu < 0 || blocks_per_cu > 64) return fail(HALOS_EINVAL, "blocks_per_cu %d outside 0..64", blocks_per_cu);
+    if (nontemporal < -1 || nontemporal > 1) return fail(HALOS_EINVAL, "nontemporal %d outside -1..1", nontemporal);
+    if (blocks_per_cu > 0) g_blocks_per_cu.store(blocks_per_cu);
+    if (nontemporal >= 0) g_nontemporal.store(nontemporal);
+    return HALOS_OK;
+}
+
+halos_status halos_gps_create(const halos_layout *layout, const halos_hparams *hp, void *const *Theta, void *const *M,
+                              void *stream, halos_gps **out) {
+    if (!out) return fail(HALOS_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (!layout || !layout->numel) return fail(HALOS_EINVAL, "layout is NULL");
+    if (layout->n_tensors < 1) return fail(HALOS_EINVAL, "n_tensors = %d, must be >= 1", layout->n_tensors);
+    halos_status st = check_hparams(hp);
+    if (st != HALOS_OK) return st;
+    for (int32_t i = 0; i < layout->n_tensors; ++i) {
+        if (layout->numel[i] < 0) return fail(HALOS_EINVAL, "numel[%d] is negative", i);
+        if (layout->numel[i] > (int64_t)0xFFFFFFFFll) return fail(HALOS_EINVAL, "numel[%d] exceeds 2^32-1", i);
+    }
+    halos_gps *g = new (std::nothrow) halos_gps;
+    if (!g) return fail(HALOS_ENOMEM, "host allocation failed");
+    hipError_t e = hipGetDevice(&g->device);
+    if (e != hipSuccess) { delete g; return fail_hip(e, "hipGetDevice"); }
+    int n_cu = 0;
+    e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, g->device);
+    if (e != hipSuccess) { delete g; return fail_hip(e, "hipDeviceGetAttribute"); }
+    g->n_cu = n_cu > 0 ? n_cu : 1;
+    g->numel.assign(layout->numel, layout->numel + layout->n_tensors);
+    for (int64_t v : g->numel) g->total += v;
+    g->hp = *hp;
+    g->rule = hp->global;
+
+    st = check_tensors(g, Theta, sizeof(float), "Theta");
+    if (st == HALOS_OK) st = check_tensors(g, M, sizeof(float), "M");
+    if (st != HALOS_OK) { delete g; return st; }
+
+    // tile table and launch ranges
+    std::vector<Tile> tiles;
+    const size_t nt = g->numel.size();
+    for (size_t base = 0; base < nt; base += MAX_ARG_TENSORS) {
+        TileRange r;
+        r.tensor_base = (uint32_t)base;
+        r.lo = (uint32_t)tiles.size();
+        for (size_t t = base; t < nt && t < base + MAX_ARG_TENSORS; ++t)
+            for (int64_t s = 0; s < g->numel[t]; s += TILE_ELEMS) {
+                Tile tl;
+                tl.tensor = (uint32_t)t;
+                tl.start = (uint64_t)s;
+                tl.len = (uint32_t)((g->numel[t] - s) < TILE_ELEMS ? (g->numel[t] - s) : TILE_ELEMS);
+                tiles.push_back(tl);
+            }
+        r.hi = (uint32_t)tiles.size();
+        if (r.hi > r.lo) g->ranges.push_back(r);
+    }
+    g->n_tiles = (uint32_t)tiles.size();
+    e = hipMalloc((void **)&g->d_tiles, tiles.empty() ? sizeof(Tile) : tiles.size() * sizeof(Tile));
+    if (e != hipSuccess) { (void)hipGetLastError(); delete g; return fail(HALOS_ENOMEM, "tile table: %s", hipGetErrorString(e)); }
+    if (!tiles.empty()) {
+        e = hipMemcpy(g->d_tiles, tiles.data(), tiles.size() * sizeof(Tile), hipMemcpyHostToDevice);
+        if (e != hipSuccess) { (void)hipFree(g->d_tiles); delete g; return fail_hip(e, "uploading the tile table"); }
+    }
+    st = upload_tables(&g->d_tables, {(const void *const *)Theta, (const void *const *)M}, nt);
+    if (st != HALOS_OK) { (void)hipFree(g->d_tiles); delete g; return st; }
+    g->d_Theta = (float **)g->d_tables;
+    g->d_M = g->d_Theta + nt;
+
+    for (const TileRange &r : g->ranges) {       // M <- 0
+        e = launch_init((hipStream_t)stream, g->d_tiles, r, nullptr, nullptr, g->d_M, nullptr, current_shape(g));
+        if (e != hipSuccess) {
+            (void)hipFree(g->d_tables); (void)hipFree(g->d_tiles); delete g;
+            return fail_hip(e, "zero-filling M");
+        }
+    }
+    *out = g;
+    return HALOS_OK;
+}
+
+void halos_gps_destroy(halos_gps *g) {
+    if (!g || g->magic != GPS_MAGIC) return;
+    (void)hipFree(g->d_tables);
+    (void)hipFree(g->d_tiles);
+    g->magic = 0;
+    delete g;
+}
+
+halos_status halos_lps_create(halos_gps *g, int32_t lps_id, int32_t n_workers, void *const *theta, void *const *m,
+                              void *const *acc, void *stream, halos_lps **out) {
+    if (!out) return fail(HALOS_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (!g || g->magic != GPS_MAGIC) return fail(HALOS_EINVAL, "gps is not a valid handle");
+    if (lps_id < 0) return fail(HALOS_EINVAL, "lps_id = %d, must be >= 0", lps_id);
+    if (n_workers < 1) return fail(HALOS_EINVAL, "n_workers = %d, must be >= 1", n_workers);
+    halos_status st = check_device(g);
+    if (st == HALOS_OK) st = check_tensors(g, theta, sizeof(float), "theta");
+    if (st == HALOS_OK) st = check_tensors(g, m, sizeof(float), "m");
+    if (st == HALOS_OK) st = check_tensors(g, acc, sizeof(float), "acc");
+    if (st != HALOS_OK) return st;
+    halos_lps *l = new (std::nothrow) halos_lps(n_workers, g->hp.K);
+    if (!l) return fail(HALOS_ENOMEM, "host allocation failed");
+    l->gps = g;
+    l->id = lps_id;
+    l->rule = g->hp.local;
+    l->alpha = g->hp.alpha;
+    l->pending.resize(n_workers);
+    l->validated.resize(n_workers);
+    l->validated_dtype.assign(n_workers, HALOS_F32);
+    const size_t nt = g->numel.size();
+    st = upload_tables(&l->d_tables, {(const void *const *)theta, (const void *const *)m, (const void *const *)acc}, nt);
+    if (st != HALOS_OK) { delete l; return st; }
+    l->d_theta = (float **)l->d_tables;
+    l->d_m = l->d_theta + nt;
+    l->d_acc = l->d_m + nt;
+    for (const TileRange &r : g->ranges) {       // theta <- Theta, m <- 0, acc <- 0
+        hipError_t e = launch_init((hipStream_t)stream, g->d_tiles, r, g->d_Theta, l->d_theta, l->d_m, l->d_acc,
+                                   current_shape(g));
+        if (e != hipSuccess) { (void)hipFree(l->d_tables); delete l; return fail_hip(e, "initialising the local server"); }
+    }
+    g->n_lps_attached += 1;
+    *out = l;
+    return HALOS_OK;
+}
+
+void halos_lps_destroy(halos_lps *l) {
+    if (!l || l->magic != LPS_MAGIC) return;
+    (void)hipFree(l->d_tables);
+    if (l->gps && l->gps->magic == GPS_MAGIC) l->gps->n_lps_attached -= 1;
+    l->magic = 0;
+    delete l;
+}
+
+halos_status halos_lps_push_update(halos_lps *l, int32_t worker, const void *const *gptrs, halos_dtype dtype,
+                                   uint32_t staleness) {
+    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    if (dtype != HALOS_F32 && dtype != HALOS_BF16) return fail(HALOS_EINVAL, "unknown delta dtype %d", (int)dtype);
+    ProtoResult pr = l->proto.can_push_delta(worker);
+    if (pr == PROTO_BAD_ARG) return fail(HALOS_EINVAL, "worker %d outside 0..%d", worker, l->proto.n_workers() - 1);
+    if (pr == PROTO_BAD_STATE) return fail(HALOS_ESTATE, "worker %d of lps %d already has a delta queued", worker, l->id);
+    if (!gptrs) return fail(HALOS_EINVAL, "g: pointer array is NULL");
+    const halos_gps *g = l->gps;
+    const size_t nt = g->numel.size();
+    std::vector<const void *> &seen = l->validated[worker];
+    const bool same = seen.size() == nt && l->validated_dtype[worker] == dtype &&
+                      std::memcmp(seen.data(), gptrs, nt * sizeof(void *)) == 0;
+    if (!same) {      // a worker normally reuses its receive buffers: their ranges are checked once
+        halos_status st = check_device(g);
+        if (st == HALOS_OK) st = check_tensors(g, gptrs, dtype == HALOS_BF16 ? 2 : 4, "g");
+        if (st != HALOS_OK) return st;
+        seen.assign(gptrs, gptrs + nt);
+        l->validated_dtype[worker] = dtype;
+    }
+    PendingDelta &p = l->pending[worker];
+    p.ptrs.assign(gptrs, gptrs + nt);
+    p.dtype = dtype;
+    p.staleness = staleness;
+    if (staleness > l->max_staleness) l->max_staleness = staleness;
+    l->proto.push_delta(worker);
+    return HALOS_OK;
+}
+
+halos_status halos_lps_push_global(halos_lps *l) {
+    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    if (l->proto.can_push_global() != PROTO_OK)
+        return fail(HALOS_ESTATE, "lps %d: no global model is on its way back (phase %d)", l->id, l->proto.phase());
+    l->proto.push_global();
+    return HALOS_OK;
+}
+
+halos_status halos_lps_step(halos_lps *l, void *stream, halos_step_info *info) {
+    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    halos_gps *g = l->gps;
+    halos_step_info out{};
+    out.worker = -1;
+    const QueueItem head = l->proto.head();
+    if (head.kind == ITEM_NONE) {
+        out.t = l->proto.t();
+        out.t_last = l->proto.t_last();
+        if (info) *info = out;
+        return HALOS_OK;
+    }
+    halos_status st = check_device(g);
+    if (st != HALOS_OK) return st;
+    const LaunchShape shape = current_shape(g);
+    if (head.kind == ITEM_DELTA) {
+        const UpdateOutcome oc = l->proto.preview_update();
+        const PendingDelta &p = l->pending[head.worker];
+        for (const TileRange &r : g->ranges) {
+            PtrArgs args;
+            fill_args(args, p.ptrs.data(), r, g->numel.size());
+            hipError_t e = launch_lps_update((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_acc, args,
+                                             p.dtype == HALOS_BF16, oc.accumulate, l->rule.eta, l->rule.beta,
+                                             l->rule.cg, shape);
+            if (e != hipSuccess) return fail_hip(e, "launching the local update");
+        }
+        l->proto.commit_update();
+        out.kind = 1;
+        out.worker = head.worker;
+        out.accumulated = oc.accumulate ? 1 : 0;
+        out.delta_ready = oc.freezes ? 1 : 0;
+    } else {
+        const float keep = 1.0f - l->alpha;
+        for (const TileRange &r : g->ranges) {
+            hipError_t e = launch_lps_merge((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_acc, l->alpha, keep, shape);
+            if (e != hipSuccess) return fail_hip(e, "launching the merge");
+        }
+        l->proto.commit_merge();
+        out.kind = 2;
+    }
+    out.t = l->proto.t();
+    out.t_last = l->proto.t_last();
+    if (info) *info = out;
+    return HALOS_OK;
+}
+
+halos_status halos_gps_merge(halos_gps *g, halos_lps *from, void *stream) {
+    if (!g || g->magic != GPS_MAGIC) return fail(HALOS_EINVAL, "gps is not a valid handle");
+    if (!from || from->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "from is not a valid handle");
+    if (from->gps != g) return fail(HALOS_EINVAL, "lps %d belongs to another global server", from->id);
+    if (from->proto.can_consume() != PROTO_OK)
+        return fail(HALOS_ESTATE, "lps %d has no accumulated update waiting (phase %d)", from->id, from->proto.phase());
+    halos_status st = check_device(g);
+    if (st != HALOS_OK) return st;
+    const LaunchShape shape = current_shape(g);
+    for (const TileRange &r : g->ranges) {
+        hipError_t e = launch_gps_update((hipStream_t)stream, g->d_tiles, r, g->d_Theta, g->d_M, from->d_acc, from->d_acc,
+                                         g->rule.eta, g->rule.beta, g->rule.cg, shape);
+        if (e != hipSuccess) return fail_hip(e, "launching the global update");
+    }
+    from->proto.consume();
+    g->updates += 1;
+    return HALOS_OK;
+}
+
+halos_status halos_pull_model(const void *server, int32_t is_gps, void *const *dst, void *stream) {
+    if (!server) return fail(HALOS_EINVAL, "server is NULL");
+    const halos_gps *g = nullptr;
+    float *const *src = nullptr;
+    halos_lps *l = nullptr;
+    if (is_gps) {
+        g = static_cast<const halos_gps *>(server);
+        if (g->magic != GPS_MAGIC) return fail(HALOS_EINVAL, "server is not a valid gps handle");
+        src = g->d_Theta;
+    } else {
+        l = const_cast<halos_lps *>(static_cast<const halos_lps *>(server));
+        if (l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "server is not a valid lps handle");
+        g = l->gps;
+        src = l->d_theta;
+    }
+    if (!dst) return fail(HALOS_EINVAL, "dst: pointer array is NULL");
+    const size_t nt = g->numel.size();
+    const bool same = l && l->validated_pull.size() == nt &&
+                      std::memcmp(l->validated_pull.data(), dst, nt * sizeof(void *)) == 0;
+    if (!same) {
+        halos_status st = check_device(g);
+        if (st == HALOS_OK) st = check_tensors(g, (const void *const *)dst, sizeof(float), "dst");
+        if (st != HALOS_OK) return st;
+        if (l) l->validated_pull.assign((const void *const *)dst, (const void *const *)dst + nt);
+    }
+    const LaunchShape shape = current_shape(g);
+    for (const TileRange &r : g->ranges) {
+        PtrArgs args;
+        fill_args(args, (const void *const *)dst, r, nt);
+        hipError_t e = launch_pull((hipStream_t)stream, g->d_tiles, r, src, args, shape);
+        if (e != hipSuccess) return fail_hip(e, "launching the model copy");
+    }
+    return HALOS_OK;
+}
+
+halos_status halos_set_hparams(void *server, int32_t is_gps, const halos_hparams *hp) {
+    if (!server) return fail(HALOS_EINVAL, "server is NULL");
+    halos_status st = check_hparams(hp);
+    if (st != HALOS_OK) return st;
+    if (is_gps) {
+        halos_gps *g = static_cast<halos_gps *>(server);
+        if (g->magic != GPS_MAGIC) return fail(HALOS_EINVAL, "server is not a valid gps handle");
+        g->rule = hp->global;
+        g->hp.global = hp->global;
+    } else {
+        halos_lps *l = static_cast<halos_lps *>(server);
+        if (l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "server is not a valid lps handle");
+        l->rule = hp->local;
+        l->alpha = hp->alpha;
+        l->proto.set_K(hp->K);
+    }
+    return HALOS_OK;
+}
+
+halos_status halos_lps_set_threshold(halos_lps *l, int32_t K) {
+    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    if (l->proto.set_K(K) != PROTO_OK) return fail(HALOS_EINVAL, "K = %d, must be >= 1", K);
+    return HALOS_OK;
+}
+
+halos_status halos_lps_get_counters(const halos_lps *l, int64_t *t, int64_t *t_last, int32_t *phase, int32_t *queued,
+                                    uint32_t *max_staleness) {
+    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    if (t) *t = l->proto.t();
+    if (t_last) *t_last = l->proto.t_last();
+    if (phase) *phase = l->proto.phase();
+    if (queued) *queued = l->proto.queued();
+    if (max_staleness) *max_staleness = l->max_staleness;
+    return HALOS_OK;
+}
+
+halos_status halos_gps_get_counters(const halos_gps *g, int64_t *updates) {
+    if (!g || g->magic != GPS_MAGIC) return fail(HALOS_EINVAL, "gps is not a valid handle");
+    if (updates) *updates = g->updates;
+    return HALOS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,397 @@
+// gfx950 kernels of the HALoS server-side update path.
+//
+// Every step of the path is an elementwise read-modify-write over parameter-sized arrays, so the
+// kernels are bandwidth machines: each wavefront issues 128-bit accesses that cover 1 KiB of
+// consecutive addresses per stream, a workgroup keeps UNROLL of them in flight per stream before it
+// consumes any, and a persistent grid walks a tile table so that one launch covers the whole tensor
+// list.  There is no contraction anywhere, hence no MFMA and no LDS staging.
+//
+// Arithmetic is written with explicit single-rounding intrinsics in one fixed order, so results do
+// not depend on compiler contraction settings:
+//     m1 = fma(beta, m, g);  u = fma(beta, m1, cg * g);  s = eta * u;  x = x - s;  acc = acc + s
+//     merge: theta = fma(alpha, Theta_i, keep * theta)
+#include <hip/hip_runtime.h>
+
+#include "kernels.hpp"
+
+namespace halos {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+
+// Pointers read from a table in memory are generic ("flat") to the compiler.  Everything this
+// library touches is global device memory, so say so: global_load/global_store instead of flat_*.
+#define HALOS_GLOBAL __attribute__((address_space(1)))
+typedef HALOS_GLOBAL float gf32;
+typedef HALOS_GLOBAL unsigned short gu16;
+typedef HALOS_GLOBAL f32x4 gf32x4;
+typedef HALOS_GLOBAL u16x4 gu16x4;
+
+__device__ __forceinline__ gf32 *to_global(float *p) { return (gf32 *)p; }
+__device__ __forceinline__ const gf32 *to_global(const float *p) { return (const gf32 *)p; }
+__device__ __forceinline__ const gu16 *to_global(const unsigned short *p) { return (const gu16 *)p; }
+
+template <bool NT>
+__device__ __forceinline__ f32x4 ld4(const gf32 *p) {
+    const gf32x4 *q = (const gf32x4 *)p;
+    if constexpr (NT) return __builtin_nontemporal_load(q);
+    else return *q;
+}
+
+template <bool NT>
+__device__ __forceinline__ void st4(gf32 *p, f32x4 v) {
+    gf32x4 *q = (gf32x4 *)p;
+    if constexpr (NT) __builtin_nontemporal_store(v, q);
+    else *q = v;
+}
+
+__device__ __forceinline__ float bf16_up(unsigned short bits) {     // bfloat16 = upper half of a binary32
+    return __uint_as_float(static_cast<uint32_t>(bits) << 16);
+}
+
+// Four consecutive delta elements as fp32, from an fp32 or a bf16 tensor.
+template <bool NT>
+__device__ __forceinline__ f32x4 ldg4(const gf32 *p) { return ld4<NT>(p); }
+
+template <bool NT>
+__device__ __forceinline__ f32x4 ldg4(const gu16 *p) {
+    const gu16x4 *q = (const gu16x4 *)p;
+    u16x4 b;
+    if constexpr (NT) b = __builtin_nontemporal_load(q);
+    else b = *q;
+    f32x4 r;
+    r[0] = bf16_up(b[0]); r[1] = bf16_up(b[1]); r[2] = bf16_up(b[2]); r[3] = bf16_up(b[3]);
+    return r;
+}
+
+__device__ __forceinline__ float ldg1(const gf32 *p) { return *p; }
+__device__ __forceinline__ float ldg1(const gu16 *p) { return bf16_up(*p); }
+
+// ModelUpdate (App. E) on one element; returns the step that was subtracted from x.
+__device__ __forceinline__ float model_update(float &x, float &m, float g, float eta, float beta, float cg) {
+    m = __fmaf_rn(beta, m, g);
+    const float u = __fmaf_rn(beta, m, __fmul_rn(cg, g));
+    const float s = __fmul_rn(eta, u);
+    x = __fsub_rn(x, s);
+    return s;
+}
+
+
+// The same on four lanes of a 128-bit access (vector elements cannot be bound to references).
+__device__ __forceinline__ f32x4 model_update4(f32x4 &x, f32x4 &m, f32x4 g, float eta, float beta, float cg) {
+    f32x4 s;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+        float xi = x[i], mi = m[i];
+        s[i] = model_update(xi, mi, g[i], eta, beta, cg);
+        x[i] = xi;
+        m[i] = mi;
+    }
+    return s;
+}
+
+__device__ __forceinline__ f32x4 add4(f32x4 a, f32x4 b) {
+    f32x4 r;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) r[i] = __fadd_rn(a[i], b[i]);
+    return r;
+}
+
+// Alg. 1 line 19 in the two-product form: exact for alpha = 0 (keep = 1) and alpha = 1 (keep = 0).
+__device__ __forceinline__ float merge1(float theta, float global, float alpha, float keep) {
+    return __fmaf_rn(alpha, global, __fmul_rn(keep, theta));
+}
+
+__device__ __forceinline__ f32x4 merge4(f32x4 theta, f32x4 global, float alpha, float keep) {
+    f32x4 r;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) r[i] = merge1(theta[i], global[i], alpha, keep);
+    return r;
+}
+
+// ---------------------------------------------------------------------------------------------
+// S1: worker-delta step of a local server.
+template <typename GT, bool ACC, bool NT>
+__global__ void __launch_bounds__(BLOCK_THREADS)
+lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, uint32_t tensor_base,
+                  float *const *__restrict__ theta_tab, float *const *__restrict__ m_tab,
+                  float *const *__restrict__ acc_tab, PtrArgs gargs, float eta, float beta, float cg) {
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t t = tile_lo + blockIdx.x; t < tile_hi; t += gridDim.x) {
+        const Tile tl = tiles[t];
+        const uint32_t tensor = tl.tensor;
+        gf32 *th = to_global(theta_tab[tensor]) + tl.start;
+        gf32 *mm = to_global(m_tab[tensor]) + tl.start;
+        gf32 *ac = ACC ? to_global(acc_tab[tensor]) + tl.start : nullptr;
+        const auto *g = to_global(static_cast<const GT *>(gargs.p[tensor - tensor_base])) + tl.start;
+        if (tl.len == TILE_ELEMS) {
+            f32x4 gv[UNROLL], mv[UNROLL], tv[UNROLL], av[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
+                gv[u] = ldg4<NT>(g + off);
+                mv[u] = ld4<NT>(mm + off);
+                tv[u] = ld4<NT>(th + off);
+                if constexpr (ACC) av[u] = ld4<NT>(ac + off);
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
+                const f32x4 s = model_update4(tv[u], mv[u], gv[u], eta, beta, cg);
+                st4<NT>(mm + off, mv[u]);
+                st4<NT>(th + off, tv[u]);
+                if constexpr (ACC) st4<NT>(ac + off, add4(av[u], s));
+            }
+        } else {
+            const uint32_t len = tl.len;
+            for (uint32_t off = tid * VEC; off < len; off += BLOCK_THREADS * VEC) {
+                if (off + VEC <= len) {
+                    f32x4 gv = ldg4<NT>(g + off), mv = ld4<NT>(mm + off), tv = ld4<NT>(th + off);
+                    const f32x4 s = model_update4(tv, mv, gv, eta, beta, cg);
+                    st4<NT>(mm + off, mv);
+                    st4<NT>(th + off, tv);
+                    if constexpr (ACC) st4<NT>(ac + off, add4(ld4<NT>(ac + off), s));
+                } else {
+                    for (uint32_t k = off; k < len; ++k) {      // ragged tail: fewer than 4 elements
+                        float mv = mm[k], tv = th[k];
+                        const float s = model_update(tv, mv, ldg1(g + k), eta, beta, cg);
+                        mm[k] = mv; th[k] = tv;
+                        if constexpr (ACC) ac[k] = __fadd_rn(ac[k], s);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// S3: global-server step.  G and out may alias.
+template <bool NT>
+__global__ void __launch_bounds__(BLOCK_THREADS)
+gps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi,
+                  float *const *__restrict__ Theta_tab, float *const *__restrict__ M_tab,
+                  float *const *G_tab, float *const *out_tab, float eta, float beta, float cg) {
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t t = tile_lo + blockIdx.x; t < tile_hi; t += gridDim.x) {
+        const Tile tl = tiles[t];
+        const uint32_t tensor = tl.tensor;
+        gf32 *Th = to_global(Theta_tab[tensor]) + tl.start;
+        gf32 *Mm = to_global(M_tab[tensor]) + tl.start;
+        const gf32 *G = to_global(G_tab[tensor]) + tl.start;
+        gf32 *out = to_global(out_tab[tensor]) + tl.start;
+        if (tl.len == TILE_ELEMS) {
+            f32x4 gv[UNROLL], mv[UNROLL], tv[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
+                gv[u] = ld4<NT>(G + off);
+                mv[u] = ld4<NT>(Mm + off);
+                tv[u] = ld4<NT>(Th + off);
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
+                model_update4(tv[u], mv[u], gv[u], eta, beta, cg);
+                st4<NT>(Mm + off, mv[u]);
+                st4<NT>(Th + off, tv[u]);
+                st4<NT>(out + off, tv[u]);
+            }
+        } else {
+            const uint32_t len = tl.len;
+            for (uint32_t off = tid * VEC; off < len; off += BLOCK_THREADS * VEC) {
+                if (off + VEC <= len) {
+                    f32x4 gv = ld4<NT>(G + off), mv = ld4<NT>(Mm + off), tv = ld4<NT>(Th + off);
+                    model_update4(tv, mv, gv, eta, beta, cg);
+                    st4<NT>(Mm + off, mv);
+                    st4<NT>(Th + off, tv);
+                    st4<NT>(out + off, tv);
+                } else {
+                    for (uint32_t k = off; k < len; ++k) {
+                        float mv = Mm[k], tv = Th[k];
+                        model_update(tv, mv, G[k], eta, beta, cg);
+                        Mm[k] = mv; Th[k] = tv; out[k] = tv;
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// S4: merge the returned global model into the local model and restart the accumulation.
+template <bool NT>
+__global__ void __launch_bounds__(BLOCK_THREADS)
+lps_merge_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi,
+                 float *const *__restrict__ theta_tab, float *const *__restrict__ inbox_tab, float alpha, float keep) {
+    const uint32_t tid = threadIdx.x;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    for (uint32_t t = tile_lo + blockIdx.x; t < tile_hi; t += gridDim.x) {
+        const Tile tl = tiles[t];
+        const uint32_t tensor = tl.tensor;
+        gf32 *th = to_global(theta_tab[tensor]) + tl.start;
+        gf32 *in = to_global(inbox_tab[tensor]) + tl.start;
+        if (tl.len == TILE_ELEMS) {
+            f32x4 tv[UNROLL], iv[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
+                tv[u] = ld4<NT>(th + off);
+                iv[u] = ld4<NT>(in + off);
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
+                st4<NT>(th + off, merge4(tv[u], iv[u], alpha, keep));
+                st4<NT>(in + off, zero);
+            }
+        } else {
+            const uint32_t len = tl.len;
+            for (uint32_t off = tid * VEC; off < len; off += BLOCK_THREADS * VEC) {
+                if (off + VEC <= len) {
+                    st4<NT>(th + off, merge4(ld4<NT>(th + off), ld4<NT>(in + off), alpha, keep));
+                    st4<NT>(in + off, zero);
+                } else {
+                    for (uint32_t k = off; k < len; ++k) {
+                        th[k] = merge1(th[k], in[k], alpha, keep);
+                        in[k] = 0.f;
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// S5: copy a model out.
+template <bool NT>
+__global__ void __launch_bounds__(BLOCK_THREADS)
+pull_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, uint32_t tensor_base,
+            float *const *__restrict__ src_tab, PtrArgs dargs) {
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t t = tile_lo + blockIdx.x; t < tile_hi; t += gridDim.x) {
+        const Tile tl = tiles[t];
+        const uint32_t tensor = tl.tensor;
+        const gf32 *src = to_global(src_tab[tensor]) + tl.start;
+        gf32 *dst = to_global(static_cast<float *>(const_cast<void *>(dargs.p[tensor - tensor_base]))) + tl.start;
+        if (tl.len == TILE_ELEMS) {
+            f32x4 v[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) v[u] = ld4<NT>(src + (u * BLOCK_THREADS + tid) * VEC);
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) st4<NT>(dst + (u * BLOCK_THREADS + tid) * VEC, v[u]);
+        } else {
+            const uint32_t len = tl.len;
+            for (uint32_t off = tid * VEC; off < len; off += BLOCK_THREADS * VEC) {
+                if (off + VEC <= len) st4<NT>(dst + off, ld4<NT>(src + off));
+                else for (uint32_t k = off; k < len; ++k) dst[k] = src[k];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Alg. 1 line 6: theta <- Theta_0, m <- 0, acc <- 0.  With src_tab == nullptr only m is zero-filled.
+__global__ void __launch_bounds__(BLOCK_THREADS)
+init_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, float *const *src_tab,
+            float *const *theta_tab, float *const *m_tab, float *const *acc_tab) {
+    const uint32_t tid = threadIdx.x;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    for (uint32_t t = tile_lo + blockIdx.x; t < tile_hi; t += gridDim.x) {
+        const Tile tl = tiles[t];
+        const uint32_t tensor = tl.tensor;
+        const uint32_t len = tl.len;
+        gf32 *mm = to_global(m_tab[tensor]) + tl.start;
+        const gf32 *src = src_tab ? to_global(src_tab[tensor]) + tl.start : nullptr;
+        gf32 *th = src_tab ? to_global(theta_tab[tensor]) + tl.start : nullptr;
+        gf32 *ac = src_tab ? to_global(acc_tab[tensor]) + tl.start : nullptr;
+        for (uint32_t off = tid * VEC; off < len; off += BLOCK_THREADS * VEC) {
+            if (off + VEC <= len) {
+                st4<false>(mm + off, zero);
+                if (src_tab) {
+                    st4<false>(th + off, ld4<false>(src + off));
+                    st4<false>(ac + off, zero);
+                }
+            } else {
+                for (uint32_t k = off; k < len; ++k) {
+                    mm[k] = 0.f;
+                    if (src_tab) { th[k] = src[k]; ac[k] = 0.f; }
+                }
+            }
+        }
+    }
+}
+
+inline dim3 grid_for(TileRange r, LaunchShape shape) {
+    uint32_t n = r.hi - r.lo;
+    uint32_t cap = shape.grid_cap > 0 ? (uint32_t)shape.grid_cap : 1u;
+    return dim3(n < cap ? n : cap);
+}
+
+}  // namespace
+
+hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
+                             float *const *acc, const PtrArgs &g, bool g_is_bf16, bool accumulate, float eta,
+                             float beta, float cg, LaunchShape shape) {
+    if (r.hi <= r.lo) return hipSuccess;
+    const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
+#define HALOS_LAUNCH_UPD(GT, ACC, NT)                                                                          \
+    lps_update_kernel<GT, ACC, NT><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, r.tensor_base, theta, m, acc, g, \
+                                                               eta, beta, cg)
+    const int variant = (g_is_bf16 ? 4 : 0) | (accumulate ? 2 : 0) | (shape.nontemporal ? 1 : 0);
+    switch (variant) {
+        case 0: HALOS_LAUNCH_UPD(float, false, false); break;
+        case 1: HALOS_LAUNCH_UPD(float, false, true); break;
+        case 2: HALOS_LAUNCH_UPD(float, true, false); break;
+        case 3: HALOS_LAUNCH_UPD(float, true, true); break;
+        case 4: HALOS_LAUNCH_UPD(unsigned short, false, false); break;
+        case 5: HALOS_LAUNCH_UPD(unsigned short, false, true); break;
+        case 6: HALOS_LAUNCH_UPD(unsigned short, true, false); break;
+        default: HALOS_LAUNCH_UPD(unsigned short, true, true); break;
+    }
+#undef HALOS_LAUNCH_UPD
+    return hipGetLastError();
+}
+
+hipError_t launch_gps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *Theta, float *const *M,
+                             float *const *G, float *const *out, float eta, float beta, float cg, LaunchShape shape) {
+    if (r.hi <= r.lo) return hipSuccess;
+    const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
+    if (shape.nontemporal)
+        gps_update_kernel<true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, Theta, M, G, out, eta, beta, cg);
+    else
+        gps_update_kernel<false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, Theta, M, G, out, eta, beta, cg);
+    return hipGetLastError();
+}
+
+hipError_t launch_lps_merge(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
+                            float *const *inbox, float alpha, float keep, LaunchShape shape) {
+    if (r.hi <= r.lo) return hipSuccess;
+    const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
+    if (shape.nontemporal)
+        lps_merge_kernel<true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, inbox, alpha, keep);
+    else
+        lps_merge_kernel<false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, inbox, alpha, keep);
+    return hipGetLastError();
+}
+
+hipError_t launch_pull(hipStream_t stream, const Tile *tiles, TileRange r, float *const *src, const PtrArgs &dst,
+                       LaunchShape shape) {
+    if (r.hi <= r.lo) return hipSuccess;
+    const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
+    if (shape.nontemporal)
+        pull_kernel<true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, r.tensor_base, src, dst);
+    else
+        pull_kernel<false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, r.tensor_base, src, dst);
+    return hipGetLastError();
+}
+
+hipError_t launch_init(hipStream_t stream, const Tile *tiles, TileRange r, float *const *src, float *const *theta,
+                       float *const *m, float *const *acc, LaunchShape shape) {
+    if (r.hi <= r.lo) return hipSuccess;
+    const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
+    init_kernel<<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, src, theta, m, acc);
+    return hipGetLastError();
+}
+
+}  // namespace halos

@@ -1,0 +1,64 @@
+// Launch interface between the C ABI (halos.cpp) and the gfx950 kernels (kernels.hip).
+#pragma once
+
+#include <hip/hip_runtime_api.h>
+
+#include <cstdint>
+
+namespace halos {
+
+// Work is cut into tiles: a tile is a run of at most TILE_ELEMS consecutive elements of ONE tensor,
+// starting at a multiple of TILE_ELEMS inside it.  The tile table is built once per layout and lives
+// in device memory; a persistent grid walks it with a grid stride.
+constexpr int BLOCK_THREADS = 256;      // 4 wavefronts of 64
+constexpr int VEC = 4;                  // fp32 elements per 128-bit access
+constexpr int UNROLL = 4;               // 128-bit accesses per thread per stream and tile
+constexpr int TILE_ELEMS = BLOCK_THREADS * VEC * UNROLL;   // 4096
+
+struct Tile {
+    uint32_t tensor;    // index into the per-tensor pointer tables
+    uint32_t len;       // 1..TILE_ELEMS
+    uint64_t start;     // element offset inside the tensor, multiple of TILE_ELEMS
+};
+
+// Pointers that change from call to call (a worker's delta tensors, a pull destination) travel in the
+// kernel-argument block, so no device table has to be rewritten while earlier launches may still read it.
+constexpr int MAX_ARG_TENSORS = 384;
+struct PtrArgs {
+    const void *p[MAX_ARG_TENSORS];     // p[i] belongs to tensor (tensor_base + i)
+};
+
+struct LaunchShape {
+    int grid_cap;       // upper bound on workgroups per launch (blocks_per_cu * compute units)
+    bool nontemporal;
+};
+
+struct TileRange {      // tiles [lo, hi) all belong to tensors [tensor_base, tensor_base + MAX_ARG_TENSORS)
+    uint32_t lo, hi;
+    uint32_t tensor_base;
+};
+
+// Worker-delta step of a local server: m <- beta m + g; s = eta (cg g + beta m); theta <- theta - s;
+// if accumulate: acc <- acc + s.   (ModelUpdate of App. E fused with the accumulation of Alg. 1 line 14.)
+hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
+                             float *const *acc, const PtrArgs &g, bool g_is_bf16, bool accumulate, float eta,
+                             float beta, float cg, LaunchShape shape);
+
+// Global-server step: M <- beta M + G; Theta <- Theta - eta (cg G + beta M); out <- Theta.
+// `G` and `out` may be the same table (each element is read before it is overwritten by the same thread).
+hipError_t launch_gps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *Theta, float *const *M,
+                             float *const *G, float *const *out, float eta, float beta, float cg, LaunchShape shape);
+
+// Merge step of a local server: theta <- alpha * inbox + keep * theta (keep = 1 - alpha); inbox buffer <- 0.
+hipError_t launch_lps_merge(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
+                            float *const *inbox, float alpha, float keep, LaunchShape shape);
+
+// dst <- src (fp32), dst pointers in the argument block.
+hipError_t launch_pull(hipStream_t stream, const Tile *tiles, TileRange r, float *const *src, const PtrArgs &dst,
+                       LaunchShape shape);
+
+// theta <- src; m <- 0; acc <- 0   (Alg. 1 line 6).  src == nullptr: only zero-fill `m` (used for the GPS momentum).
+hipError_t launch_init(hipStream_t stream, const Tile *tiles, TileRange r, float *const *src, float *const *theta,
+                       float *const *m, float *const *acc, LaunchShape shape);
+
+}  // namespace halos

@@ -46,6 +46,17 @@ class Workload:
                        name=self.name if name is None else name)
 
 
+def delta_scales(w: Workload):
+    """Per-tensor fp32 factor handed to the delta generator: sigma, divided by sqrt(fan_in) if the workload says so."""
+    import numpy as np
+    from .tensors import scale_f32
+    out = np.empty(w.layout.n_tensors, dtype=np.float32)
+    for i, fan in enumerate(w.layout.fan_in):
+        sigma = w.delta_sigma / (float(fan) ** 0.5 if w.scale_by_fan_in else 1.0)
+        out[i] = scale_f32(sigma)
+    return out
+
+
 def _mk() -> Dict[str, Workload]:
     w = {}
     w["tiny"] = Workload(

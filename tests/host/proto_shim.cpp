@@ -1,0 +1,46 @@
+// Test-only C wrapper around the library's host-side protocol state machine
+// (paper_2506_04531_amd/csrc/protocol.hpp), so that its decisions can be checked without a GPU.
+#include "../../paper_2506_04531_amd/csrc/protocol.hpp"
+
+using halos::LpsProtocol;
+
+extern "C" {
+void *proto_new(int n_workers, int K) { return new LpsProtocol(n_workers, K); }
+void proto_free(void *p) { delete (LpsProtocol *)p; }
+int proto_set_K(void *p, int K) { return ((LpsProtocol *)p)->set_K(K); }
+int proto_push_delta(void *p, int worker) {
+    LpsProtocol *s = (LpsProtocol *)p;
+    int rc = s->can_push_delta(worker);
+    if (rc == halos::PROTO_OK) s->push_delta(worker);
+    return rc;
+}
+int proto_push_global(void *p) {
+    LpsProtocol *s = (LpsProtocol *)p;
+    int rc = s->can_push_global();
+    if (rc == halos::PROTO_OK) s->push_global();
+    return rc;
+}
+// out = {kind, worker, accumulate, freezes, t, t_last}
+int proto_step(void *p, long long *out) {
+    LpsProtocol *s = (LpsProtocol *)p;
+    halos::QueueItem h = s->head();
+    out[0] = h.kind; out[1] = h.worker; out[2] = 0; out[3] = 0;
+    if (h.kind == halos::ITEM_DELTA) {
+        halos::UpdateOutcome o = s->preview_update();
+        out[2] = o.accumulate; out[3] = o.freezes;
+        s->commit_update();
+    } else if (h.kind == halos::ITEM_GLOBAL) {
+        s->commit_merge();
+    }
+    out[4] = s->t(); out[5] = s->t_last();
+    return 0;
+}
+int proto_consume(void *p) {
+    LpsProtocol *s = (LpsProtocol *)p;
+    int rc = s->can_consume();
+    if (rc == halos::PROTO_OK) s->consume();
+    return rc;
+}
+int proto_phase(void *p) { return ((LpsProtocol *)p)->phase(); }
+int proto_queued(void *p) { return ((LpsProtocol *)p)->queued(); }
+}

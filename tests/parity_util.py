@@ -1,0 +1,114 @@
+"""Shared helpers of the GPU parity tests: run the CPU oracle on (a sample of) a workload and
+compare a GPU cluster's state with it."""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+import oracle as O
+import synth
+from oracle import HalosOracle
+from oracle.replay import replay as oracle_replay
+from synth.tensors import scale_f32
+
+# fp32 state vs the fp64 reference: tolerance of the benchmark definition (max relative error per
+# element after the full event sequence).  "Relative" is taken against the largest magnitude the
+# element had along the sequence (never smaller than its final magnitude): fp32 rounding errors are
+# proportional to the operand magnitudes at the time they are made, so this is the scale against
+# which 2^-24-sized errors accumulate.  See the error model in the design notes.
+REL_TOL = 1e-5
+
+
+def sample_indices(lay: synth.Layout, n_random: int, seed: int = 0, tile: int = 4096, edge: int = 6) -> np.ndarray:
+    """Random packed flat indices plus the places where indexing mistakes show: the first and last
+    `edge` elements of every tensor, and of the first, second and last tile of every tensor."""
+    rng = np.random.default_rng(seed)
+    total = lay.total
+    picks = [rng.integers(0, total, size=min(n_random, total), dtype=np.int64)]
+    off, numel = lay.offsets, lay.numel
+    for i in range(lay.n_tensors):
+        n = int(numel[i])
+        if n == 0:
+            continue
+        marks = {0, n}
+        for b in (tile, 2 * tile, (n // tile) * tile, ((n - 1) // tile) * tile):
+            if 0 < b < n:
+                marks.add(b)
+        loc = []
+        for b in marks:
+            loc.extend(range(max(0, b - edge), min(n, b + edge)))
+        picks.append(off[i] + np.array(sorted(set(loc)), dtype=np.int64))
+    return np.unique(np.concatenate(picks))
+
+
+def oracle_run(w: synth.Workload, trace: synth.Trace, idx: Optional[np.ndarray], precision: int, form: int):
+    """Replay `trace` through the oracle on the packed flat indices `idx` (None = every element)."""
+    lay = w.layout
+    if idx is None:
+        idx = np.arange(lay.total, dtype=np.int64)
+    tidx = torch.from_numpy(idx)
+    theta0 = synth.normal_at(w.seed, 0, tidx, scale_f32(w.init_sigma)).numpy()
+    scale = torch.from_numpy(synth.delta_scales(w)[lay.tensor_of(idx)])
+    cache: Dict[int, np.ndarray] = {}
+
+    def delta(slot: int) -> np.ndarray:
+        if slot not in cache:
+            g = synth.normal_at(w.seed, 1 + slot, tidx, scale)
+            cache[slot] = synth.to_bf16_bits(g).numpy() if w.delta_dtype == "bf16" else g.numpy()
+        return cache[slot]
+
+    o = HalosOracle(theta0, w.n_lps, eta_l=w.eta_l, beta_l=w.beta_l, eta_g=w.eta_g, beta_g=w.beta_g,
+                    alpha=w.alpha, K=trace.k_initial, precision=precision, form=form)
+    log = oracle_replay(o, trace.events, delta)
+    return o, log
+
+
+def oracle_state(o: HalosOracle, n_lps: int, with_scale: bool = True):
+    names = {"Theta": (O.GPS_THETA, 0), "M": (O.GPS_MOM, 0)}
+    for l in range(n_lps):
+        names[f"theta{l}"] = (O.THETA, l)
+        names[f"m{l}"] = (O.MOM, l)
+        names[f"aux{l}"] = (O.AUX, l)
+    out = {}
+    for k, (what, l) in names.items():
+        out[k] = (o.get(what, l), o.get(what + O.SCALE, l) if with_scale else None)
+    return out
+
+
+def compare_state(gpu_values: Dict[str, np.ndarray], ref: Dict[str, tuple], bitwise: bool):
+    """Returns (worst relative error, number of differing elements, name of the worst array).
+
+    bitwise=True  compares with an fp32 oracle that performs the same operations in the same order:
+                  relative error against |ref| itself, and the count of elements whose bits differ.
+    bitwise=False compares with the fp64 reference using the path-scale metric described above.
+    """
+    worst, worst_name, n_diff = 0.0, "", 0
+    for k, (x_ref, scale) in ref.items():
+        x = gpu_values[k].astype(np.float64)
+        assert x.shape == x_ref.shape, k
+        assert np.all(np.isfinite(x)), k
+        if bitwise:
+            r32 = x_ref.astype(np.float32)
+            n_diff += int((gpu_values[k].view(np.uint32) != r32.view(np.uint32)).sum())
+            denom = np.maximum(np.abs(x_ref), 1e-30)
+        else:
+            denom = np.maximum(np.maximum(np.abs(x_ref), scale), 1e-30)
+            n_diff += int((x != x_ref).sum())
+        err = float((np.abs(x - x_ref) / denom).max()) if x.size else 0.0
+        if err > worst:
+            worst, worst_name = err, k
+    return worst, n_diff, worst_name
+
+
+def check_step_logs(trace: synth.Trace, gpu_log, oracle_log):
+    """Event ordering and protocol decisions must agree exactly: GPU library, oracle, and the schedule
+    generator's own bookkeeping."""
+    assert gpu_log == oracle_log
+    ev = trace.events
+    steps = ev[ev["kind"] == synth.EV_LPS_STEP]
+    assert len(steps) == len(gpu_log)
+    for rec, (i, kind, t, t_last, ready, acc) in zip(steps, gpu_log):
+        assert (kind, t, t_last, ready, acc) == (int(rec["exp_kind"]), int(rec["exp_t"]), int(rec["exp_t_last"]),
+                                                 int(rec["exp_send"]), int(rec["exp_accumulate"]))

@@ -1,0 +1,46 @@
+"""The C-ABI library loads and exports every function include/halos.h declares (no GPU needed, no compute calls)."""
+import ctypes
+import os
+import re
+
+import paper_2506_04531_amd as pkg
+
+
+def _declared_functions():
+    text = open(pkg.HEADER_PATH).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(halos_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_calls_of_the_boundary():
+    names = _declared_functions()
+    for required in ("halos_gps_create", "halos_lps_create", "halos_lps_push_update", "halos_lps_step",
+                     "halos_gps_merge", "halos_pull_model"):
+        assert required in names
+
+
+def test_library_exports_every_declared_symbol():
+    if not os.path.exists(pkg.LIB_PATH):
+        pkg.build()
+    lib = ctypes.CDLL(pkg.LIB_PATH)
+    for name in _declared_functions():
+        assert hasattr(lib, name), f"{name} is declared in halos.h but not exported"
+
+
+def test_argument_errors_that_need_no_device():
+    """Calls that fail on their arguments before touching the GPU report EINVAL and a message."""
+    from paper_2506_04531_amd import binding as B
+    lib = B.load_library()
+    assert lib.halos_gps_create(None, None, None, None, None, None) == B.EINVAL
+    out = ctypes.c_void_p()
+    assert lib.halos_gps_create(None, None, None, None, None, ctypes.byref(out)) == B.EINVAL
+    assert "layout" in B.halos_last_error()
+    assert lib.halos_lps_step(None, None, None) == B.EINVAL
+    assert lib.halos_lps_push_global(None) == B.EINVAL
+    assert lib.halos_gps_merge(None, None, None) == B.EINVAL
+    assert lib.halos_pull_model(None, 0, None, None) == B.EINVAL
+    assert lib.halos_set_launch_config(65, 0) == B.EINVAL
+    assert lib.halos_set_launch_config(0, 2) == B.EINVAL
+    assert lib.halos_set_launch_config(0, -1) == B.OK
+    lib.halos_lps_destroy(None)
+    lib.halos_gps_destroy(None)
