@@ -92,6 +92,24 @@ inline R model_update(R &x, R &m, R grad, const Rule<R> &r) {
     return step;
 }
 
+// Error-scale bookkeeping (not part of the algorithm).  A reduced-precision implementation's error
+// in an element is proportional to the largest magnitudes that ever flowed into it, not to its current
+// value: momentum that has cancelled down to almost nothing still carries the rounding error of its
+// former size, and a step whose two terms cancel is tiny while its rounding error is not.  So every
+// array carries, per element, a scale that is propagated like the values themselves but with absolute
+// values and max instead of signed sums:
+//     scale(m)    >= |grad|, |m|                              (and it never shrinks)
+//     step scale   = |eta| (|cg| |grad scale| + |beta| scale(m))
+//     scale(x)    >= step scale, |x|        for the model and for the accumulated update
+// and a merge or a hand-over copies the source's scale along with its values.
+template <class R>
+inline R step_scale(R m_scale, R grad_scale, const Rule<R> &r) {
+    return std::fabs(r.eta) * (std::fabs(r.cg) * grad_scale + std::fabs(r.beta) * m_scale);
+}
+
+template <class R>
+inline void raise_to(R &scale, R v) { if (v > scale) scale = v; }
+
 template <class R>
 struct QueueItem {
     int kind;
@@ -106,7 +124,7 @@ struct Lps {
     std::vector<R> acc;          // form 1: sum of steps since t_last
     std::vector<R> frozen;       // G = theta_{t_last} - theta_t at the send (= -Delta)
     std::vector<R> inbox;        // the global model returned for this LPS
-    std::vector<R> sc_theta, sc_m, sc_aux;   // running max |value| (error scale for fp32 comparisons)
+    std::vector<R> sc_theta, sc_m, sc_aux;   // error scales, see step_scale()
     std::deque<QueueItem<R>> queue;
     std::vector<char> worker_queued;
     int64_t t = 0, t_last = 0;
@@ -187,15 +205,17 @@ struct Oracle {
             s.t += 1;                                                   // line 10
             const bool accumulate = (s.phase == ACCUMULATING);
             for (int64_t j = 0; j < n; ++j) {                           // line 11
-                R step = model_update<R>(s.theta[j], s.m[j], R(it.grad[j]), local);
+                const R grad = R(it.grad[j]);
+                R step = model_update<R>(s.theta[j], s.m[j], grad, local);
                 if (form == 1 && accumulate) s.acc[j] = s.acc[j] + step;
-            }
-            grow(s.sc_theta, s.theta); grow(s.sc_m, s.m);
-            if (accumulate) {
-                if (form == 1) grow(s.sc_aux, s.acc);
-                else for (int64_t j = 0; j < n; ++j) {
-                    R a = std::fabs(s.snap[j] - s.theta[j]);
-                    if (a > s.sc_aux[j]) s.sc_aux[j] = a;
+                raise_to(s.sc_m[j], std::fabs(grad));
+                raise_to(s.sc_m[j], std::fabs(s.m[j]));
+                const R terms = step_scale<R>(s.sc_m[j], std::fabs(grad), local);
+                raise_to(s.sc_theta[j], terms);
+                raise_to(s.sc_theta[j], std::fabs(s.theta[j]));
+                if (accumulate) {
+                    raise_to(s.sc_aux[j], terms);
+                    raise_to(s.sc_aux[j], std::fabs(form == 1 ? s.acc[j] : s.snap[j] - s.theta[j]));
                 }
             }
             s.worker_queued[it.worker] = 0;
@@ -210,8 +230,10 @@ struct Oracle {
             if (s.phase != QUEUED) return -3;
             s.t_last = s.t;                                             // line 18
             const R keep = R(1) - alpha;
-            for (int64_t j = 0; j < n; ++j)                             // line 19
+            for (int64_t j = 0; j < n; ++j) {                           // line 19
+                raise_to(s.sc_theta[j], s.sc_aux[j]);                   // scale of the merged global model
                 s.theta[j] = std::fma(alpha, s.inbox[j], keep * s.theta[j]);
+            }
             grow(s.sc_theta, s.theta);
             s.snap = s.theta;                                           // theta_{t_last}: the post-merge model
             std::fill(s.acc.begin(), s.acc.end(), R(0));
@@ -229,9 +251,13 @@ struct Oracle {
         Lps<R> &s = lps[l];
         if (s.phase != SENT) return -2;
         gps_updates += 1;
-        for (int64_t j = 0; j < n; ++j)
+        for (int64_t j = 0; j < n; ++j) {
             model_update<R>(Theta[j], M[j], s.frozen[j], global);       // line 3
-        grow(sc_Theta, Theta); grow(sc_M, M);
+            raise_to(sc_M[j], s.sc_aux[j]);                             // the scale of G travels with it
+            raise_to(sc_M[j], std::fabs(M[j]));
+            raise_to(sc_Theta[j], step_scale<R>(sc_M[j], s.sc_aux[j], global));
+            raise_to(sc_Theta[j], std::fabs(Theta[j]));
+        }
         s.inbox = Theta;                                                // line 4: this Theta_i, frozen
         s.sc_aux = sc_Theta;
         s.phase = RETURNING;

@@ -14,10 +14,12 @@ from oracle.replay import replay as oracle_replay
 from synth.tensors import scale_f32
 
 # fp32 state vs the fp64 reference: tolerance of the benchmark definition (max relative error per
-# element after the full event sequence).  "Relative" is taken against the largest magnitude the
-# element had along the sequence (never smaller than its final magnitude): fp32 rounding errors are
-# proportional to the operand magnitudes at the time they are made, so this is the scale against
-# which 2^-24-sized errors accumulate.  See the error model in the design notes.
+# element after the full event sequence).  "Relative" is taken against the element's error scale as
+# the oracle tracks it: the largest magnitude among the values the element has held and the operands
+# that were combined to make them (delta, momentum term, the two terms of a step, the merged global
+# model).  fp32 rounding errors are proportional to those operand magnitudes -- a step whose two terms
+# nearly cancel is tiny, its rounding error is not -- so this is the scale on which 2^-24-sized errors
+# accumulate.  The scale is never smaller than the element's final magnitude.
 REL_TOL = 1e-5
 
 
