@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the HALoS server-side update path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1b] [--also tiny,70m,...]
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: the replay of one
+workload-sized slice of a seeded event trace (every worker-delta update, every accumulated-update
+hand-over, GPS update, global-model merge and worker pull it contains), through the C ABI, with all
+state resident in HBM.  One JSON line is printed.
+
+  value        parameters updated per second = N x (LPS updates + GPS updates + merges) / elapsed,
+               elapsed including the pull copies that belong to the same events
+  roofline     the dominant kernel (the LPS update) against the 8 TB/s HBM peak, from HIP events
+               recorded around every launch of the timed region on the launch stream
+  cpu_baseline the CPU oracle, as it stands, timed on a bounded sample of the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# Algorithmic bytes per parameter per launch (fp32 state; delta fp32 or bf16).
+BYTES = {
+    "lps_update_acc": {"f32": 28, "bf16": 26},     # read g, m, theta, acc; write m, theta, acc
+    "lps_update_noacc": {"f32": 20, "bf16": 18},   # accumulated update in flight: acc untouched
+    "gps_update": {"f32": 24, "bf16": 24},         # read G, M, Theta; write M, Theta, returned model
+    "lps_merge": {"f32": 16, "bf16": 16},          # read theta, returned model; write theta, zeroed acc
+    "pull": {"f32": 8, "bf16": 8},
+}
+
+# HBM traffic per parameter per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), valid
+# only for the kernel source it was measured on: {sha256 of kernels.hip: {kernel label: bytes/param}}.
+MEASURED_TRAFFIC: dict = {}
+
+
+def kernels_digest() -> str:
+    with open(os.path.join(ROOT, "paper_2506_04531_amd", "csrc", "kernels.hip"), "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()
+
+
+def split_steps(events, n_updates_per_step: int, n_steps: int):
+    """Cut a long trace into consecutive slices that each contain n_updates_per_step worker updates."""
+    import numpy as np
+    import synth
+    is_upd = (events["kind"] == synth.EV_LPS_STEP) & (events["exp_kind"] == 1)
+    cum = np.cumsum(is_upd)
+    cuts = [0]
+    for s in range(1, n_steps + 1):
+        # slice s ends right after the pull that follows its last update (or after the update itself)
+        pos = int(np.searchsorted(cum, s * n_updates_per_step, side="left")) + 1
+        while pos < len(events) and events[pos]["kind"] == synth.EV_PULL and cum[pos] == s * n_updates_per_step:
+            pos += 1
+        cuts.append(min(pos, len(events)))
+    return [events[cuts[i]:cuts[i + 1]] for i in range(n_steps)]
+
+
+def run_workload(name: str, steps: int, warmup: int, verbose: bool):
+    import numpy as np
+    import torch
+    import synth
+    from paper_2506_04531_amd.harness import Cluster
+
+    w = synth.get_workload(name)
+    long_w = w.scaled(w.layout, n_updates=w.n_updates * (steps + warmup))
+    trace = synth.make_trace(long_w)
+    slices = split_steps(trace.events, w.n_updates, steps + warmup)
+    N = w.layout.total
+    t0 = time.time()
+    c = Cluster(w, "cuda:0", k_initial=trace.k_initial)
+    if verbose:
+        print(f"[bench] {name}: N={N} tensors={w.layout.n_tensors} state resident after {time.time() - t0:.1f}s, "
+              f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB", file=sys.stderr, flush=True)
+    try:
+        for s in range(warmup):
+            c.replay(slices[s])
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        timings = {}
+        n_events = {"update": 0, "gps": 0, "merge": 0, "pull": 0}
+        for s in range(warmup, warmup + steps):
+            log, tm = c.replay(slices[s], timed=True)
+            for k, v in tm.items():
+                timings.setdefault(k, []).extend(v)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t_start
+    finally:
+        c.close()
+        del c
+        torch.cuda.empty_cache()
+
+    kernels = {}
+    for label, pairs in timings.items():
+        if not pairs:
+            continue
+        ms = np.array([a.elapsed_time(b) for a, b in pairs], dtype=np.float64)
+        bpp = BYTES[label][w.delta_dtype]
+        kernels[label] = {
+            "launches": int(ms.size),
+            "avg_ms": float(ms.mean()),
+            "p50_ms": float(np.median(ms)),
+            "bytes_per_param": bpp,
+            "achieved_GBps": float(N * bpp / (ms.mean() * 1e-3) / 1e9),
+            "params_per_s": float(N / (ms.mean() * 1e-3)),
+            "total_ms": float(ms.sum()),
+        }
+    n_upd = sum(kernels[k]["launches"] for k in ("lps_update_acc", "lps_update_noacc") if k in kernels)
+    n_gps = kernels.get("gps_update", {}).get("launches", 0)
+    n_mrg = kernels.get("lps_merge", {}).get("launches", 0)
+    updates = n_upd + n_gps + n_mrg
+    value = N * updates / elapsed
+    # dominant kernel: the LPS update variant that takes the most time
+    dom = max((k for k in ("lps_update_acc", "lps_update_noacc") if k in kernels), key=lambda k: kernels[k]["total_ms"])
+    traffic = MEASURED_TRAFFIC.get(kernels_digest(), {}).get(f"{name}:{dom}")
+    roofline = {
+        "bound": "hbm", "kernel": dom, "achieved": kernels[dom]["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": kernels[dom]["achieved_GBps"] / HBM_PEAK_GBS,
+        "traffic": (traffic * N) if traffic is not None else None,
+        "algorithmic_bytes_per_launch": N * kernels[dom]["bytes_per_param"],
+        "avg_launch_ms": kernels[dom]["avg_ms"],
+    }
+    total_bytes = sum(v["launches"] * v["bytes_per_param"] * N for v in kernels.values())
+    return {
+        "workload": name, "description": w.description, "params": N, "tensors": w.layout.n_tensors,
+        "delta_dtype": w.delta_dtype, "n_lps": w.n_lps, "workers_per_lps": w.workers_per_lps,
+        "steps": steps, "warmup": warmup, "elapsed_s": elapsed, "ms_per_step": elapsed / steps * 1e3,
+        "events_per_step": {"lps_update": n_upd / steps, "gps_update": n_gps / steps, "lps_merge": n_mrg / steps,
+                            "pull": kernels.get("pull", {}).get("launches", 0) / steps},
+        "params_updated_per_s": value,
+        "whole_path_GBps": total_bytes / elapsed / 1e9,
+        "whole_path_frac_of_peak": total_bytes / elapsed / 1e9 / HBM_PEAK_GBS,
+        "kernels": kernels, "roofline": roofline,
+    }
+
+
+def cpu_baseline(name: str, budget_elements: int = 1 << 22):
+    """Time the CPU oracle (fp64, literal form, single thread) on a bounded sample: every event of one
+    workload-sized trace, on `budget_elements` evenly spaced parameters of the workload."""
+    import numpy as np
+    import torch
+    import synth
+    from oracle import FORM_LITERAL, HalosOracle
+    from oracle.replay import replay
+    from synth.tensors import scale_f32
+
+    w = synth.get_workload(name)
+    trace = synth.make_trace(w)
+    N = w.layout.total
+    n_s = min(N, budget_elements)
+    idx = (np.arange(n_s, dtype=np.int64) * (N // n_s))
+    tidx = torch.from_numpy(idx)
+    theta0 = synth.normal_at(w.seed, 0, tidx, scale_f32(w.init_sigma)).numpy()
+    scale = torch.from_numpy(synth.delta_scales(w)[w.layout.tensor_of(idx)])
+    pool = {}
+    for s in range(w.pool_slots):
+        g = synth.normal_at(w.seed, 1 + s, tidx, scale)
+        pool[s] = synth.to_bf16_bits(g).numpy() if w.delta_dtype == "bf16" else g.numpy()
+    o = HalosOracle(theta0, w.n_lps, eta_l=w.eta_l, beta_l=w.beta_l, eta_g=w.eta_g, beta_g=w.beta_g, alpha=w.alpha,
+                    K=trace.k_initial, precision=64, form=FORM_LITERAL)
+    ev = trace.events
+    ev = ev[ev["kind"] != synth.EV_PULL]          # the oracle's pull is a host copy for tests, not timed work
+    t0 = time.perf_counter()
+    log = replay(o, ev, lambda s: pool[s])
+    dt = time.perf_counter() - t0
+    updates = len(log) + trace.count(synth.EV_GPS_MERGE)
+    return {
+        "value": n_s * updates / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
+        "sample": f"{n_s} evenly spaced parameters of the {name} workload, all {updates} update/merge events of one "
+                  f"trace (fp64, single thread, {dt:.1f} s); host has {os.cpu_count()} logical cores",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="1b", help="headline workload: tiny, 70m, 160m, 410m or 1b")
+    ap.add_argument("--also", default="tiny,70m,160m,410m",
+                    help="comma-separated further workloads reported under 'workloads' ('' for none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--blocks-per-cu", type=int, default=0)
+    ap.add_argument("--nontemporal", type=int, default=-1)
+    ap.add_argument("--quiet", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on ONE GPU: every server copy lives in one device's memory and links are a "
+              "seeded schedule; --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    import paper_2506_04531_amd as halos
+    halos.load_library()
+    if args.blocks_per_cu or args.nontemporal >= 0:
+        halos.halos_set_launch_config(args.blocks_per_cu, args.nontemporal)
+
+    head = run_workload(args.workload, args.steps, args.warmup, not args.quiet)
+    others = []
+    for name in [x for x in args.also.split(",") if x and x != args.workload]:
+        others.append(run_workload(name, args.steps, args.warmup, not args.quiet))
+    cpu = None if args.no_cpu_baseline else cpu_baseline(args.workload)
+
+    def brief(r):
+        return {k: r[k] for k in ("workload", "params", "delta_dtype", "ms_per_step", "params_updated_per_s",
+                                  "whole_path_GBps", "whole_path_frac_of_peak", "kernels", "roofline")}
+
+    line = {
+        "metric": "params_updated_per_sec", "value": head["params_updated_per_s"], "unit": "params/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {head['description']}", "params": head["params"],
+                   "tensors": head["tensors"], "n_lps": head["n_lps"], "workers_per_lps": head["workers_per_lps"],
+                   "delta_dtype": head["delta_dtype"], "events_per_step": head["events_per_step"]},
+        "roofline": head["roofline"],
+        "cpu_baseline": cpu,
+        "whole_path_GBps": head["whole_path_GBps"],
+        "kernels": head["kernels"],
+        "workloads": [brief(r) for r in others],
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
