@@ -64,7 +64,7 @@ def split_steps(events, n_updates_per_step: int, n_steps: int):
     return [events[cuts[i]:cuts[i + 1]] for i in range(n_steps)]
 
 
-def run_workload(name: str, steps: int, warmup: int, verbose: bool):
+def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: str = "regions"):
     import numpy as np
     import torch
     import synth
@@ -76,7 +76,8 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool):
     slices = split_steps(trace.events, w.n_updates, steps + warmup)
     N = w.layout.total
     t0 = time.time()
-    c = Cluster(w, "cuda:0", k_initial=trace.k_initial)
+    c = Cluster(w, "cuda:0", k_initial=trace.k_initial, placement=placement, verbose=verbose)
+    n_regions = c.region_arena.n_regions if c.region_arena is not None else 0
     if verbose:
         print(f"[bench] {name}: N={N} tensors={w.layout.n_tensors} state resident after {time.time() - t0:.1f}s, "
               f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB", file=sys.stderr, flush=True)
@@ -138,7 +139,7 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool):
         "params_updated_per_s": value,
         "whole_path_GBps": total_bytes / elapsed / 1e9,
         "whole_path_frac_of_peak": total_bytes / elapsed / 1e9 / HBM_PEAK_GBS,
-        "kernels": kernels, "roofline": roofline,
+        "kernels": kernels, "roofline": roofline, "placement": placement, "hbm_regions_found": n_regions,
     }
 
 
@@ -190,6 +191,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--nontemporal", type=int, default=-1)
+    ap.add_argument("--placement", default="regions", choices=["regions", "plain"],
+                    help="regions: models / momenta / third buffers in three different HBM regions; plain: torch allocations")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
 
@@ -207,10 +210,10 @@ def main():
     if args.blocks_per_cu or args.nontemporal >= 0:
         halos.halos_set_launch_config(args.blocks_per_cu, args.nontemporal)
 
-    head = run_workload(args.workload, args.steps, args.warmup, not args.quiet)
+    head = run_workload(args.workload, args.steps, args.warmup, not args.quiet, args.placement)
     others = []
     for name in [x for x in args.also.split(",") if x and x != args.workload]:
-        others.append(run_workload(name, args.steps, args.warmup, not args.quiet))
+        others.append(run_workload(name, args.steps, args.warmup, not args.quiet, args.placement))
     cpu = None if args.no_cpu_baseline else cpu_baseline(args.workload)
 
     def brief(r):
@@ -223,7 +226,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {head['description']}", "params": head["params"],
                    "tensors": head["tensors"], "n_lps": head["n_lps"], "workers_per_lps": head["workers_per_lps"],
-                   "delta_dtype": head["delta_dtype"], "events_per_step": head["events_per_step"]},
+                   "delta_dtype": head["delta_dtype"], "events_per_step": head["events_per_step"],
+                   "placement": head["placement"], "hbm_regions_found": head["hbm_regions_found"]},
         "roofline": head["roofline"],
         "cpu_baseline": cpu,
         "whole_path_GBps": head["whole_path_GBps"],

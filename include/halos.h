@@ -203,6 +203,22 @@ halos_status halos_gps_get_counters(const halos_gps *gps, int64_t *updates);
  */
 halos_status halos_set_launch_config(int32_t blocks_per_cu, int32_t nontemporal);
 
+/*
+ * Memory-placement helper (not a step of the algorithm).  An MI355X serves its 288 GB of HBM from a few
+ * independent regions, and a kernel whose read-modify-write streams live in different regions gets
+ * noticeably more bandwidth than one whose streams share a region.  This call sweeps the two device
+ * buffers `reps` times on `stream` (each element is read and written back unchanged), waits for the
+ * sweeps, and reports the achieved GB/s (4 x bytes per sweep).  Two buffers in the same region report a
+ * visibly lower figure than two buffers in different regions, which lets a caller that allocates its
+ * state in slabs sort the slabs by region and put theta, m and acc of a server into different ones.
+ *   a, b    16-byte aligned device buffers of at least `bytes` bytes each; must not overlap; no other
+ *           work may write them while the call runs
+ *   bytes   >= 16 KiB; rounded down to a multiple of 16 KiB
+ *   reps    1..1000 timed sweeps (one untimed sweep runs first)
+ * Errors: EINVAL, EHIP.
+ */
+halos_status halos_probe_pair(void *a, void *b, uint64_t bytes, int32_t reps, void *stream, double *gbps);
+
 /* Release the handle's tables.  Caller buffers are untouched.  NULL is ignored. */
 void halos_lps_destroy(halos_lps *lps);
 void halos_gps_destroy(halos_gps *gps);

@@ -83,6 +83,7 @@ def load_library():
         "halos_lps_get_counters": [vp, P(i64), P(i64), P(i32), P(i32), P(u32)],
         "halos_gps_get_counters": [vp, P(i64)],
         "halos_set_launch_config": [i32, i32],
+        "halos_probe_pair": [vp, vp, ctypes.c_uint64, i32, vp, P(ctypes.c_double)],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -196,6 +197,15 @@ def halos_gps_get_counters(gps: int) -> dict:
 
 def halos_set_launch_config(blocks_per_cu: int = 0, nontemporal: int = -1) -> None:
     _check(load_library().halos_set_launch_config(blocks_per_cu, nontemporal))
+
+
+def halos_probe_pair(a, b, nbytes: int, reps: int = 2, stream=None) -> float:
+    """GB/s of a read-modify-write sweep over two device buffers (torch tensors or raw addresses)."""
+    pa = a if isinstance(a, int) else a.data_ptr()
+    pb = b if isinstance(b, int) else b.data_ptr()
+    out = ctypes.c_double()
+    _check(load_library().halos_probe_pair(pa, pb, int(nbytes), reps, _stream(stream), ctypes.byref(out)))
+    return out.value
 
 
 def halos_lps_destroy(lps: Optional[int]) -> None:

@@ -187,6 +187,59 @@ halos_status halos_set_launch_config(int32_t blocks_per_cu, int32_t nontemporal)
     return HALOS_OK;
 }
 
+halos_status halos_probe_pair(void *a, void *b, uint64_t bytes, int32_t reps, void *stream, double *gbps) {
+    if (!a || !b || !gbps) return fail(HALOS_EINVAL, "NULL argument");
+    if (((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 15u) != 0)
+        return fail(HALOS_EINVAL, "buffers must be 16-byte aligned");
+    const uint64_t tile_bytes = (uint64_t)TILE_ELEMS * sizeof(float);
+    if (bytes < tile_bytes) return fail(HALOS_EINVAL, "bytes = %llu, must be >= %llu", (unsigned long long)bytes,
+                                        (unsigned long long)tile_bytes);
+    if (reps < 1 || reps > 1000) return fail(HALOS_EINVAL, "reps = %d outside 1..1000", reps);
+    const uint64_t n_tiles64 = bytes / tile_bytes;
+    if (n_tiles64 > 0xFFFFFFFFull) return fail(HALOS_EINVAL, "bytes too large");
+    const uint64_t used = n_tiles64 * tile_bytes;
+    const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
+    if ((pa <= pb && pa + used > pb) || (pb <= pa && pb + used > pa)) return fail(HALOS_EINVAL, "buffers overlap");
+    for (void *p : {a, b}) {       // both buffers must be device memory with room for `used` bytes
+        hipPointerAttribute_t attr;
+        hipError_t e = hipPointerGetAttributes(&attr, p);
+        if (e != hipSuccess || (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged)) {
+            (void)hipGetLastError();
+            return fail(HALOS_EINVAL, "not a device pointer");
+        }
+        hipDeviceptr_t base = nullptr;
+        size_t size = 0;
+        e = hipMemGetAddressRange(&base, &size, p);
+        if (e != hipSuccess) { (void)hipGetLastError(); return fail(HALOS_EINVAL, "cannot query the allocation"); }
+        if (reinterpret_cast<uintptr_t>(p) + used > reinterpret_cast<uintptr_t>(base) + size)
+            return fail(HALOS_EINVAL, "buffer is smaller than `bytes`");
+    }
+    int dev = 0, n_cu = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return fail_hip(e, "querying the device");
+    LaunchShape shape;
+    shape.grid_cap = g_blocks_per_cu.load() * (n_cu > 0 ? n_cu : 1);
+    shape.nontemporal = true;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    if (e != hipSuccess) { if (e0) (void)hipEventDestroy(e0); return fail_hip(e, "hipEventCreate"); }
+    hipStream_t s = (hipStream_t)stream;
+    e = launch_probe_pair(s, (float *)a, (float *)b, (uint32_t)n_tiles64, shape);
+    if (e == hipSuccess) e = hipEventRecord(e0, s);
+    for (int r = 0; r < reps && e == hipSuccess; ++r) e = launch_probe_pair(s, (float *)a, (float *)b, (uint32_t)n_tiles64, shape);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return fail_hip(e, "timing the probe");
+    *gbps = ms > 0.f ? (double)used * 4.0 * reps / ((double)ms * 1e-3) / 1e9 : 0.0;
+    return HALOS_OK;
+}
+
 halos_status halos_gps_create(const halos_layout *layout, const halos_hparams *hp, void *const *Theta, void *const *M,
                               void *stream, halos_gps **out) {
     if (!out) return fail(HALOS_EINVAL, "out is NULL");

@@ -322,6 +322,35 @@ init_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, 
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Placement probe: read two buffers and write both back unchanged, tile by tile.  Only its duration
+// matters: two buffers served by the same HBM region sweep measurably slower than two served by
+// different regions.
+__global__ void __launch_bounds__(BLOCK_THREADS)
+probe_pair_kernel(float *a, float *b, uint32_t n_tiles) {
+    const uint32_t tid = threadIdx.x;
+    gf32 *ga = to_global(a), *gb = to_global(b);
+    for (uint32_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const size_t base = static_cast<size_t>(t) * TILE_ELEMS;
+        f32x4 va[UNROLL], vb[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const size_t off = base + (u * BLOCK_THREADS + tid) * VEC;
+            va[u] = ld4<true>(ga + off);
+            vb[u] = ld4<true>(gb + off);
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const size_t off = base + (u * BLOCK_THREADS + tid) * VEC;
+            // The values go back unchanged, but the compiler must not know that, or it would drop the
+            // stores (and then the loads) as redundant: pass them through an empty asm statement.
+            asm volatile("" : "+v"(va[u]), "+v"(vb[u]));
+            st4<true>(ga + off, va[u]);
+            st4<true>(gb + off, vb[u]);
+        }
+    }
+}
+
 inline dim3 grid_for(TileRange r, LaunchShape shape) {
     uint32_t n = r.hi - r.lo;
     uint32_t cap = shape.grid_cap > 0 ? (uint32_t)shape.grid_cap : 1u;
@@ -391,6 +420,13 @@ hipError_t launch_init(hipStream_t stream, const Tile *tiles, TileRange r, float
     if (r.hi <= r.lo) return hipSuccess;
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
     init_kernel<<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, src, theta, m, acc);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_pair(hipStream_t stream, float *a, float *b, uint32_t n_tiles, LaunchShape shape) {
+    if (n_tiles == 0) return hipSuccess;
+    const uint32_t cap = shape.grid_cap > 0 ? (uint32_t)shape.grid_cap : 1u;
+    probe_pair_kernel<<<dim3(n_tiles < cap ? n_tiles : cap), dim3(BLOCK_THREADS), 0, stream>>>(a, b, n_tiles);
     return hipGetLastError();
 }
 

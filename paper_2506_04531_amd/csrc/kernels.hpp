@@ -61,4 +61,7 @@ hipError_t launch_pull(hipStream_t stream, const Tile *tiles, TileRange r, float
 hipError_t launch_init(hipStream_t stream, const Tile *tiles, TileRange r, float *const *src, float *const *theta,
                        float *const *m, float *const *acc, LaunchShape shape);
 
+// Sweep the first n_tiles * TILE_ELEMS floats of two buffers (read both, write both back unchanged).
+hipError_t launch_probe_pair(hipStream_t stream, float *a, float *b, uint32_t n_tiles, LaunchShape shape);
+
 }  // namespace halos

@@ -35,6 +35,116 @@ def alloc_tensor_list(numel: Sequence[int], dtype: torch.dtype, device, arena: b
     return [buf[o:o + int(n)] for o, n in zip(offs, numel)]
 
 
+class RegionArena:
+    """Device memory sorted by HBM region.
+
+    On an MI355X a read-modify-write kernel runs ~20 % faster when the arrays it writes are served by
+    different regions of the HBM (measured with halos_probe_pair: two buffers from the same region
+    sweep at 5.1-5.7 TB/s, two from different regions at 6.1-6.5 TB/s).  Regions are large -- about a
+    third of the memory each -- so the arena allocates 2 GiB slabs until it holds enough slabs from
+    `len(need)` different regions, classifying every new slab by probing it against one representative
+    slab per known region: slow against a representative means "same region".  The reference for
+    "slow" is the speed of a slab's own two halves against each other.  Slabs that are not needed
+    (whatever lay in between) are released again.
+
+    need[c] is the number of bytes wanted in placement class c; alloc(c, ...) hands out 256-byte aligned
+    views from the slabs of the region that class c was mapped to.  If fewer regions than classes are
+    found (other memory users, a smaller device) classes share regions: slower, still correct.
+    """
+
+    SLAB = 1 << 31
+    HALF = 1 << 30
+
+    def __init__(self, device, need: Sequence[int], max_bytes: Optional[int] = None, verbose: bool = False):
+        self.device = torch.device(device)
+        n_classes = len(need)
+        free_b, _ = torch.cuda.mem_get_info(self.device)
+        budget = min(free_b - (8 << 30), max_bytes if max_bytes else free_b)
+        want = [(int(b) + self.SLAB - 1) // self.SLAB + 1 for b in need]       # slabs per class (+1: tensors do not straddle slabs)
+        regions: List[List[torch.Tensor]] = []
+        ballast: List[torch.Tensor] = []      # held until the end so the allocator cannot hand the same memory out again
+        self.log = []
+        used = 0
+        same_ref = None
+        probe = lambda x, y: B.halos_probe_pair(x, y, self.HALF, 2)
+
+        def enough():
+            have = sorted((len(r) for r in regions), reverse=True)
+            return len(have) >= n_classes and all(h >= w for h, w in zip(have, sorted(want, reverse=True)))
+
+        def classify(ptr, last):
+            """Region index of the 1 GiB at ptr (len(regions) = none of the known ones)."""
+            order = ([last] if last is not None else []) + [r for r in range(len(regions)) if r != last]
+            speeds = {}
+            for r in order:
+                speeds[r] = probe(regions[r][0].data_ptr(), ptr)
+                if speeds[r] <= thr:
+                    return r, speeds
+            return len(regions), speeds
+
+        try:
+            last = None
+            while used + self.SLAB <= budget and not enough():
+                slab = torch.empty(self.SLAB, dtype=torch.uint8, device=self.device)
+                used += self.SLAB
+                p = slab.data_ptr()
+                if same_ref is None:
+                    same_ref = probe(p, p + self.HALF)                         # a slab against itself: same region
+                    thr = 1.08 * same_ref
+                    regions.append([slab])
+                    last = 0
+                    continue
+                r_head, sp_h = classify(p, last)
+                r_tail, sp_t = classify(p + self.HALF, r_head if r_head < len(regions) else last)
+                self.log.append((used >> 30, r_head, r_tail, sp_h, sp_t))
+                if r_head != r_tail:
+                    ballast.append(slab)                                        # straddles a region boundary
+                elif r_head == len(regions):
+                    regions.append([slab])
+                    last = r_head
+                else:
+                    regions[r_head].append(slab)
+                    last = r_head
+        except torch.cuda.OutOfMemoryError:
+            pass
+        self.n_regions = len(regions)
+        # the largest classes get the regions with the most slabs; release everything that is not needed
+        by_size = sorted(range(len(regions)), key=lambda r: -len(regions[r]))
+        cls_order = sorted(range(n_classes), key=lambda c: -want[c])
+        self.slabs: List[List[torch.Tensor]] = [[] for _ in range(n_classes)]
+        self.region_of_class = [0] * n_classes
+        for k, c in enumerate(cls_order):
+            r = by_size[k % len(by_size)]
+            self.region_of_class[c] = r
+            take = min(len(regions[r]), want[c])
+            self.slabs[c] = regions[r][:take]
+            del regions[r][:take]
+        del regions, ballast
+        torch.cuda.empty_cache()
+        self._cursor = [(0, 0)] * n_classes
+        if verbose:
+            import sys
+            print(f"[arena] walked {used >> 30} GiB, regions found: {self.n_regions}, same-region reference "
+                  f"{same_ref:.0f} GB/s; slabs kept per class: {[len(x) for x in self.slabs]} in regions {self.region_of_class}",
+                  file=sys.stderr, flush=True)
+
+    def alloc(self, cls: int, numel: int, dtype: torch.dtype) -> torch.Tensor:
+        esize = torch.empty(0, dtype=dtype).element_size()
+        nbytes = (int(numel) * esize + 255) // 256 * 256
+        if nbytes > self.SLAB:
+            raise ValueError("tensor larger than one slab")
+        i, off = self._cursor[cls]
+        if off + nbytes > self.SLAB:
+            i, off = i + 1, 0
+        if i >= len(self.slabs[cls]):
+            self.slabs[cls].append(torch.empty(self.SLAB, dtype=torch.uint8, device=self.device))   # overflow: anywhere
+        self._cursor[cls] = (i, off + nbytes)
+        return self.slabs[cls][i][off:off + int(numel) * esize].view(dtype)
+
+    def alloc_list(self, cls: int, numel: Sequence[int], dtype: torch.dtype) -> List[torch.Tensor]:
+        return [self.alloc(cls, n, dtype) for n in numel]
+
+
 def fill_initial_model(w: synth.Workload, tensors: List[torch.Tensor]) -> None:
     off = w.layout.offsets
     for i, t in enumerate(tensors):
@@ -66,7 +176,11 @@ class Cluster:
     """GPS + n_lps LPSs + delta pool for one workload, resident on `device`."""
 
     def __init__(self, w: synth.Workload, device="cuda:0", arena: bool = False, hp: Optional[B.HParams] = None,
-                 k_initial: Optional[Sequence[int]] = None, pull_buffers: bool = True):
+                 k_initial: Optional[Sequence[int]] = None, pull_buffers: bool = True, placement: str = "plain",
+                 verbose: bool = False):
+        """placement "plain": every tensor is its own torch allocation (or one arena per list if arena=True).
+        placement "regions": models (Theta, theta_l) / momenta (M, m_l) / third buffers (acc_l) are placed in
+        three different HBM regions through a RegionArena, so that every kernel's written streams are spread."""
         self.w = w
         self.device = torch.device(device)
         lay = w.layout
@@ -74,14 +188,24 @@ class Cluster:
         self.offsets = lay.offsets
         self.n = lay.total
         f32 = torch.float32
-        mk = lambda dt=f32: alloc_tensor_list(self.numel, dt, self.device, arena)
-        self.Theta, self.M = mk(), mk()
+        self.region_arena = None
+        if placement == "regions":
+            ddt_size = 2 if w.delta_dtype == "bf16" else 4
+            S = sum((n * 4 + 255) // 256 * 256 for n in self.numel)
+            L = w.n_lps
+            need = [(L + 1) * S, (L + 1) * S + (L * S if pull_buffers else 0), L * S + w.pool_slots * S * ddt_size // 4]
+            self.region_arena = RegionArena(self.device, need, verbose=verbose)
+            ra = self.region_arena
+            mk = lambda dt=f32, cls=2: ra.alloc_list(cls, self.numel, dt)
+        else:
+            mk = lambda dt=f32, cls=0: alloc_tensor_list(self.numel, dt, self.device, arena)
+        self.Theta, self.M = mk(cls=0), mk(cls=1)
         fill_initial_model(w, self.Theta)
         self.hp = hp if hp is not None else B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0])
         self.gps = B.halos_gps_create(self.numel, self.hp, self.Theta, self.M)
         self.theta, self.m, self.acc, self.lps = [], [], [], []
         for l in range(w.n_lps):
-            th, m, acc = mk(), mk(), mk()
+            th, m, acc = mk(cls=0), mk(cls=1), mk(cls=2)
             self.theta.append(th); self.m.append(m); self.acc.append(acc)
             h = B.halos_lps_create(self.gps, l, w.workers_per_lps, th, m, acc)
             if k_initial is not None:
@@ -91,10 +215,10 @@ class Cluster:
         ddt = torch.bfloat16 if w.delta_dtype == "bf16" else f32
         self.pool = []
         for s in range(w.pool_slots):
-            ts = mk(ddt)
+            ts = mk(ddt, cls=2)
             fill_delta_slot(w, s, ts)
             self.pool.append(ts)
-        self.pull_dst = [mk() for _ in range(w.n_lps)] if pull_buffers else None
+        self.pull_dst = [mk(cls=1) for _ in range(w.n_lps)] if pull_buffers else None
         # pointer arrays marshalled once: the replay loop then costs a few ctypes calls per event
         self._pool_ptrs = [B._ptrs(ts) for ts in self.pool]
         self._pull_ptrs = [B._ptrs(ts) for ts in self.pull_dst] if pull_buffers else None

@@ -147,3 +147,44 @@ def test_launch_shapes_give_identical_results():
     for r in results[1:]:
         for k in results[0]:
             assert np.array_equal(results[0][k].view(np.uint32), r[k].view(np.uint32)), k
+
+
+def test_region_placement_changes_nothing_but_speed():
+    """State spread over HBM regions through the arena: same bits as with plain allocations."""
+    from paper_2506_04531_amd.harness import Cluster
+    w = synth.get_workload("160m").scaled(synth.gpt_layout(96, 2, vocab=1031), n_updates=64, name="regions")
+    trace = synth.make_trace(w)
+    print(f"[parity] workload={w.name} placement=regions n={w.layout.total}", flush=True)
+    c = Cluster(w, "cuda:0", k_initial=trace.k_initial, placement="regions", verbose=True)
+    try:
+        assert c.region_arena.n_regions >= 1
+        print(f"[parity] regions found: {c.region_arena.n_regions}", flush=True)
+        gpu_log, _ = c.replay(trace.events)
+        torch.cuda.synchronize()
+        gpu = {k: c.flat(k) for k in c.state_lists()}
+    finally:
+        c.close()
+        del c
+        torch.cuda.empty_cache()
+    o32, log32 = oracle_run(w, trace, None, 32, FORM_ACCUMULATOR)
+    check_step_logs(trace, gpu_log, log32)
+    worst, n_diff, name = compare_state(gpu, oracle_state(o32, w.n_lps), bitwise=True)
+    assert n_diff == 0 and worst <= REL_TOL, (n_diff, worst, name)
+
+
+def test_probe_pair_reports_bandwidth_and_preserves_contents():
+    from paper_2506_04531_amd import binding as B
+    n = 1 << 24
+    a = torch.randn(n, device="cuda:0")
+    b = torch.randn(n, device="cuda:0")
+    a0, b0 = a.clone(), b.clone()
+    gbps = B.halos_probe_pair(a, b, n * 4, 2)
+    assert 50.0 < gbps < 20000.0
+    assert torch.equal(a, a0) and torch.equal(b, b0)
+    with pytest.raises(B.HalosError) as e:
+        B.halos_probe_pair(a, a, n * 4, 2)                     # overlapping buffers
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.HalosError):
+        B.halos_probe_pair(a, b, n * 8, 2)                     # longer than the allocation
+    with pytest.raises(B.HalosError):
+        B.halos_probe_pair(a.data_ptr() + 4, b, n * 2, 2)      # misaligned
