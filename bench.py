@@ -33,6 +33,8 @@ HBM_PEAK_GBS = 8000.0
 BYTES = {
     "lps_update_acc": {"f32": 28, "bf16": 26},     # read g, m, theta, acc; write m, theta, acc
     "lps_update_noacc": {"f32": 20, "bf16": 18},   # accumulated update in flight: acc untouched
+    "lps_update_acc_pull": {"f32": 32, "bf16": 30},    # ... plus the updated model written to the worker's buffer
+    "lps_update_noacc_pull": {"f32": 24, "bf16": 22},
     "gps_update": {"f32": 24, "bf16": 24},         # read G, M, Theta; write M, Theta, returned model
     "lps_merge": {"f32": 16, "bf16": 16},          # read theta, returned model; write theta, zeroed acc
     "pull": {"f32": 8, "bf16": 8},
@@ -64,7 +66,7 @@ def split_steps(events, n_updates_per_step: int, n_steps: int):
     return [events[cuts[i]:cuts[i + 1]] for i in range(n_steps)]
 
 
-def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: str = "regions"):
+def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: str = "regions", fuse_pull: bool = True):
     import numpy as np
     import torch
     import synth
@@ -83,13 +85,13 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
               f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB", file=sys.stderr, flush=True)
     try:
         for s in range(warmup):
-            c.replay(slices[s])
+            c.replay(slices[s], fuse_pull=fuse_pull)
         torch.cuda.synchronize()
         t_start = time.perf_counter()
         timings = {}
         n_events = {"update": 0, "gps": 0, "merge": 0, "pull": 0}
         for s in range(warmup, warmup + steps):
-            log, tm = c.replay(slices[s], timed=True)
+            log, tm = c.replay(slices[s], timed=True, fuse_pull=fuse_pull)
             for k, v in tm.items():
                 timings.setdefault(k, []).extend(v)
         torch.cuda.synchronize()
@@ -114,13 +116,16 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
             "params_per_s": float(N / (ms.mean() * 1e-3)),
             "total_ms": float(ms.sum()),
         }
-    n_upd = sum(kernels[k]["launches"] for k in ("lps_update_acc", "lps_update_noacc") if k in kernels)
+    upd_labels = ("lps_update_acc", "lps_update_noacc", "lps_update_acc_pull", "lps_update_noacc_pull")
+    n_upd = sum(kernels[k]["launches"] for k in upd_labels if k in kernels)
+    n_pull_events = kernels.get("pull", {}).get("launches", 0) + sum(
+        kernels[k]["launches"] for k in ("lps_update_acc_pull", "lps_update_noacc_pull") if k in kernels)
     n_gps = kernels.get("gps_update", {}).get("launches", 0)
     n_mrg = kernels.get("lps_merge", {}).get("launches", 0)
     updates = n_upd + n_gps + n_mrg
     value = N * updates / elapsed
     # dominant kernel: the LPS update variant that takes the most time
-    dom = max((k for k in ("lps_update_acc", "lps_update_noacc") if k in kernels), key=lambda k: kernels[k]["total_ms"])
+    dom = max((k for k in upd_labels if k in kernels), key=lambda k: kernels[k]["total_ms"])
     traffic = MEASURED_TRAFFIC.get(kernels_digest(), {}).get(f"{name}:{dom}")
     roofline = {
         "bound": "hbm", "kernel": dom, "achieved": kernels[dom]["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -135,11 +140,12 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
         "delta_dtype": w.delta_dtype, "n_lps": w.n_lps, "workers_per_lps": w.workers_per_lps,
         "steps": steps, "warmup": warmup, "elapsed_s": elapsed, "ms_per_step": elapsed / steps * 1e3,
         "events_per_step": {"lps_update": n_upd / steps, "gps_update": n_gps / steps, "lps_merge": n_mrg / steps,
-                            "pull": kernels.get("pull", {}).get("launches", 0) / steps},
+                            "pull": n_pull_events / steps},
         "params_updated_per_s": value,
         "whole_path_GBps": total_bytes / elapsed / 1e9,
         "whole_path_frac_of_peak": total_bytes / elapsed / 1e9 / HBM_PEAK_GBS,
         "kernels": kernels, "roofline": roofline, "placement": placement, "hbm_regions_found": n_regions,
+        "fuse_pull": fuse_pull,
     }
 
 
@@ -193,6 +199,8 @@ def main():
     ap.add_argument("--nontemporal", type=int, default=-1)
     ap.add_argument("--placement", default="regions", choices=["regions", "plain"],
                     help="regions: models / momenta / third buffers in three different HBM regions; plain: torch allocations")
+    ap.add_argument("--no-fuse-pull", action="store_true",
+                    help="issue every worker pull as its own copy instead of fusing it into the update pass")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
 
@@ -210,10 +218,10 @@ def main():
     if args.blocks_per_cu or args.nontemporal >= 0:
         halos.halos_set_launch_config(args.blocks_per_cu, args.nontemporal)
 
-    head = run_workload(args.workload, args.steps, args.warmup, not args.quiet, args.placement)
+    head = run_workload(args.workload, args.steps, args.warmup, not args.quiet, args.placement, not args.no_fuse_pull)
     others = []
     for name in [x for x in args.also.split(",") if x and x != args.workload]:
-        others.append(run_workload(name, args.steps, args.warmup, not args.quiet, args.placement))
+        others.append(run_workload(name, args.steps, args.warmup, not args.quiet, args.placement, not args.no_fuse_pull))
     cpu = None if args.no_cpu_baseline else cpu_baseline(args.workload)
 
     def brief(r):
@@ -227,7 +235,8 @@ def main():
         "config": {"workload": f"{args.workload}: {head['description']}", "params": head["params"],
                    "tensors": head["tensors"], "n_lps": head["n_lps"], "workers_per_lps": head["workers_per_lps"],
                    "delta_dtype": head["delta_dtype"], "events_per_step": head["events_per_step"],
-                   "placement": head["placement"], "hbm_regions_found": head["hbm_regions_found"]},
+                   "placement": head["placement"], "hbm_regions_found": head["hbm_regions_found"],
+                   "fuse_pull": head["fuse_pull"]},
         "roofline": head["roofline"],
         "cpu_baseline": cpu,
         "whole_path_GBps": head["whole_path_GBps"],

@@ -158,6 +158,25 @@ halos_status halos_lps_push_global(halos_lps *lps);
 halos_status halos_lps_step(halos_lps *lps, void *stream, halos_step_info *info);
 
 /*
+ * Register the device tensors in which worker `worker` keeps the model it starts a round from, so that
+ * halos_lps_step_pull can hand the updated model back in the same pass that applies the worker's delta.
+ * The pointers are copied into a device table; the call waits for the device to go idle first, so it
+ * belongs to set-up, not to the event loop.  The buffers are borrowed for the life of the handle (or
+ * until re-registered).
+ */
+halos_status halos_lps_set_worker_model(halos_lps *lps, int32_t worker, void *const *model);
+
+/*
+ * halos_lps_step with "Schedule the worker theta_t" (Algorithm 1 line 12) fused in: if the head of the
+ * queue is a worker delta, the pass that applies it also writes the updated model theta_t into that
+ * worker's registered model buffer -- one read-modify-write pass instead of an update pass plus a copy
+ * (halos_pull_model).  Results are identical to halos_lps_step followed by halos_pull_model.  If the head
+ * is a global model the call behaves exactly like halos_lps_step.
+ * ESTATE if the worker at the head has no registered model buffer (nothing is modified).
+ */
+halos_status halos_lps_step_pull(halos_lps *lps, void *stream, halos_step_info *info);
+
+/*
  * The accumulated update of LPS `from` reaches the GPS (Algorithm 1 lines 2-4): one fused pass applies
  * ModelUpdate(Theta, G, eta_g, beta_g) and writes the new global model Theta_i over `from`'s third buffer,
  * where it stays frozen until `from` merges it -- later GPS updates do not change it.

@@ -76,6 +76,8 @@ def load_library():
         "halos_lps_push_update": [vp, i32, P(vp), i32, u32],
         "halos_lps_push_global": [vp],
         "halos_lps_step": [vp, vp, P(StepInfo)],
+        "halos_lps_step_pull": [vp, vp, P(StepInfo)],
+        "halos_lps_set_worker_model": [vp, i32, P(vp)],
         "halos_gps_merge": [vp, vp, vp],
         "halos_pull_model": [vp, i32, P(vp), vp],
         "halos_set_hparams": [vp, i32, P(HParams)],
@@ -163,6 +165,16 @@ def halos_lps_step(lps: int, stream=None) -> StepInfo:
     info = StepInfo()
     _check(load_library().halos_lps_step(lps, _stream(stream), ctypes.byref(info)))
     return info
+
+
+def halos_lps_step_pull(lps: int, stream=None) -> StepInfo:
+    info = StepInfo()
+    _check(load_library().halos_lps_step_pull(lps, _stream(stream), ctypes.byref(info)))
+    return info
+
+
+def halos_lps_set_worker_model(lps: int, worker: int, model) -> None:
+    _check(load_library().halos_lps_set_worker_model(lps, worker, _ptrs(model)))
 
 
 def halos_gps_merge(gps: int, from_lps: int, stream=None) -> None:

@@ -87,6 +87,8 @@ struct halos_lps {
     int32_t id = 0;
     void *d_tables = nullptr;          // one allocation: [theta | m | acc] pointer tables
     float **d_theta = nullptr, **d_m = nullptr, **d_acc = nullptr;
+    float **d_worker_model = nullptr;  // n_workers tables of n_tensors pointers, appended to d_tables
+    std::vector<char> worker_has_model;
     halos_rule rule{};
     float alpha = 0.f;
     LpsProtocol proto;
@@ -156,15 +158,17 @@ void fill_args(PtrArgs &a, const void *const *ptrs, const TileRange &r, size_t n
     }
 }
 
-halos_status upload_tables(void **d_out, const std::vector<const void *const *> &host_tabs, size_t n_tensors) {
-    const size_t bytes = host_tabs.size() * n_tensors * sizeof(void *);
+halos_status upload_tables(void **d_out, const std::vector<const void *const *> &host_tabs, size_t n_tensors,
+                           size_t extra_null_tables = 0) {
+    const size_t bytes = (host_tabs.size() + extra_null_tables) * n_tensors * sizeof(void *);
     void *d = nullptr;
     hipError_t e = hipMalloc(&d, bytes ? bytes : sizeof(void *));
     if (e != hipSuccess) { (void)hipGetLastError(); return fail(HALOS_ENOMEM, "pointer tables: %s", hipGetErrorString(e)); }
     std::vector<const void *> flat;
-    flat.reserve(host_tabs.size() * n_tensors);
+    flat.reserve((host_tabs.size() + extra_null_tables) * n_tensors);
     for (const void *const *tab : host_tabs)
         for (size_t i = 0; i < n_tensors; ++i) flat.push_back(tab[i]);
+    flat.resize((host_tabs.size() + extra_null_tables) * n_tensors, nullptr);
     if (bytes) {
         e = hipMemcpy(d, flat.data(), bytes, hipMemcpyHostToDevice);
         if (e != hipSuccess) { (void)hipFree(d); return fail_hip(e, "uploading pointer tables"); }
@@ -340,11 +344,14 @@ halos_status halos_lps_create(halos_gps *g, int32_t lps_id, int32_t n_workers, v
     l->validated.resize(n_workers);
     l->validated_dtype.assign(n_workers, HALOS_F32);
     const size_t nt = g->numel.size();
-    st = upload_tables(&l->d_tables, {(const void *const *)theta, (const void *const *)m, (const void *const *)acc}, nt);
+    st = upload_tables(&l->d_tables, {(const void *const *)theta, (const void *const *)m, (const void *const *)acc}, nt,
+                       (size_t)n_workers);
     if (st != HALOS_OK) { delete l; return st; }
     l->d_theta = (float **)l->d_tables;
     l->d_m = l->d_theta + nt;
     l->d_acc = l->d_m + nt;
+    l->d_worker_model = l->d_acc + nt;
+    l->worker_has_model.assign(n_workers, 0);
     for (const TileRange &r : g->ranges) {       // theta <- Theta, m <- 0, acc <- 0
         hipError_t e = launch_init((hipStream_t)stream, g->d_tiles, r, g->d_Theta, l->d_theta, l->d_m, l->d_acc,
                                    current_shape(g));
@@ -400,7 +407,24 @@ halos_status halos_lps_push_global(halos_lps *l) {
     return HALOS_OK;
 }
 
-halos_status halos_lps_step(halos_lps *l, void *stream, halos_step_info *info) {
+halos_status halos_lps_set_worker_model(halos_lps *l, int32_t worker, void *const *model) {
+    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    if (worker < 0 || worker >= l->proto.n_workers())
+        return fail(HALOS_EINVAL, "worker %d outside 0..%d", worker, l->proto.n_workers() - 1);
+    const halos_gps *g = l->gps;
+    halos_status st = check_device(g);
+    if (st == HALOS_OK) st = check_tensors(g, (const void *const *)model, sizeof(float), "model");
+    if (st != HALOS_OK) return st;
+    const size_t nt = g->numel.size();
+    hipError_t e = hipDeviceSynchronize();      // no launch that still reads the old table may be in flight
+    if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
+    e = hipMemcpy(l->d_worker_model + (size_t)worker * nt, model, nt * sizeof(void *), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail_hip(e, "uploading the worker's pointer table");
+    l->worker_has_model[worker] = 1;
+    return HALOS_OK;
+}
+
+static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *info, bool pull) {
     if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
     halos_gps *g = l->gps;
     halos_step_info out{};
@@ -418,11 +442,17 @@ halos_status halos_lps_step(halos_lps *l, void *stream, halos_step_info *info) {
     if (head.kind == ITEM_DELTA) {
         const UpdateOutcome oc = l->proto.preview_update();
         const PendingDelta &p = l->pending[head.worker];
+        float *const *pull_tab = nullptr;
+        if (pull) {
+            if (!l->worker_has_model[head.worker])
+                return fail(HALOS_ESTATE, "worker %d of lps %d has no model buffer registered", head.worker, l->id);
+            pull_tab = l->d_worker_model + (size_t)head.worker * g->numel.size();
+        }
         for (const TileRange &r : g->ranges) {
             PtrArgs args;
             fill_args(args, p.ptrs.data(), r, g->numel.size());
-            hipError_t e = launch_lps_update((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_acc, args,
-                                             p.dtype == HALOS_BF16, oc.accumulate, l->rule.eta, l->rule.beta,
+            hipError_t e = launch_lps_update((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_acc, pull_tab,
+                                             args, p.dtype == HALOS_BF16, oc.accumulate, l->rule.eta, l->rule.beta,
                                              l->rule.cg, shape);
             if (e != hipSuccess) return fail_hip(e, "launching the local update");
         }
@@ -444,6 +474,14 @@ halos_status halos_lps_step(halos_lps *l, void *stream, halos_step_info *info) {
     out.t_last = l->proto.t_last();
     if (info) *info = out;
     return HALOS_OK;
+}
+
+halos_status halos_lps_step(halos_lps *l, void *stream, halos_step_info *info) {
+    return lps_step_impl(l, stream, info, false);
+}
+
+halos_status halos_lps_step_pull(halos_lps *l, void *stream, halos_step_info *info) {
+    return lps_step_impl(l, stream, info, true);
 }
 
 halos_status halos_gps_merge(halos_gps *g, halos_lps *from, void *stream) {

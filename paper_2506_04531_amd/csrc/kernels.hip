@@ -112,11 +112,14 @@ __device__ __forceinline__ f32x4 merge4(f32x4 theta, f32x4 global, float alpha, 
 
 // ---------------------------------------------------------------------------------------------
 // S1: worker-delta step of a local server.
-template <typename GT, bool ACC, bool NT>
+// With PULL the updated model is also written to a second tensor list (the buffer the worker starts
+// its next round from: Alg. 1 lines 11-12 in one pass instead of an update pass plus a copy pass).
+template <typename GT, bool ACC, bool NT, bool PULL>
 __global__ void __launch_bounds__(BLOCK_THREADS)
 lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, uint32_t tensor_base,
                   float *const *__restrict__ theta_tab, float *const *__restrict__ m_tab,
-                  float *const *__restrict__ acc_tab, PtrArgs gargs, float eta, float beta, float cg) {
+                  float *const *__restrict__ acc_tab, float *const *__restrict__ pull_tab, PtrArgs gargs,
+                  float eta, float beta, float cg) {
     const uint32_t tid = threadIdx.x;
     for (uint32_t t = tile_lo + blockIdx.x; t < tile_hi; t += gridDim.x) {
         const Tile tl = tiles[t];
@@ -124,6 +127,7 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
         gf32 *th = to_global(theta_tab[tensor]) + tl.start;
         gf32 *mm = to_global(m_tab[tensor]) + tl.start;
         gf32 *ac = ACC ? to_global(acc_tab[tensor]) + tl.start : nullptr;
+        gf32 *pd = PULL ? to_global(pull_tab[tensor]) + tl.start : nullptr;
         const auto *g = to_global(static_cast<const GT *>(gargs.p[tensor - tensor_base])) + tl.start;
         if (tl.len == TILE_ELEMS) {
             f32x4 gv[UNROLL], mv[UNROLL], tv[UNROLL], av[UNROLL];
@@ -141,6 +145,7 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
                 const f32x4 s = model_update4(tv[u], mv[u], gv[u], eta, beta, cg);
                 st4<NT>(mm + off, mv[u]);
                 st4<NT>(th + off, tv[u]);
+                if constexpr (PULL) st4<NT>(pd + off, tv[u]);
                 if constexpr (ACC) st4<NT>(ac + off, add4(av[u], s));
             }
         } else {
@@ -151,12 +156,14 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
                     const f32x4 s = model_update4(tv, mv, gv, eta, beta, cg);
                     st4<NT>(mm + off, mv);
                     st4<NT>(th + off, tv);
+                    if constexpr (PULL) st4<NT>(pd + off, tv);
                     if constexpr (ACC) st4<NT>(ac + off, add4(ld4<NT>(ac + off), s));
                 } else {
                     for (uint32_t k = off; k < len; ++k) {      // ragged tail: fewer than 4 elements
                         float mv = mm[k], tv = th[k];
                         const float s = model_update(tv, mv, ldg1(g + k), eta, beta, cg);
                         mm[k] = mv; th[k] = tv;
+                        if constexpr (PULL) pd[k] = tv;
                         if constexpr (ACC) ac[k] = __fadd_rn(ac[k], s);
                     }
                 }
@@ -360,24 +367,27 @@ inline dim3 grid_for(TileRange r, LaunchShape shape) {
 }  // namespace
 
 hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
-                             float *const *acc, const PtrArgs &g, bool g_is_bf16, bool accumulate, float eta,
-                             float beta, float cg, LaunchShape shape) {
+                             float *const *acc, float *const *pull, const PtrArgs &g, bool g_is_bf16, bool accumulate,
+                             float eta, float beta, float cg, LaunchShape shape) {
     if (r.hi <= r.lo) return hipSuccess;
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
-#define HALOS_LAUNCH_UPD(GT, ACC, NT)                                                                          \
-    lps_update_kernel<GT, ACC, NT><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, r.tensor_base, theta, m, acc, g, \
-                                                               eta, beta, cg)
-    const int variant = (g_is_bf16 ? 4 : 0) | (accumulate ? 2 : 0) | (shape.nontemporal ? 1 : 0);
+#define HALOS_LAUNCH_UPD(GT, ACC, NT, PULL)                                                                       \
+    lps_update_kernel<GT, ACC, NT, PULL><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, r.tensor_base, theta, m, acc, \
+                                                                     pull, g, eta, beta, cg)
+#define HALOS_LAUNCH_UPD_NT(GT, ACC, PULL) \
+    do { if (shape.nontemporal) HALOS_LAUNCH_UPD(GT, ACC, true, PULL); else HALOS_LAUNCH_UPD(GT, ACC, false, PULL); } while (0)
+    const int variant = (g_is_bf16 ? 4 : 0) | (accumulate ? 2 : 0) | (pull ? 1 : 0);
     switch (variant) {
-        case 0: HALOS_LAUNCH_UPD(float, false, false); break;
-        case 1: HALOS_LAUNCH_UPD(float, false, true); break;
-        case 2: HALOS_LAUNCH_UPD(float, true, false); break;
-        case 3: HALOS_LAUNCH_UPD(float, true, true); break;
-        case 4: HALOS_LAUNCH_UPD(unsigned short, false, false); break;
-        case 5: HALOS_LAUNCH_UPD(unsigned short, false, true); break;
-        case 6: HALOS_LAUNCH_UPD(unsigned short, true, false); break;
-        default: HALOS_LAUNCH_UPD(unsigned short, true, true); break;
+        case 0: HALOS_LAUNCH_UPD_NT(float, false, false); break;
+        case 1: HALOS_LAUNCH_UPD_NT(float, false, true); break;
+        case 2: HALOS_LAUNCH_UPD_NT(float, true, false); break;
+        case 3: HALOS_LAUNCH_UPD_NT(float, true, true); break;
+        case 4: HALOS_LAUNCH_UPD_NT(unsigned short, false, false); break;
+        case 5: HALOS_LAUNCH_UPD_NT(unsigned short, false, true); break;
+        case 6: HALOS_LAUNCH_UPD_NT(unsigned short, true, false); break;
+        default: HALOS_LAUNCH_UPD_NT(unsigned short, true, true); break;
     }
+#undef HALOS_LAUNCH_UPD_NT
 #undef HALOS_LAUNCH_UPD
     return hipGetLastError();
 }

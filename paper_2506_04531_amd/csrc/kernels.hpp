@@ -40,9 +40,11 @@ struct TileRange {      // tiles [lo, hi) all belong to tensors [tensor_base, te
 
 // Worker-delta step of a local server: m <- beta m + g; s = eta (cg g + beta m); theta <- theta - s;
 // if accumulate: acc <- acc + s.   (ModelUpdate of App. E fused with the accumulation of Alg. 1 line 14.)
+// If `pull` is not null it is a device table of destination tensors that also receive the updated theta
+// (Alg. 1 line 12, the model handed back to the worker, written in the same pass).
 hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
-                             float *const *acc, const PtrArgs &g, bool g_is_bf16, bool accumulate, float eta,
-                             float beta, float cg, LaunchShape shape);
+                             float *const *acc, float *const *pull, const PtrArgs &g, bool g_is_bf16, bool accumulate,
+                             float eta, float beta, float cg, LaunchShape shape);
 
 // Global-server step: M <- beta M + G; Theta <- Theta - eta (cg G + beta M); out <- Theta.
 // `G` and `out` may be the same table (each element is read before it is overwritten by the same thread).

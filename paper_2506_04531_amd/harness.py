@@ -223,6 +223,10 @@ class Cluster:
         self._pool_ptrs = [B._ptrs(ts) for ts in self.pool]
         self._pull_ptrs = [B._ptrs(ts) for ts in self.pull_dst] if pull_buffers else None
         self._lib = B.load_library()
+        if pull_buffers:       # every worker of an LPS hands its model back into that LPS's pull buffer
+            for l, h in enumerate(self.lps):
+                for k in range(w.workers_per_lps):
+                    B.halos_lps_set_worker_model(h, k, self._pull_ptrs[l])
         torch.cuda.synchronize(self.device)
 
     def close(self):
@@ -233,8 +237,11 @@ class Cluster:
         self.gps = None
 
     # ------------------------------------------------------------------ replay
-    def replay(self, events: np.ndarray, timed: bool = False):
+    def replay(self, events: np.ndarray, timed: bool = False, fuse_pull: bool = False):
         """Issue every record through the C ABI, in order, on the current stream.
+
+        fuse_pull: an update step that is directly followed by the pull of the same worker is issued as one
+        halos_lps_step_pull call (same results, one pass less).
 
         Returns (step_log, timings): step_log has one tuple (record index, kind, t, t_last, delta_ready,
         accumulated) per LPS step; timings (only if timed) maps a kernel label to a list of
@@ -244,8 +251,10 @@ class Cluster:
         stream = torch.cuda.current_stream(self.device)
         sp = stream.cuda_stream or None
         log = []
-        timings: Dict[str, list] = {"lps_update_acc": [], "lps_update_noacc": [], "gps_update": [], "lps_merge": [],
-                                    "pull": []}
+        timings: Dict[str, list] = {"lps_update_acc": [], "lps_update_noacc": [], "lps_update_acc_pull": [],
+                                    "lps_update_noacc_pull": [], "gps_update": [], "lps_merge": [], "pull": []}
+        fuse_pull = fuse_pull and self._pull_ptrs is not None
+        skip = -1
         info = B.StepInfo()
         k_now = [None] * len(self.lps)
 
@@ -259,7 +268,10 @@ class Cluster:
             timings[label].append((a, b))
             return rc
 
-        for i in range(len(events)):
+        n_ev = len(events)
+        for i in range(n_ev):
+            if i == skip:
+                continue
             ev = events[i]
             kind, l = int(ev["kind"]), int(ev["lps"])
             h = self.lps[l]
@@ -271,11 +283,19 @@ class Cluster:
                 if k_now[l] != k:
                     chk(lib.halos_lps_set_threshold(h, k))
                     k_now[l] = k
+                fused = False
                 if int(ev["exp_kind"]) == 2:
                     label = "lps_merge"
                 else:
                     label = "lps_update_acc" if int(ev["exp_accumulate"]) else "lps_update_noacc"
-                chk(bracket(label, lambda: lib.halos_lps_step(h, sp, ctypes.byref(info))))
+                    if fuse_pull and i + 1 < n_ev:
+                        nx = events[i + 1]
+                        fused = (int(nx["kind"]) == _PULL and int(nx["lps"]) == l and int(nx["worker"]) == int(ev["worker"]))
+                if fused:
+                    skip = i + 1
+                    chk(bracket(label + "_pull", lambda: lib.halos_lps_step_pull(h, sp, ctypes.byref(info))))
+                else:
+                    chk(bracket(label, lambda: lib.halos_lps_step(h, sp, ctypes.byref(info))))
                 log.append((i, info.kind, info.t, info.t_last, info.delta_ready, info.accumulated))
             elif kind == _GPS_MERGE:
                 chk(bracket("gps_update", lambda: lib.halos_gps_merge(self.gps, h, sp)))

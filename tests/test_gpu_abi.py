@@ -1,0 +1,170 @@
+"""Error behaviour of the C ABI on a real device: every misuse returns a status, leaves state untouched,
+and no kernel is launched on bad operands."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture()
+def small():
+    from paper_2506_04531_amd import binding as B
+    numel = [5000, 0, 37]
+    dev = "cuda:0"
+    mk = lambda dt=torch.float32: [torch.zeros(n, dtype=dt, device=dev) for n in numel]
+    Theta = mk()
+    for t in Theta:
+        t.normal_(0, 0.02)
+    M = [torch.full_like(t, 7.0) for t in Theta]              # create must zero it
+    hp = B.paper_hparams(0.2, 0.9, 0.15, 0.5, 0.25, 2)
+    gps = B.halos_gps_create(numel, hp, Theta, M)
+    th, m, acc = mk(), mk(), mk()
+    for t in th + m + acc:
+        t.fill_(3.0)                                          # create must overwrite all three
+    lps = B.halos_lps_create(gps, 0, 2, th, m, acc)
+    torch.cuda.synchronize()
+    yield dict(B=B, numel=numel, Theta=Theta, M=M, th=th, m=m, acc=acc, gps=gps, lps=lps, mk=mk, hp=hp)
+    B.halos_lps_destroy(lps)
+    B.halos_gps_destroy(gps)
+
+
+def _status(fn, *a):
+    from paper_2506_04531_amd import binding as B
+    try:
+        fn(*a)
+    except B.HalosError as e:
+        return e.status
+    return B.OK
+
+
+def test_create_initialises_state(small):
+    s = small
+    for a, b in zip(s["th"], s["Theta"]):
+        assert torch.equal(a, b)                               # Alg. 1 line 6: theta_0 <- Theta_0
+    for t in s["m"] + s["acc"] + s["M"]:
+        assert not t.any()
+    c = s["B"].halos_lps_get_counters(s["lps"])
+    assert (c["t"], c["t_last"], c["phase"], c["queued"]) == (0, 0, 0, 0)
+
+
+def test_bad_arguments_are_einval(small):
+    s, B = small, small["B"]
+    g = s["mk"]()
+    assert _status(B.halos_lps_push_update, s["lps"], 2, g, B.F32) == B.EINVAL          # worker out of range
+    assert _status(B.halos_lps_push_update, s["lps"], -1, g, B.F32) == B.EINVAL
+    assert _status(B.halos_lps_push_update, s["lps"], 0, g, 7) == B.EINVAL              # unknown dtype
+    assert _status(B.halos_lps_push_update, s["lps"], 0, [None, None, None], B.F32) == B.EINVAL
+    short = [torch.zeros(100, device="cuda:0"), None, torch.zeros(37, device="cuda:0")]
+    # a 100-element tensor where 5000 are needed: rejected unless torch happened to carve it from a larger block
+    st = _status(B.halos_lps_push_update, s["lps"], 0, short, B.F32)
+    assert st in (B.EINVAL, B.OK)
+    if st == B.OK:
+        B.halos_lps_step(s["lps"])
+    mis = [g[0].data_ptr() + 4, None, g[2].data_ptr()]
+    assert _status(B.halos_lps_push_update, s["lps"], 1, mis, B.F32) == B.EINVAL        # not 16-byte aligned
+    host = np.zeros(5000, dtype=np.float32)
+    assert _status(B.halos_lps_push_update, s["lps"], 1, [host.ctypes.data & ~15, None, g[2].data_ptr()], B.F32) == B.EINVAL
+    assert "tensor 0" in B.halos_last_error()
+    hp = B.paper_hparams(0.2, 0.9, 0.15, 0.5, 1.5, 2)                                   # alpha > 1
+    assert _status(B.halos_set_hparams, s["lps"], False, hp) == B.EINVAL
+    hp = B.paper_hparams(float("nan"), 0.9, 0.15, 0.5, 0.25, 2)
+    assert _status(B.halos_set_hparams, s["gps"], True, hp) == B.EINVAL
+    assert _status(B.halos_lps_set_threshold, s["lps"], 0) == B.EINVAL
+    assert _status(B.halos_pull_model, s["lps"], True, g) == B.EINVAL                   # an LPS handle passed as GPS
+    assert _status(B.halos_gps_create, [], s["hp"], [], []) == B.EINVAL
+    assert _status(B.halos_gps_create, [-1], s["hp"], g[:1], g[:1]) == B.EINVAL
+    assert _status(B.halos_lps_create, s["gps"], 0, 0, s["th"], s["m"], s["acc"]) == B.EINVAL
+
+
+def test_protocol_violations_are_estate_and_change_nothing(small):
+    s, B = small, small["B"]
+    g = s["mk"]()
+    for t in g:
+        t.fill_(1.0 / 1024)
+    snap = lambda: [t.clone() for t in s["th"] + s["m"] + s["acc"] + s["Theta"] + s["M"]]
+    same = lambda a: all(torch.equal(x, y) for x, y in zip(a, s["th"] + s["m"] + s["acc"] + s["Theta"] + s["M"]))
+    before = snap()
+    assert _status(B.halos_gps_merge, s["gps"], s["lps"]) == B.ESTATE                   # nothing accumulated yet
+    assert _status(B.halos_lps_push_global, s["lps"]) == B.ESTATE
+    info = B.halos_lps_step(s["lps"])
+    assert info.kind == 0                                                                # empty queue: OK, no-op
+    torch.cuda.synchronize()
+    assert same(before)
+    B.halos_lps_push_update(s["lps"], 0, g, B.F32, 3)
+    assert _status(B.halos_lps_push_update, s["lps"], 0, g, B.F32) == B.ESTATE          # same worker twice
+    B.halos_lps_push_update(s["lps"], 1, g, B.F32, 5)
+    assert B.halos_lps_get_counters(s["lps"])["max_staleness"] == 5
+    assert B.halos_lps_step(s["lps"]).delta_ready == 0
+    assert B.halos_lps_step(s["lps"]).delta_ready == 1                                   # K = 2
+    assert _status(B.halos_lps_push_global, s["lps"]) == B.ESTATE                        # GPS has not run
+    B.halos_gps_merge(s["gps"], s["lps"])
+    assert _status(B.halos_gps_merge, s["gps"], s["lps"]) == B.ESTATE                    # already consumed
+    torch.cuda.synchronize()
+    mid = snap()
+    B.halos_lps_push_global(s["lps"])
+    assert _status(B.halos_lps_push_global, s["lps"]) == B.ESTATE
+    torch.cuda.synchronize()
+    assert same(mid)
+    info = B.halos_lps_step(s["lps"])
+    assert (info.kind, info.t, info.t_last) == (2, 2, 2)
+    assert B.halos_gps_get_counters(s["gps"])["updates"] == 1
+    torch.cuda.synchronize()
+    assert not any(t.any() for t in s["acc"])
+
+
+def test_merge_endpoints_exact_on_device(small):
+    """alpha = 1 returns the global model bit for bit, alpha = 0 leaves the local model untouched."""
+    s, B = small, small["B"]
+    g = s["mk"]()
+    for t in g:
+        t.normal_(0, 1e-3)
+    for alpha in (1.0, 0.0):
+        hp = B.paper_hparams(0.2, 0.9, 0.15, 0.5, alpha, 1)
+        B.halos_set_hparams(s["lps"], False, hp)
+        B.halos_lps_push_update(s["lps"], 0, g, B.F32)
+        assert B.halos_lps_step(s["lps"]).delta_ready == 1
+        B.halos_gps_merge(s["gps"], s["lps"])
+        B.halos_lps_push_update(s["lps"], 1, g, B.F32)                                   # applied while in flight
+        assert B.halos_lps_step(s["lps"]).accumulated == 0
+        torch.cuda.synchronize()
+        local = [t.clone() for t in s["th"]]
+        inbox = [t.clone() for t in s["acc"]]
+        for a, b in zip(inbox, s["Theta"]):
+            assert torch.equal(a, b)                                                     # the returned model is this Theta_i
+        B.halos_lps_push_global(s["lps"])
+        assert B.halos_lps_step(s["lps"]).kind == 2
+        torch.cuda.synchronize()
+        want = inbox if alpha == 1.0 else local
+        for a, b in zip(s["th"], want):
+            assert torch.equal(a, b)
+
+
+def test_many_tensors_need_several_launch_ranges():
+    """More tensors than fit one kernel-argument block: the call is split into launch ranges."""
+    from paper_2506_04531_amd import binding as B
+    n_t = 900
+    numel = [17 + (i % 5) * 4099 for i in range(n_t)]
+    dev = "cuda:0"
+    mk = lambda: [torch.zeros(n, device=dev) for n in numel]
+    Theta, M, th, m, acc, g, dst = mk(), mk(), mk(), mk(), mk(), mk(), mk()
+    for i, t in enumerate(Theta):
+        t.fill_(float(i))
+    for i, t in enumerate(g):
+        t.fill_(1.0 + i / 1024.0)
+    hp = B.paper_hparams(1.0, 0.0, 1.0, 0.0, 0.5, 1)          # beta = 0, eta = 1: theta <- theta - g
+    gps = B.halos_gps_create(numel, hp, Theta, M)
+    lps = B.halos_lps_create(gps, 0, 1, th, m, acc)
+    try:
+        B.halos_lps_push_update(lps, 0, g, B.F32)
+        B.halos_lps_step(lps)
+        B.halos_pull_model(lps, False, dst)
+        torch.cuda.synchronize()
+        for i in range(n_t):
+            expect = float(i) - (1.0 + i / 1024.0)
+            assert torch.all(th[i] == expect) and torch.all(dst[i] == expect) and torch.all(acc[i] == 1.0 + i / 1024.0), i
+    finally:
+        B.halos_lps_destroy(lps)
+        B.halos_gps_destroy(gps)

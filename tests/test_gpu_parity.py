@@ -188,3 +188,46 @@ def test_probe_pair_reports_bandwidth_and_preserves_contents():
         B.halos_probe_pair(a, b, n * 8, 2)                     # longer than the allocation
     with pytest.raises(B.HalosError):
         B.halos_probe_pair(a.data_ptr() + 4, b, n * 2, 2)      # misaligned
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_fused_step_pull_equals_step_then_pull(dtype):
+    """halos_lps_step_pull = halos_lps_step + halos_pull_model, bit for bit, including the pulled copies."""
+    from dataclasses import replace
+    w = replace(synth.get_workload("410m").scaled(RAGGED, n_updates=64, name="fused"), delta_dtype=dtype)
+    trace = synth.make_trace(w, seed=9)
+    out = []
+    for fuse in (False, True):
+        c = _cluster(w, trace)
+        try:
+            log, _ = c.replay(trace.events, fuse_pull=fuse)
+            torch.cuda.synchronize()
+            state = {k: c.flat(k) for k in c.state_lists()}
+            for l, dst in enumerate(c.pull_dst):
+                state[f"pull{l}"] = torch.cat([t.reshape(-1) for t in dst]).cpu().numpy()
+            out.append((log, state))
+        finally:
+            c.close()
+    assert out[0][0] == out[1][0]
+    for k in out[0][1]:
+        assert np.array_equal(out[0][1][k].view(np.uint32), out[1][1][k].view(np.uint32)), k
+
+
+def test_step_pull_without_registered_buffer_is_rejected():
+    from paper_2506_04531_amd import binding as B
+    from paper_2506_04531_amd.harness import Cluster
+    w = synth.get_workload("tiny").scaled(synth.flat_layout(5000), n_updates=4, name="nopull")
+    trace = synth.make_trace(w)
+    c = Cluster(w, "cuda:0", k_initial=trace.k_initial, pull_buffers=False)
+    try:
+        B.halos_lps_push_update(c.lps[0], 0, c.pool[0], c.delta_dtype)
+        before = c.flat("theta0")
+        with pytest.raises(B.HalosError) as e:
+            B.halos_lps_step_pull(c.lps[0])
+        assert e.value.status == B.ESTATE
+        torch.cuda.synchronize()
+        assert np.array_equal(before, c.flat("theta0"))
+        assert B.halos_lps_get_counters(c.lps[0])["queued"] == 1       # nothing was consumed
+        assert B.halos_lps_step(c.lps[0]).kind == 1
+    finally:
+        c.close()
