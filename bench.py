@@ -42,7 +42,12 @@ BYTES = {
 
 # HBM traffic per parameter per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), valid
 # only for the kernel source it was measured on: {sha256 of kernels.hip: {kernel label: bytes/param}}.
-MEASURED_TRAFFIC: dict = {}
+MEASURED_TRAFFIC: dict = {
+    # profiles/lps_update_1b_hbm_traffic.md
+    "04f3ec6ce4de6d2851405687e3d4f19a9f16d4a4835446b56e1be1d70e4877cf": {
+        "1b:lps_update_acc_pull": 30.034, "1b:lps_update_noacc_pull": 22.035,
+    },
+}
 
 
 def kernels_digest() -> str:
