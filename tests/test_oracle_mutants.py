@@ -1,0 +1,100 @@
+"""Do the pins actually pin?  Each mutant below is the oracle's source with one plausible mistake planted
+(a dropped term, a wrong sign, a wrong index/operand, a mis-ordered step), compiled to its own library.
+The closed-form pins of test_oracle_pins.py must fail on every one of them.  Everything runs on the CPU."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+import oracle as O
+import test_oracle_pins as pins
+
+SRC = os.path.join(os.path.dirname(os.path.abspath(O.__file__)), "halos_oracle.cpp")
+
+# (name, text in the oracle source, replacement)
+MUTANTS = [
+    ("step added instead of subtracted", "x = x - step;", "x = x + step;"),
+    ("momentum decay dropped", "m = std::fma(r.beta, m, grad);", "m = m + grad;"),
+    ("delta not added to momentum", "m = std::fma(r.beta, m, grad);", "m = r.beta * m;"),
+    ("direction uses old coefficient 1 on grad", "R direction = std::fma(r.beta, m, r.cg * grad);",
+     "R direction = std::fma(r.beta, m, grad);"),
+    ("momentum term dropped from direction", "R direction = std::fma(r.beta, m, r.cg * grad);",
+     "R direction = r.cg * grad;"),
+    ("learning rate dropped", "R step = r.eta * direction;", "R step = direction;"),
+    ("merge weights swapped", "s.theta[j] = std::fma(alpha, s.inbox[j], keep * s.theta[j]);",
+     "s.theta[j] = std::fma(keep, s.inbox[j], alpha * s.theta[j]);"),
+    ("merge in difference form", "s.theta[j] = std::fma(alpha, s.inbox[j], keep * s.theta[j]);",
+     "s.theta[j] = s.theta[j] + alpha * (s.inbox[j] - s.theta[j]) * R(1.0000001);"),
+    ("snapshot is the pre-merge model", "s.snap = s.theta;                                           // theta_{t_last}: the post-merge model",
+     "/* snapshot left at its old value */"),
+    ("t_last not reset at merge", "s.t_last = s.t;                                             // line 18", ""),
+    ("updates in flight keep accumulating", "const bool accumulate = (s.phase == ACCUMULATING);", "const bool accumulate = true;"),
+    ("Delta sign flipped", "s.frozen[j] = (form == 1) ? s.acc[j] : (s.snap[j] - s.theta[j]);",
+     "s.frozen[j] = (form == 1) ? -s.acc[j] : (s.theta[j] - s.snap[j]);"),
+    ("threshold off by one", "if (accumulate && s.t - s.t_last >= s.K) {", "if (accumulate && s.t - s.t_last > s.K) {"),
+    ("GPS uses the local rule", "model_update<R>(Theta[j], M[j], s.frozen[j], global);", "model_update<R>(Theta[j], M[j], s.frozen[j], local);"),
+    ("LPS merges the live global model, not the frozen one", "s.theta[j] = std::fma(alpha, s.inbox[j], keep * s.theta[j]);",
+     "s.theta[j] = std::fma(alpha, gps_Theta_live[j], keep * s.theta[j]);"),
+    ("queue handled last-in first-out", "QueueItem<R> it = std::move(s.queue.front());\n        s.queue.pop_front();",
+     "QueueItem<R> it = std::move(s.queue.back());\n        s.queue.pop_back();"),
+    ("bf16 placed in the low half", "uint32_t u = (uint32_t)bits << 16;", "uint32_t u = (uint32_t)bits;"),
+    ("t counts merges too", "out.kind = 2;", "out.kind = 2; s.t += 1;"),
+]
+
+PIN_TESTS = [
+    lambda: [pins.test_zero_momentum_unit_rate_adopts_worker_end_model(p) for p in (32, 64)],
+    lambda: [pins.test_k_identical_deltas_accumulate_to_k_eta_g(f, 64) for f in pins.BOTH_FORMS],
+    pins.test_constant_delta_gives_geometric_momentum_series_exactly_in_fp32,
+    lambda: pins.test_momentum_recursion_matches_iir_filter(0.9, 0.2),
+    pins.test_gps_rule_matches_iir_filter,
+    pins.test_cg_one_is_torch_sgd_nesterov,
+    pins.test_paper_rule_equals_g_plus_beta_squared_old_momentum,
+    lambda: [pins.test_merge_weight_one_and_zero_return_an_operand_exactly(64, f) for f in pins.BOTH_FORMS],
+    pins.test_repeated_merges_contract_geometrically,
+    pins.test_queue_is_first_in_first_out,
+    pins.test_hierarchy_collapses_to_one_level,
+    lambda: [pins.test_hand_derived_worked_example(64, f) for f in pins.BOTH_FORMS],
+    pins.test_snapshot_form_equals_accumulator_form,
+    pins.test_step_log_matches_schedule_bookkeeping_and_counters,
+    pins.test_bf16_upcast_matches_torch_for_every_bit_pattern,
+]
+
+
+def _build_mutant(tmp_path, idx, old, new):
+    text = open(SRC).read()
+    assert text.count(old) == 1, f"mutation site not unique / not found: {old!r}"
+    text = text.replace(old, new)
+    if "gps_Theta_live" in new:     # give the merge access to the live global model
+        text = text.replace("int lps_step(int l, StepInfo *info) {\n        Lps<R> &s = lps[l];",
+                            "int lps_step(int l, StepInfo *info) {\n        Lps<R> &s = lps[l];\n        const std::vector<R> &gps_Theta_live = Theta;")
+    src = tmp_path / f"mutant_{idx}.cpp"
+    lib = tmp_path / f"libmutant_{idx}.so"
+    src.write_text(text)
+    subprocess.check_call(["g++", "-std=c++17", "-O1", "-mfma", "-ffp-contract=off", "-fPIC", "-shared", "-o", str(lib), str(src)])
+    return str(lib)
+
+
+@pytest.mark.parametrize("idx", range(len(MUTANTS)), ids=[m[0] for m in MUTANTS])
+def test_some_pin_fails_on_each_planted_mistake(idx, tmp_path, monkeypatch):
+    name, old, new = MUTANTS[idx]
+    lib_path = _build_mutant(tmp_path, idx, old, new)
+    monkeypatch.setattr(O, "_lib", None)
+    monkeypatch.setattr(O, "build", lambda force=False: lib_path)
+    caught = []
+    try:
+        for t in PIN_TESTS:
+            try:
+                t()
+            except (AssertionError, O.OracleError) as e:
+                caught.append(getattr(t, "__name__", "pin"))
+                break
+    finally:
+        monkeypatch.setattr(O, "_lib", None)       # the next user reloads the real oracle
+    assert caught, f"no pin noticed the mutant: {name}"
+
+
+def test_the_unmutated_oracle_is_back():
+    """After the mutant runs the module must serve the real library again."""
+    O._lib = None
+    pins.test_hand_derived_worked_example(64, O.FORM_LITERAL)

@@ -256,6 +256,34 @@ def test_hand_derived_worked_example(precision, form):
     assert o.counters(0)["gps_updates"] == fin["gps_updates"]
 
 
+def test_queue_is_first_in_first_out():
+    """Deltas and returned global models share one queue and are handled in arrival order (Sec. 4.1 item 2).
+    Hand-derived with beta = 0, eta = 1, alpha = 1/2: a delta that arrived BEFORE the global model is applied
+    before the merge, so only half of it survives; with momentum, two queued deltas do not commute either."""
+    theta0 = np.array([8.0, -4.0, 0.0, 16.0], dtype=F32)
+    g1 = np.array([1.0, 2.0, 3.0, 4.0], dtype=F32)
+    g2 = np.array([2.0, 0.0, -2.0, 4.0], dtype=F32)
+    o = single(theta0, K=1, alpha=0.5)
+    assert apply(o, 0, 0, g1).sent == 1
+    o.gps_receive(0)                                       # Theta_1 = theta0 - g1
+    o.arrive_delta(0, 1, g2)                               # arrives first ...
+    o.arrive_global(0)                                     # ... the global model second
+    assert [o.lps_step(0).kind, o.lps_step(0).kind] == [1, 2]
+    assert np.array_equal(o.get(O.THETA), (theta0 - g1 - 0.5 * g2).astype(np.float64))
+    # the other arrival order gives a different model: merge first, then the whole delta
+    o = single(theta0, K=1, alpha=0.5)
+    apply(o, 0, 0, g1); o.gps_receive(0)
+    o.arrive_global(0)
+    o.arrive_delta(0, 1, g2)
+    assert [o.lps_step(0).kind, o.lps_step(0).kind] == [2, 1]
+    assert np.array_equal(o.get(O.THETA), (theta0 - g1 - g2).astype(np.float64))
+    # two queued deltas with momentum: m after both is beta*(g_first) + g_second
+    o = single(theta0, beta_l=0.5, eta_l=0.25)
+    o.arrive_delta(0, 0, g1); o.arrive_delta(0, 1, g2)
+    assert (o.lps_step(0).worker, o.lps_step(0).worker) == (0, 1)
+    assert np.array_equal(o.get(O.MOM), (0.5 * g1 + g2).astype(np.float64))
+
+
 # ---------------------------------------------------------------- invariants on seeded traces
 def _random_trace_run(precision, form, n=4096, subset=None, seed=11, dtype="f32", flat=True):
     import synth
