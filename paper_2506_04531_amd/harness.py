@@ -179,8 +179,8 @@ class Cluster:
                  k_initial: Optional[Sequence[int]] = None, pull_buffers: bool = True, placement: str = "plain",
                  verbose: bool = False):
         """placement "plain": every tensor is its own torch allocation (or one arena per list if arena=True).
-        placement "regions": models (Theta, theta_l) / momenta (M, m_l) / third buffers (acc_l) are placed in
-        three different HBM regions through a RegionArena, so that every kernel's written streams are spread."""
+        placement "regions": models and momenta / third buffers / worker model buffers are placed in three
+        different HBM regions through a RegionArena (see the comment below for the measured reason)."""
         self.w = w
         self.device = torch.device(device)
         lay = w.layout
@@ -190,22 +190,33 @@ class Cluster:
         f32 = torch.float32
         self.region_arena = None
         if placement == "regions":
+            # Measured on MI355X (all 243 assignments of g, m, theta, acc, worker model to three regions): the
+            # update pass is fastest when two of its read-modify-write arrays and the delta share one region, the
+            # third read-modify-write array sits in a second region and the worker's model copy in a third
+            # (6.4 TB/s against 6.1 TB/s for an even spread and 5.0 TB/s for everything in one region).
+            #   class 0: models and momenta (Theta, M, theta_l, m_l) and, if it still fits, the delta pool
+            #   class 1: third buffers acc_l (and the delta pool otherwise)
+            #   class 2: worker model buffers (pull destinations)
             ddt_size = 2 if w.delta_dtype == "bf16" else 4
             S = sum((n * 4 + 255) // 256 * 256 for n in self.numel)
             L = w.n_lps
-            need = [(L + 1) * S, (L + 1) * S + (L * S if pull_buffers else 0), L * S + w.pool_slots * S * ddt_size // 4]
+            pool_bytes = w.pool_slots * S * ddt_size // 4
+            self._pool_cls = 0 if (2 * L + 2) * S + pool_bytes <= (72 << 30) else 1
+            need = [(2 * L + 2) * S, L * S, L * S if pull_buffers else 0]
+            need[self._pool_cls] += pool_bytes
             self.region_arena = RegionArena(self.device, need, verbose=verbose)
             ra = self.region_arena
-            mk = lambda dt=f32, cls=2: ra.alloc_list(cls, self.numel, dt)
+            mk = lambda dt=f32, cls=0: ra.alloc_list(cls, self.numel, dt)
         else:
+            self._pool_cls = 0
             mk = lambda dt=f32, cls=0: alloc_tensor_list(self.numel, dt, self.device, arena)
-        self.Theta, self.M = mk(cls=0), mk(cls=1)
+        self.Theta, self.M = mk(cls=0), mk(cls=0)
         fill_initial_model(w, self.Theta)
         self.hp = hp if hp is not None else B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0])
         self.gps = B.halos_gps_create(self.numel, self.hp, self.Theta, self.M)
         self.theta, self.m, self.acc, self.lps = [], [], [], []
         for l in range(w.n_lps):
-            th, m, acc = mk(cls=0), mk(cls=1), mk(cls=2)
+            th, m, acc = mk(cls=0), mk(cls=0), mk(cls=1)
             self.theta.append(th); self.m.append(m); self.acc.append(acc)
             h = B.halos_lps_create(self.gps, l, w.workers_per_lps, th, m, acc)
             if k_initial is not None:
@@ -215,10 +226,10 @@ class Cluster:
         ddt = torch.bfloat16 if w.delta_dtype == "bf16" else f32
         self.pool = []
         for s in range(w.pool_slots):
-            ts = mk(ddt, cls=2)
+            ts = mk(ddt, cls=self._pool_cls)
             fill_delta_slot(w, s, ts)
             self.pool.append(ts)
-        self.pull_dst = [mk(cls=1) for _ in range(w.n_lps)] if pull_buffers else None
+        self.pull_dst = [mk(cls=2) for _ in range(w.n_lps)] if pull_buffers else None
         # pointer arrays marshalled once: the replay loop then costs a few ctypes calls per event
         self._pool_ptrs = [B._ptrs(ts) for ts in self.pool]
         self._pull_ptrs = [B._ptrs(ts) for ts in self.pull_dst] if pull_buffers else None
