@@ -9,10 +9,23 @@ are allowed to share.
 from .layouts import Layout, gpt_layout, flat_layout
 from .configs import Workload, WORKLOADS, get_workload, delta_scales
 from .tensors import normal_at, normal_flat, to_bf16_bits
-from .schedule import Trace, make_trace, EV_ARRIVE_DELTA, EV_ARRIVE_GLOBAL, EV_LPS_STEP, EV_GPS_MERGE, EV_PULL
+from .schedule import Trace, EV_ARRIVE_DELTA, EV_ARRIVE_GLOBAL, EV_LPS_STEP, EV_GPS_MERGE, EV_PULL
+from .schedule import make_trace as make_seeded_trace
+from .paper_cluster import PaperClusterSpec, make_paper_trace
+
+
+def make_trace(w: Workload, seed=None, with_pulls: bool = True) -> Trace:
+    """The event schedule of a workload: the seeded simulator, or the paper's cluster model if the workload asks for it."""
+    if w.schedule == "paper":
+        spec = PaperClusterSpec(model=w.paper_model, n_params=w.layout.total, K=w.k_range[0], pool_slots=w.pool_slots,
+                                seed=w.seed if seed is None else seed)
+        return make_paper_trace(spec, w.n_updates, with_pulls)
+    return make_seeded_trace(w, seed, with_pulls)
+
 
 __all__ = [
     "Layout", "gpt_layout", "flat_layout", "Workload", "WORKLOADS", "get_workload", "delta_scales",
-    "normal_at", "normal_flat", "to_bf16_bits", "Trace", "make_trace",
+    "normal_at", "normal_flat", "to_bf16_bits", "Trace", "make_trace", "make_seeded_trace", "make_paper_trace",
+    "PaperClusterSpec",
     "EV_ARRIVE_DELTA", "EV_ARRIVE_GLOBAL", "EV_LPS_STEP", "EV_GPS_MERGE", "EV_PULL",
 ]

@@ -38,6 +38,8 @@ class Workload:
     alpha: float = 0.25
     seed: int = 0
     pool_slots: int = 8            # number of distinct resident delta buffers
+    schedule: str = "seeded"       # "seeded": synth.schedule; "paper": the paper's own cluster model (synth.paper_cluster)
+    paper_model: str = ""          # key of the profiled-step-time table when schedule == "paper"
 
     def scaled(self, layout: Layout, n_updates: int | None = None, name: str | None = None) -> "Workload":
         """Same cluster / schedule recipe on another (usually smaller) layout."""
@@ -85,6 +87,15 @@ def _mk() -> Dict[str, Workload]:
         description="1B-param GPT tensor list (d2048, L16, ff8192); 8 LPS x 4 workers; 256 updates; bf16 deltas",
         layout=gpt_layout(2048, 16, d_ff=8192), n_lps=8, workers_per_lps=4, n_updates=256,
         delta_dtype="bf16", k_range=(8, 8), max_link_delay=4, seed=1005)
+    # The paper's evaluation cluster (App. A): 4 regions x 4 workers, one LPS per region, K = 32, fp32 messages,
+    # arrival order from its bandwidth, worker-speed and profiled-step-time tables.
+    for key, lay in (("70m", gpt_layout(512, 6)), ("160m", gpt_layout(768, 12)), ("410m", gpt_layout(1024, 24))):
+        w["paper-" + key] = Workload(
+            name="paper-" + key,
+            description=f"Pythia-{key.upper()}-shaped tensor list on the paper's 4-region x 4-worker cluster "
+                        f"(its bandwidth / speed / step-time tables), K=32, 512 updates, fp32 deltas",
+            layout=lay, n_lps=4, workers_per_lps=4, n_updates=512, delta_dtype="f32", k_range=(32, 32),
+            staleness_bound=64, seed=2000 + len(w), schedule="paper", paper_model=key)
     return w
 
 

@@ -59,7 +59,7 @@ def test_ragged_tensor_list_every_element(dtype, arena):
     _full_parity(w, synth.make_trace(w, seed=77), arena=arena)
 
 
-@pytest.mark.parametrize("recipe", ["70m", "160m", "410m", "1b"])
+@pytest.mark.parametrize("recipe", ["70m", "160m", "410m", "1b", "paper-70m"])
 def test_scaled_down_workloads_every_element(recipe):
     """The cluster shape, delta dtype, rates and threshold rule of each benchmark workload on a
     GPT tensor list small enough for the oracle to replay in full."""
@@ -69,7 +69,7 @@ def test_scaled_down_workloads_every_element(recipe):
     _full_parity(w, synth.make_trace(w))
 
 
-@pytest.mark.parametrize("name", ["70m", "160m", "410m", "1b"])
+@pytest.mark.parametrize("name", ["70m", "160m", "410m", "1b", "paper-410m"])
 def test_full_size_workloads_on_sampled_elements(name):
     """Full benchmark sizes in the benchmark's launch configuration.  Every step is elementwise, so the
     oracle replays exactly the sampled elements (random ones plus every tensor and tile boundary)."""

@@ -57,7 +57,7 @@ def test_threshold_and_single_update_in_flight(shim):
     shim.proto_free(p)
 
 
-@pytest.mark.parametrize("name", ["tiny", "70m", "160m", "410m", "1b"])
+@pytest.mark.parametrize("name", ["tiny", "70m", "160m", "410m", "1b", "paper-70m", "paper-410m"])
 def test_protocol_follows_the_schedule_bookkeeping(shim, name):
     """Replaying a benchmark trace through the state machine reproduces the generator's expectations."""
     w = synth.get_workload(name)

