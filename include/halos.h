@@ -80,8 +80,15 @@ typedef struct {
     halos_rule global;   /* eta_g, beta_g: used by the GPS                         */
     float alpha;         /* merge weight of the global model, 0 <= alpha <= 1      */
     int32_t K;           /* local updates accumulated before a Delta is sent, >= 1 */
-    uint32_t flags;      /* reserved, must be 0                                    */
+    uint32_t flags;      /* 0 or HALOS_FLAG_NORMS; other bits must be 0            */
 } halos_hparams;
+
+/* Monitor the two quantities that the convergence analysis bounds (Sec. 4.2, assumptions "bounded gradients"
+ * and "bounded staleness"): the squared norm of every applied worker delta and the squared distance between
+ * the local model and the global model it is about to merge.  Computed inside the update and merge passes
+ * (wavefront reductions, per-workgroup partial sums, one small reduction kernel); they never feed back into
+ * the state.  Honoured at halos_gps_create; every LPS of that GPS then owns a small scratch buffer. */
+#define HALOS_FLAG_NORMS 1u
 
 /* What one halos_lps_step did. */
 typedef struct {
@@ -210,6 +217,14 @@ halos_status halos_lps_set_threshold(halos_lps *lps, int32_t K);
  */
 halos_status halos_lps_get_counters(const halos_lps *lps, int64_t *t, int64_t *t_last, int32_t *phase,
                                     int32_t *queued, uint32_t *max_staleness);
+
+/*
+ * Read the monitors of an LPS created under HALOS_FLAG_NORMS: out[0] = sum of g^2 over all parameters for the
+ * most recent worker update, out[1] = sum of (theta - Theta_i)^2 just before the most recent merge (0 until the
+ * first one).  `out` is a host array of two doubles.  The call waits for `stream`.
+ * ESTATE if the flag was not set when the GPS was created.
+ */
+halos_status halos_lps_get_norms(const halos_lps *lps, void *stream, double *out);
 
 /* Number of accumulated updates the GPS has applied (the index i of Algorithm 1's GPS loop). */
 halos_status halos_gps_get_counters(const halos_gps *gps, int64_t *updates);

@@ -57,6 +57,7 @@ def _load():
         lib.ho_set_rules.argtypes = [vp, f32, f32, f32, f32, f32, f32, f32]
         lib.ho_get.argtypes = [vp, i32, i32, vp]
         lib.ho_counters.argtypes = [vp, i32] + [vp] * 5
+        lib.ho_norms.argtypes = [vp, i32, vp]
         lib.ho_bf16_to_f32.restype = f32
         lib.ho_bf16_to_f32.argtypes = [ctypes.c_uint16]
         _lib = lib
@@ -140,6 +141,12 @@ class HalosOracle:
         out = np.empty(self.n, dtype=np.float64)
         self._chk(self._lib.ho_get(self._h, what, l, out.ctypes.data), "get")
         return out
+
+    def norms(self, l: int):
+        """(sum of g^2 of the last applied delta, sum of (theta - Theta_i)^2 before the last merge), fp64."""
+        out = (ctypes.c_double * 2)()
+        self._lib.ho_norms(self._h, l, out)
+        return float(out[0]), float(out[1])
 
     def counters(self, l: int):
         t, tl, gu = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()

@@ -130,6 +130,9 @@ struct Lps {
     int64_t t = 0, t_last = 0;
     int32_t K = 1;
     int phase = ACCUMULATING;
+    // monitors (Sec. 4.2, assumptions 4 and 5): squared norm of the last applied delta, squared distance between
+    // the local model and the global model at the last merge (before merging).  Plain fp64 sums.
+    double last_delta_sq = 0.0, last_merge_dist_sq = 0.0;
 };
 
 template <class R>
@@ -204,6 +207,8 @@ struct Oracle {
         if (it.kind == ITEM_DELTA) {
             s.t += 1;                                                   // line 10
             const bool accumulate = (s.phase == ACCUMULATING);
+            s.last_delta_sq = 0.0;
+            for (int64_t j = 0; j < n; ++j) s.last_delta_sq += (double)it.grad[j] * (double)it.grad[j];
             for (int64_t j = 0; j < n; ++j) {                           // line 11
                 const R grad = R(it.grad[j]);
                 R step = model_update<R>(s.theta[j], s.m[j], grad, local);
@@ -230,6 +235,11 @@ struct Oracle {
             if (s.phase != QUEUED) return -3;
             s.t_last = s.t;                                             // line 18
             const R keep = R(1) - alpha;
+            s.last_merge_dist_sq = 0.0;
+            for (int64_t j = 0; j < n; ++j) {
+                const double d = (double)s.theta[j] - (double)s.inbox[j];
+                s.last_merge_dist_sq += d * d;
+            }
             for (int64_t j = 0; j < n; ++j) {                           // line 19
                 raise_to(s.sc_theta[j], s.sc_aux[j]);                   // scale of the merged global model
                 s.theta[j] = std::fma(alpha, s.inbox[j], keep * s.theta[j]);
@@ -397,6 +407,13 @@ int ho_counters(void *p, int32_t l, int64_t *t, int64_t *t_last, int32_t *phase,
         auto &s = h->d->lps[l]; *t = s.t; *t_last = s.t_last; *phase = s.phase; *queued = (int32_t)s.queue.size();
         *gps_updates = h->d->gps_updates;
     }
+    return 0;
+}
+
+int ho_norms(void *p, int32_t l, double *out) {
+    Handle *h = (Handle *)p;
+    if (h->precision == 32) { out[0] = h->f->lps[l].last_delta_sq; out[1] = h->f->lps[l].last_merge_dist_sq; }
+    else { out[0] = h->d->lps[l].last_delta_sq; out[1] = h->d->lps[l].last_merge_dist_sq; }
     return 0;
 }
 

@@ -40,7 +40,7 @@ def build(verbose: bool = False) -> str:
 from .binding import (  # noqa: E402
     HalosError, HParams, Rule, StepInfo, F32, BF16,
     halos_gps_create, halos_lps_create, halos_lps_push_update, halos_lps_push_global, halos_lps_step,
-    halos_lps_step_pull, halos_lps_set_worker_model,
+    halos_lps_step_pull, halos_lps_set_worker_model, halos_lps_get_norms,
     halos_gps_merge, halos_pull_model, halos_set_hparams, halos_lps_set_threshold, halos_lps_get_counters,
     halos_gps_get_counters, halos_set_launch_config, halos_probe_pair, halos_lps_destroy, halos_gps_destroy, halos_last_error,
     load_library, paper_hparams,
@@ -49,7 +49,7 @@ from .binding import (  # noqa: E402
 __all__ = [
     "build", "LIB_PATH", "HEADER_PATH", "HalosError", "HParams", "Rule", "StepInfo", "F32", "BF16",
     "halos_gps_create", "halos_lps_create", "halos_lps_push_update", "halos_lps_push_global", "halos_lps_step",
-    "halos_lps_step_pull", "halos_lps_set_worker_model",
+    "halos_lps_step_pull", "halos_lps_set_worker_model", "halos_lps_get_norms",
     "halos_gps_merge", "halos_pull_model", "halos_set_hparams", "halos_lps_set_threshold",
     "halos_lps_get_counters", "halos_gps_get_counters", "halos_set_launch_config", "halos_probe_pair",
     "halos_lps_destroy",

@@ -15,6 +15,7 @@ import numpy as np
 
 OK, EINVAL, ESTATE, ENOMEM, EHIP = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1
+FLAG_NORMS = 1
 PHASE_ACCUMULATING, PHASE_SENT, PHASE_RETURNING, PHASE_QUEUED = 0, 1, 2, 3
 
 
@@ -44,7 +45,7 @@ class HalosError(RuntimeError):
 
 
 def paper_hparams(eta_l: float, beta_l: float, eta_g: float, beta_g: float, alpha: float, K: int,
-                  cg_l: Optional[float] = None, cg_g: Optional[float] = None) -> HParams:
+                  cg_l: Optional[float] = None, cg_g: Optional[float] = None, flags: int = 0) -> HParams:
     """Hyper-parameter block with the paper's coefficient cg = 1 - beta (formed in fp32) unless given."""
     f = np.float32
     hp = HParams()
@@ -52,7 +53,7 @@ def paper_hparams(eta_l: float, beta_l: float, eta_g: float, beta_g: float, alph
     hp.glob = Rule(f(eta_g), f(beta_g), f(f(1) - f(beta_g)) if cg_g is None else f(cg_g))
     hp.alpha = f(alpha)
     hp.K = int(K)
-    hp.flags = 0
+    hp.flags = int(flags)
     return hp
 
 
@@ -84,6 +85,7 @@ def load_library():
         "halos_lps_set_threshold": [vp, i32],
         "halos_lps_get_counters": [vp, P(i64), P(i64), P(i32), P(i32), P(u32)],
         "halos_gps_get_counters": [vp, P(i64)],
+        "halos_lps_get_norms": [vp, vp, P(ctypes.c_double)],
         "halos_set_launch_config": [i32, i32],
         "halos_probe_pair": [vp, vp, ctypes.c_uint64, i32, vp, P(ctypes.c_double)],
     }
@@ -199,6 +201,13 @@ def halos_lps_get_counters(lps: int) -> dict:
     _check(load_library().halos_lps_get_counters(lps, ctypes.byref(t), ctypes.byref(tl), ctypes.byref(ph),
                                                  ctypes.byref(q), ctypes.byref(ms)))
     return {"t": t.value, "t_last": tl.value, "phase": ph.value, "queued": q.value, "max_staleness": ms.value}
+
+
+def halos_lps_get_norms(lps: int, stream=None) -> tuple:
+    """(sum g^2 of the last update, sum (theta - Theta_i)^2 before the last merge)."""
+    out = (ctypes.c_double * 2)()
+    _check(load_library().halos_lps_get_norms(lps, _stream(stream), out))
+    return float(out[0]), float(out[1])
 
 
 def halos_gps_get_counters(gps: int) -> dict:

@@ -52,7 +52,7 @@ halos_status check_hparams(const halos_hparams *hp) {
     if (!rule_ok(hp->local) || !rule_ok(hp->global)) return fail(HALOS_EINVAL, "non-finite eta/beta/cg");
     if (!(hp->alpha >= 0.0f && hp->alpha <= 1.0f)) return fail(HALOS_EINVAL, "alpha %g outside [0,1]", (double)hp->alpha);
     if (hp->K < 1) return fail(HALOS_EINVAL, "K = %d, must be >= 1", hp->K);
-    if (hp->flags != 0) return fail(HALOS_EINVAL, "flags must be 0");
+    if ((hp->flags & ~(uint32_t)HALOS_FLAG_NORMS) != 0) return fail(HALOS_EINVAL, "unknown bits in flags");
     return HALOS_OK;
 }
 
@@ -89,6 +89,11 @@ struct halos_lps {
     float **d_theta = nullptr, **d_m = nullptr, **d_acc = nullptr;
     float **d_worker_model = nullptr;  // n_workers tables of n_tensors pointers, appended to d_tables
     std::vector<char> worker_has_model;
+    // update-norm monitors (HALOS_FLAG_NORMS): per-workgroup partial sums, then [ |g|^2 of the last update,
+    // |theta - Theta_i|^2 before the last merge ]
+    double *d_norm_partials = nullptr;
+    double *d_norm_results = nullptr;
+    uint32_t norm_partial_cap = 0;
     halos_rule rule{};
     float alpha = 0.f;
     LpsProtocol proto;
@@ -357,6 +362,20 @@ halos_status halos_lps_create(halos_gps *g, int32_t lps_id, int32_t n_workers, v
                                    current_shape(g));
         if (e != hipSuccess) { (void)hipFree(l->d_tables); delete l; return fail_hip(e, "initialising the local server"); }
     }
+    if (g->hp.flags & HALOS_FLAG_NORMS) {
+        l->norm_partial_cap = (uint32_t)(g->ranges.size() ? g->ranges.size() : 1) * 64u * (uint32_t)g->n_cu;
+        const size_t bytes = ((size_t)l->norm_partial_cap + 2) * sizeof(double);
+        hipError_t e = hipMalloc((void **)&l->d_norm_partials, bytes);
+        if (e == hipSuccess) e = hipMemset(l->d_norm_partials, 0, bytes);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            if (l->d_norm_partials) (void)hipFree(l->d_norm_partials);
+            (void)hipFree(l->d_tables);
+            delete l;
+            return fail(HALOS_ENOMEM, "norm scratch: %s", hipGetErrorString(e));
+        }
+        l->d_norm_results = l->d_norm_partials + l->norm_partial_cap;
+    }
     g->n_lps_attached += 1;
     *out = l;
     return HALOS_OK;
@@ -365,6 +384,7 @@ halos_status halos_lps_create(halos_gps *g, int32_t lps_id, int32_t n_workers, v
 void halos_lps_destroy(halos_lps *l) {
     if (!l || l->magic != LPS_MAGIC) return;
     (void)hipFree(l->d_tables);
+    if (l->d_norm_partials) (void)hipFree(l->d_norm_partials);
     if (l->gps && l->gps->magic == GPS_MAGIC) l->gps->n_lps_attached -= 1;
     l->magic = 0;
     delete l;
@@ -448,13 +468,20 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
                 return fail(HALOS_ESTATE, "worker %d of lps %d has no model buffer registered", head.worker, l->id);
             pull_tab = l->d_worker_model + (size_t)head.worker * g->numel.size();
         }
+        uint32_t n_partials = 0;
         for (const TileRange &r : g->ranges) {
             PtrArgs args;
             fill_args(args, p.ptrs.data(), r, g->numel.size());
+            double *partials = l->d_norm_partials ? l->d_norm_partials + n_partials : nullptr;
             hipError_t e = launch_lps_update((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_acc, pull_tab,
                                              args, p.dtype == HALOS_BF16, oc.accumulate, l->rule.eta, l->rule.beta,
-                                             l->rule.cg, shape);
+                                             l->rule.cg, partials, shape);
             if (e != hipSuccess) return fail_hip(e, "launching the local update");
+            n_partials += launch_grid_size(r, shape);
+        }
+        if (l->d_norm_partials) {
+            hipError_t e = launch_norm_finalize((hipStream_t)stream, l->d_norm_partials, n_partials, l->d_norm_results + 0);
+            if (e != hipSuccess) return fail_hip(e, "launching the norm reduction");
         }
         l->proto.commit_update();
         out.kind = 1;
@@ -463,9 +490,17 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
         out.delta_ready = oc.freezes ? 1 : 0;
     } else {
         const float keep = 1.0f - l->alpha;
+        uint32_t n_partials = 0;
         for (const TileRange &r : g->ranges) {
-            hipError_t e = launch_lps_merge((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_acc, l->alpha, keep, shape);
+            double *partials = l->d_norm_partials ? l->d_norm_partials + n_partials : nullptr;
+            hipError_t e = launch_lps_merge((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_acc, l->alpha, keep,
+                                            partials, shape);
             if (e != hipSuccess) return fail_hip(e, "launching the merge");
+            n_partials += launch_grid_size(r, shape);
+        }
+        if (l->d_norm_partials) {
+            hipError_t e = launch_norm_finalize((hipStream_t)stream, l->d_norm_partials, n_partials, l->d_norm_results + 1);
+            if (e != hipSuccess) return fail_hip(e, "launching the norm reduction");
         }
         l->proto.commit_merge();
         out.kind = 2;
@@ -571,6 +606,16 @@ halos_status halos_lps_get_counters(const halos_lps *l, int64_t *t, int64_t *t_l
     if (phase) *phase = l->proto.phase();
     if (queued) *queued = l->proto.queued();
     if (max_staleness) *max_staleness = l->max_staleness;
+    return HALOS_OK;
+}
+
+halos_status halos_lps_get_norms(const halos_lps *l, void *stream, double *out) {
+    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    if (!out) return fail(HALOS_EINVAL, "out is NULL");
+    if (!l->d_norm_results) return fail(HALOS_ESTATE, "lps %d was created without HALOS_FLAG_NORMS", l->id);
+    hipError_t e = hipMemcpyAsync(out, l->d_norm_results, 2 * sizeof(double), hipMemcpyDeviceToHost, (hipStream_t)stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(e, "reading the norms");
     return HALOS_OK;
 }
 

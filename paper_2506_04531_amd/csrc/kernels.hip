@@ -110,17 +110,49 @@ __device__ __forceinline__ f32x4 merge4(f32x4 theta, f32x4 global, float alpha, 
     return r;
 }
 
+// Sum of squares of four lanes, in fp32 (16 values per thread and tile are added in fp32, tiles in fp64).
+__device__ __forceinline__ float sumsq4(f32x4 v, float q) {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) q = __fmaf_rn(v[i], v[i], q);
+    return q;
+}
+
+__device__ __forceinline__ f32x4 sub4(f32x4 a, f32x4 b) {
+    f32x4 r;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) r[i] = __fsub_rn(a[i], b[i]);
+    return r;
+}
+
+// Wavefront reduction (64 lanes, shuffles), then the four wavefronts of the workgroup through LDS.
+// Every thread of the workgroup must call it.  Thread 0 stores the workgroup's total.
+__device__ __forceinline__ void block_sum_store(double v, double *dst) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    __shared__ double wave_total[BLOCK_THREADS / 64];
+    if ((threadIdx.x & 63) == 0) wave_total[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < BLOCK_THREADS / 64; ++w) t += wave_total[w];
+        *dst = t;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // S1: worker-delta step of a local server.
 // With PULL the updated model is also written to a second tensor list (the buffer the worker starts
 // its next round from: Alg. 1 lines 11-12 in one pass instead of an update pass plus a copy pass).
-template <typename GT, bool ACC, bool NT, bool PULL>
+// With NORM every workgroup also leaves the sum of g^2 over its tiles in partials[blockIdx.x].
+template <typename GT, bool ACC, bool NT, bool PULL, bool NORM>
 __global__ void __launch_bounds__(BLOCK_THREADS)
 lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, uint32_t tensor_base,
                   float *const *__restrict__ theta_tab, float *const *__restrict__ m_tab,
                   float *const *__restrict__ acc_tab, float *const *__restrict__ pull_tab, PtrArgs gargs,
-                  float eta, float beta, float cg) {
+                  float eta, float beta, float cg, double *__restrict__ partials) {
     const uint32_t tid = threadIdx.x;
+    double norm_acc = 0.0;
     for (uint32_t t = tile_lo + blockIdx.x; t < tile_hi; t += gridDim.x) {
         const Tile tl = tiles[t];
         const uint32_t tensor = tl.tensor;
@@ -139,6 +171,12 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
                 tv[u] = ld4<NT>(th + off);
                 if constexpr (ACC) av[u] = ld4<NT>(ac + off);
             }
+            if constexpr (NORM) {
+                float q = 0.f;
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) q = sumsq4(gv[u], q);
+                norm_acc += static_cast<double>(q);
+            }
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
@@ -153,6 +191,7 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
             for (uint32_t off = tid * VEC; off < len; off += BLOCK_THREADS * VEC) {
                 if (off + VEC <= len) {
                     f32x4 gv = ldg4<NT>(g + off), mv = ld4<NT>(mm + off), tv = ld4<NT>(th + off);
+                    if constexpr (NORM) norm_acc += static_cast<double>(sumsq4(gv, 0.f));
                     const f32x4 s = model_update4(tv, mv, gv, eta, beta, cg);
                     st4<NT>(mm + off, mv);
                     st4<NT>(th + off, tv);
@@ -161,7 +200,9 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
                 } else {
                     for (uint32_t k = off; k < len; ++k) {      // ragged tail: fewer than 4 elements
                         float mv = mm[k], tv = th[k];
-                        const float s = model_update(tv, mv, ldg1(g + k), eta, beta, cg);
+                        const float gk = ldg1(g + k);
+                        if constexpr (NORM) norm_acc += static_cast<double>(__fmul_rn(gk, gk));
+                        const float s = model_update(tv, mv, gk, eta, beta, cg);
                         mm[k] = mv; th[k] = tv;
                         if constexpr (PULL) pd[k] = tv;
                         if constexpr (ACC) ac[k] = __fadd_rn(ac[k], s);
@@ -170,6 +211,7 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
             }
         }
     }
+    if constexpr (NORM) block_sum_store(norm_acc, partials + blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -227,12 +269,15 @@ gps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
 
 // ---------------------------------------------------------------------------------------------
 // S4: merge the returned global model into the local model and restart the accumulation.
-template <bool NT>
+// With NORM every workgroup also leaves the sum of (theta - Theta_i)^2 before the merge in partials[blockIdx.x].
+template <bool NT, bool NORM>
 __global__ void __launch_bounds__(BLOCK_THREADS)
 lps_merge_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi,
-                 float *const *__restrict__ theta_tab, float *const *__restrict__ inbox_tab, float alpha, float keep) {
+                 float *const *__restrict__ theta_tab, float *const *__restrict__ inbox_tab, float alpha, float keep,
+                 double *__restrict__ partials) {
     const uint32_t tid = threadIdx.x;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    double norm_acc = 0.0;
     for (uint32_t t = tile_lo + blockIdx.x; t < tile_hi; t += gridDim.x) {
         const Tile tl = tiles[t];
         const uint32_t tensor = tl.tensor;
@@ -246,6 +291,12 @@ lps_merge_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile
                 tv[u] = ld4<NT>(th + off);
                 iv[u] = ld4<NT>(in + off);
             }
+            if constexpr (NORM) {
+                float q = 0.f;
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) q = sumsq4(sub4(tv[u], iv[u]), q);
+                norm_acc += static_cast<double>(q);
+            }
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
@@ -256,17 +307,33 @@ lps_merge_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile
             const uint32_t len = tl.len;
             for (uint32_t off = tid * VEC; off < len; off += BLOCK_THREADS * VEC) {
                 if (off + VEC <= len) {
-                    st4<NT>(th + off, merge4(ld4<NT>(th + off), ld4<NT>(in + off), alpha, keep));
+                    const f32x4 tv = ld4<NT>(th + off), iv = ld4<NT>(in + off);
+                    if constexpr (NORM) norm_acc += static_cast<double>(sumsq4(sub4(tv, iv), 0.f));
+                    st4<NT>(th + off, merge4(tv, iv, alpha, keep));
                     st4<NT>(in + off, zero);
                 } else {
                     for (uint32_t k = off; k < len; ++k) {
-                        th[k] = merge1(th[k], in[k], alpha, keep);
+                        const float tk = th[k], ik = in[k];
+                        if constexpr (NORM) {
+                            const float d = __fsub_rn(tk, ik);
+                            norm_acc += static_cast<double>(__fmul_rn(d, d));
+                        }
+                        th[k] = merge1(tk, ik, alpha, keep);
                         in[k] = 0.f;
                     }
                 }
             }
         }
     }
+    if constexpr (NORM) block_sum_store(norm_acc, partials + blockIdx.x);
+}
+
+// Add up the per-workgroup partial sums in a fixed order (one workgroup, fp64): *out = sum(partials[0..n)).
+__global__ void __launch_bounds__(BLOCK_THREADS)
+norm_finalize_kernel(const double *__restrict__ partials, uint32_t n, double *__restrict__ out) {
+    double v = 0.0;
+    for (uint32_t i = threadIdx.x; i < n; i += BLOCK_THREADS) v += partials[i];
+    block_sum_store(v, out);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -366,14 +433,24 @@ inline dim3 grid_for(TileRange r, LaunchShape shape) {
 
 }  // namespace
 
+uint32_t launch_grid_size(TileRange r, LaunchShape shape) { return r.hi > r.lo ? grid_for(r, shape).x : 0u; }
+
 hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
                              float *const *acc, float *const *pull, const PtrArgs &g, bool g_is_bf16, bool accumulate,
-                             float eta, float beta, float cg, LaunchShape shape) {
+                             float eta, float beta, float cg, double *norm_partials, LaunchShape shape) {
     if (r.hi <= r.lo) return hipSuccess;
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
-#define HALOS_LAUNCH_UPD(GT, ACC, NT, PULL)                                                                       \
-    lps_update_kernel<GT, ACC, NT, PULL><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, r.tensor_base, theta, m, acc, \
-                                                                     pull, g, eta, beta, cg)
+#define HALOS_LAUNCH_UPD(GT, ACC, NT, PULL)                                                                              \
+    do {                                                                                                                 \
+        if (norm_partials)                                                                                               \
+            lps_update_kernel<GT, ACC, NT, PULL, true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, r.tensor_base, theta, \
+                                                                                   m, acc, pull, g, eta, beta, cg,       \
+                                                                                   norm_partials);                       \
+        else                                                                                                             \
+            lps_update_kernel<GT, ACC, NT, PULL, false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, r.tensor_base,     \
+                                                                                    theta, m, acc, pull, g, eta, beta,   \
+                                                                                    cg, nullptr);                        \
+    } while (0)
 #define HALOS_LAUNCH_UPD_NT(GT, ACC, PULL) \
     do { if (shape.nontemporal) HALOS_LAUNCH_UPD(GT, ACC, true, PULL); else HALOS_LAUNCH_UPD(GT, ACC, false, PULL); } while (0)
     const int variant = (g_is_bf16 ? 4 : 0) | (accumulate ? 2 : 0) | (pull ? 1 : 0);
@@ -404,13 +481,25 @@ hipError_t launch_gps_update(hipStream_t stream, const Tile *tiles, TileRange r,
 }
 
 hipError_t launch_lps_merge(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
-                            float *const *inbox, float alpha, float keep, LaunchShape shape) {
+                            float *const *inbox, float alpha, float keep, double *norm_partials, LaunchShape shape) {
     if (r.hi <= r.lo) return hipSuccess;
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
-    if (shape.nontemporal)
-        lps_merge_kernel<true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, inbox, alpha, keep);
-    else
-        lps_merge_kernel<false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, inbox, alpha, keep);
+    if (norm_partials) {
+        if (shape.nontemporal)
+            lps_merge_kernel<true, true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, inbox, alpha, keep, norm_partials);
+        else
+            lps_merge_kernel<false, true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, inbox, alpha, keep, norm_partials);
+    } else {
+        if (shape.nontemporal)
+            lps_merge_kernel<true, false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, inbox, alpha, keep, nullptr);
+        else
+            lps_merge_kernel<false, false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, inbox, alpha, keep, nullptr);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_norm_finalize(hipStream_t stream, const double *partials, uint32_t n, double *out) {
+    norm_finalize_kernel<<<dim3(1), dim3(BLOCK_THREADS), 0, stream>>>(partials, n, out);
     return hipGetLastError();
 }
 

@@ -42,9 +42,17 @@ struct TileRange {      // tiles [lo, hi) all belong to tensors [tensor_base, te
 // if accumulate: acc <- acc + s.   (ModelUpdate of App. E fused with the accumulation of Alg. 1 line 14.)
 // If `pull` is not null it is a device table of destination tensors that also receive the updated theta
 // (Alg. 1 line 12, the model handed back to the worker, written in the same pass).
+// If `norm_partials` is not null the launch also leaves, per workgroup, the sum of g^2 over the workgroup's tiles in
+// norm_partials[0 .. launch_grid_size(r, shape)).
 hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
                              float *const *acc, float *const *pull, const PtrArgs &g, bool g_is_bf16, bool accumulate,
-                             float eta, float beta, float cg, LaunchShape shape);
+                             float eta, float beta, float cg, double *norm_partials, LaunchShape shape);
+
+// Number of workgroups a launch over range r uses (0 for an empty range).
+uint32_t launch_grid_size(TileRange r, LaunchShape shape);
+
+// *out = sum of partials[0..n), added in a fixed order by one workgroup.
+hipError_t launch_norm_finalize(hipStream_t stream, const double *partials, uint32_t n, double *out);
 
 // Global-server step: M <- beta M + G; Theta <- Theta - eta (cg G + beta M); out <- Theta.
 // `G` and `out` may be the same table (each element is read before it is overwritten by the same thread).
@@ -52,8 +60,9 @@ hipError_t launch_gps_update(hipStream_t stream, const Tile *tiles, TileRange r,
                              float *const *G, float *const *out, float eta, float beta, float cg, LaunchShape shape);
 
 // Merge step of a local server: theta <- alpha * inbox + keep * theta (keep = 1 - alpha); inbox buffer <- 0.
+// With `norm_partials`: per workgroup, the sum of (theta - inbox)^2 before the merge (same layout as above).
 hipError_t launch_lps_merge(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
-                            float *const *inbox, float alpha, float keep, LaunchShape shape);
+                            float *const *inbox, float alpha, float keep, double *norm_partials, LaunchShape shape);
 
 // dst <- src (fp32), dst pointers in the argument block.
 hipError_t launch_pull(hipStream_t stream, const Tile *tiles, TileRange r, float *const *src, const PtrArgs &dst,

@@ -231,3 +231,55 @@ def test_step_pull_without_registered_buffer_is_rejected():
         assert B.halos_lps_step(c.lps[0]).kind == 1
     finally:
         c.close()
+
+
+def test_norm_monitors_match_the_oracle():
+    """HALOS_FLAG_NORMS: |g|^2 per update and |theta - Theta_i|^2 per merge, against fp64 sums of the oracle, and the
+    state itself is bit-identical to a run without the monitors."""
+    from dataclasses import replace
+    from paper_2506_04531_amd import binding as B
+    from paper_2506_04531_amd.harness import Cluster
+    w = replace(synth.get_workload("410m").scaled(RAGGED, n_updates=80, name="norms"), delta_dtype="bf16")
+    trace = synth.make_trace(w, seed=21)
+    hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0], flags=B.FLAG_NORMS)
+    c = Cluster(w, "cuda:0", k_initial=trace.k_initial, hp=hp)
+    plain = Cluster(w, "cuda:0", k_initial=trace.k_initial)
+    try:
+        # replay event by event on both, comparing the monitors after every LPS step
+        from oracle import HalosOracle
+        idx = torch.arange(w.layout.total, dtype=torch.int64)
+        theta0 = synth.normal_at(w.seed, 0, idx, synth.tensors.scale_f32(w.init_sigma)).numpy()
+        scale = torch.from_numpy(synth.delta_scales(w)[w.layout.tensor_of(idx.numpy())])
+        pool = {s: synth.to_bf16_bits(synth.normal_at(w.seed, 1 + s, idx, scale)).numpy() for s in range(w.pool_slots)}
+        ref = HalosOracle(theta0, w.n_lps, eta_l=w.eta_l, beta_l=w.beta_l, eta_g=w.eta_g, beta_g=w.beta_g, alpha=w.alpha,
+                          K=trace.k_initial)
+        checked = 0
+        for ev in trace.events:
+            kind, l = int(ev["kind"]), int(ev["lps"])
+            one = np.array([ev], dtype=trace.events.dtype)
+            c.replay(one)
+            plain.replay(one)
+            if kind == synth.EV_ARRIVE_DELTA:
+                ref.arrive_delta(l, int(ev["worker"]), pool[int(ev["slot"])])
+            elif kind == synth.EV_ARRIVE_GLOBAL:
+                ref.arrive_global(l)
+            elif kind == synth.EV_GPS_MERGE:
+                ref.gps_receive(l)
+            elif kind == synth.EV_LPS_STEP:
+                ref.set_K(l, int(ev["k_cur"]))
+                ref.lps_step(l)
+                got = B.halos_lps_get_norms(c.lps[l])
+                want = ref.norms(l)
+                for a, b in zip(got, want):
+                    assert abs(a - b) <= 1e-4 * max(abs(b), 1e-30), (got, want)
+                checked += 1
+        assert checked == len(trace.events[trace.events["kind"] == synth.EV_LPS_STEP])
+        torch.cuda.synchronize()
+        for k in c.state_lists():
+            assert np.array_equal(c.flat(k).view(np.uint32), plain.flat(k).view(np.uint32)), k
+        with pytest.raises(B.HalosError) as e:
+            B.halos_lps_get_norms(plain.lps[0])
+        assert e.value.status == B.ESTATE
+    finally:
+        c.close()
+        plain.close()

@@ -436,6 +436,24 @@ def test_bf16_delta_path_equals_f32_path_fed_prerounded_deltas():
         assert np.array_equal(sa[k][0], sb[k][0]), k
 
 
+# ---------------------------------------------------------------- monitors
+def test_norm_monitors_on_known_vectors():
+    """|g|^2 of the last delta and |theta - Theta_i|^2 before the last merge (the quantities bounded by
+    assumptions 4 and 5 of Sec. 4.2), on integer vectors where the sums are obvious."""
+    theta0 = np.array([8.0, -4.0, 0.0, 16.0], dtype=F32)
+    g1 = np.array([1.0, 2.0, 3.0, 4.0], dtype=F32)
+    g2 = np.array([2.0, 0.0, -2.0, 4.0], dtype=F32)
+    o = single(theta0, K=1, alpha=0.5)
+    assert o.norms(0) == (0.0, 0.0)
+    apply(o, 0, 0, g1)
+    assert o.norms(0) == (30.0, 0.0)                                   # 1 + 4 + 9 + 16
+    o.gps_receive(0)                                                   # Theta_1 = theta0 - g1
+    apply(o, 0, 1, g2)                                                 # theta = theta0 - g1 - g2
+    assert o.norms(0) == (24.0, 0.0)
+    o.arrive_global(0); o.lps_step(0)
+    assert o.norms(0) == (24.0, 24.0)                                  # theta - Theta_1 = -g2 before the merge
+
+
 # ---------------------------------------------------------------- protocol violations
 def test_protocol_violations_are_rejected():
     o = single(np.zeros(4, dtype=F32), K=1)
