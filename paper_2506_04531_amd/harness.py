@@ -212,7 +212,8 @@ class Cluster:
             mk = lambda dt=f32, cls=0: alloc_tensor_list(self.numel, dt, self.device, arena)
         self.Theta, self.M = mk(cls=0), mk(cls=0)
         fill_initial_model(w, self.Theta)
-        self.hp = hp if hp is not None else B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0])
+        self.hp = hp if hp is not None else B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0],
+                                                                 cg_l=w.cg_l, cg_g=w.cg_g)
         self.gps = B.halos_gps_create(self.numel, self.hp, self.Theta, self.M)
         self.theta, self.m, self.acc, self.lps = [], [], [], []
         for l in range(w.n_lps):

@@ -36,6 +36,8 @@ class Workload:
     eta_g: float = 0.15
     beta_g: float = 0.5
     alpha: float = 0.25
+    cg_l: float | None = None      # coefficient on the delta in the LPS rule; None = the paper's 1 - beta_l
+    cg_g: float | None = None      # same for the GPS rule
     seed: int = 0
     pool_slots: int = 8            # number of distinct resident delta buffers
     schedule: str = "seeded"       # "seeded": synth.schedule; "paper": the paper's own cluster model (synth.paper_cluster)

@@ -62,7 +62,7 @@ def oracle_run(w: synth.Workload, trace: synth.Trace, idx: Optional[np.ndarray],
         return cache[slot]
 
     o = HalosOracle(theta0, w.n_lps, eta_l=w.eta_l, beta_l=w.beta_l, eta_g=w.eta_g, beta_g=w.beta_g,
-                    alpha=w.alpha, K=trace.k_initial, precision=precision, form=form)
+                    alpha=w.alpha, K=trace.k_initial, cg_l=w.cg_l, cg_g=w.cg_g, precision=precision, form=form)
     log = oracle_replay(o, trace.events, delta)
     return o, log
 

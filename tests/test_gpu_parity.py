@@ -283,3 +283,85 @@ def test_norm_monitors_match_the_oracle():
     finally:
         c.close()
         plain.close()
+
+
+DEGENERATE = {
+    "no momentum, unit rates, alpha 1, K 1": dict(beta_l=0.0, eta_l=1.0, beta_g=0.0, eta_g=1.0, alpha=1.0, k_range=(1, 1)),
+    "textbook Nesterov (cg = 1) on both tiers": dict(cg_l=1.0, cg_g=1.0),
+    "alpha 0: the global model is ignored": dict(alpha=0.0),
+    "zero learning rates": dict(eta_l=0.0, eta_g=0.0),
+    "no global momentum (non-i.i.d. setting of Sec. 5.4)": dict(beta_g=0.0),
+    "one server, one worker": dict(n_lps=1, workers_per_lps=1, k_range=(3, 3)),
+    "heavy momentum, large K": dict(beta_l=0.99, beta_g=0.9, k_range=(32, 32)),
+}
+
+
+@pytest.mark.parametrize("case", list(DEGENERATE))
+def test_degenerate_and_unusual_hyper_parameters(case):
+    from dataclasses import replace
+    base = synth.get_workload("410m").scaled(RAGGED, n_updates=72, name="degenerate")
+    w = replace(base, **DEGENERATE[case])
+    _full_parity(w, synth.make_trace(w, seed=31))
+
+
+def test_hyper_parameters_changed_between_events():
+    """A caller-side schedule: eta_l, alpha and K change in the middle of the trace (halos_set_hparams)."""
+    from paper_2506_04531_amd import binding as B
+    w = synth.get_workload("70m").scaled(RAGGED, n_updates=60, name="sched")
+    trace = synth.make_trace(w, seed=41)
+    ev = trace.events
+    half = len(ev) // 2
+    c = _cluster(w, trace)
+    idx = torch.arange(w.layout.total, dtype=torch.int64)
+    try:
+        c.replay(ev[:half])
+        hp2 = B.paper_hparams(0.05, 0.5, 0.3, 0.25, 0.75, 8)
+        for h in c.lps:
+            B.halos_set_hparams(h, False, hp2)
+        B.halos_set_hparams(c.gps, True, hp2)
+        c.replay(ev[half:])
+        torch.cuda.synchronize()
+        gpu = {k: c.flat(k) for k in c.state_lists()}
+    finally:
+        c.close()
+    import oracle as O
+    from oracle import HalosOracle
+    from oracle.replay import replay as oreplay
+    theta0 = synth.normal_at(w.seed, 0, idx, synth.tensors.scale_f32(w.init_sigma)).numpy()
+    scale = torch.from_numpy(synth.delta_scales(w)[w.layout.tensor_of(idx.numpy())])
+    pool = {s: synth.normal_at(w.seed, 1 + s, idx, scale).numpy() for s in range(w.pool_slots)}
+    o = HalosOracle(theta0, w.n_lps, eta_l=w.eta_l, beta_l=w.beta_l, eta_g=w.eta_g, beta_g=w.beta_g, alpha=w.alpha,
+                    K=trace.k_initial, precision=32, form=FORM_ACCUMULATOR)
+    oreplay(o, ev[:half], lambda s: pool[s])
+    f = np.float32
+    o.set_rules(eta_l=0.05, beta_l=0.5, cg_l=f(1) - f(0.5), eta_g=0.3, beta_g=0.25, cg_g=f(1) - f(0.25), alpha=0.75)
+    oreplay(o, ev[half:], lambda s: pool[s])
+    # the trace's K stays in force (the replay sets it before every step), so only the rules changed
+    worst, n_diff, name = compare_state(gpu, oracle_state(o, w.n_lps), bitwise=True)
+    assert n_diff == 0, (n_diff, worst, name)
+
+
+def test_one_tensor_larger_than_2_to_31_elements():
+    """64-bit element offsets: a single tensor of 2^31 + 5003 elements, checked on sampled elements."""
+    from dataclasses import replace
+    n = (1 << 31) + 5003
+    lay = synth.Layout(("huge",), ((n,),), (1,))
+    w = replace(synth.get_workload("tiny").scaled(lay, n_updates=5, name="huge"), pool_slots=2, scale_by_fan_in=False,
+                n_lps=1, workers_per_lps=2, k_range=(2, 2))
+    trace = synth.make_trace(w, seed=51)
+    idx = np.unique(np.concatenate([sample_indices(lay, 1 << 15, seed=2),
+                                    np.arange((1 << 31) - 4100, (1 << 31) + 4100, dtype=np.int64)]))
+    print(f"[parity] workload=huge n={n} sample={idx.size} events={len(trace.events)}", flush=True)
+    c = _cluster(w, trace)
+    try:
+        gpu_log, _ = c.replay(trace.events, fuse_pull=True)
+        torch.cuda.synchronize()
+        gpu = {k: c.gather(k, torch.from_numpy(idx)) for k in c.state_lists()}
+    finally:
+        c.close()
+        del c
+        torch.cuda.empty_cache()
+    o32, log32 = oracle_run(w, trace, idx, 32, FORM_ACCUMULATOR)
+    check_step_logs(trace, gpu_log, log32)
+    worst, n_diff, name = compare_state(gpu, oracle_state(o32, w.n_lps), bitwise=True)
+    assert n_diff == 0 and worst <= REL_TOL, (n_diff, worst, name)
