@@ -44,8 +44,8 @@ BYTES = {
 # only for the kernel source it was measured on: {sha256 of kernels.hip: {kernel label: bytes/param}}.
 MEASURED_TRAFFIC: dict = {
     # profiles/lps_update_1b_hbm_traffic.md
-    "04f3ec6ce4de6d2851405687e3d4f19a9f16d4a4835446b56e1be1d70e4877cf": {
-        "1b:lps_update_acc_pull": 30.034, "1b:lps_update_noacc_pull": 22.035,
+    "d1f334747cb9dfceffb9403b951175d7a3868bc7fbf365d8357d7eafe7153613": {
+        "1b:lps_update_acc_pull": 30.034, "1b:lps_update_noacc_pull": 22.033,
     },
 }
 
@@ -94,7 +94,6 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
         torch.cuda.synchronize()
         t_start = time.perf_counter()
         timings = {}
-        n_events = {"update": 0, "gps": 0, "merge": 0, "pull": 0}
         for s in range(warmup, warmup + steps):
             log, tm = c.replay(slices[s], timed=True, fuse_pull=fuse_pull)
             for k, v in tm.items():
