@@ -30,7 +30,10 @@
  *   Threads      a handle may be used by one host thread at a time.
  *   Errors       every call returns a halos_status; on anything but HALOS_OK no
  *                host or device state has been modified and halos_last_error()
- *                describes the problem (thread-local string).
+ *                describes the problem (thread-local string).  The one
+ *                exception is HALOS_EHIP out of a step on a tensor list so long
+ *                that it needs several launches: earlier launches of that step
+ *                may already have run.
  *   Sign         a "delta" handed to this library is the PSEUDO-GRADIENT
  *                g = (model the sender started from) - (model it ended with),
  *                i.e. the negative of Algorithm 1's delta / Delta, so that
@@ -253,7 +256,8 @@ halos_status halos_set_launch_config(int32_t blocks_per_cu, int32_t nontemporal)
  */
 halos_status halos_probe_pair(void *a, void *b, uint64_t bytes, int32_t reps, void *stream, double *gbps);
 
-/* Release the handle's tables.  Caller buffers are untouched.  NULL is ignored. */
+/* Release the handle's tables (this waits for the device: work that still uses them finishes first).
+ * Caller buffers are untouched.  NULL is ignored. */
 void halos_lps_destroy(halos_lps *lps);
 void halos_gps_destroy(halos_gps *gps);
 

@@ -357,11 +357,6 @@ halos_status halos_lps_create(halos_gps *g, int32_t lps_id, int32_t n_workers, v
     l->d_acc = l->d_m + nt;
     l->d_worker_model = l->d_acc + nt;
     l->worker_has_model.assign(n_workers, 0);
-    for (const TileRange &r : g->ranges) {       // theta <- Theta, m <- 0, acc <- 0
-        hipError_t e = launch_init((hipStream_t)stream, g->d_tiles, r, g->d_Theta, l->d_theta, l->d_m, l->d_acc,
-                                   current_shape(g));
-        if (e != hipSuccess) { (void)hipFree(l->d_tables); delete l; return fail_hip(e, "initialising the local server"); }
-    }
     if (g->hp.flags & HALOS_FLAG_NORMS) {
         l->norm_partial_cap = (uint32_t)(g->ranges.size() ? g->ranges.size() : 1) * 64u * (uint32_t)g->n_cu;
         const size_t bytes = ((size_t)l->norm_partial_cap + 2) * sizeof(double);
@@ -375,6 +370,16 @@ halos_status halos_lps_create(halos_gps *g, int32_t lps_id, int32_t n_workers, v
             return fail(HALOS_ENOMEM, "norm scratch: %s", hipGetErrorString(e));
         }
         l->d_norm_results = l->d_norm_partials + l->norm_partial_cap;
+    }
+    for (const TileRange &r : g->ranges) {       // theta <- Theta, m <- 0, acc <- 0
+        hipError_t e = launch_init((hipStream_t)stream, g->d_tiles, r, g->d_Theta, l->d_theta, l->d_m, l->d_acc,
+                                   current_shape(g));
+        if (e != hipSuccess) {
+            if (l->d_norm_partials) (void)hipFree(l->d_norm_partials);
+            (void)hipFree(l->d_tables);
+            delete l;
+            return fail_hip(e, "initialising the local server");
+        }
     }
     g->n_lps_attached += 1;
     *out = l;

@@ -365,3 +365,27 @@ def test_one_tensor_larger_than_2_to_31_elements():
     check_step_logs(trace, gpu_log, log32)
     worst, n_diff, name = compare_state(gpu, oracle_state(o32, w.n_lps), bitwise=True)
     assert n_diff == 0 and worst <= REL_TOL, (n_diff, worst, name)
+
+
+def test_replay_on_a_side_stream():
+    """All device work goes to the stream handed to the library; a non-default stream gives the same bits."""
+    w = synth.get_workload("70m").scaled(RAGGED, n_updates=40, name="stream")
+    trace = synth.make_trace(w, seed=61)
+    out = []
+    for side in (False, True):
+        c = _cluster(w, trace)
+        try:
+            if side:
+                s = torch.cuda.Stream()
+                s.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(s):
+                    c.replay(trace.events, fuse_pull=True)
+                s.synchronize()
+            else:
+                c.replay(trace.events, fuse_pull=True)
+            torch.cuda.synchronize()
+            out.append({k: c.flat(k) for k in c.state_lists()})
+        finally:
+            c.close()
+    for k in out[0]:
+        assert np.array_equal(out[0][k].view(np.uint32), out[1][k].view(np.uint32)), k
