@@ -168,3 +168,57 @@ def test_many_tensors_need_several_launch_ranges():
     finally:
         B.halos_lps_destroy(lps)
         B.halos_gps_destroy(gps)
+
+
+def test_hand_derived_worked_example_through_the_library():
+    """The integer example derived by hand from Algorithm 1 (tests/golden) replayed through the C ABI: the GPU
+    path is held to the paper-derived numbers directly, not only to the oracle."""
+    import json
+    import os
+    from paper_2506_04531_amd import binding as B
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "alg1_worked_example.json")) as f:
+        ex = json.load(f)
+    dev = "cuda:0"
+    n = len(ex["theta0"])
+    T = lambda v: torch.tensor(v, dtype=torch.float32, device=dev)
+    Theta, M = [T(ex["theta0"])], [torch.zeros(n, device=dev)]
+    hp = B.paper_hparams(ex["eta_l"], ex["beta_l"], ex["eta_g"], ex["beta_g"], ex["alpha"], ex["K"],
+                         cg_l=ex["cg_l"], cg_g=ex["cg_g"])
+    gps = B.halos_gps_create([n], hp, Theta, M)
+    state = [([torch.empty(n, device=dev)], [torch.empty(n, device=dev)], [torch.empty(n, device=dev)])
+             for _ in range(ex["n_lps"])]
+    lps = [B.halos_lps_create(gps, l, 2, *state[l]) for l in range(ex["n_lps"])]
+    keep = []
+    try:
+        for step in ex["script"]:
+            l = step["lps"]
+            if step["op"] == "delta":
+                g = [T(step["g"])]
+                keep.append(g)
+                B.halos_lps_push_update(lps[l], step["worker"], g, B.F32)
+            elif step["op"] == "step":
+                info = B.halos_lps_step(lps[l])
+                e = step["expect"]
+                assert (info.kind, info.t, info.t_last, info.delta_ready) == (e["kind"], e["t"], e["t_last"], e["sent"]), step
+                if "expect_theta" in step:
+                    torch.cuda.synchronize()
+                    assert state[l][0][0].tolist() == step["expect_theta"]
+            elif step["op"] == "gps":
+                B.halos_gps_merge(gps, lps[l])
+                torch.cuda.synchronize()
+                assert Theta[0].tolist() == step["expect_Theta"]
+            elif step["op"] == "global":
+                B.halos_lps_push_global(lps[l])
+        torch.cuda.synchronize()
+        fin = ex["final"]
+        for l in range(ex["n_lps"]):
+            assert state[l][0][0].tolist() == fin["theta"][l]
+            assert state[l][2][0].tolist() == fin["aux"][l]
+            c = B.halos_lps_get_counters(lps[l])
+            assert (c["t"], c["t_last"]) == (fin["t"][l], fin["t_last"][l])
+        assert Theta[0].tolist() == fin["Theta"]
+        assert B.halos_gps_get_counters(gps)["updates"] == fin["gps_updates"]
+    finally:
+        for h in lps:
+            B.halos_lps_destroy(h)
+        B.halos_gps_destroy(gps)
