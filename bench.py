@@ -35,6 +35,8 @@ BYTES = {
     "lps_update_noacc": {"f32": 20, "bf16": 18},   # accumulated update in flight: acc untouched
     "lps_update_acc_pull": {"f32": 32, "bf16": 30},    # ... plus the updated model written to the worker's buffer
     "lps_update_noacc_pull": {"f32": 24, "bf16": 22},
+    "lps_update_freeze": {"f32": 28, "bf16": 26},      # snapshot form: read the snapshot, write theta_{t_last} - theta_t
+    "lps_update_freeze_pull": {"f32": 32, "bf16": 30},
     "gps_update": {"f32": 24, "bf16": 24},         # read G, M, Theta; write M, Theta, returned model
     "lps_merge": {"f32": 16, "bf16": 16},          # read theta, returned model; write theta, zeroed acc
     "pull": {"f32": 8, "bf16": 8},
@@ -71,7 +73,8 @@ def split_steps(events, n_updates_per_step: int, n_steps: int):
     return [events[cuts[i]:cuts[i + 1]] for i in range(n_steps)]
 
 
-def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: str = "regions", fuse_pull: bool = True):
+def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: str = "regions", fuse_pull: bool = True,
+                 snapshot: bool = False):
     import numpy as np
     import torch
     import synth
@@ -83,7 +86,12 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
     slices = split_steps(trace.events, w.n_updates, steps + warmup)
     N = w.layout.total
     t0 = time.time()
-    c = Cluster(w, "cuda:0", k_initial=trace.k_initial, placement=placement, verbose=verbose)
+    hp = None
+    if snapshot:
+        from paper_2506_04531_amd import binding as B
+        hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0], cg_l=w.cg_l, cg_g=w.cg_g,
+                             flags=B.FLAG_SNAPSHOT)
+    c = Cluster(w, "cuda:0", k_initial=trace.k_initial, placement=placement, verbose=verbose, hp=hp)
     n_regions = c.region_arena.n_regions if c.region_arena is not None else 0
     if verbose:
         print(f"[bench] {name}: N={N} tensors={w.layout.n_tensors} state resident after {time.time() - t0:.1f}s, "
@@ -120,10 +128,11 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
             "params_per_s": float(N / (ms.mean() * 1e-3)),
             "total_ms": float(ms.sum()),
         }
-    upd_labels = ("lps_update_acc", "lps_update_noacc", "lps_update_acc_pull", "lps_update_noacc_pull")
+    upd_labels = ("lps_update_acc", "lps_update_noacc", "lps_update_acc_pull", "lps_update_noacc_pull",
+                  "lps_update_freeze", "lps_update_freeze_pull")
     n_upd = sum(kernels[k]["launches"] for k in upd_labels if k in kernels)
     n_pull_events = kernels.get("pull", {}).get("launches", 0) + sum(
-        kernels[k]["launches"] for k in ("lps_update_acc_pull", "lps_update_noacc_pull") if k in kernels)
+        kernels[k]["launches"] for k in ("lps_update_acc_pull", "lps_update_noacc_pull", "lps_update_freeze_pull") if k in kernels)
     n_gps = kernels.get("gps_update", {}).get("launches", 0)
     n_mrg = kernels.get("lps_merge", {}).get("launches", 0)
     updates = n_upd + n_gps + n_mrg
@@ -149,7 +158,7 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
         "whole_path_GBps": total_bytes / elapsed / 1e9,
         "whole_path_frac_of_peak": total_bytes / elapsed / 1e9 / HBM_PEAK_GBS,
         "kernels": kernels, "roofline": roofline, "placement": placement, "hbm_regions_found": n_regions,
-        "fuse_pull": fuse_pull,
+        "fuse_pull": fuse_pull, "delta_form": "snapshot" if snapshot else "accumulator",
     }
 
 
@@ -205,6 +214,9 @@ def main():
                     help="regions: models / momenta / third buffers in three different HBM regions; plain: torch allocations")
     ap.add_argument("--no-fuse-pull", action="store_true",
                     help="issue every worker pull as its own copy instead of fusing it into the update pass")
+    ap.add_argument("--snapshot", action="store_true",
+                    help="form the accumulated update by subtracting the snapshot theta_{t_last} (Alg. 1 line 14 as "
+                         "written) instead of keeping a running sum: fewer bytes per update, larger rounding error")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
 
@@ -222,10 +234,10 @@ def main():
     if args.blocks_per_cu or args.nontemporal >= 0:
         halos.halos_set_launch_config(args.blocks_per_cu, args.nontemporal)
 
-    head = run_workload(args.workload, args.steps, args.warmup, not args.quiet, args.placement, not args.no_fuse_pull)
+    head = run_workload(args.workload, args.steps, args.warmup, not args.quiet, args.placement, not args.no_fuse_pull, args.snapshot)
     others = []
     for name in [x for x in args.also.split(",") if x and x != args.workload]:
-        others.append(run_workload(name, args.steps, args.warmup, not args.quiet, args.placement, not args.no_fuse_pull))
+        others.append(run_workload(name, args.steps, args.warmup, not args.quiet, args.placement, not args.no_fuse_pull, args.snapshot))
     cpu = None if args.no_cpu_baseline else cpu_baseline(args.workload)
 
     def brief(r):
@@ -240,7 +252,7 @@ def main():
                    "tensors": head["tensors"], "n_lps": head["n_lps"], "workers_per_lps": head["workers_per_lps"],
                    "delta_dtype": head["delta_dtype"], "events_per_step": head["events_per_step"],
                    "placement": head["placement"], "hbm_regions_found": head["hbm_regions_found"],
-                   "fuse_pull": head["fuse_pull"]},
+                   "fuse_pull": head["fuse_pull"], "delta_form": head["delta_form"]},
         "roofline": head["roofline"],
         "cpu_baseline": cpu,
         "whole_path_GBps": head["whole_path_GBps"],

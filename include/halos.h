@@ -83,7 +83,7 @@ typedef struct {
     halos_rule global;   /* eta_g, beta_g: used by the GPS                         */
     float alpha;         /* merge weight of the global model, 0 <= alpha <= 1      */
     int32_t K;           /* local updates accumulated before a Delta is sent, >= 1 */
-    uint32_t flags;      /* 0 or HALOS_FLAG_NORMS; other bits must be 0            */
+    uint32_t flags;      /* HALOS_FLAG_* bits; all others must be 0                */
 } halos_hparams;
 
 /* Monitor the two quantities that the convergence analysis bounds (Sec. 4.2, assumptions "bounded gradients"
@@ -92,6 +92,15 @@ typedef struct {
  * (wavefront reductions, per-workgroup partial sums, one small reduction kernel); they never feed back into
  * the state.  Honoured at halos_gps_create; every LPS of that GPS then owns a small scratch buffer. */
 #define HALOS_FLAG_NORMS 1u
+
+/* Form the accumulated update the way Algorithm 1 line 14 writes it, Delta = theta_t - theta_{t_last}, instead of
+ * keeping a running sum: the third buffer of every LPS then holds the snapshot theta_{t_last} (written by
+ * halos_lps_create and by every merge), ordinary updates do not touch it (20 or 18 bytes per parameter instead of
+ * 28 or 26), and the update that completes the accumulation overwrites it with theta_{t_last} - theta_t.  Same
+ * quantity as the running sum, but rounded differently: the difference of two model-sized fp32 numbers carries an
+ * absolute error of about one unit in the last place of the MODEL, i.e. a relative error near 1e-4 of a typical
+ * accumulated update, against 1e-7 for the running sum.  Honoured at halos_gps_create. */
+#define HALOS_FLAG_SNAPSHOT 2u
 
 /* What one halos_lps_step did. */
 typedef struct {
@@ -129,7 +138,7 @@ halos_status halos_gps_create(const halos_layout *layout, const halos_hparams *h
  *   lps_id      caller's label for this server, >= 0 (reported in error strings only)
  *   n_workers   number of workers that may push to it, >= 1
  *   theta,m,acc device tensors of the layout.  On `stream` this call copies the GPS's CURRENT model into
- *               theta and zero-fills m and acc.  `acc` is the server's third buffer: it holds the
+ *               theta and zero-fills m and acc (under HALOS_FLAG_SNAPSHOT acc receives the model too).  `acc` is the server's third buffer: it holds the
  *               accumulated update G = theta_{t_last} - theta_t while collecting, stays frozen while that
  *               update is in flight, is overwritten with the returned global model by halos_gps_merge,
  *               and is zeroed again by the merge step.

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "halos_oracle.cpp")
 _LIB = os.path.join(_HERE, "libhalos_oracle.so")
 
-THETA, MOM, AUX, GPS_THETA, GPS_MOM = 0, 1, 2, 3, 4
+THETA, MOM, AUX, GPS_THETA, GPS_MOM, AUX_SNAPSHOT = 0, 1, 2, 3, 4, 5
 SCALE = 10   # add to the ids above for the running max-magnitude of the same array
 
 FORM_LITERAL = 0       # Delta by snapshot subtraction (Algorithm 1 line 14 as written)

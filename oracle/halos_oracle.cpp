@@ -289,6 +289,20 @@ struct Oracle {
     }
 };
 
+// The third buffer as an implementation that keeps the SNAPSHOT theta_{t_last} would hold it (form 0 only):
+// the snapshot while accumulating, then the frozen G, then the returned model.  Its error scale while it is G:
+// G was formed by subtracting two model-sized numbers, so rounding errors of the model's size flowed into it.
+template <class R>
+void aux_snapshot_form(const Oracle<R> &o, int l, std::vector<R> &out, std::vector<R> &scale) {
+    const Lps<R> &s = o.lps[l];
+    if (s.phase == ACCUMULATING) { out = s.snap; scale = s.sc_theta; }
+    else if (s.phase == SENT) {
+        out = s.frozen;
+        scale = s.sc_aux;
+        for (size_t j = 0; j < scale.size(); ++j) if (s.sc_theta[j] > scale[j]) scale[j] = s.sc_theta[j];
+    } else { out = s.inbox; scale = s.sc_aux; }
+}
+
 struct Handle {
     int precision;
     Oracle<float> *f = nullptr;
@@ -302,11 +316,13 @@ void copy_out(const std::vector<R> &v, double *out) {
 
 template <class R>
 int get_impl(Oracle<R> *o, int what, int l, double *out) {
-    if (what >= 0 && what <= 2 && (l < 0 || (size_t)l >= o->lps.size())) return -1;
+    if (((what >= 0 && what <= 2) || what == 5 || what == 15) && (l < 0 || (size_t)l >= o->lps.size())) return -1;
     switch (what) {
         case 0: copy_out(o->lps[l].theta, out); return 0;
         case 1: copy_out(o->lps[l].m, out); return 0;
         case 2: { std::vector<R> a; o->aux(l, a); copy_out(a, out); return 0; }
+        case 5: { std::vector<R> a, sc; aux_snapshot_form(*o, l, a, sc); copy_out(a, out); return 0; }
+        case 15: { std::vector<R> a, sc; aux_snapshot_form(*o, l, a, sc); copy_out(sc, out); return 0; }
         case 3: copy_out(o->Theta, out); return 0;
         case 4: copy_out(o->M, out); return 0;
         case 10: copy_out(o->lps[l].sc_theta, out); return 0;
@@ -392,7 +408,8 @@ int ho_set_rules(void *p, float eta_l, float beta_l, float cg_l, float eta_g, fl
 }
 
 // what: 0 theta_l, 1 m_l, 2 third buffer of l (accumulation / frozen G / returned model),
-//       3 Theta, 4 M;  10..14 the running max-magnitude of the same five arrays.
+//       3 Theta, 4 M, 5 third buffer of l in snapshot form (theta_{t_last} / frozen G / returned model);
+//       10..15 the error scales of the same six arrays.
 int ho_get(void *p, int32_t what, int32_t l, double *out) {
     Handle *h = (Handle *)p;
     return h->precision == 32 ? get_impl(h->f, what, l, out) : get_impl(h->d, what, l, out);

@@ -16,6 +16,7 @@ import numpy as np
 OK, EINVAL, ESTATE, ENOMEM, EHIP = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1
 FLAG_NORMS = 1
+FLAG_SNAPSHOT = 2
 PHASE_ACCUMULATING, PHASE_SENT, PHASE_RETURNING, PHASE_QUEUED = 0, 1, 2, 3
 
 

@@ -52,7 +52,8 @@ halos_status check_hparams(const halos_hparams *hp) {
     if (!rule_ok(hp->local) || !rule_ok(hp->global)) return fail(HALOS_EINVAL, "non-finite eta/beta/cg");
     if (!(hp->alpha >= 0.0f && hp->alpha <= 1.0f)) return fail(HALOS_EINVAL, "alpha %g outside [0,1]", (double)hp->alpha);
     if (hp->K < 1) return fail(HALOS_EINVAL, "K = %d, must be >= 1", hp->K);
-    if ((hp->flags & ~(uint32_t)HALOS_FLAG_NORMS) != 0) return fail(HALOS_EINVAL, "unknown bits in flags");
+    if ((hp->flags & ~(uint32_t)(HALOS_FLAG_NORMS | HALOS_FLAG_SNAPSHOT)) != 0)
+        return fail(HALOS_EINVAL, "unknown bits in flags");
     return HALOS_OK;
 }
 
@@ -96,6 +97,7 @@ struct halos_lps {
     uint32_t norm_partial_cap = 0;
     halos_rule rule{};
     float alpha = 0.f;
+    bool snapshot = false;             // third buffer holds theta_{t_last}; Delta is formed by subtraction at the send
     LpsProtocol proto;
     std::vector<PendingDelta> pending;           // per worker: the delta it has queued
     std::vector<std::vector<const void *>> validated;   // per worker: last pointer set whose ranges were checked
@@ -309,7 +311,7 @@ halos_status halos_gps_create(const halos_layout *layout, const halos_hparams *h
     g->d_M = g->d_Theta + nt;
 
     for (const TileRange &r : g->ranges) {       // M <- 0
-        e = launch_init((hipStream_t)stream, g->d_tiles, r, nullptr, nullptr, g->d_M, nullptr, current_shape(g));
+        e = launch_init((hipStream_t)stream, g->d_tiles, r, nullptr, nullptr, g->d_M, nullptr, false, current_shape(g));
         if (e != hipSuccess) {
             (void)hipFree(g->d_tables); (void)hipFree(g->d_tiles); delete g;
             return fail_hip(e, "zero-filling M");
@@ -343,6 +345,7 @@ halos_status halos_lps_create(halos_gps *g, int32_t lps_id, int32_t n_workers, v
     if (!l) return fail(HALOS_ENOMEM, "host allocation failed");
     l->gps = g;
     l->id = lps_id;
+    l->snapshot = (g->hp.flags & HALOS_FLAG_SNAPSHOT) != 0;
     l->rule = g->hp.local;
     l->alpha = g->hp.alpha;
     l->pending.resize(n_workers);
@@ -373,7 +376,7 @@ halos_status halos_lps_create(halos_gps *g, int32_t lps_id, int32_t n_workers, v
     }
     for (const TileRange &r : g->ranges) {       // theta <- Theta, m <- 0, acc <- 0
         hipError_t e = launch_init((hipStream_t)stream, g->d_tiles, r, g->d_Theta, l->d_theta, l->d_m, l->d_acc,
-                                   current_shape(g));
+                                   l->snapshot, current_shape(g));
         if (e != hipSuccess) {
             if (l->d_norm_partials) (void)hipFree(l->d_norm_partials);
             (void)hipFree(l->d_tables);
@@ -473,13 +476,17 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
                 return fail(HALOS_ESTATE, "worker %d of lps %d has no model buffer registered", head.worker, l->id);
             pull_tab = l->d_worker_model + (size_t)head.worker * g->numel.size();
         }
+        // what this update does to the third buffer: add its step (running accumulation), or nothing (an accumulated
+        // update is in flight, or the buffer holds the snapshot), or -- snapshot form, accumulation complete --
+        // turn the snapshot into theta_{t_last} - theta_t
+        const int third_mode = l->snapshot ? (oc.freezes ? 2 : 0) : (oc.accumulate ? 1 : 0);
         uint32_t n_partials = 0;
         for (const TileRange &r : g->ranges) {
             PtrArgs args;
             fill_args(args, p.ptrs.data(), r, g->numel.size());
             double *partials = l->d_norm_partials ? l->d_norm_partials + n_partials : nullptr;
             hipError_t e = launch_lps_update((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_acc, pull_tab,
-                                             args, p.dtype == HALOS_BF16, oc.accumulate, l->rule.eta, l->rule.beta,
+                                             args, p.dtype == HALOS_BF16, third_mode, l->rule.eta, l->rule.beta,
                                              l->rule.cg, partials, shape);
             if (e != hipSuccess) return fail_hip(e, "launching the local update");
             n_partials += launch_grid_size(r, shape);
@@ -499,7 +506,7 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
         for (const TileRange &r : g->ranges) {
             double *partials = l->d_norm_partials ? l->d_norm_partials + n_partials : nullptr;
             hipError_t e = launch_lps_merge((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_acc, l->alpha, keep,
-                                            partials, shape);
+                                            l->snapshot, partials, shape);
             if (e != hipSuccess) return fail_hip(e, "launching the merge");
             n_partials += launch_grid_size(r, shape);
         }

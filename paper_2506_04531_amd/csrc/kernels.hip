@@ -142,10 +142,13 @@ __device__ __forceinline__ void block_sum_store(double v, double *dst) {
 
 // ---------------------------------------------------------------------------------------------
 // S1: worker-delta step of a local server.
+// THIRD says what happens to the server's third buffer: 0 untouched, 1 running accumulation (acc <- acc + s),
+// 2 it holds the snapshot theta_{t_last} and this update completes the accumulation: it is overwritten with
+// G = theta_{t_last} - theta_t (Alg. 1 line 14, sign flipped).
 // With PULL the updated model is also written to a second tensor list (the buffer the worker starts
 // its next round from: Alg. 1 lines 11-12 in one pass instead of an update pass plus a copy pass).
 // With NORM every workgroup also leaves the sum of g^2 over its tiles in partials[blockIdx.x].
-template <typename GT, bool ACC, bool NT, bool PULL, bool NORM>
+template <typename GT, int THIRD, bool NT, bool PULL, bool NORM>
 __global__ void __launch_bounds__(BLOCK_THREADS)
 lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, uint32_t tensor_base,
                   float *const *__restrict__ theta_tab, float *const *__restrict__ m_tab,
@@ -158,7 +161,7 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
         const uint32_t tensor = tl.tensor;
         gf32 *th = to_global(theta_tab[tensor]) + tl.start;
         gf32 *mm = to_global(m_tab[tensor]) + tl.start;
-        gf32 *ac = ACC ? to_global(acc_tab[tensor]) + tl.start : nullptr;
+        gf32 *ac = THIRD != 0 ? to_global(acc_tab[tensor]) + tl.start : nullptr;
         gf32 *pd = PULL ? to_global(pull_tab[tensor]) + tl.start : nullptr;
         const auto *g = to_global(static_cast<const GT *>(gargs.p[tensor - tensor_base])) + tl.start;
         if (tl.len == TILE_ELEMS) {
@@ -169,7 +172,7 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
                 gv[u] = ldg4<NT>(g + off);
                 mv[u] = ld4<NT>(mm + off);
                 tv[u] = ld4<NT>(th + off);
-                if constexpr (ACC) av[u] = ld4<NT>(ac + off);
+                if constexpr (THIRD != 0) av[u] = ld4<NT>(ac + off);
             }
             if constexpr (NORM) {
                 float q = 0.f;
@@ -184,7 +187,8 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
                 st4<NT>(mm + off, mv[u]);
                 st4<NT>(th + off, tv[u]);
                 if constexpr (PULL) st4<NT>(pd + off, tv[u]);
-                if constexpr (ACC) st4<NT>(ac + off, add4(av[u], s));
+                if constexpr (THIRD == 1) st4<NT>(ac + off, add4(av[u], s));
+                if constexpr (THIRD == 2) st4<NT>(ac + off, sub4(av[u], tv[u]));
             }
         } else {
             const uint32_t len = tl.len;
@@ -196,7 +200,8 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
                     st4<NT>(mm + off, mv);
                     st4<NT>(th + off, tv);
                     if constexpr (PULL) st4<NT>(pd + off, tv);
-                    if constexpr (ACC) st4<NT>(ac + off, add4(ld4<NT>(ac + off), s));
+                    if constexpr (THIRD == 1) st4<NT>(ac + off, add4(ld4<NT>(ac + off), s));
+                    if constexpr (THIRD == 2) st4<NT>(ac + off, sub4(ld4<NT>(ac + off), tv));
                 } else {
                     for (uint32_t k = off; k < len; ++k) {      // ragged tail: fewer than 4 elements
                         float mv = mm[k], tv = th[k];
@@ -205,7 +210,8 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
                         const float s = model_update(tv, mv, gk, eta, beta, cg);
                         mm[k] = mv; th[k] = tv;
                         if constexpr (PULL) pd[k] = tv;
-                        if constexpr (ACC) ac[k] = __fadd_rn(ac[k], s);
+                        if constexpr (THIRD == 1) ac[k] = __fadd_rn(ac[k], s);
+                        if constexpr (THIRD == 2) ac[k] = __fsub_rn(ac[k], tv);
                     }
                 }
             }
@@ -270,7 +276,8 @@ gps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
 // ---------------------------------------------------------------------------------------------
 // S4: merge the returned global model into the local model and restart the accumulation.
 // With NORM every workgroup also leaves the sum of (theta - Theta_i)^2 before the merge in partials[blockIdx.x].
-template <bool NT, bool NORM>
+// With SNAP the third buffer receives the merged model (the new snapshot theta_{t_last}) instead of zeros.
+template <bool NT, bool NORM, bool SNAP>
 __global__ void __launch_bounds__(BLOCK_THREADS)
 lps_merge_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi,
                  float *const *__restrict__ theta_tab, float *const *__restrict__ inbox_tab, float alpha, float keep,
@@ -300,8 +307,9 @@ lps_merge_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
-                st4<NT>(th + off, merge4(tv[u], iv[u], alpha, keep));
-                st4<NT>(in + off, zero);
+                const f32x4 merged = merge4(tv[u], iv[u], alpha, keep);
+                st4<NT>(th + off, merged);
+                st4<NT>(in + off, SNAP ? merged : zero);
             }
         } else {
             const uint32_t len = tl.len;
@@ -309,8 +317,9 @@ lps_merge_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile
                 if (off + VEC <= len) {
                     const f32x4 tv = ld4<NT>(th + off), iv = ld4<NT>(in + off);
                     if constexpr (NORM) norm_acc += static_cast<double>(sumsq4(sub4(tv, iv), 0.f));
-                    st4<NT>(th + off, merge4(tv, iv, alpha, keep));
-                    st4<NT>(in + off, zero);
+                    const f32x4 merged = merge4(tv, iv, alpha, keep);
+                    st4<NT>(th + off, merged);
+                    st4<NT>(in + off, SNAP ? merged : zero);
                 } else {
                     for (uint32_t k = off; k < len; ++k) {
                         const float tk = th[k], ik = in[k];
@@ -318,8 +327,9 @@ lps_merge_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile
                             const float d = __fsub_rn(tk, ik);
                             norm_acc += static_cast<double>(__fmul_rn(d, d));
                         }
-                        th[k] = merge1(tk, ik, alpha, keep);
-                        in[k] = 0.f;
+                        const float merged = merge1(tk, ik, alpha, keep);
+                        th[k] = merged;
+                        in[k] = SNAP ? merged : 0.f;
                     }
                 }
             }
@@ -365,10 +375,11 @@ pull_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Alg. 1 line 6: theta <- Theta_0, m <- 0, acc <- 0.  With src_tab == nullptr only m is zero-filled.
+// Alg. 1 line 6: theta <- Theta_0, m <- 0, third buffer <- 0 (or <- Theta_0 if it is to hold the snapshot
+// theta_{t_last}).  With src_tab == nullptr only m is zero-filled.
 __global__ void __launch_bounds__(BLOCK_THREADS)
 init_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, float *const *src_tab,
-            float *const *theta_tab, float *const *m_tab, float *const *acc_tab) {
+            float *const *theta_tab, float *const *m_tab, float *const *acc_tab, bool snapshot) {
     const uint32_t tid = threadIdx.x;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
     for (uint32_t t = tile_lo + blockIdx.x; t < tile_hi; t += gridDim.x) {
@@ -383,13 +394,14 @@ init_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, 
             if (off + VEC <= len) {
                 st4<false>(mm + off, zero);
                 if (src_tab) {
-                    st4<false>(th + off, ld4<false>(src + off));
-                    st4<false>(ac + off, zero);
+                    const f32x4 v = ld4<false>(src + off);
+                    st4<false>(th + off, v);
+                    st4<false>(ac + off, snapshot ? v : zero);
                 }
             } else {
                 for (uint32_t k = off; k < len; ++k) {
                     mm[k] = 0.f;
-                    if (src_tab) { th[k] = src[k]; ac[k] = 0.f; }
+                    if (src_tab) { th[k] = src[k]; ac[k] = snapshot ? src[k] : 0.f; }
                 }
             }
         }
@@ -436,33 +448,37 @@ inline dim3 grid_for(TileRange r, LaunchShape shape) {
 uint32_t launch_grid_size(TileRange r, LaunchShape shape) { return r.hi > r.lo ? grid_for(r, shape).x : 0u; }
 
 hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
-                             float *const *acc, float *const *pull, const PtrArgs &g, bool g_is_bf16, bool accumulate,
+                             float *const *acc, float *const *pull, const PtrArgs &g, bool g_is_bf16, int third_mode,
                              float eta, float beta, float cg, double *norm_partials, LaunchShape shape) {
     if (r.hi <= r.lo) return hipSuccess;
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
-#define HALOS_LAUNCH_UPD(GT, ACC, NT, PULL)                                                                              \
+#define HALOS_LAUNCH_UPD(GT, THIRD, NT, PULL)                                                                              \
     do {                                                                                                                 \
         if (norm_partials)                                                                                               \
-            lps_update_kernel<GT, ACC, NT, PULL, true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, r.tensor_base, theta, \
+            lps_update_kernel<GT, THIRD, NT, PULL, true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, r.tensor_base, theta, \
                                                                                    m, acc, pull, g, eta, beta, cg,       \
                                                                                    norm_partials);                       \
         else                                                                                                             \
-            lps_update_kernel<GT, ACC, NT, PULL, false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, r.tensor_base,     \
+            lps_update_kernel<GT, THIRD, NT, PULL, false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, r.tensor_base,     \
                                                                                     theta, m, acc, pull, g, eta, beta,   \
                                                                                     cg, nullptr);                        \
     } while (0)
-#define HALOS_LAUNCH_UPD_NT(GT, ACC, PULL) \
-    do { if (shape.nontemporal) HALOS_LAUNCH_UPD(GT, ACC, true, PULL); else HALOS_LAUNCH_UPD(GT, ACC, false, PULL); } while (0)
-    const int variant = (g_is_bf16 ? 4 : 0) | (accumulate ? 2 : 0) | (pull ? 1 : 0);
+#define HALOS_LAUNCH_UPD_NT(GT, THIRD, PULL) \
+    do { if (shape.nontemporal) HALOS_LAUNCH_UPD(GT, THIRD, true, PULL); else HALOS_LAUNCH_UPD(GT, THIRD, false, PULL); } while (0)
+    const int variant = (g_is_bf16 ? 6 : 0) + 2 * third_mode + (pull ? 1 : 0);
     switch (variant) {
-        case 0: HALOS_LAUNCH_UPD_NT(float, false, false); break;
-        case 1: HALOS_LAUNCH_UPD_NT(float, false, true); break;
-        case 2: HALOS_LAUNCH_UPD_NT(float, true, false); break;
-        case 3: HALOS_LAUNCH_UPD_NT(float, true, true); break;
-        case 4: HALOS_LAUNCH_UPD_NT(unsigned short, false, false); break;
-        case 5: HALOS_LAUNCH_UPD_NT(unsigned short, false, true); break;
-        case 6: HALOS_LAUNCH_UPD_NT(unsigned short, true, false); break;
-        default: HALOS_LAUNCH_UPD_NT(unsigned short, true, true); break;
+        case 0: HALOS_LAUNCH_UPD_NT(float, 0, false); break;
+        case 1: HALOS_LAUNCH_UPD_NT(float, 0, true); break;
+        case 2: HALOS_LAUNCH_UPD_NT(float, 1, false); break;
+        case 3: HALOS_LAUNCH_UPD_NT(float, 1, true); break;
+        case 4: HALOS_LAUNCH_UPD_NT(float, 2, false); break;
+        case 5: HALOS_LAUNCH_UPD_NT(float, 2, true); break;
+        case 6: HALOS_LAUNCH_UPD_NT(unsigned short, 0, false); break;
+        case 7: HALOS_LAUNCH_UPD_NT(unsigned short, 0, true); break;
+        case 8: HALOS_LAUNCH_UPD_NT(unsigned short, 1, false); break;
+        case 9: HALOS_LAUNCH_UPD_NT(unsigned short, 1, true); break;
+        case 10: HALOS_LAUNCH_UPD_NT(unsigned short, 2, false); break;
+        default: HALOS_LAUNCH_UPD_NT(unsigned short, 2, true); break;
     }
 #undef HALOS_LAUNCH_UPD_NT
 #undef HALOS_LAUNCH_UPD
@@ -481,20 +497,24 @@ hipError_t launch_gps_update(hipStream_t stream, const Tile *tiles, TileRange r,
 }
 
 hipError_t launch_lps_merge(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
-                            float *const *inbox, float alpha, float keep, double *norm_partials, LaunchShape shape) {
+                            float *const *inbox, float alpha, float keep, bool snapshot, double *norm_partials,
+                            LaunchShape shape) {
     if (r.hi <= r.lo) return hipSuccess;
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
-    if (norm_partials) {
-        if (shape.nontemporal)
-            lps_merge_kernel<true, true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, inbox, alpha, keep, norm_partials);
-        else
-            lps_merge_kernel<false, true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, inbox, alpha, keep, norm_partials);
-    } else {
-        if (shape.nontemporal)
-            lps_merge_kernel<true, false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, inbox, alpha, keep, nullptr);
-        else
-            lps_merge_kernel<false, false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, inbox, alpha, keep, nullptr);
+#define HALOS_LAUNCH_MERGE(NT, NORM, SNAP) \
+    lps_merge_kernel<NT, NORM, SNAP><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, inbox, alpha, keep, norm_partials)
+    const int variant = (shape.nontemporal ? 4 : 0) | (norm_partials ? 2 : 0) | (snapshot ? 1 : 0);
+    switch (variant) {
+        case 0: HALOS_LAUNCH_MERGE(false, false, false); break;
+        case 1: HALOS_LAUNCH_MERGE(false, false, true); break;
+        case 2: HALOS_LAUNCH_MERGE(false, true, false); break;
+        case 3: HALOS_LAUNCH_MERGE(false, true, true); break;
+        case 4: HALOS_LAUNCH_MERGE(true, false, false); break;
+        case 5: HALOS_LAUNCH_MERGE(true, false, true); break;
+        case 6: HALOS_LAUNCH_MERGE(true, true, false); break;
+        default: HALOS_LAUNCH_MERGE(true, true, true); break;
     }
+#undef HALOS_LAUNCH_MERGE
     return hipGetLastError();
 }
 
@@ -515,10 +535,10 @@ hipError_t launch_pull(hipStream_t stream, const Tile *tiles, TileRange r, float
 }
 
 hipError_t launch_init(hipStream_t stream, const Tile *tiles, TileRange r, float *const *src, float *const *theta,
-                       float *const *m, float *const *acc, LaunchShape shape) {
+                       float *const *m, float *const *acc, bool snapshot, LaunchShape shape) {
     if (r.hi <= r.lo) return hipSuccess;
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
-    init_kernel<<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, src, theta, m, acc);
+    init_kernel<<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, src, theta, m, acc, snapshot);
     return hipGetLastError();
 }
 

@@ -39,13 +39,15 @@ struct TileRange {      // tiles [lo, hi) all belong to tensors [tensor_base, te
 };
 
 // Worker-delta step of a local server: m <- beta m + g; s = eta (cg g + beta m); theta <- theta - s;
-// if accumulate: acc <- acc + s.   (ModelUpdate of App. E fused with the accumulation of Alg. 1 line 14.)
+// third_mode 1: acc <- acc + s (ModelUpdate of App. E fused with the accumulation of Alg. 1 line 14);
+// third_mode 2: the third buffer holds theta_{t_last} and is overwritten with theta_{t_last} - theta_t (line 14 as
+// written, sign flipped); third_mode 0: the third buffer is not touched.
 // If `pull` is not null it is a device table of destination tensors that also receive the updated theta
 // (Alg. 1 line 12, the model handed back to the worker, written in the same pass).
 // If `norm_partials` is not null the launch also leaves, per workgroup, the sum of g^2 over the workgroup's tiles in
 // norm_partials[0 .. launch_grid_size(r, shape)).
 hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
-                             float *const *acc, float *const *pull, const PtrArgs &g, bool g_is_bf16, bool accumulate,
+                             float *const *acc, float *const *pull, const PtrArgs &g, bool g_is_bf16, int third_mode,
                              float eta, float beta, float cg, double *norm_partials, LaunchShape shape);
 
 // Number of workgroups a launch over range r uses (0 for an empty range).
@@ -61,16 +63,19 @@ hipError_t launch_gps_update(hipStream_t stream, const Tile *tiles, TileRange r,
 
 // Merge step of a local server: theta <- alpha * inbox + keep * theta (keep = 1 - alpha); inbox buffer <- 0.
 // With `norm_partials`: per workgroup, the sum of (theta - inbox)^2 before the merge (same layout as above).
+// `snapshot`: the inbox buffer receives the merged model (the new theta_{t_last}) instead of zeros.
 hipError_t launch_lps_merge(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
-                            float *const *inbox, float alpha, float keep, double *norm_partials, LaunchShape shape);
+                            float *const *inbox, float alpha, float keep, bool snapshot, double *norm_partials,
+                            LaunchShape shape);
 
 // dst <- src (fp32), dst pointers in the argument block.
 hipError_t launch_pull(hipStream_t stream, const Tile *tiles, TileRange r, float *const *src, const PtrArgs &dst,
                        LaunchShape shape);
 
 // theta <- src; m <- 0; acc <- 0   (Alg. 1 line 6).  src == nullptr: only zero-fill `m` (used for the GPS momentum).
+// `snapshot`: acc <- src instead of 0.
 hipError_t launch_init(hipStream_t stream, const Tile *tiles, TileRange r, float *const *src, float *const *theta,
-                       float *const *m, float *const *acc, LaunchShape shape);
+                       float *const *m, float *const *acc, bool snapshot, LaunchShape shape);
 
 // Sweep the first n_tiles * TILE_ELEMS floats of two buffers (read both, write both back unchanged).
 hipError_t launch_probe_pair(hipStream_t stream, float *a, float *b, uint32_t n_tiles, LaunchShape shape);

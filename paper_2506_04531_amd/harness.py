@@ -214,6 +214,7 @@ class Cluster:
         fill_initial_model(w, self.Theta)
         self.hp = hp if hp is not None else B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0],
                                                                  cg_l=w.cg_l, cg_g=w.cg_g)
+        self.snapshot = bool(self.hp.flags & B.FLAG_SNAPSHOT)
         self.gps = B.halos_gps_create(self.numel, self.hp, self.Theta, self.M)
         self.theta, self.m, self.acc, self.lps = [], [], [], []
         for l in range(w.n_lps):
@@ -264,7 +265,8 @@ class Cluster:
         sp = stream.cuda_stream or None
         log = []
         timings: Dict[str, list] = {"lps_update_acc": [], "lps_update_noacc": [], "lps_update_acc_pull": [],
-                                    "lps_update_noacc_pull": [], "gps_update": [], "lps_merge": [], "pull": []}
+                                    "lps_update_noacc_pull": [], "lps_update_freeze": [], "lps_update_freeze_pull": [],
+                                    "gps_update": [], "lps_merge": [], "pull": []}
         fuse_pull = fuse_pull and self._pull_ptrs is not None
         skip = -1
         info = B.StepInfo()
@@ -299,7 +301,10 @@ class Cluster:
                 if int(ev["exp_kind"]) == 2:
                     label = "lps_merge"
                 else:
-                    label = "lps_update_acc" if int(ev["exp_accumulate"]) else "lps_update_noacc"
+                    if self.snapshot:      # third buffer untouched except by the update that completes the accumulation
+                        label = "lps_update_freeze" if int(ev["exp_send"]) else "lps_update_noacc"
+                    else:
+                        label = "lps_update_acc" if int(ev["exp_accumulate"]) else "lps_update_noacc"
                     if fuse_pull and i + 1 < n_ev:
                         nx = events[i + 1]
                         fused = (int(nx["kind"]) == _PULL and int(nx["lps"]) == l and int(nx["worker"]) == int(ev["worker"]))

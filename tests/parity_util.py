@@ -67,12 +67,14 @@ def oracle_run(w: synth.Workload, trace: synth.Trace, idx: Optional[np.ndarray],
     return o, log
 
 
-def oracle_state(o: HalosOracle, n_lps: int, with_scale: bool = True):
+def oracle_state(o: HalosOracle, n_lps: int, with_scale: bool = True, snapshot_form: bool = False):
+    """Every state array of the oracle (value, error scale).  snapshot_form: the third buffers as an implementation
+    that keeps theta_{t_last} holds them (only meaningful for an oracle created with FORM_LITERAL)."""
     names = {"Theta": (O.GPS_THETA, 0), "M": (O.GPS_MOM, 0)}
     for l in range(n_lps):
         names[f"theta{l}"] = (O.THETA, l)
         names[f"m{l}"] = (O.MOM, l)
-        names[f"aux{l}"] = (O.AUX, l)
+        names[f"aux{l}"] = (O.AUX_SNAPSHOT if snapshot_form else O.AUX, l)
     out = {}
     for k, (what, l) in names.items():
         out[k] = (o.get(what, l), o.get(what + O.SCALE, l) if with_scale else None)

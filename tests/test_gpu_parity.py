@@ -389,3 +389,39 @@ def test_replay_on_a_side_stream():
             c.close()
     for k in out[0]:
         assert np.array_equal(out[0][k].view(np.uint32), out[1][k].view(np.uint32)), k
+
+
+@pytest.mark.parametrize("recipe", ["70m", "160m", "410m"])
+def test_snapshot_form_every_element(recipe):
+    """HALOS_FLAG_SNAPSHOT: Delta by subtraction of the snapshot theta_{t_last} (Alg. 1 line 14 as written).  Bit-exact
+    against the fp32 literal-form oracle, within tolerance of the fp64 reference, third buffers included."""
+    from paper_2506_04531_amd import binding as B
+    base = synth.get_workload(recipe)
+    w = base.scaled(RAGGED if recipe == "410m" else synth.gpt_layout(96, 2, vocab=1031), n_updates=120, name=recipe + "-snap")
+    trace = synth.make_trace(w)
+    hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0], flags=B.FLAG_SNAPSHOT)
+    c = _cluster(w, trace, hp=hp)
+    try:
+        gpu_log, _ = c.replay(trace.events, fuse_pull=True)
+        torch.cuda.synchronize()
+        gpu = {k: c.flat(k) for k in c.state_lists()}
+    finally:
+        c.close()
+    o32, log32 = oracle_run(w, trace, None, 32, FORM_LITERAL)
+    check_step_logs(trace, gpu_log, log32)
+    worst, n_diff, name = compare_state(gpu, oracle_state(o32, w.n_lps, snapshot_form=True), bitwise=True)
+    assert n_diff == 0, (n_diff, worst, name)
+    # Against fp64: a Delta formed by subtracting two model-sized fp32 numbers carries rounding error of the MODEL's
+    # size (2^-24 of |theta|), and passes it on to the GPS momentum.  So in this form M and the third buffers are held
+    # to 1e-5 of the model's scale, not of their own much smaller one -- the price of saving 8 bytes per update.
+    o64, _ = oracle_run(w, trace, None, 64, FORM_LITERAL)
+    ref = oracle_state(o64, w.n_lps, snapshot_form=True)
+    model_scale = ref["Theta"][1]
+    for k in list(ref):
+        if k == "M" or k.startswith("aux"):
+            ref[k] = (ref[k][0], np.maximum(ref[k][1], model_scale))
+    worst, _, name = compare_state(gpu, ref, bitwise=False)
+    own_scale_worst, _, own_name = compare_state(gpu, oracle_state(o64, w.n_lps, snapshot_form=True), bitwise=False)
+    print(f"[parity] {w.name}: snapshot form bit-exact vs fp32 literal oracle; vs fp64: {worst:.3g} of the model scale "
+          f"({name}), {own_scale_worst:.3g} of each array's own scale ({own_name})", flush=True)
+    assert worst <= REL_TOL, (worst, name)
