@@ -122,7 +122,9 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
         kernels[label] = {
             "launches": int(ms.size),
             "avg_ms": float(ms.mean()),
+            "p10_ms": float(np.percentile(ms, 10)),
             "p50_ms": float(np.median(ms)),
+            "p90_ms": float(np.percentile(ms, 90)),
             "bytes_per_param": bpp,
             "achieved_GBps": float(N * bpp / (ms.mean() * 1e-3) / 1e9),
             "params_per_s": float(N / (ms.mean() * 1e-3)),

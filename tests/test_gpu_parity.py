@@ -71,16 +71,17 @@ def test_scaled_down_workloads_every_element(recipe):
 
 @pytest.mark.parametrize("name", ["70m", "160m", "410m", "1b", "paper-410m"])
 def test_full_size_workloads_on_sampled_elements(name):
-    """Full benchmark sizes in the benchmark's launch configuration.  Every step is elementwise, so the
-    oracle replays exactly the sampled elements (random ones plus every tensor and tile boundary)."""
+    """Full benchmark sizes in the configuration bench.py times (state placed by HBM region, worker pulls fused into
+    the update pass, default launch shape).  Every step is elementwise, so the oracle replays exactly the sampled
+    elements (random ones plus every tensor and tile boundary)."""
     w = synth.get_workload(name)
     trace = synth.make_trace(w)
     idx = sample_indices(w.layout, 1 << 17, seed=5)
     print(f"[parity] workload={name} full size n={w.layout.total} sample={idx.size} events={len(trace.events)}", flush=True)
     tidx = torch.from_numpy(idx)
-    c = _cluster(w, trace)
+    c = _cluster(w, trace, placement="regions")
     try:
-        gpu_log, _ = c.replay(trace.events)
+        gpu_log, _ = c.replay(trace.events, fuse_pull=True)
         torch.cuda.synchronize()
         gpu = {k: c.gather(k, tidx) for k in c.state_lists()}
         # the last pull of every LPS copied the model it had at that moment; the final pull target of the
