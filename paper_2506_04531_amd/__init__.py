@@ -34,6 +34,16 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
     if verbose:
         print(res.stderr)
+    # a client of the ABI written in plain C (tests/host/abi_client.c), linked against the library just built
+    client_src = os.path.join(os.path.dirname(_HERE), "tests", "host", "abi_client.c")
+    if os.path.exists(client_src):
+        client = os.path.join(os.path.dirname(client_src), "abi_client")
+        cmd = ["gcc", "-std=c11", "-O1", "-Wall", "-I/opt/rocm/include", "-D__HIP_PLATFORM_AMD__", "-o", client,
+               client_src, "-L" + _HERE, "-lhalos", "-L/opt/rocm/lib", "-lamdhip64",
+               "-Wl,-rpath,$ORIGIN/../../paper_2506_04531_amd", "-Wl,-rpath,/opt/rocm/lib"]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("gcc failed on the C client:\n" + res.stdout + res.stderr)
     return LIB_PATH
 
 

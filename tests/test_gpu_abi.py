@@ -222,3 +222,15 @@ def test_hand_derived_worked_example_through_the_library():
         for h in lps:
             B.halos_lps_destroy(h)
         B.halos_gps_destroy(gps)
+
+
+def test_plain_c_client_of_the_abi():
+    """tests/host/abi_client.c: the boundary used from C with hipMalloc'ed memory, no Python in the loop."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "host", "abi_client")
+    assert os.path.exists(exe), "abi_client is built by __graft_entry__.build()"
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    print(res.stdout, res.stderr)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert "all values as derived" in res.stdout
