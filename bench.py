@@ -46,8 +46,8 @@ BYTES = {
 # only for the kernel source it was measured on: {sha256 of kernels.hip: {kernel label: bytes/param}}.
 MEASURED_TRAFFIC: dict = {
     # profiles/lps_update_1b_hbm_traffic.md
-    "d1f334747cb9dfceffb9403b951175d7a3868bc7fbf365d8357d7eafe7153613": {
-        "1b:lps_update_acc_pull": 30.034, "1b:lps_update_noacc_pull": 22.033,
+    "fed6c6a49b64eebab3891b61aac58572ba41632c5f2075300900342ee1bcdf4e": {
+        "1b:lps_update_acc_pull": 30.033, "1b:lps_update_noacc_pull": 22.033,
     },
 }
 

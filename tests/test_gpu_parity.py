@@ -426,3 +426,12 @@ def test_snapshot_form_every_element(recipe):
     print(f"[parity] {w.name}: snapshot form bit-exact vs fp32 literal oracle; vs fp64: {worst:.3g} of the model scale "
           f"({name}), {own_scale_worst:.3g} of each array's own scale ({own_name})", flush=True)
     assert worst <= REL_TOL, (worst, name)
+
+
+@pytest.mark.parametrize("seed", [101, 102, 103, 104, 105, 106])
+def test_many_schedules_on_a_ragged_list(seed):
+    """Different arrival orders, queue depths and accumulation counts (the seed changes the whole schedule)."""
+    from dataclasses import replace
+    base = synth.get_workload("160m" if seed % 2 else "410m")
+    w = replace(base.scaled(RAGGED, n_updates=64, name=f"seed{seed}"), seed=seed)
+    _full_parity(w, synth.make_trace(w, seed=seed))
