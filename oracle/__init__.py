@@ -17,6 +17,7 @@ _SRC = os.path.join(_HERE, "halos_oracle.cpp")
 _LIB = os.path.join(_HERE, "libhalos_oracle.so")
 
 THETA, MOM, AUX, GPS_THETA, GPS_MOM, AUX_SNAPSHOT = 0, 1, 2, 3, 4, 5
+BUFFER, GPS_BUFFER = 6, 7   # gradient buffers of the delayed momentum (an LPS's, the GPS's)
 SCALE = 10   # add to the ids above for the running max-magnitude of the same array
 
 FORM_LITERAL = 0       # Delta by snapshot subtraction (Algorithm 1 line 14 as written)
@@ -54,6 +55,8 @@ def _load():
         lib.ho_lps_step.argtypes = [vp, i32, ctypes.POINTER(StepInfo)]
         lib.ho_gps_receive.argtypes = [vp, i32]
         lib.ho_set_K.argtypes = [vp, i32, i32]
+        lib.ho_set_delay.argtypes = [vp, i32, i32]
+        lib.ho_delay_seen.argtypes = [vp, i32]
         lib.ho_set_rules.argtypes = [vp, f32, f32, f32, f32, f32, f32, f32]
         lib.ho_get.argtypes = [vp, i32, i32, vp]
         lib.ho_counters.argtypes = [vp, i32] + [vp] * 5
@@ -132,6 +135,14 @@ class HalosOracle:
 
     def set_K(self, l: int, K: int):
         self._chk(self._lib.ho_set_K(self._h, l, K), "set_K")
+
+    def set_delay(self, which: int, d: int):
+        """Delayed Nesterov momentum with delay d >= 1 for LPS `which` (or the GPS if which < 0); d = 0 switches back
+        to the plain rule.  Only between cycles."""
+        self._chk(self._lib.ho_set_delay(self._h, which, d), "set_delay")
+
+    def delay_seen(self, which: int) -> int:
+        return int(self._lib.ho_delay_seen(self._h, which))
 
     def set_rules(self, *, eta_l, beta_l, cg_l, eta_g, beta_g, cg_g, alpha):
         f = np.float32

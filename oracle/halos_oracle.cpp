@@ -35,6 +35,17 @@
 //     was applied, even if other LPSs update the GPS before it is merged.
 //   * Delta is applied at the GPS unnormalised (no 1/K, no 1/M).
 //
+// Delayed Nesterov momentum (optional, per tier).  The paper's runs use, at both tiers, the delayed
+// Nesterov optimizer of the Async-Local-SGD work it cites (Sec. 5.1; App. D lists the delays d_l, d_g and
+// says the method "effectively divides the learning rate by the delay interval"), but does not restate
+// it.  The rule implemented here is that published algorithm with its default momentum activation of
+// zero, carried over to this paper's ModelUpdate by keeping the coefficient cg on the gradient term:
+//     every update:        buffer <- buffer + grad;  x <- x - eta * (cg / d) * grad
+//     every d-th update:   m <- beta * m + buffer / d;  x <- x - eta * [ (cg / d) * grad + beta * m ];
+//                          buffer <- 0
+// With d = 1 every update is a "d-th" one and the rule is exactly ModelUpdate above.  The buffer and the
+// position in the cycle belong to the server; merges do not touch them.
+//
 // Two numerical forms are provided and selected at creation:
 //   form 0 (literal)      keeps the snapshot theta_{t_last} and forms Delta by
 //                         subtraction exactly as Algorithm 1 line 14 writes it;
@@ -92,6 +103,33 @@ inline R model_update(R &x, R &m, R grad, const Rule<R> &r) {
     return step;
 }
 
+// Delayed Nesterov momentum: one server's position in its cycle of d updates.
+template <class R>
+struct Delay {
+    bool enabled = false;   // false: plain ModelUpdate (the default); true: the delayed rule, also for d = 1
+    int32_t d = 1;
+    int32_t seen = 0;       // updates applied since the last momentum refresh, 0 .. d-1
+    R inv_d = R(1);         // 1 / d
+    void set(int32_t d_) { enabled = true; d = d_; seen = 0; inv_d = R(1) / R(d_); }
+};
+
+// One element of the delayed rule.  `first`: this update opens a cycle (the buffer holds nothing yet);
+// `refresh`: it closes one (momentum is refreshed from the cycle's mean gradient and applied).
+template <class R>
+inline R delayed_update(R &x, R &m, R &buffer, R grad, const Rule<R> &r, R inv_d, bool first, bool refresh) {
+    buffer = first ? grad : buffer + grad;               // sum of the cycle's gradients so far
+    const R grad_part = (r.cg * inv_d) * grad;           // the rate on the gradient is divided by d
+    R direction = grad_part;
+    if (refresh) {
+        m = std::fma(r.beta, m, buffer * inv_d);         // m <- beta m + mean gradient of the cycle
+        direction = std::fma(r.beta, m, grad_part);
+        buffer = R(0);
+    }
+    R applied = r.eta * direction;
+    x = x - applied;
+    return applied;
+}
+
 // Error-scale bookkeeping (not part of the algorithm).  A reduced-precision implementation's error
 // in an element is proportional to the largest magnitudes that ever flowed into it, not to its current
 // value: momentum that has cancelled down to almost nothing still carries the rounding error of its
@@ -110,6 +148,21 @@ inline R step_scale(R m_scale, R grad_scale, const Rule<R> &r) {
 template <class R>
 inline void raise_to(R &scale, R v) { if (v > scale) scale = v; }
 
+// The same bookkeeping for the delayed rule: the buffer's scale is the sum of the magnitudes added to it, the
+// momentum's scale rises to the mean it absorbs at a refresh; returns the step's scale.
+template <class R>
+inline R delayed_scales(R &m_scale, R &buffer_scale, R m_now, R grad, const Rule<R> &r, R inv_d, bool first, bool refresh) {
+    const R g_mag = std::fabs(grad);
+    buffer_scale = first ? g_mag : buffer_scale + g_mag;
+    R terms = std::fabs(r.eta) * std::fabs(r.cg) * inv_d * g_mag;
+    if (refresh) {
+        raise_to(m_scale, buffer_scale * inv_d);
+        raise_to(m_scale, std::fabs(m_now));
+        terms += std::fabs(r.eta) * std::fabs(r.beta) * m_scale;
+    }
+    return terms;
+}
+
 template <class R>
 struct QueueItem {
     int kind;
@@ -125,6 +178,8 @@ struct Lps {
     std::vector<R> frozen;       // G = theta_{t_last} - theta_t at the send (= -Delta)
     std::vector<R> inbox;        // the global model returned for this LPS
     std::vector<R> sc_theta, sc_m, sc_aux;   // error scales, see step_scale()
+    Delay<R> delay;              // delayed Nesterov momentum of this server
+    std::vector<R> buffer, sc_buffer;        // its gradient buffer (sum over the open cycle) and error scale
     std::deque<QueueItem<R>> queue;
     std::vector<char> worker_queued;
     int64_t t = 0, t_last = 0;
@@ -142,6 +197,8 @@ struct Oracle {
     Rule<R> local, global;
     R alpha;
     std::vector<R> Theta, M, sc_Theta, sc_M;
+    Delay<R> gps_delay;
+    std::vector<R> gps_buffer, sc_gps_buffer;
     int64_t gps_updates = 0;
     std::vector<Lps<R>> lps;
 
@@ -158,6 +215,7 @@ struct Oracle {
         Theta.assign(theta0, theta0 + n);
         M.assign(n, R(0));
         sc_Theta.assign(n, R(0)); sc_M.assign(n, R(0));
+        gps_buffer.assign(n, R(0)); sc_gps_buffer.assign(n, R(0));
         grow(sc_Theta, Theta);
         lps.resize(n_lps);
         for (int l = 0; l < n_lps; ++l) {
@@ -169,6 +227,7 @@ struct Oracle {
             s.frozen.assign(n, R(0));
             s.inbox.assign(n, R(0));
             s.sc_theta.assign(n, R(0)); s.sc_m.assign(n, R(0)); s.sc_aux.assign(n, R(0));
+            s.buffer.assign(n, R(0)); s.sc_buffer.assign(n, R(0));
             grow(s.sc_theta, s.theta);
             s.K = K[l];
         }
@@ -209,13 +268,20 @@ struct Oracle {
             const bool accumulate = (s.phase == ACCUMULATING);
             s.last_delta_sq = 0.0;
             for (int64_t j = 0; j < n; ++j) s.last_delta_sq += (double)it.grad[j] * (double)it.grad[j];
+            const bool first = s.delay.seen == 0, refresh = s.delay.seen + 1 == s.delay.d;
             for (int64_t j = 0; j < n; ++j) {                           // line 11
                 const R grad = R(it.grad[j]);
-                R step = model_update<R>(s.theta[j], s.m[j], grad, local);
+                R step, terms;
+                if (s.delay.enabled) {
+                    step = delayed_update<R>(s.theta[j], s.m[j], s.buffer[j], grad, local, s.delay.inv_d, first, refresh);
+                    terms = delayed_scales<R>(s.sc_m[j], s.sc_buffer[j], s.m[j], grad, local, s.delay.inv_d, first, refresh);
+                } else {
+                    step = model_update<R>(s.theta[j], s.m[j], grad, local);
+                    raise_to(s.sc_m[j], std::fabs(grad));
+                    raise_to(s.sc_m[j], std::fabs(s.m[j]));
+                    terms = step_scale<R>(s.sc_m[j], std::fabs(grad), local);
+                }
                 if (form == 1 && accumulate) s.acc[j] = s.acc[j] + step;
-                raise_to(s.sc_m[j], std::fabs(grad));
-                raise_to(s.sc_m[j], std::fabs(s.m[j]));
-                const R terms = step_scale<R>(s.sc_m[j], std::fabs(grad), local);
                 raise_to(s.sc_theta[j], terms);
                 raise_to(s.sc_theta[j], std::fabs(s.theta[j]));
                 if (accumulate) {
@@ -223,6 +289,7 @@ struct Oracle {
                     raise_to(s.sc_aux[j], std::fabs(form == 1 ? s.acc[j] : s.snap[j] - s.theta[j]));
                 }
             }
+            if (s.delay.enabled) s.delay.seen = refresh ? 0 : s.delay.seen + 1;
             s.worker_queued[it.worker] = 0;
             out.kind = 1; out.worker = it.worker; out.accumulated = accumulate ? 1 : 0;
             if (accumulate && s.t - s.t_last >= s.K) {                  // line 13
@@ -261,13 +328,22 @@ struct Oracle {
         Lps<R> &s = lps[l];
         if (s.phase != SENT) return -2;
         gps_updates += 1;
+        const bool first = gps_delay.seen == 0, refresh = gps_delay.seen + 1 == gps_delay.d;
         for (int64_t j = 0; j < n; ++j) {
+            if (gps_delay.enabled) {
+                delayed_update<R>(Theta[j], M[j], gps_buffer[j], s.frozen[j], global, gps_delay.inv_d, first, refresh);
+                raise_to(sc_Theta[j], delayed_scales<R>(sc_M[j], sc_gps_buffer[j], M[j], s.sc_aux[j], global,
+                                                        gps_delay.inv_d, first, refresh));
+                raise_to(sc_Theta[j], std::fabs(Theta[j]));
+                continue;
+            }
             model_update<R>(Theta[j], M[j], s.frozen[j], global);       // line 3
             raise_to(sc_M[j], s.sc_aux[j]);                             // the scale of G travels with it
             raise_to(sc_M[j], std::fabs(M[j]));
             raise_to(sc_Theta[j], step_scale<R>(sc_M[j], s.sc_aux[j], global));
             raise_to(sc_Theta[j], std::fabs(Theta[j]));
         }
+        if (gps_delay.enabled) gps_delay.seen = refresh ? 0 : gps_delay.seen + 1;
         s.inbox = Theta;                                                // line 4: this Theta_i, frozen
         s.sc_aux = sc_Theta;
         s.phase = RETURNING;
@@ -316,13 +392,17 @@ void copy_out(const std::vector<R> &v, double *out) {
 
 template <class R>
 int get_impl(Oracle<R> *o, int what, int l, double *out) {
-    if (((what >= 0 && what <= 2) || what == 5 || what == 15) && (l < 0 || (size_t)l >= o->lps.size())) return -1;
+    if (((what >= 0 && what <= 2) || what == 5 || what == 6 || what == 15 || what == 16) && (l < 0 || (size_t)l >= o->lps.size())) return -1;
     switch (what) {
         case 0: copy_out(o->lps[l].theta, out); return 0;
         case 1: copy_out(o->lps[l].m, out); return 0;
         case 2: { std::vector<R> a; o->aux(l, a); copy_out(a, out); return 0; }
         case 5: { std::vector<R> a, sc; aux_snapshot_form(*o, l, a, sc); copy_out(a, out); return 0; }
         case 15: { std::vector<R> a, sc; aux_snapshot_form(*o, l, a, sc); copy_out(sc, out); return 0; }
+        case 6: copy_out(o->lps[l].buffer, out); return 0;
+        case 7: copy_out(o->gps_buffer, out); return 0;
+        case 16: copy_out(o->lps[l].sc_buffer, out); return 0;
+        case 17: copy_out(o->sc_gps_buffer, out); return 0;
         case 3: copy_out(o->Theta, out); return 0;
         case 4: copy_out(o->M, out); return 0;
         case 10: copy_out(o->lps[l].sc_theta, out); return 0;
@@ -397,6 +477,30 @@ int ho_set_K(void *p, int32_t l, int32_t K) {
     return 0;
 }
 
+// Switch a tier to the delayed rule with delay d >= 1 (d = 0: back to plain ModelUpdate).  which: -1 the GPS,
+// otherwise the index of an LPS.  Only between cycles.
+int ho_set_delay(void *p, int32_t which, int32_t d) {
+    Handle *h = (Handle *)p;
+    if (d < 0) return -1;
+    if (h->precision == 32) {
+        auto &dl = which < 0 ? h->f->gps_delay : h->f->lps[which].delay;
+        if (dl.seen != 0) return -2;
+        if (d == 0) dl = decltype(h->f->gps_delay)(); else dl.set(d);
+    } else {
+        auto &dl = which < 0 ? h->d->gps_delay : h->d->lps[which].delay;
+        if (dl.seen != 0) return -2;
+        if (d == 0) dl = decltype(h->d->gps_delay)(); else dl.set(d);
+    }
+    return 0;
+}
+
+// Updates applied since the last momentum refresh (0 .. d-1) of the GPS (which = -1) or an LPS.
+int ho_delay_seen(void *p, int32_t which) {
+    Handle *h = (Handle *)p;
+    if (h->precision == 32) return which < 0 ? h->f->gps_delay.seen : h->f->lps[which].delay.seen;
+    return which < 0 ? h->d->gps_delay.seen : h->d->lps[which].delay.seen;
+}
+
 int ho_set_rules(void *p, float eta_l, float beta_l, float cg_l, float eta_g, float beta_g, float cg_g, float alpha) {
     Handle *h = (Handle *)p;
     if (h->precision == 32) {
@@ -409,7 +513,7 @@ int ho_set_rules(void *p, float eta_l, float beta_l, float cg_l, float eta_g, fl
 
 // what: 0 theta_l, 1 m_l, 2 third buffer of l (accumulation / frozen G / returned model),
 //       3 Theta, 4 M, 5 third buffer of l in snapshot form (theta_{t_last} / frozen G / returned model);
-//       10..15 the error scales of the same six arrays.
+//       6 gradient buffer of l's delayed momentum, 7 the GPS's; 10..17 the error scales of the same arrays.
 int ho_get(void *p, int32_t what, int32_t l, double *out) {
     Handle *h = (Handle *)p;
     return h->precision == 32 ? get_impl(h->f, what, l, out) : get_impl(h->d, what, l, out);

@@ -9,6 +9,7 @@ import pytest
 
 import oracle as O
 import test_oracle_pins as pins
+import test_oracle_delayed_momentum as dpins
 
 SRC = os.path.join(os.path.dirname(os.path.abspath(O.__file__)), "halos_oracle.cpp")
 
@@ -40,6 +41,19 @@ MUTANTS = [
      "QueueItem<R> it = std::move(s.queue.back());\n        s.queue.pop_back();"),
     ("bf16 placed in the low half", "uint32_t u = (uint32_t)bits << 16;", "uint32_t u = (uint32_t)bits;"),
     ("t counts merges too", "out.kind = 2;", "out.kind = 2; s.t += 1;"),
+    # delayed Nesterov momentum
+    ("delayed: step added instead of subtracted", "x = x - applied;", "x = x + applied;"),
+    ("delayed: buffer not cleared at the refresh", "        buffer = R(0);\n", ""),
+    ("delayed: momentum takes the sum, not the mean", "m = std::fma(r.beta, m, buffer * inv_d);", "m = std::fma(r.beta, m, buffer);"),
+    ("delayed: gradient rate not divided by d", "const R grad_part = (r.cg * inv_d) * grad;", "const R grad_part = r.cg * grad;"),
+    ("delayed: momentum applied on every update", "direction = std::fma(r.beta, m, grad_part);\n        buffer = R(0);\n    }",
+     "buffer = R(0);\n    }\n    direction = std::fma(r.beta, m, grad_part);"),
+    ("delayed: refresh one update late", "refresh = s.delay.seen + 1 == s.delay.d;", "refresh = s.delay.seen == s.delay.d;"),
+    ("delayed: momentum refreshed from the last gradient only", "m = std::fma(r.beta, m, buffer * inv_d);", "m = std::fma(r.beta, m, grad);"),
+    ("delayed: GPS cycle counts LPS updates", "if (gps_delay.enabled) gps_delay.seen = refresh ? 0 : gps_delay.seen + 1;",
+     "if (gps_delay.enabled) gps_delay.seen = s.delay.seen;"),
+    ("delayed: merge clears the gradient buffer", "            s.phase = ACCUMULATING;\n            out.kind = 2;",
+     "            s.phase = ACCUMULATING; std::fill(s.buffer.begin(), s.buffer.end(), R(0));\n            out.kind = 2;"),
 ]
 
 PIN_TESTS = [
@@ -58,6 +72,12 @@ PIN_TESTS = [
     pins.test_snapshot_form_equals_accumulator_form,
     pins.test_step_log_matches_schedule_bookkeeping_and_counters,
     pins.test_bf16_upcast_matches_torch_for_every_bit_pattern,
+    dpins.test_delay_one_is_the_plain_rule_bit_for_bit,
+    lambda: dpins.test_without_momentum_the_delay_only_divides_the_rate(64),
+    lambda: dpins.test_delayed_momentum_is_a_filter_over_cycle_means(6, 0.9, 3.2),
+    dpins.test_constant_delta_closed_form_is_exact_in_fp32,
+    dpins.test_gps_delayed_rule_is_a_filter_over_cycle_means,
+    dpins.test_merge_leaves_the_cycle_alone,
 ]
 
 
