@@ -30,17 +30,37 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 # Algorithmic bytes per parameter per launch (fp32 state; delta fp32 or bf16).
-BYTES = {
-    "lps_update_acc": {"f32": 28, "bf16": 26},     # read g, m, theta, acc; write m, theta, acc
-    "lps_update_noacc": {"f32": 20, "bf16": 18},   # accumulated update in flight: acc untouched
-    "lps_update_acc_pull": {"f32": 32, "bf16": 30},    # ... plus the updated model written to the worker's buffer
-    "lps_update_noacc_pull": {"f32": 24, "bf16": 22},
-    "lps_update_freeze": {"f32": 28, "bf16": 26},      # snapshot form: read the snapshot, write theta_{t_last} - theta_t
-    "lps_update_freeze_pull": {"f32": 32, "bf16": 30},
-    "gps_update": {"f32": 24, "bf16": 24},         # read G, M, Theta; write M, Theta, returned model
-    "lps_merge": {"f32": 16, "bf16": 16},          # read theta, returned model; write theta, zeroed acc
-    "pull": {"f32": 8, "bf16": 8},
-}
+def bytes_per_param(label: str, delta_dtype: str, delayed: bool) -> int:
+    """Algorithmic bytes per parameter of one launch, from the kernel label the harness gave it.
+
+    Every array the event needs is read once and written once (fp32 = 4 bytes, a bf16 delta 2):
+      lps_update_*  read g, theta; write theta (+4 with "_pull": the worker's model buffer).  "acc": the accumulated
+                    update is read and written (+8); "noacc": it is in flight and untouched; "freeze": snapshot form,
+                    read the snapshot and write theta_{t_last} - theta_t (+8).
+                    Plain rule: momentum read and written (+8) -> 28/26 for "acc", 20/18 for "noacc".
+                    Delayed momentum: "_first" writes the gradient buffer (+4), an inner update reads and writes it
+                    (+8), "_refresh" reads it and reads and writes the momentum (+12).
+      gps_update*   read G, Theta; write Theta and the returned model (16), plus the momentum (+8) or, delayed, the
+                    same buffer / momentum terms as above.
+      lps_merge     read theta and the returned model, write theta and the cleared third buffer (16).
+      pull          read and write a model (8).
+    """
+    if label == "lps_merge":
+        return 16
+    if label == "pull":
+        return 8
+    parts = label.split("_")
+    if delayed:
+        rule = 4 if "first" in parts else (12 if "refresh" in parts else 8)
+    else:
+        rule = 8
+    if label.startswith("gps_update"):
+        return 16 + rule
+    assert label.startswith("lps_update"), label
+    g = 2 if delta_dtype == "bf16" else 4
+    third = 0 if "noacc" in parts else 8
+    return g + 8 + third + rule + (4 if "pull" in parts else 0)
+
 
 # HBM traffic per parameter per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), valid
 # only for the kernel source it was measured on: {sha256 of kernels.hip: {kernel label: bytes/param}}.
@@ -118,7 +138,7 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
         if not pairs:
             continue
         ms = np.array([a.elapsed_time(b) for a, b in pairs], dtype=np.float64)
-        bpp = BYTES[label][w.delta_dtype]
+        bpp = bytes_per_param(label, w.delta_dtype, (w.d_g if label.startswith("gps") else w.d_l) > 1)
         kernels[label] = {
             "launches": int(ms.size),
             "avg_ms": float(ms.mean()),
@@ -130,17 +150,16 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
             "params_per_s": float(N / (ms.mean() * 1e-3)),
             "total_ms": float(ms.sum()),
         }
-    upd_labels = ("lps_update_acc", "lps_update_noacc", "lps_update_acc_pull", "lps_update_noacc_pull",
-                  "lps_update_freeze", "lps_update_freeze_pull")
-    n_upd = sum(kernels[k]["launches"] for k in upd_labels if k in kernels)
+    upd_labels = [k for k in kernels if k.startswith("lps_update")]
+    n_upd = sum(kernels[k]["launches"] for k in upd_labels)
     n_pull_events = kernels.get("pull", {}).get("launches", 0) + sum(
-        kernels[k]["launches"] for k in ("lps_update_acc_pull", "lps_update_noacc_pull", "lps_update_freeze_pull") if k in kernels)
-    n_gps = kernels.get("gps_update", {}).get("launches", 0)
+        kernels[k]["launches"] for k in upd_labels if k.endswith("_pull"))
+    n_gps = sum(v["launches"] for k, v in kernels.items() if k.startswith("gps_update"))
     n_mrg = kernels.get("lps_merge", {}).get("launches", 0)
     updates = n_upd + n_gps + n_mrg
     value = N * updates / elapsed
     # dominant kernel: the LPS update variant that takes the most time
-    dom = max((k for k in upd_labels if k in kernels), key=lambda k: kernels[k]["total_ms"])
+    dom = max(upd_labels, key=lambda k: kernels[k]["total_ms"])
     traffic = MEASURED_TRAFFIC.get(kernels_digest(), {}).get(f"{name}:{dom}")
     roofline = {
         "bound": "hbm", "kernel": dom, "achieved": kernels[dom]["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -161,6 +180,7 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
         "whole_path_frac_of_peak": total_bytes / elapsed / 1e9 / HBM_PEAK_GBS,
         "kernels": kernels, "roofline": roofline, "placement": placement, "hbm_regions_found": n_regions,
         "fuse_pull": fuse_pull, "delta_form": "snapshot" if snapshot else "accumulator",
+        "momentum_delay": {"d_l": w.d_l, "d_g": w.d_g},
     }
 
 
@@ -188,6 +208,11 @@ def cpu_baseline(name: str, budget_elements: int = 1 << 22):
         pool[s] = synth.to_bf16_bits(g).numpy() if w.delta_dtype == "bf16" else g.numpy()
     o = HalosOracle(theta0, w.n_lps, eta_l=w.eta_l, beta_l=w.beta_l, eta_g=w.eta_g, beta_g=w.beta_g, alpha=w.alpha,
                     K=trace.k_initial, precision=64, form=FORM_LITERAL)
+    if w.d_l > 1:
+        for l in range(w.n_lps):
+            o.set_delay(l, w.d_l)
+    if w.d_g > 1:
+        o.set_delay(-1, w.d_g)
     ev = trace.events
     ev = ev[ev["kind"] != synth.EV_PULL]          # the oracle's pull is a host copy for tests, not timed work
     t0 = time.perf_counter()

@@ -242,6 +242,44 @@ halos_status halos_lps_get_norms(const halos_lps *lps, void *stream, double *out
 halos_status halos_gps_get_counters(const halos_gps *gps, int64_t *updates);
 
 /*
+ * Delayed Nesterov momentum at a server (the optimizer of the paper's runs at both tiers: Sec. 5.1; the
+ * hyper-parameter table of App. D lists the delays d_l, d_g and notes that the rule effectively divides
+ * the learning rate by the delay).  The paper takes the rule from the Async-Local-SGD work it cites; with
+ * that work's default of no momentum between refreshes, and this paper's coefficient cg on the gradient
+ * term, a server with rule (eta, beta, cg) and delay d handles its updates in cycles of d:
+ *     every update:            buffer <- buffer + g;   x <- x - eta * (cg / d) * g
+ *     the d-th of a cycle:     m <- beta * m + buffer / d;   x <- x - eta * [ (cg / d) * g + beta * m ];
+ *                              buffer <- 0
+ * (x is theta_l with g a worker's pseudo-gradient, or Theta with g the accumulated update G.)  d = 1 is
+ * ModelUpdate of App. E, the rule the servers start with.  The accumulated update, the threshold K, the
+ * merge and the pull are unchanged; a merge does not touch the buffer or the position in the cycle.
+ *
+ *   d       delay, >= 1.  d = 1 switches back to the plain rule; `buffer` is then ignored and may be NULL.
+ *   buffer  for d > 1: device tensors of the layout, fp32, 16-byte aligned, borrowed for the life of the handle
+ *           (or until replaced).  They need no initialisation: the first update of a cycle overwrites them,
+ *           and between a refresh and the next update their contents are unspecified (logically zero).
+ *
+ * fp32 operation order per element (1/d and cg * (1/d) are formed once, in fp32, on the host):
+ *     b1 = b + g  (b1 = g for the first update of a cycle);  gp = (cg/d) * g;
+ *     plain update:  s = eta * gp;                          refresh:  m1 = fma(beta, m, b1 * (1/d));
+ *                                                                     s = eta * fma(beta, m1, gp);
+ *     x = x - s;  accumulated update as in halos_lps_step.
+ * Updates that do not refresh never read or write the momentum, so they move as many bytes as a plain update.
+ *
+ * The call copies the pointers into a device table and waits for the device to go idle first: set-up, not
+ * event loop.  Allowed only between cycles (before the first update, or when the last update was a refresh):
+ * ESTATE otherwise.  ESTATE also for an LPS created under HALOS_FLAG_NORMS with d > 1 (the delayed kernels
+ * carry no |g|^2 monitor).  EINVAL for d < 1, or a bad `buffer` with d > 1.  The delayed kernels always use
+ * non-temporal accesses (halos_set_launch_config's `nontemporal` does not apply to them).
+ */
+halos_status halos_lps_set_momentum_delay(halos_lps *lps, int32_t d, void *const *buffer);
+halos_status halos_gps_set_momentum_delay(halos_gps *gps, int32_t d, void *const *buffer);
+
+/* The delay d of a server and the number of updates applied since its last refresh (0 .. d-1).  Either may be NULL. */
+halos_status halos_lps_get_momentum_delay(const halos_lps *lps, int32_t *d, int32_t *seen);
+halos_status halos_gps_get_momentum_delay(const halos_gps *gps, int32_t *d, int32_t *seen);
+
+/*
  * Launch shape for all later kernel launches of the calling process.
  *   blocks_per_cu  persistent workgroups per compute unit, 1..64 (0 = keep)
  *   nontemporal    1 = stream state through the caches with non-temporal accesses, 0 = plain, -1 = keep

@@ -87,6 +87,10 @@ def load_library():
         "halos_lps_get_counters": [vp, P(i64), P(i64), P(i32), P(i32), P(u32)],
         "halos_gps_get_counters": [vp, P(i64)],
         "halos_lps_get_norms": [vp, vp, P(ctypes.c_double)],
+        "halos_lps_set_momentum_delay": [vp, i32, P(vp)],
+        "halos_gps_set_momentum_delay": [vp, i32, P(vp)],
+        "halos_lps_get_momentum_delay": [vp, P(i32), P(i32)],
+        "halos_gps_get_momentum_delay": [vp, P(i32), P(i32)],
         "halos_set_launch_config": [i32, i32],
         "halos_probe_pair": [vp, vp, ctypes.c_uint64, i32, vp, P(ctypes.c_double)],
     }
@@ -215,6 +219,26 @@ def halos_gps_get_counters(gps: int) -> dict:
     u = ctypes.c_int64()
     _check(load_library().halos_gps_get_counters(gps, ctypes.byref(u)))
     return {"updates": u.value}
+
+
+def halos_lps_set_momentum_delay(lps: int, d: int, buffer=None) -> None:
+    _check(load_library().halos_lps_set_momentum_delay(lps, d, _ptrs(buffer) if buffer is not None else None))
+
+
+def halos_gps_set_momentum_delay(gps: int, d: int, buffer=None) -> None:
+    _check(load_library().halos_gps_set_momentum_delay(gps, d, _ptrs(buffer) if buffer is not None else None))
+
+
+def halos_lps_get_momentum_delay(lps: int) -> dict:
+    d, seen = ctypes.c_int32(), ctypes.c_int32()
+    _check(load_library().halos_lps_get_momentum_delay(lps, ctypes.byref(d), ctypes.byref(seen)))
+    return {"d": d.value, "seen": seen.value}
+
+
+def halos_gps_get_momentum_delay(gps: int) -> dict:
+    d, seen = ctypes.c_int32(), ctypes.c_int32()
+    _check(load_library().halos_gps_get_momentum_delay(gps, ctypes.byref(d), ctypes.byref(seen)))
+    return {"d": d.value, "seen": seen.value}
 
 
 def halos_set_launch_config(blocks_per_cu: int = 0, nontemporal: int = -1) -> None:

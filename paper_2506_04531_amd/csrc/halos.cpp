@@ -70,6 +70,8 @@ struct halos_gps {
     uint32_t n_tiles = 0;
     void *d_tables = nullptr;          // one allocation: [Theta pointers | M pointers]
     float **d_Theta = nullptr, **d_M = nullptr;
+    float **d_buffer = nullptr;        // gradient buffer of the delayed momentum (third table of d_tables; null until set)
+    MomentumCycle cycle;
     halos_rule rule{};
     halos_hparams hp{};
     int64_t updates = 0;
@@ -89,6 +91,8 @@ struct halos_lps {
     void *d_tables = nullptr;          // one allocation: [theta | m | acc] pointer tables
     float **d_theta = nullptr, **d_m = nullptr, **d_acc = nullptr;
     float **d_worker_model = nullptr;  // n_workers tables of n_tensors pointers, appended to d_tables
+    float **d_buffer = nullptr;        // gradient buffer of the delayed momentum (last table of d_tables; null until set)
+    MomentumCycle cycle;
     std::vector<char> worker_has_model;
     // update-norm monitors (HALOS_FLAG_NORMS): per-workgroup partial sums, then [ |g|^2 of the last update,
     // |theta - Theta_i|^2 before the last merge ]
@@ -108,6 +112,9 @@ struct halos_lps {
 };
 
 namespace {
+
+static_assert(POS_FIRST == CYCLE_FIRST && POS_INNER == CYCLE_INNER && POS_REFRESH == CYCLE_REFRESH,
+              "the protocol's cycle positions are the kernels' rule selectors");
 
 LaunchShape current_shape(const halos_gps *g) {
     LaunchShape s;
@@ -305,10 +312,11 @@ halos_status halos_gps_create(const halos_layout *layout, const halos_hparams *h
         e = hipMemcpy(g->d_tiles, tiles.data(), tiles.size() * sizeof(Tile), hipMemcpyHostToDevice);
         if (e != hipSuccess) { (void)hipFree(g->d_tiles); delete g; return fail_hip(e, "uploading the tile table"); }
     }
-    st = upload_tables(&g->d_tables, {(const void *const *)Theta, (const void *const *)M}, nt);
+    st = upload_tables(&g->d_tables, {(const void *const *)Theta, (const void *const *)M}, nt, 1);
     if (st != HALOS_OK) { (void)hipFree(g->d_tiles); delete g; return st; }
     g->d_Theta = (float **)g->d_tables;
     g->d_M = g->d_Theta + nt;
+    g->d_buffer = g->d_M + nt;
 
     for (const TileRange &r : g->ranges) {       // M <- 0
         e = launch_init((hipStream_t)stream, g->d_tiles, r, nullptr, nullptr, g->d_M, nullptr, false, current_shape(g));
@@ -353,12 +361,13 @@ halos_status halos_lps_create(halos_gps *g, int32_t lps_id, int32_t n_workers, v
     l->validated_dtype.assign(n_workers, HALOS_F32);
     const size_t nt = g->numel.size();
     st = upload_tables(&l->d_tables, {(const void *const *)theta, (const void *const *)m, (const void *const *)acc}, nt,
-                       (size_t)n_workers);
+                       (size_t)n_workers + 1);
     if (st != HALOS_OK) { delete l; return st; }
     l->d_theta = (float **)l->d_tables;
     l->d_m = l->d_theta + nt;
     l->d_acc = l->d_m + nt;
     l->d_worker_model = l->d_acc + nt;
+    l->d_buffer = l->d_worker_model + (size_t)n_workers * nt;
     l->worker_has_model.assign(n_workers, 0);
     if (g->hp.flags & HALOS_FLAG_NORMS) {
         l->norm_partial_cap = (uint32_t)(g->ranges.size() ? g->ranges.size() : 1) * 64u * (uint32_t)g->n_cu;
@@ -485,9 +494,17 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
             PtrArgs args;
             fill_args(args, p.ptrs.data(), r, g->numel.size());
             double *partials = l->d_norm_partials ? l->d_norm_partials + n_partials : nullptr;
-            hipError_t e = launch_lps_update((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_acc, pull_tab,
-                                             args, p.dtype == HALOS_BF16, third_mode, l->rule.eta, l->rule.beta,
-                                             l->rule.cg, partials, shape);
+            hipError_t e;
+            if (l->cycle.d() > 1) {
+                const float inv_d = 1.0f / (float)l->cycle.d();
+                e = launch_lps_update_delayed((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_buffer, l->d_acc,
+                                              pull_tab, args, p.dtype == HALOS_BF16, third_mode, (int)l->cycle.next(),
+                                              l->rule.eta, l->rule.beta, l->rule.cg * inv_d, inv_d, shape);
+            } else {
+                e = launch_lps_update((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_acc, pull_tab, args,
+                                      p.dtype == HALOS_BF16, third_mode, l->rule.eta, l->rule.beta, l->rule.cg, partials,
+                                      shape);
+            }
             if (e != hipSuccess) return fail_hip(e, "launching the local update");
             n_partials += launch_grid_size(r, shape);
         }
@@ -496,6 +513,7 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
             if (e != hipSuccess) return fail_hip(e, "launching the norm reduction");
         }
         l->proto.commit_update();
+        l->cycle.commit();
         out.kind = 1;
         out.worker = head.worker;
         out.accumulated = oc.accumulate ? 1 : 0;
@@ -541,10 +559,19 @@ halos_status halos_gps_merge(halos_gps *g, halos_lps *from, void *stream) {
     if (st != HALOS_OK) return st;
     const LaunchShape shape = current_shape(g);
     for (const TileRange &r : g->ranges) {
-        hipError_t e = launch_gps_update((hipStream_t)stream, g->d_tiles, r, g->d_Theta, g->d_M, from->d_acc, from->d_acc,
-                                         g->rule.eta, g->rule.beta, g->rule.cg, shape);
+        hipError_t e;
+        if (g->cycle.d() > 1) {
+            const float inv_d = 1.0f / (float)g->cycle.d();
+            e = launch_gps_update_delayed((hipStream_t)stream, g->d_tiles, r, g->d_Theta, g->d_M, g->d_buffer, from->d_acc,
+                                          from->d_acc, (int)g->cycle.next(), g->rule.eta, g->rule.beta, g->rule.cg * inv_d,
+                                          inv_d, shape);
+        } else {
+            e = launch_gps_update((hipStream_t)stream, g->d_tiles, r, g->d_Theta, g->d_M, from->d_acc, from->d_acc,
+                                  g->rule.eta, g->rule.beta, g->rule.cg, shape);
+        }
         if (e != hipSuccess) return fail_hip(e, "launching the global update");
     }
+    g->cycle.commit();
     from->proto.consume();
     g->updates += 1;
     return HALOS_OK;
@@ -628,6 +655,53 @@ halos_status halos_lps_get_norms(const halos_lps *l, void *stream, double *out) 
     hipError_t e = hipMemcpyAsync(out, l->d_norm_results, 2 * sizeof(double), hipMemcpyDeviceToHost, (hipStream_t)stream);
     if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
     if (e != hipSuccess) return fail_hip(e, "reading the norms");
+    return HALOS_OK;
+}
+
+// Shared by both tiers: check, wait for the device, store the buffer's pointers in the server's table slot.
+static halos_status set_momentum_delay(const halos_gps *g, MomentumCycle &cycle, float **d_slot, int32_t d,
+                                       void *const *buffer, const char *who) {
+    if (d < 1) return fail(HALOS_EINVAL, "d = %d, must be >= 1", d);
+    if (cycle.seen() != 0)
+        return fail(HALOS_ESTATE, "%s is %d updates into a cycle of %d: the delay can change only between cycles", who,
+                    cycle.seen(), cycle.d());
+    if (d > 1) {
+        halos_status st = check_device(g);
+        if (st == HALOS_OK) st = check_tensors(g, (const void *const *)buffer, sizeof(float), "buffer");
+        if (st != HALOS_OK) return st;
+        const size_t nt = g->numel.size();
+        hipError_t e = hipDeviceSynchronize();      // no launch that still reads the old table may be in flight
+        if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
+        e = hipMemcpy(d_slot, buffer, nt * sizeof(void *), hipMemcpyHostToDevice);
+        if (e != hipSuccess) return fail_hip(e, "uploading the buffer's pointer table");
+    }
+    cycle.set_d(d);
+    return HALOS_OK;
+}
+
+halos_status halos_lps_set_momentum_delay(halos_lps *l, int32_t d, void *const *buffer) {
+    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    if (d > 1 && l->d_norm_partials)
+        return fail(HALOS_ESTATE, "lps %d was created under HALOS_FLAG_NORMS: no delayed momentum", l->id);
+    return set_momentum_delay(l->gps, l->cycle, l->d_buffer, d, buffer, "the local server");
+}
+
+halos_status halos_gps_set_momentum_delay(halos_gps *g, int32_t d, void *const *buffer) {
+    if (!g || g->magic != GPS_MAGIC) return fail(HALOS_EINVAL, "gps is not a valid handle");
+    return set_momentum_delay(g, g->cycle, g->d_buffer, d, buffer, "the global server");
+}
+
+halos_status halos_lps_get_momentum_delay(const halos_lps *l, int32_t *d, int32_t *seen) {
+    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    if (d) *d = l->cycle.d();
+    if (seen) *seen = l->cycle.seen();
+    return HALOS_OK;
+}
+
+halos_status halos_gps_get_momentum_delay(const halos_gps *g, int32_t *d, int32_t *seen) {
+    if (!g || g->magic != GPS_MAGIC) return fail(HALOS_EINVAL, "gps is not a valid handle");
+    if (d) *d = g->cycle.d();
+    if (seen) *seen = g->cycle.seen();
     return HALOS_OK;
 }
 

@@ -10,6 +10,8 @@
 // not depend on compiler contraction settings:
 //     m1 = fma(beta, m, g);  u = fma(beta, m1, cg * g);  s = eta * u;  x = x - s;  acc = acc + s
 //     merge: theta = fma(alpha, Theta_i, keep * theta)
+//     delayed momentum: b1 = b + g;  gp = (cg/d) * g;  s = eta * gp,  or at a refresh
+//                       m1 = fma(beta, m, b1 * (1/d));  s = eta * fma(beta, m1, gp)
 #include <hip/hip_runtime.h>
 
 #include "kernels.hpp"
@@ -274,6 +276,182 @@ gps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
 }
 
 // ---------------------------------------------------------------------------------------------
+// Delayed Nesterov momentum (Sec. 5.1; App. D, delays d_l and d_g).  A server handles its updates in cycles
+// of d: every update adds g to a buffer and steps the model by eta (cg/d) g; the last one of a cycle also
+// refreshes the momentum from the buffer's mean and applies it.  RULE says where in the cycle an update is:
+//   CYCLE_FIRST    opens a cycle: buffer <- g (the buffer is not read)
+//   CYCLE_INNER    buffer <- buffer + g
+//   CYCLE_REFRESH  closes it: m <- beta m + (buffer + g)/d, applied; the buffer is not written
+// Only a refresh touches the momentum.
+
+template <int RULE>
+__device__ __forceinline__ float delayed_update(float &x, float &m, float &b, float g, float eta, float beta, float cgd,
+                                                float inv_d) {
+    const float b1 = RULE == CYCLE_FIRST ? g : __fadd_rn(b, g);
+    const float gp = __fmul_rn(cgd, g);
+    float u = gp;
+    if constexpr (RULE == CYCLE_REFRESH) {
+        m = __fmaf_rn(beta, m, __fmul_rn(b1, inv_d));
+        u = __fmaf_rn(beta, m, gp);
+    }
+    b = b1;
+    const float s = __fmul_rn(eta, u);
+    x = __fsub_rn(x, s);
+    return s;
+}
+
+template <int RULE>
+__device__ __forceinline__ f32x4 delayed_update4(f32x4 &x, f32x4 &m, f32x4 &b, f32x4 g, float eta, float beta, float cgd,
+                                                 float inv_d) {
+    f32x4 s;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+        float xi = x[i], mi = m[i], bi = b[i];
+        s[i] = delayed_update<RULE>(xi, mi, bi, g[i], eta, beta, cgd, inv_d);
+        x[i] = xi;
+        m[i] = mi;
+        b[i] = bi;
+    }
+    return s;
+}
+
+// S1 under the delayed rule.  THIRD and PULL as in lps_update_kernel; accesses are non-temporal.
+template <typename GT, int THIRD, bool PULL, int RULE>
+__global__ void __launch_bounds__(BLOCK_THREADS)
+lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, uint32_t tensor_base,
+                          float *const *__restrict__ theta_tab, float *const *__restrict__ m_tab,
+                          float *const *__restrict__ buf_tab, float *const *__restrict__ acc_tab,
+                          float *const *__restrict__ pull_tab, PtrArgs gargs, float eta, float beta, float cgd,
+                          float inv_d) {
+    constexpr bool NT = true;
+    constexpr bool LOAD_B = RULE != CYCLE_FIRST, STORE_B = RULE != CYCLE_REFRESH, USE_M = RULE == CYCLE_REFRESH;
+    const uint32_t tid = threadIdx.x;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    for (uint32_t t = tile_lo + blockIdx.x; t < tile_hi; t += gridDim.x) {
+        const Tile tl = tiles[t];
+        const uint32_t tensor = tl.tensor;
+        gf32 *th = to_global(theta_tab[tensor]) + tl.start;
+        gf32 *mm = USE_M ? to_global(m_tab[tensor]) + tl.start : nullptr;
+        gf32 *bb = to_global(buf_tab[tensor]) + tl.start;
+        gf32 *ac = THIRD != 0 ? to_global(acc_tab[tensor]) + tl.start : nullptr;
+        gf32 *pd = PULL ? to_global(pull_tab[tensor]) + tl.start : nullptr;
+        const auto *g = to_global(static_cast<const GT *>(gargs.p[tensor - tensor_base])) + tl.start;
+        if (tl.len == TILE_ELEMS) {
+            f32x4 gv[UNROLL], bv[UNROLL], mv[UNROLL], tv[UNROLL], av[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
+                gv[u] = ldg4<NT>(g + off);
+                bv[u] = LOAD_B ? ld4<NT>(bb + off) : zero;
+                mv[u] = USE_M ? ld4<NT>(mm + off) : zero;
+                tv[u] = ld4<NT>(th + off);
+                if constexpr (THIRD != 0) av[u] = ld4<NT>(ac + off);
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
+                const f32x4 s = delayed_update4<RULE>(tv[u], mv[u], bv[u], gv[u], eta, beta, cgd, inv_d);
+                if constexpr (STORE_B) st4<NT>(bb + off, bv[u]);
+                if constexpr (USE_M) st4<NT>(mm + off, mv[u]);
+                st4<NT>(th + off, tv[u]);
+                if constexpr (PULL) st4<NT>(pd + off, tv[u]);
+                if constexpr (THIRD == 1) st4<NT>(ac + off, add4(av[u], s));
+                if constexpr (THIRD == 2) st4<NT>(ac + off, sub4(av[u], tv[u]));
+            }
+        } else {
+            const uint32_t len = tl.len;
+            for (uint32_t off = tid * VEC; off < len; off += BLOCK_THREADS * VEC) {
+                if (off + VEC <= len) {
+                    f32x4 gv = ldg4<NT>(g + off), tv = ld4<NT>(th + off);
+                    f32x4 bv = LOAD_B ? ld4<NT>(bb + off) : zero, mv = USE_M ? ld4<NT>(mm + off) : zero;
+                    const f32x4 s = delayed_update4<RULE>(tv, mv, bv, gv, eta, beta, cgd, inv_d);
+                    if constexpr (STORE_B) st4<NT>(bb + off, bv);
+                    if constexpr (USE_M) st4<NT>(mm + off, mv);
+                    st4<NT>(th + off, tv);
+                    if constexpr (PULL) st4<NT>(pd + off, tv);
+                    if constexpr (THIRD == 1) st4<NT>(ac + off, add4(ld4<NT>(ac + off), s));
+                    if constexpr (THIRD == 2) st4<NT>(ac + off, sub4(ld4<NT>(ac + off), tv));
+                } else {
+                    for (uint32_t k = off; k < len; ++k) {      // ragged tail: fewer than 4 elements
+                        float tv = th[k], bv = LOAD_B ? bb[k] : 0.f, mv = USE_M ? mm[k] : 0.f;
+                        const float s = delayed_update<RULE>(tv, mv, bv, ldg1(g + k), eta, beta, cgd, inv_d);
+                        if constexpr (STORE_B) bb[k] = bv;
+                        if constexpr (USE_M) mm[k] = mv;
+                        th[k] = tv;
+                        if constexpr (PULL) pd[k] = tv;
+                        if constexpr (THIRD == 1) ac[k] = __fadd_rn(ac[k], s);
+                        if constexpr (THIRD == 2) ac[k] = __fsub_rn(ac[k], tv);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// S3 under the delayed rule.  G and out may alias.
+template <int RULE>
+__global__ void __launch_bounds__(BLOCK_THREADS)
+gps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi,
+                          float *const *__restrict__ Theta_tab, float *const *__restrict__ M_tab,
+                          float *const *__restrict__ buf_tab, float *const *G_tab, float *const *out_tab, float eta,
+                          float beta, float cgd, float inv_d) {
+    constexpr bool NT = true;
+    constexpr bool LOAD_B = RULE != CYCLE_FIRST, STORE_B = RULE != CYCLE_REFRESH, USE_M = RULE == CYCLE_REFRESH;
+    const uint32_t tid = threadIdx.x;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    for (uint32_t t = tile_lo + blockIdx.x; t < tile_hi; t += gridDim.x) {
+        const Tile tl = tiles[t];
+        const uint32_t tensor = tl.tensor;
+        gf32 *Th = to_global(Theta_tab[tensor]) + tl.start;
+        gf32 *Mm = USE_M ? to_global(M_tab[tensor]) + tl.start : nullptr;
+        gf32 *Bb = to_global(buf_tab[tensor]) + tl.start;
+        const gf32 *G = to_global(G_tab[tensor]) + tl.start;
+        gf32 *out = to_global(out_tab[tensor]) + tl.start;
+        if (tl.len == TILE_ELEMS) {
+            f32x4 gv[UNROLL], bv[UNROLL], mv[UNROLL], tv[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
+                gv[u] = ld4<NT>(G + off);
+                bv[u] = LOAD_B ? ld4<NT>(Bb + off) : zero;
+                mv[u] = USE_M ? ld4<NT>(Mm + off) : zero;
+                tv[u] = ld4<NT>(Th + off);
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
+                delayed_update4<RULE>(tv[u], mv[u], bv[u], gv[u], eta, beta, cgd, inv_d);
+                if constexpr (STORE_B) st4<NT>(Bb + off, bv[u]);
+                if constexpr (USE_M) st4<NT>(Mm + off, mv[u]);
+                st4<NT>(Th + off, tv[u]);
+                st4<NT>(out + off, tv[u]);
+            }
+        } else {
+            const uint32_t len = tl.len;
+            for (uint32_t off = tid * VEC; off < len; off += BLOCK_THREADS * VEC) {
+                if (off + VEC <= len) {
+                    f32x4 gv = ld4<NT>(G + off), tv = ld4<NT>(Th + off);
+                    f32x4 bv = LOAD_B ? ld4<NT>(Bb + off) : zero, mv = USE_M ? ld4<NT>(Mm + off) : zero;
+                    delayed_update4<RULE>(tv, mv, bv, gv, eta, beta, cgd, inv_d);
+                    if constexpr (STORE_B) st4<NT>(Bb + off, bv);
+                    if constexpr (USE_M) st4<NT>(Mm + off, mv);
+                    st4<NT>(Th + off, tv);
+                    st4<NT>(out + off, tv);
+                } else {
+                    for (uint32_t k = off; k < len; ++k) {
+                        float tv = Th[k], bv = LOAD_B ? Bb[k] : 0.f, mv = USE_M ? Mm[k] : 0.f;
+                        delayed_update<RULE>(tv, mv, bv, G[k], eta, beta, cgd, inv_d);
+                        if constexpr (STORE_B) Bb[k] = bv;
+                        if constexpr (USE_M) Mm[k] = mv;
+                        Th[k] = tv; out[k] = tv;
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // S4: merge the returned global model into the local model and restart the accumulation.
 // With NORM every workgroup also leaves the sum of (theta - Theta_i)^2 before the merge in partials[blockIdx.x].
 // With SNAP the third buffer receives the merged model (the new snapshot theta_{t_last}) instead of zeros.
@@ -493,6 +671,58 @@ hipError_t launch_gps_update(hipStream_t stream, const Tile *tiles, TileRange r,
         gps_update_kernel<true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, Theta, M, G, out, eta, beta, cg);
     else
         gps_update_kernel<false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, Theta, M, G, out, eta, beta, cg);
+    return hipGetLastError();
+}
+
+hipError_t launch_lps_update_delayed(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
+                                     float *const *m, float *const *buffer, float *const *acc, float *const *pull,
+                                     const PtrArgs &g, bool g_is_bf16, int third_mode, int cycle_pos, float eta,
+                                     float beta, float cgd, float inv_d, LaunchShape shape) {
+    if (r.hi <= r.lo) return hipSuccess;
+    if (cycle_pos < CYCLE_FIRST || cycle_pos > CYCLE_REFRESH || third_mode < 0 || third_mode > 2) return hipErrorInvalidValue;
+    const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
+#define HALOS_LAUNCH_DN(GT, THIRD, PULL, RULE)                                                                          \
+    lps_update_delayed_kernel<GT, THIRD, PULL, RULE><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, r.tensor_base, theta, m, \
+                                                                                buffer, acc, pull, g, eta, beta, cgd,    \
+                                                                                inv_d)
+#define HALOS_LAUNCH_DN_RULE(GT, THIRD, PULL)                                  \
+    do {                                                                       \
+        if (cycle_pos == CYCLE_FIRST) HALOS_LAUNCH_DN(GT, THIRD, PULL, CYCLE_FIRST); \
+        else if (cycle_pos == CYCLE_INNER) HALOS_LAUNCH_DN(GT, THIRD, PULL, CYCLE_INNER); \
+        else HALOS_LAUNCH_DN(GT, THIRD, PULL, CYCLE_REFRESH);                     \
+    } while (0)
+    const int variant = (g_is_bf16 ? 6 : 0) + 2 * third_mode + (pull ? 1 : 0);
+    switch (variant) {
+        case 0: HALOS_LAUNCH_DN_RULE(float, 0, false); break;
+        case 1: HALOS_LAUNCH_DN_RULE(float, 0, true); break;
+        case 2: HALOS_LAUNCH_DN_RULE(float, 1, false); break;
+        case 3: HALOS_LAUNCH_DN_RULE(float, 1, true); break;
+        case 4: HALOS_LAUNCH_DN_RULE(float, 2, false); break;
+        case 5: HALOS_LAUNCH_DN_RULE(float, 2, true); break;
+        case 6: HALOS_LAUNCH_DN_RULE(unsigned short, 0, false); break;
+        case 7: HALOS_LAUNCH_DN_RULE(unsigned short, 0, true); break;
+        case 8: HALOS_LAUNCH_DN_RULE(unsigned short, 1, false); break;
+        case 9: HALOS_LAUNCH_DN_RULE(unsigned short, 1, true); break;
+        case 10: HALOS_LAUNCH_DN_RULE(unsigned short, 2, false); break;
+        default: HALOS_LAUNCH_DN_RULE(unsigned short, 2, true); break;
+    }
+#undef HALOS_LAUNCH_DN_RULE
+#undef HALOS_LAUNCH_DN
+    return hipGetLastError();
+}
+
+hipError_t launch_gps_update_delayed(hipStream_t stream, const Tile *tiles, TileRange r, float *const *Theta,
+                                     float *const *M, float *const *buffer, float *const *G, float *const *out,
+                                     int cycle_pos, float eta, float beta, float cgd, float inv_d, LaunchShape shape) {
+    if (r.hi <= r.lo) return hipSuccess;
+    if (cycle_pos < CYCLE_FIRST || cycle_pos > CYCLE_REFRESH) return hipErrorInvalidValue;
+    const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
+    if (cycle_pos == CYCLE_FIRST)
+        gps_update_delayed_kernel<CYCLE_FIRST><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, Theta, M, buffer, G, out, eta, beta, cgd, inv_d);
+    else if (cycle_pos == CYCLE_INNER)
+        gps_update_delayed_kernel<CYCLE_INNER><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, Theta, M, buffer, G, out, eta, beta, cgd, inv_d);
+    else
+        gps_update_delayed_kernel<CYCLE_REFRESH><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, Theta, M, buffer, G, out, eta, beta, cgd, inv_d);
     return hipGetLastError();
 }
 

@@ -61,6 +61,19 @@ hipError_t launch_norm_finalize(hipStream_t stream, const double *partials, uint
 hipError_t launch_gps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *Theta, float *const *M,
                              float *const *G, float *const *out, float eta, float beta, float cg, LaunchShape shape);
 
+// The same two steps under delayed Nesterov momentum (Sec. 5.1; App. D, delays d_l and d_g).  cycle_pos says where
+// in its cycle of d updates the server is: CYCLE_FIRST (buffer <- g), CYCLE_INNER (buffer <- buffer + g) or
+// CYCLE_REFRESH (m <- beta m + (buffer + g) * inv_d, then applied; the buffer is left as it is).  Every update
+// steps the model by eta * cgd * g (cgd = cg / d); only a refresh reads or writes m.  Always non-temporal.
+constexpr int CYCLE_FIRST = 1, CYCLE_INNER = 2, CYCLE_REFRESH = 3;
+hipError_t launch_lps_update_delayed(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
+                                     float *const *m, float *const *buffer, float *const *acc, float *const *pull,
+                                     const PtrArgs &g, bool g_is_bf16, int third_mode, int cycle_pos, float eta,
+                                     float beta, float cgd, float inv_d, LaunchShape shape);
+hipError_t launch_gps_update_delayed(hipStream_t stream, const Tile *tiles, TileRange r, float *const *Theta,
+                                     float *const *M, float *const *buffer, float *const *G, float *const *out,
+                                     int cycle_pos, float eta, float beta, float cgd, float inv_d, LaunchShape shape);
+
 // Merge step of a local server: theta <- alpha * inbox + keep * theta (keep = 1 - alpha); inbox buffer <- 0.
 // With `norm_partials`: per workgroup, the sum of (theta - inbox)^2 before the merge (same layout as above).
 // `snapshot`: the inbox buffer receives the merged model (the new theta_{t_last}) instead of zeros.

@@ -109,4 +109,34 @@ private:
     std::vector<char> worker_queued_;
 };
 
+// Where a server stands in its cycle of d updates under delayed Nesterov momentum (Sec. 5.1; App. D, delays d_l
+// and d_g): the first update of a cycle restarts the gradient buffer, the d-th refreshes the momentum.  d = 1 is
+// the plain rule (every update refreshes; no buffer).
+enum CyclePos : int32_t { POS_FIRST = 1, POS_INNER = 2, POS_REFRESH = 3 };
+
+class MomentumCycle {
+public:
+    int32_t d() const { return d_; }
+    int32_t seen() const { return seen_; }          // updates since the last refresh, 0 .. d-1
+
+    // The delay may change only between cycles.
+    ProtoResult set_d(int32_t d) {
+        if (d < 1) return PROTO_BAD_ARG;
+        if (seen_ != 0) return PROTO_BAD_STATE;
+        d_ = d;
+        return PROTO_OK;
+    }
+
+    // Position of the NEXT update.  For d = 1 it is a refresh that is also the first.
+    CyclePos next() const {
+        if (seen_ + 1 >= d_) return POS_REFRESH;
+        return seen_ == 0 ? POS_FIRST : POS_INNER;
+    }
+    void commit() { seen_ = (seen_ + 1 >= d_) ? 0 : seen_ + 1; }
+
+private:
+    int32_t d_ = 1;
+    int32_t seen_ = 0;
+};
+
 }  // namespace halos

@@ -201,8 +201,15 @@ class Cluster:
             S = sum((n * 4 + 255) // 256 * 256 for n in self.numel)
             L = w.n_lps
             pool_bytes = w.pool_slots * S * ddt_size // 4
-            self._pool_cls = 0 if (2 * L + 2) * S + pool_bytes <= (72 << 30) else 1
+            cls0 = (2 * L + 2 + (1 if w.d_g > 1 else 0)) * S
+            self._pool_cls = 0 if cls0 + pool_bytes <= (72 << 30) else 1
             need = [(2 * L + 2) * S, L * S, L * S if pull_buffers else 0]
+            # Delayed momentum: the gradient buffer takes the momentum's place in all but one update of a cycle, so it
+            # goes where the momentum would (class 0) and the momentum, touched once per cycle, moves to class 1.
+            if w.d_l > 1:
+                need[1] += L * S
+            if w.d_g > 1:
+                need[0] += S
             need[self._pool_cls] += pool_bytes
             self.region_arena = RegionArena(self.device, need, verbose=verbose)
             ra = self.region_arena
@@ -216,11 +223,18 @@ class Cluster:
                                                                  cg_l=w.cg_l, cg_g=w.cg_g)
         self.snapshot = bool(self.hp.flags & B.FLAG_SNAPSHOT)
         self.gps = B.halos_gps_create(self.numel, self.hp, self.Theta, self.M)
-        self.theta, self.m, self.acc, self.lps = [], [], [], []
+        self.gps_buffer = None
+        if w.d_g > 1:
+            self.gps_buffer = mk(cls=0)
+            B.halos_gps_set_momentum_delay(self.gps, w.d_g, self.gps_buffer)
+        self.theta, self.m, self.acc, self.buffer, self.lps = [], [], [], [], []
         for l in range(w.n_lps):
-            th, m, acc = mk(cls=0), mk(cls=0), mk(cls=1)
+            th, m, acc = mk(cls=0), mk(cls=1 if w.d_l > 1 else 0), mk(cls=1)
             self.theta.append(th); self.m.append(m); self.acc.append(acc)
             h = B.halos_lps_create(self.gps, l, w.workers_per_lps, th, m, acc)
+            if w.d_l > 1:
+                self.buffer.append(mk(cls=0))
+                B.halos_lps_set_momentum_delay(h, w.d_l, self.buffer[l])
             if k_initial is not None:
                 B.halos_lps_set_threshold(h, int(k_initial[l]))
             self.lps.append(h)
@@ -264,13 +278,14 @@ class Cluster:
         stream = torch.cuda.current_stream(self.device)
         sp = stream.cuda_stream or None
         log = []
-        timings: Dict[str, list] = {"lps_update_acc": [], "lps_update_noacc": [], "lps_update_acc_pull": [],
-                                    "lps_update_noacc_pull": [], "lps_update_freeze": [], "lps_update_freeze_pull": [],
-                                    "gps_update": [], "lps_merge": [], "pull": []}
+        from collections import defaultdict
+        timings: Dict[str, list] = defaultdict(list)
         fuse_pull = fuse_pull and self._pull_ptrs is not None
         skip = -1
         info = B.StepInfo()
         k_now = [None] * len(self.lps)
+        seen_l = [B.halos_lps_get_momentum_delay(h)["seen"] for h in self.lps]
+        seen_g = B.halos_gps_get_momentum_delay(self.gps)["seen"]
 
         def bracket(label, call):
             if not timed:
@@ -305,6 +320,10 @@ class Cluster:
                         label = "lps_update_freeze" if int(ev["exp_send"]) else "lps_update_noacc"
                     else:
                         label = "lps_update_acc" if int(ev["exp_accumulate"]) else "lps_update_noacc"
+                    if self.w.d_l > 1:      # delayed momentum: an update that refreshes the momentum moves more bytes
+                        seen = seen_l[l]
+                        label += "_refresh" if seen + 1 == self.w.d_l else ("_first" if seen == 0 else "")
+                        seen_l[l] = (seen + 1) % self.w.d_l
                     if fuse_pull and i + 1 < n_ev:
                         nx = events[i + 1]
                         fused = (int(nx["kind"]) == _PULL and int(nx["lps"]) == l and int(nx["worker"]) == int(ev["worker"]))
@@ -315,7 +334,11 @@ class Cluster:
                     chk(bracket(label, lambda: lib.halos_lps_step(h, sp, ctypes.byref(info))))
                 log.append((i, info.kind, info.t, info.t_last, info.delta_ready, info.accumulated))
             elif kind == _GPS_MERGE:
-                chk(bracket("gps_update", lambda: lib.halos_gps_merge(self.gps, h, sp)))
+                glabel = "gps_update"
+                if self.w.d_g > 1:
+                    glabel += "_refresh" if seen_g + 1 == self.w.d_g else ("_first" if seen_g == 0 else "")
+                    seen_g = (seen_g + 1) % self.w.d_g
+                chk(bracket(glabel, lambda: lib.halos_gps_merge(self.gps, h, sp)))
             elif kind == _ARRIVE_GLOBAL:
                 chk(lib.halos_lps_push_global(h))
             elif kind == _PULL:
@@ -323,7 +346,7 @@ class Cluster:
                     chk(bracket("pull", lambda: lib.halos_pull_model(h, 0, self._pull_ptrs[l], sp)))
             else:
                 raise ValueError(f"unknown event kind {kind}")
-        return log, (timings if timed else None)
+        return log, (dict(timings) if timed else None)
 
     # ------------------------------------------------------------------ inspection
     def state_lists(self) -> Dict[str, List[torch.Tensor]]:
@@ -332,6 +355,10 @@ class Cluster:
             out[f"theta{l}"] = self.theta[l]
             out[f"m{l}"] = self.m[l]
             out[f"aux{l}"] = self.acc[l]
+            if self.buffer:
+                out[f"buffer{l}"] = self.buffer[l]
+        if self.gps_buffer is not None:
+            out["B"] = self.gps_buffer
         return out
 
     def gather(self, name: str, flat_idx: torch.Tensor) -> np.ndarray:

@@ -38,6 +38,8 @@ class Workload:
     alpha: float = 0.25
     cg_l: float | None = None      # coefficient on the delta in the LPS rule; None = the paper's 1 - beta_l
     cg_g: float | None = None      # same for the GPS rule
+    d_l: int = 1                   # momentum update delay of the LPS rule (delayed Nesterov momentum); 1 = plain rule
+    d_g: int = 1                   # same for the GPS rule
     seed: int = 0
     pool_slots: int = 8            # number of distinct resident delta buffers
     schedule: str = "seeded"       # "seeded": synth.schedule; "paper": the paper's own cluster model (synth.paper_cluster)
@@ -98,6 +100,12 @@ def _mk() -> Dict[str, Workload]:
                         f"(its bandwidth / speed / step-time tables), K=32, 512 updates, fp32 deltas",
             layout=lay, n_lps=4, workers_per_lps=4, n_updates=512, delta_dtype="f32", k_range=(32, 32),
             staleness_bound=64, seed=2000 + len(w), schedule="paper", paper_model=key)
+    # The optimizer setting of the paper's runs (App. D, hyper-parameter table): delayed Nesterov momentum with
+    # d_l = 16, d_g = 2; the table lists the rates divided by the delays (0.2 and 0.15), so eta = rate x delay.
+    for key in ("1b", "410m", "paper-410m"):
+        base = w[key]
+        w[key + "-dn"] = replace(base, name=key + "-dn", d_l=16, d_g=2, eta_l=0.2 * 16, eta_g=0.15 * 2,
+                                 description=base.description + "; delayed Nesterov momentum d_l=16, d_g=2")
     return w
 
 

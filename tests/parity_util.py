@@ -63,6 +63,11 @@ def oracle_run(w: synth.Workload, trace: synth.Trace, idx: Optional[np.ndarray],
 
     o = HalosOracle(theta0, w.n_lps, eta_l=w.eta_l, beta_l=w.beta_l, eta_g=w.eta_g, beta_g=w.beta_g,
                     alpha=w.alpha, K=trace.k_initial, cg_l=w.cg_l, cg_g=w.cg_g, precision=precision, form=form)
+    if w.d_l > 1:
+        for l in range(w.n_lps):
+            o.set_delay(l, w.d_l)
+    if w.d_g > 1:
+        o.set_delay(-1, w.d_g)
     log = oracle_replay(o, trace.events, delta)
     return o, log
 
@@ -75,6 +80,13 @@ def oracle_state(o: HalosOracle, n_lps: int, with_scale: bool = True, snapshot_f
         names[f"theta{l}"] = (O.THETA, l)
         names[f"m{l}"] = (O.MOM, l)
         names[f"aux{l}"] = (O.AUX_SNAPSHOT if snapshot_form else O.AUX, l)
+    # gradient buffers of the delayed momentum: defined only while a cycle is open (after a refresh an
+    # implementation may leave anything there until the next update overwrites it)
+    for l in range(n_lps):
+        if o.delay_seen(l) > 0:
+            names[f"buffer{l}"] = (O.BUFFER, l)
+    if o.delay_seen(-1) > 0:
+        names["B"] = (O.GPS_BUFFER, 0)
     out = {}
     for k, (what, l) in names.items():
         out[k] = (o.get(what, l), o.get(what + O.SCALE, l) if with_scale else None)
