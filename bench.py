@@ -231,8 +231,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="1b", help="headline workload: tiny, 70m, 160m, 410m or 1b")
-    ap.add_argument("--also", default="tiny,70m,160m,410m",
+    ap.add_argument("--workload", default="1b", help="headline workload: tiny, 70m, 160m, 410m, 1b; paper-70m/160m/410m (the paper's cluster model); "
+                         "1b-dn, 410m-dn, paper-410m-dn (the same with delayed Nesterov momentum, d_l=16, d_g=2)")
+    ap.add_argument("--also", default="tiny,70m,160m,410m,1b-dn",
                     help="comma-separated further workloads reported under 'workloads' ('' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
@@ -268,7 +269,7 @@ def main():
     cpu = None if args.no_cpu_baseline else cpu_baseline(args.workload)
 
     def brief(r):
-        return {k: r[k] for k in ("workload", "params", "delta_dtype", "ms_per_step", "params_updated_per_s",
+        return {k: r[k] for k in ("workload", "params", "delta_dtype", "momentum_delay", "ms_per_step", "params_updated_per_s",
                                   "whole_path_GBps", "whole_path_frac_of_peak", "kernels", "roofline")}
 
     line = {
@@ -279,7 +280,8 @@ def main():
                    "tensors": head["tensors"], "n_lps": head["n_lps"], "workers_per_lps": head["workers_per_lps"],
                    "delta_dtype": head["delta_dtype"], "events_per_step": head["events_per_step"],
                    "placement": head["placement"], "hbm_regions_found": head["hbm_regions_found"],
-                   "fuse_pull": head["fuse_pull"], "delta_form": head["delta_form"]},
+                   "fuse_pull": head["fuse_pull"], "delta_form": head["delta_form"],
+                   "momentum_delay": head["momentum_delay"]},
         "roofline": head["roofline"],
         "cpu_baseline": cpu,
         "whole_path_GBps": head["whole_path_GBps"],

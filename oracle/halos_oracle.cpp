@@ -60,6 +60,10 @@
 // identity from the proof, merge endpoints alpha in {0, 1}, geometric
 // contraction of repeated merges, hierarchy collapse to one level, linearity,
 // snapshot == accumulator, bf16 upcast vs torch, protocol counters.
+// Delayed momentum has its own pins (tests/test_oracle_delayed_momentum.py): d = 1 equals the plain rule bit
+// for bit, beta = 0 is SGD at rate eta / d (the paper's statement about the rule), momentum as a filter over
+// cycle means, a constant-delta closed form, merges leave the cycle alone.  Its DEFINITION, though, is the cited
+// work's, not this paper's: on that count parity unpinned.
 // Full-size end states (hundreds of events on 70M..1B parameters) have no
 // external reference: they are pinned only through the tiny cases above plus
 // elementwise independence -- otherwise parity unpinned.
