@@ -184,6 +184,63 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
     }
 
 
+def end_model_ab(name: str, reps: int = 20, verbose: bool = True):
+    """The update pass fed an fp32 delta against the same pass fed the worker's end model (halos_lps_push_end_model:
+    the subtraction of Alg. 1 line 26 done by the server), on the workload's tensor list with the same placement:
+    one LPS, one worker, always accumulating, pull fused.  HIP events around every launch on the launch stream."""
+    import numpy as np
+    import torch
+    import synth
+    from paper_2506_04531_amd import binding as B
+    from paper_2506_04531_amd.harness import RegionArena, fill_delta_slot, fill_initial_model
+
+    w = synth.get_workload(name)
+    numel = [int(x) for x in w.layout.numel]
+    N = w.layout.total
+    S = sum((n * 4 + 255) // 256 * 256 for n in numel)
+    dev = torch.device("cuda:0")
+    ra = RegionArena(dev, [5 * S, S, S], verbose=verbose)
+    f32 = torch.float32
+    Theta, M, th, m, inp = (ra.alloc_list(0, numel, f32) for _ in range(5))
+    acc, wm = ra.alloc_list(1, numel, f32), ra.alloc_list(2, numel, f32)
+    fill_initial_model(w, Theta)
+    fill_delta_slot(w, 0, inp)
+    hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, 1 << 30)
+    gps = B.halos_gps_create(numel, hp, Theta, M)
+    lps = B.halos_lps_create(gps, 0, 1, th, m, acc)
+    out = {}
+    try:
+        B.halos_lps_set_worker_model(lps, 0, wm)
+        B.halos_pull_model(lps, False, wm)
+        stream = torch.cuda.current_stream(dev)
+        for mode, bpp in (("fp32_delta", 32), ("end_model", 36)):
+            push = (lambda: B.halos_lps_push_update(lps, 0, inp, B.F32)) if mode == "fp32_delta" else \
+                   (lambda: B.halos_lps_push_end_model(lps, 0, inp))
+            pairs = []
+            for i in range(reps + 2):
+                push()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(stream)
+                B.halos_lps_step_pull(lps)
+                b.record(stream)
+                if i >= 2:
+                    pairs.append((a, b))
+            torch.cuda.synchronize()
+            ms = np.array([a.elapsed_time(b) for a, b in pairs])
+            out[mode] = {"launches": int(ms.size), "avg_ms": float(ms.mean()), "bytes_per_param": bpp,
+                         "achieved_GBps": float(N * bpp / (ms.mean() * 1e-3) / 1e9),
+                         "frac_of_peak": float(N * bpp / (ms.mean() * 1e-3) / 1e9 / HBM_PEAK_GBS)}
+    finally:
+        B.halos_lps_destroy(lps)
+        B.halos_gps_destroy(gps)
+        del ra, Theta, M, th, m, inp, acc, wm
+        torch.cuda.empty_cache()
+    out["workload"] = name
+    out["note"] = ("end_model: the server reads the worker's start and end models (8 B) instead of an fp32 delta (4 B) "
+                   "and the worker skips its own 12 B/parameter subtraction pass")
+    return out
+
+
 def cpu_baseline(name: str, budget_elements: int = 1 << 22):
     """Time the CPU oracle (fp64, literal form, single thread) on a bounded sample: every event of one
     workload-sized trace, on `budget_elements` evenly spaced parameters of the workload."""
@@ -245,6 +302,8 @@ def main():
     ap.add_argument("--snapshot", action="store_true",
                     help="form the accumulated update by subtracting the snapshot theta_{t_last} (Alg. 1 line 14 as "
                          "written) instead of keeping a running sum: fewer bytes per update, larger rounding error")
+    ap.add_argument("--no-end-model-ab", action="store_true",
+                    help="skip the A/B of the update pass fed a delta vs fed the worker's end model")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
 
@@ -266,6 +325,7 @@ def main():
     others = []
     for name in [x for x in args.also.split(",") if x and x != args.workload]:
         others.append(run_workload(name, args.steps, args.warmup, not args.quiet, args.placement, not args.no_fuse_pull, args.snapshot))
+    ab = None if args.no_end_model_ab else end_model_ab(args.workload, verbose=not args.quiet)
     cpu = None if args.no_cpu_baseline else cpu_baseline(args.workload)
 
     def brief(r):
@@ -287,6 +347,7 @@ def main():
         "whole_path_GBps": head["whole_path_GBps"],
         "kernels": head["kernels"],
         "workloads": [brief(r) for r in others],
+        "end_model_ab": ab,
     }
     print(json.dumps(line))
 

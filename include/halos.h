@@ -160,6 +160,22 @@ halos_status halos_lps_push_update(halos_lps *lps, int32_t worker, const void *c
                                    halos_dtype dtype, uint32_t staleness);
 
 /*
+ * The same arrival with the worker's END model theta_{t,H} in place of its delta: the subtraction of Algorithm 1
+ * line 26 (delta = theta_{t,H} - theta_{t,0}) moves from the worker into the server's update pass, which forms the
+ * pseudo-gradient g = theta_{t,0} - theta_{t,H} per element in fp32 -- the value a worker computing it in fp32
+ * would have sent -- and then proceeds exactly as for halos_lps_push_update.  theta_{t,0} is read from the buffer
+ * registered for the worker with halos_lps_set_worker_model: the model the server wrote there when the worker last
+ * pulled, which the worker must have left unchanged (it trains in `end_model`).  The update must be applied with
+ * halos_lps_step_pull, whose pass replaces theta_{t,0} by the new model right after reading it; halos_lps_step on
+ * such an item is ESTATE.  The worker saves its subtraction pass and the delta buffer; the server reads 4 more
+ * bytes per parameter than for an fp32 delta.
+ *   end_model  device tensors of the layout, fp32, 16-byte aligned; borrowed like `g` above
+ * ESTATE if the worker has no registered model buffer or already has an item queued; otherwise as halos_lps_push_update.
+ * The |g|^2 monitor, where enabled, sees the g formed here.
+ */
+halos_status halos_lps_push_end_model(halos_lps *lps, int32_t worker, const void *const *end_model, uint32_t staleness);
+
+/*
  * The global model sent back by the GPS arrives (Algorithm 1 line 17).  Appends it to the same queue as
  * the worker deltas; no device work.  ESTATE unless a halos_gps_merge for this LPS has run and its
  * result has not been delivered yet.

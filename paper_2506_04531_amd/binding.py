@@ -76,6 +76,7 @@ def load_library():
         "halos_gps_create": [P(_Layout), P(HParams), P(vp), P(vp), vp, P(vp)],
         "halos_lps_create": [vp, i32, i32, P(vp), P(vp), P(vp), vp, P(vp)],
         "halos_lps_push_update": [vp, i32, P(vp), i32, u32],
+        "halos_lps_push_end_model": [vp, i32, P(vp), u32],
         "halos_lps_push_global": [vp],
         "halos_lps_step": [vp, vp, P(StepInfo)],
         "halos_lps_step_pull": [vp, vp, P(StepInfo)],
@@ -162,6 +163,10 @@ def halos_lps_create(gps: int, lps_id: int, n_workers: int, theta, m, acc, strea
 
 def halos_lps_push_update(lps: int, worker: int, g, dtype: int, staleness: int = 0) -> None:
     _check(load_library().halos_lps_push_update(lps, worker, _ptrs(g), dtype, staleness))
+
+
+def halos_lps_push_end_model(lps: int, worker: int, end_model, staleness: int = 0) -> None:
+    _check(load_library().halos_lps_push_end_model(lps, worker, _ptrs(end_model), staleness))
 
 
 def halos_lps_push_global(lps: int) -> None:

@@ -81,6 +81,7 @@ struct halos_gps {
 struct PendingDelta {
     std::vector<const void *> ptrs;
     halos_dtype dtype = HALOS_F32;
+    bool end_model = false;            // ptrs hold the worker's end model, not a pseudo-gradient
     uint32_t staleness = 0;
 };
 
@@ -407,14 +408,17 @@ void halos_lps_destroy(halos_lps *l) {
     delete l;
 }
 
-halos_status halos_lps_push_update(halos_lps *l, int32_t worker, const void *const *gptrs, halos_dtype dtype,
-                                   uint32_t staleness) {
+static halos_status push_delta_impl(halos_lps *l, int32_t worker, const void *const *gptrs, halos_dtype dtype,
+                                    uint32_t staleness, bool end_model) {
     if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
     if (dtype != HALOS_F32 && dtype != HALOS_BF16) return fail(HALOS_EINVAL, "unknown delta dtype %d", (int)dtype);
     ProtoResult pr = l->proto.can_push_delta(worker);
     if (pr == PROTO_BAD_ARG) return fail(HALOS_EINVAL, "worker %d outside 0..%d", worker, l->proto.n_workers() - 1);
     if (pr == PROTO_BAD_STATE) return fail(HALOS_ESTATE, "worker %d of lps %d already has a delta queued", worker, l->id);
-    if (!gptrs) return fail(HALOS_EINVAL, "g: pointer array is NULL");
+    if (end_model && !l->worker_has_model[worker])
+        return fail(HALOS_ESTATE, "worker %d of lps %d has no model buffer registered: its start model is unknown", worker, l->id);
+    const char *what = end_model ? "end_model" : "g";
+    if (!gptrs) return fail(HALOS_EINVAL, "%s: pointer array is NULL", what);
     const halos_gps *g = l->gps;
     const size_t nt = g->numel.size();
     std::vector<const void *> &seen = l->validated[worker];
@@ -422,7 +426,7 @@ halos_status halos_lps_push_update(halos_lps *l, int32_t worker, const void *con
                       std::memcmp(seen.data(), gptrs, nt * sizeof(void *)) == 0;
     if (!same) {      // a worker normally reuses its receive buffers: their ranges are checked once
         halos_status st = check_device(g);
-        if (st == HALOS_OK) st = check_tensors(g, gptrs, dtype == HALOS_BF16 ? 2 : 4, "g");
+        if (st == HALOS_OK) st = check_tensors(g, gptrs, dtype == HALOS_BF16 ? 2 : 4, what);
         if (st != HALOS_OK) return st;
         seen.assign(gptrs, gptrs + nt);
         l->validated_dtype[worker] = dtype;
@@ -430,10 +434,20 @@ halos_status halos_lps_push_update(halos_lps *l, int32_t worker, const void *con
     PendingDelta &p = l->pending[worker];
     p.ptrs.assign(gptrs, gptrs + nt);
     p.dtype = dtype;
+    p.end_model = end_model;
     p.staleness = staleness;
     if (staleness > l->max_staleness) l->max_staleness = staleness;
     l->proto.push_delta(worker);
     return HALOS_OK;
+}
+
+halos_status halos_lps_push_update(halos_lps *l, int32_t worker, const void *const *gptrs, halos_dtype dtype,
+                                   uint32_t staleness) {
+    return push_delta_impl(l, worker, gptrs, dtype, staleness, false);
+}
+
+halos_status halos_lps_push_end_model(halos_lps *l, int32_t worker, const void *const *end_model, uint32_t staleness) {
+    return push_delta_impl(l, worker, end_model, HALOS_F32, staleness, true);
 }
 
 halos_status halos_lps_push_global(halos_lps *l) {
@@ -480,6 +494,10 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
         const UpdateOutcome oc = l->proto.preview_update();
         const PendingDelta &p = l->pending[head.worker];
         float *const *pull_tab = nullptr;
+        if (p.end_model && !pull)
+            return fail(HALOS_ESTATE, "lps %d: worker %d sent its end model; halos_lps_step_pull applies it (the pass "
+                        "that reads the worker's start model also replaces it)", l->id, head.worker);
+        const int g_kind = p.end_model ? GRAD_END_MODEL : (p.dtype == HALOS_BF16 ? GRAD_BF16 : GRAD_F32);
         if (pull) {
             if (!l->worker_has_model[head.worker])
                 return fail(HALOS_ESTATE, "worker %d of lps %d has no model buffer registered", head.worker, l->id);
@@ -498,12 +516,11 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
             if (l->cycle.d() > 1) {
                 const float inv_d = 1.0f / (float)l->cycle.d();
                 e = launch_lps_update_delayed((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_buffer, l->d_acc,
-                                              pull_tab, args, p.dtype == HALOS_BF16, third_mode, (int)l->cycle.next(),
+                                              pull_tab, args, g_kind, third_mode, (int)l->cycle.next(),
                                               l->rule.eta, l->rule.beta, l->rule.cg * inv_d, inv_d, shape);
             } else {
                 e = launch_lps_update((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_acc, pull_tab, args,
-                                      p.dtype == HALOS_BF16, third_mode, l->rule.eta, l->rule.beta, l->rule.cg, partials,
-                                      shape);
+                                      g_kind, third_mode, l->rule.eta, l->rule.beta, l->rule.cg, partials, shape);
             }
             if (e != hipSuccess) return fail_hip(e, "launching the local update");
             n_partials += launch_grid_size(r, shape);

@@ -70,6 +70,23 @@ __device__ __forceinline__ f32x4 ldg4(const gu16 *p) {
 __device__ __forceinline__ float ldg1(const gf32 *p) { return *p; }
 __device__ __forceinline__ float ldg1(const gu16 *p) { return bf16_up(*p); }
 
+__device__ __forceinline__ f32x4 sub4(f32x4 a, f32x4 b);
+
+// The pseudo-gradient of four consecutive elements: read from the worker's delta tensor, or (FROM_END) formed here
+// as start - end from the worker's start model (the buffer the server filled at the worker's last pull) and the end
+// model the worker sent (Alg. 1 line 26 moved to the server, sign flipped).
+template <bool FROM_END, bool NT, typename GP>
+__device__ __forceinline__ f32x4 grad4(const GP *g, const gf32 *start, uint32_t off) {
+    if constexpr (FROM_END) return sub4(ld4<NT>(start + off), ld4<NT>(g + off));
+    else return ldg4<NT>(g + off);
+}
+
+template <bool FROM_END, typename GP>
+__device__ __forceinline__ float grad1(const GP *g, const gf32 *start, uint32_t k) {
+    if constexpr (FROM_END) return __fsub_rn(start[k], ldg1(g + k));
+    else return ldg1(g + k);
+}
+
 // ModelUpdate (App. E) on one element; returns the step that was subtracted from x.
 __device__ __forceinline__ float model_update(float &x, float &m, float g, float eta, float beta, float cg) {
     m = __fmaf_rn(beta, m, g);
@@ -150,12 +167,14 @@ __device__ __forceinline__ void block_sum_store(double v, double *dst) {
 // With PULL the updated model is also written to a second tensor list (the buffer the worker starts
 // its next round from: Alg. 1 lines 11-12 in one pass instead of an update pass plus a copy pass).
 // With NORM every workgroup also leaves the sum of g^2 over its tiles in partials[blockIdx.x].
-template <typename GT, int THIRD, bool NT, bool PULL, bool NORM>
+// With FROM_END (needs PULL) the delta tensors hold the worker's end model and pull_tab its start model.
+template <typename GT, int THIRD, bool NT, bool PULL, bool NORM, bool FROM_END = false>
 __global__ void __launch_bounds__(BLOCK_THREADS)
 lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, uint32_t tensor_base,
                   float *const *__restrict__ theta_tab, float *const *__restrict__ m_tab,
                   float *const *__restrict__ acc_tab, float *const *__restrict__ pull_tab, PtrArgs gargs,
                   float eta, float beta, float cg, double *__restrict__ partials) {
+    static_assert(!FROM_END || (PULL && sizeof(GT) == 4), "an end model is fp32 and needs the worker's start model");
     const uint32_t tid = threadIdx.x;
     double norm_acc = 0.0;
     for (uint32_t t = tile_lo + blockIdx.x; t < tile_hi; t += gridDim.x) {
@@ -171,7 +190,7 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
-                gv[u] = ldg4<NT>(g + off);
+                gv[u] = grad4<FROM_END, NT>(g, pd, off);
                 mv[u] = ld4<NT>(mm + off);
                 tv[u] = ld4<NT>(th + off);
                 if constexpr (THIRD != 0) av[u] = ld4<NT>(ac + off);
@@ -196,7 +215,7 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
             const uint32_t len = tl.len;
             for (uint32_t off = tid * VEC; off < len; off += BLOCK_THREADS * VEC) {
                 if (off + VEC <= len) {
-                    f32x4 gv = ldg4<NT>(g + off), mv = ld4<NT>(mm + off), tv = ld4<NT>(th + off);
+                    f32x4 gv = grad4<FROM_END, NT>(g, pd, off), mv = ld4<NT>(mm + off), tv = ld4<NT>(th + off);
                     if constexpr (NORM) norm_acc += static_cast<double>(sumsq4(gv, 0.f));
                     const f32x4 s = model_update4(tv, mv, gv, eta, beta, cg);
                     st4<NT>(mm + off, mv);
@@ -207,7 +226,7 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
                 } else {
                     for (uint32_t k = off; k < len; ++k) {      // ragged tail: fewer than 4 elements
                         float mv = mm[k], tv = th[k];
-                        const float gk = ldg1(g + k);
+                        const float gk = grad1<FROM_END>(g, pd, k);
                         if constexpr (NORM) norm_acc += static_cast<double>(__fmul_rn(gk, gk));
                         const float s = model_update(tv, mv, gk, eta, beta, cg);
                         mm[k] = mv; th[k] = tv;
@@ -316,13 +335,14 @@ __device__ __forceinline__ f32x4 delayed_update4(f32x4 &x, f32x4 &m, f32x4 &b, f
 }
 
 // S1 under the delayed rule.  THIRD and PULL as in lps_update_kernel; accesses are non-temporal.
-template <typename GT, int THIRD, bool PULL, int RULE>
+template <typename GT, int THIRD, bool PULL, int RULE, bool FROM_END = false>
 __global__ void __launch_bounds__(BLOCK_THREADS)
 lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, uint32_t tensor_base,
                           float *const *__restrict__ theta_tab, float *const *__restrict__ m_tab,
                           float *const *__restrict__ buf_tab, float *const *__restrict__ acc_tab,
                           float *const *__restrict__ pull_tab, PtrArgs gargs, float eta, float beta, float cgd,
                           float inv_d) {
+    static_assert(!FROM_END || (PULL && sizeof(GT) == 4), "an end model is fp32 and needs the worker's start model");
     constexpr bool NT = true;
     constexpr bool LOAD_B = RULE != CYCLE_FIRST, STORE_B = RULE != CYCLE_REFRESH, USE_M = RULE == CYCLE_REFRESH;
     const uint32_t tid = threadIdx.x;
@@ -341,7 +361,7 @@ lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
-                gv[u] = ldg4<NT>(g + off);
+                gv[u] = grad4<FROM_END, NT>(g, pd, off);
                 bv[u] = LOAD_B ? ld4<NT>(bb + off) : zero;
                 mv[u] = USE_M ? ld4<NT>(mm + off) : zero;
                 tv[u] = ld4<NT>(th + off);
@@ -362,7 +382,7 @@ lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint
             const uint32_t len = tl.len;
             for (uint32_t off = tid * VEC; off < len; off += BLOCK_THREADS * VEC) {
                 if (off + VEC <= len) {
-                    f32x4 gv = ldg4<NT>(g + off), tv = ld4<NT>(th + off);
+                    f32x4 gv = grad4<FROM_END, NT>(g, pd, off), tv = ld4<NT>(th + off);
                     f32x4 bv = LOAD_B ? ld4<NT>(bb + off) : zero, mv = USE_M ? ld4<NT>(mm + off) : zero;
                     const f32x4 s = delayed_update4<RULE>(tv, mv, bv, gv, eta, beta, cgd, inv_d);
                     if constexpr (STORE_B) st4<NT>(bb + off, bv);
@@ -374,7 +394,7 @@ lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint
                 } else {
                     for (uint32_t k = off; k < len; ++k) {      // ragged tail: fewer than 4 elements
                         float tv = th[k], bv = LOAD_B ? bb[k] : 0.f, mv = USE_M ? mm[k] : 0.f;
-                        const float s = delayed_update<RULE>(tv, mv, bv, ldg1(g + k), eta, beta, cgd, inv_d);
+                        const float s = delayed_update<RULE>(tv, mv, bv, grad1<FROM_END>(g, pd, k), eta, beta, cgd, inv_d);
                         if constexpr (STORE_B) bb[k] = bv;
                         if constexpr (USE_M) mm[k] = mv;
                         th[k] = tv;
@@ -626,38 +646,33 @@ inline dim3 grid_for(TileRange r, LaunchShape shape) {
 uint32_t launch_grid_size(TileRange r, LaunchShape shape) { return r.hi > r.lo ? grid_for(r, shape).x : 0u; }
 
 hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
-                             float *const *acc, float *const *pull, const PtrArgs &g, bool g_is_bf16, int third_mode,
+                             float *const *acc, float *const *pull, const PtrArgs &g, int g_kind, int third_mode,
                              float eta, float beta, float cg, double *norm_partials, LaunchShape shape) {
     if (r.hi <= r.lo) return hipSuccess;
+    if (g_kind < GRAD_F32 || g_kind > GRAD_END_MODEL || third_mode < 0 || third_mode > 2 || (g_kind == GRAD_END_MODEL && !pull))
+        return hipErrorInvalidValue;
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
-#define HALOS_LAUNCH_UPD(GT, THIRD, NT, PULL)                                                                              \
+#define HALOS_LAUNCH_UPD(GT, THIRD, NT, PULL, END)                                                                         \
     do {                                                                                                                 \
         if (norm_partials)                                                                                               \
-            lps_update_kernel<GT, THIRD, NT, PULL, true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, r.tensor_base, theta, \
-                                                                                   m, acc, pull, g, eta, beta, cg,       \
-                                                                                   norm_partials);                       \
+            lps_update_kernel<GT, THIRD, NT, PULL, true, END><<<grid, block, 0, stream>>>(                               \
+                tiles, r.lo, r.hi, r.tensor_base, theta, m, acc, pull, g, eta, beta, cg, norm_partials);                 \
         else                                                                                                             \
-            lps_update_kernel<GT, THIRD, NT, PULL, false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, r.tensor_base,     \
-                                                                                    theta, m, acc, pull, g, eta, beta,   \
-                                                                                    cg, nullptr);                        \
+            lps_update_kernel<GT, THIRD, NT, PULL, false, END><<<grid, block, 0, stream>>>(                              \
+                tiles, r.lo, r.hi, r.tensor_base, theta, m, acc, pull, g, eta, beta, cg, nullptr);                       \
     } while (0)
-#define HALOS_LAUNCH_UPD_NT(GT, THIRD, PULL) \
-    do { if (shape.nontemporal) HALOS_LAUNCH_UPD(GT, THIRD, true, PULL); else HALOS_LAUNCH_UPD(GT, THIRD, false, PULL); } while (0)
-    const int variant = (g_is_bf16 ? 6 : 0) + 2 * third_mode + (pull ? 1 : 0);
-    switch (variant) {
-        case 0: HALOS_LAUNCH_UPD_NT(float, 0, false); break;
-        case 1: HALOS_LAUNCH_UPD_NT(float, 0, true); break;
-        case 2: HALOS_LAUNCH_UPD_NT(float, 1, false); break;
-        case 3: HALOS_LAUNCH_UPD_NT(float, 1, true); break;
-        case 4: HALOS_LAUNCH_UPD_NT(float, 2, false); break;
-        case 5: HALOS_LAUNCH_UPD_NT(float, 2, true); break;
-        case 6: HALOS_LAUNCH_UPD_NT(unsigned short, 0, false); break;
-        case 7: HALOS_LAUNCH_UPD_NT(unsigned short, 0, true); break;
-        case 8: HALOS_LAUNCH_UPD_NT(unsigned short, 1, false); break;
-        case 9: HALOS_LAUNCH_UPD_NT(unsigned short, 1, true); break;
-        case 10: HALOS_LAUNCH_UPD_NT(unsigned short, 2, false); break;
-        default: HALOS_LAUNCH_UPD_NT(unsigned short, 2, true); break;
-    }
+#define HALOS_LAUNCH_UPD_NT(GT, THIRD, PULL, END) \
+    do { if (shape.nontemporal) HALOS_LAUNCH_UPD(GT, THIRD, true, PULL, END); else HALOS_LAUNCH_UPD(GT, THIRD, false, PULL, END); } while (0)
+#define HALOS_LAUNCH_UPD_THIRD(GT, PULL, END)                                  \
+    do {                                                                       \
+        if (third_mode == 0) HALOS_LAUNCH_UPD_NT(GT, 0, PULL, END);            \
+        else if (third_mode == 1) HALOS_LAUNCH_UPD_NT(GT, 1, PULL, END);       \
+        else HALOS_LAUNCH_UPD_NT(GT, 2, PULL, END);                            \
+    } while (0)
+    if (g_kind == GRAD_END_MODEL) HALOS_LAUNCH_UPD_THIRD(float, true, true);
+    else if (g_kind == GRAD_BF16) { if (pull) HALOS_LAUNCH_UPD_THIRD(unsigned short, true, false); else HALOS_LAUNCH_UPD_THIRD(unsigned short, false, false); }
+    else { if (pull) HALOS_LAUNCH_UPD_THIRD(float, true, false); else HALOS_LAUNCH_UPD_THIRD(float, false, false); }
+#undef HALOS_LAUNCH_UPD_THIRD
 #undef HALOS_LAUNCH_UPD_NT
 #undef HALOS_LAUNCH_UPD
     return hipGetLastError();
@@ -676,36 +691,32 @@ hipError_t launch_gps_update(hipStream_t stream, const Tile *tiles, TileRange r,
 
 hipError_t launch_lps_update_delayed(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
                                      float *const *m, float *const *buffer, float *const *acc, float *const *pull,
-                                     const PtrArgs &g, bool g_is_bf16, int third_mode, int cycle_pos, float eta,
+                                     const PtrArgs &g, int g_kind, int third_mode, int cycle_pos, float eta,
                                      float beta, float cgd, float inv_d, LaunchShape shape) {
     if (r.hi <= r.lo) return hipSuccess;
-    if (cycle_pos < CYCLE_FIRST || cycle_pos > CYCLE_REFRESH || third_mode < 0 || third_mode > 2) return hipErrorInvalidValue;
+    if (cycle_pos < CYCLE_FIRST || cycle_pos > CYCLE_REFRESH || third_mode < 0 || third_mode > 2 ||
+        g_kind < GRAD_F32 || g_kind > GRAD_END_MODEL || (g_kind == GRAD_END_MODEL && !pull))
+        return hipErrorInvalidValue;
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
-#define HALOS_LAUNCH_DN(GT, THIRD, PULL, RULE)                                                                          \
-    lps_update_delayed_kernel<GT, THIRD, PULL, RULE><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, r.tensor_base, theta, m, \
-                                                                                buffer, acc, pull, g, eta, beta, cgd,    \
-                                                                                inv_d)
-#define HALOS_LAUNCH_DN_RULE(GT, THIRD, PULL)                                  \
-    do {                                                                       \
-        if (cycle_pos == CYCLE_FIRST) HALOS_LAUNCH_DN(GT, THIRD, PULL, CYCLE_FIRST); \
-        else if (cycle_pos == CYCLE_INNER) HALOS_LAUNCH_DN(GT, THIRD, PULL, CYCLE_INNER); \
-        else HALOS_LAUNCH_DN(GT, THIRD, PULL, CYCLE_REFRESH);                     \
+#define HALOS_LAUNCH_DN(GT, THIRD, PULL, RULE, END)                                                                     \
+    lps_update_delayed_kernel<GT, THIRD, PULL, RULE, END><<<grid, block, 0, stream>>>(                                  \
+        tiles, r.lo, r.hi, r.tensor_base, theta, m, buffer, acc, pull, g, eta, beta, cgd, inv_d)
+#define HALOS_LAUNCH_DN_RULE(GT, THIRD, PULL, END)                                       \
+    do {                                                                                 \
+        if (cycle_pos == CYCLE_FIRST) HALOS_LAUNCH_DN(GT, THIRD, PULL, CYCLE_FIRST, END); \
+        else if (cycle_pos == CYCLE_INNER) HALOS_LAUNCH_DN(GT, THIRD, PULL, CYCLE_INNER, END); \
+        else HALOS_LAUNCH_DN(GT, THIRD, PULL, CYCLE_REFRESH, END);                       \
     } while (0)
-    const int variant = (g_is_bf16 ? 6 : 0) + 2 * third_mode + (pull ? 1 : 0);
-    switch (variant) {
-        case 0: HALOS_LAUNCH_DN_RULE(float, 0, false); break;
-        case 1: HALOS_LAUNCH_DN_RULE(float, 0, true); break;
-        case 2: HALOS_LAUNCH_DN_RULE(float, 1, false); break;
-        case 3: HALOS_LAUNCH_DN_RULE(float, 1, true); break;
-        case 4: HALOS_LAUNCH_DN_RULE(float, 2, false); break;
-        case 5: HALOS_LAUNCH_DN_RULE(float, 2, true); break;
-        case 6: HALOS_LAUNCH_DN_RULE(unsigned short, 0, false); break;
-        case 7: HALOS_LAUNCH_DN_RULE(unsigned short, 0, true); break;
-        case 8: HALOS_LAUNCH_DN_RULE(unsigned short, 1, false); break;
-        case 9: HALOS_LAUNCH_DN_RULE(unsigned short, 1, true); break;
-        case 10: HALOS_LAUNCH_DN_RULE(unsigned short, 2, false); break;
-        default: HALOS_LAUNCH_DN_RULE(unsigned short, 2, true); break;
-    }
+#define HALOS_LAUNCH_DN_THIRD(GT, PULL, END)                                   \
+    do {                                                                       \
+        if (third_mode == 0) HALOS_LAUNCH_DN_RULE(GT, 0, PULL, END);           \
+        else if (third_mode == 1) HALOS_LAUNCH_DN_RULE(GT, 1, PULL, END);      \
+        else HALOS_LAUNCH_DN_RULE(GT, 2, PULL, END);                           \
+    } while (0)
+    if (g_kind == GRAD_END_MODEL) HALOS_LAUNCH_DN_THIRD(float, true, true);
+    else if (g_kind == GRAD_BF16) { if (pull) HALOS_LAUNCH_DN_THIRD(unsigned short, true, false); else HALOS_LAUNCH_DN_THIRD(unsigned short, false, false); }
+    else { if (pull) HALOS_LAUNCH_DN_THIRD(float, true, false); else HALOS_LAUNCH_DN_THIRD(float, false, false); }
+#undef HALOS_LAUNCH_DN_THIRD
 #undef HALOS_LAUNCH_DN_RULE
 #undef HALOS_LAUNCH_DN
     return hipGetLastError();

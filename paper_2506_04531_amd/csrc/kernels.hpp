@@ -46,8 +46,12 @@ struct TileRange {      // tiles [lo, hi) all belong to tensors [tensor_base, te
 // (Alg. 1 line 12, the model handed back to the worker, written in the same pass).
 // If `norm_partials` is not null the launch also leaves, per workgroup, the sum of g^2 over the workgroup's tiles in
 // norm_partials[0 .. launch_grid_size(r, shape)).
+// g_kind says what the tensors in `g` hold: the pseudo-gradient in fp32 or bf16, or (GRAD_END_MODEL, needs `pull`)
+// the worker's END model in fp32 -- the pseudo-gradient is then formed in the kernel as start - end, the start model
+// being what `pull` points to before this launch overwrites it (Alg. 1 line 26 on the server, sign flipped).
+constexpr int GRAD_F32 = 0, GRAD_BF16 = 1, GRAD_END_MODEL = 2;
 hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
-                             float *const *acc, float *const *pull, const PtrArgs &g, bool g_is_bf16, int third_mode,
+                             float *const *acc, float *const *pull, const PtrArgs &g, int g_kind, int third_mode,
                              float eta, float beta, float cg, double *norm_partials, LaunchShape shape);
 
 // Number of workgroups a launch over range r uses (0 for an empty range).
@@ -68,7 +72,7 @@ hipError_t launch_gps_update(hipStream_t stream, const Tile *tiles, TileRange r,
 constexpr int CYCLE_FIRST = 1, CYCLE_INNER = 2, CYCLE_REFRESH = 3;
 hipError_t launch_lps_update_delayed(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
                                      float *const *m, float *const *buffer, float *const *acc, float *const *pull,
-                                     const PtrArgs &g, bool g_is_bf16, int third_mode, int cycle_pos, float eta,
+                                     const PtrArgs &g, int g_kind, int third_mode, int cycle_pos, float eta,
                                      float beta, float cgd, float inv_d, LaunchShape shape);
 hipError_t launch_gps_update_delayed(hipStream_t stream, const Tile *tiles, TileRange r, float *const *Theta,
                                      float *const *M, float *const *buffer, float *const *G, float *const *out,

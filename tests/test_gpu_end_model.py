@@ -1,0 +1,121 @@
+"""halos_lps_push_end_model: the worker sends its end model and the server's update pass forms the pseudo-gradient
+start - end itself (Alg. 1 line 26 moved into the pass that applies it).  Checked against the CPU oracle, which is fed
+the fp32 difference a worker would have computed from the same two models."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import FORM_ACCUMULATOR, FORM_LITERAL, HalosOracle
+import oracle as O
+from parity_util import REL_TOL, compare_state
+from synth.tensors import scale_f32
+from test_gpu_parity import RAGGED
+
+pytestmark = pytest.mark.gpu
+F32 = np.float32
+
+
+def _upload(tensors, offsets, flat):
+    for t, o in zip(tensors, offsets):
+        if t.numel():
+            t.copy_(torch.from_numpy(np.ascontiguousarray(flat[int(o):int(o) + t.numel()])))
+
+
+def _download(tensors):
+    return torch.cat([t.reshape(-1) for t in tensors]).cpu().numpy()
+
+
+@pytest.mark.parametrize("d_l,d_g", [(1, 1), (2, 3)])
+def test_end_model_rounds_match_the_oracle(d_l, d_g):
+    from paper_2506_04531_amd import binding as B
+    from paper_2506_04531_amd.harness import alloc_tensor_list
+    lay = RAGGED
+    n, numel, off = lay.total, [int(x) for x in lay.numel], lay.offsets
+    dev = "cuda:0"
+    n_workers, K, rounds, seed = 3, 3, 26, 4242
+    hyper = dict(eta_l=0.2 * d_l, beta_l=0.9, eta_g=0.15 * d_g, beta_g=0.5, alpha=0.25)
+    idx = torch.arange(n, dtype=torch.int64)
+    theta0 = synth.normal_at(seed, 0, idx, scale_f32(0.02)).numpy()
+    print(f"[parity] end-model rounds n={n} d_l={d_l} d_g={d_g} rounds={rounds}", flush=True)
+
+    oracles = [HalosOracle(theta0, 1, K=K, precision=p, form=f, **hyper)
+               for p, f in ((32, FORM_ACCUMULATOR), (64, FORM_LITERAL))]
+    for o in oracles:
+        if d_l > 1:
+            o.set_delay(0, d_l)
+        if d_g > 1:
+            o.set_delay(-1, d_g)
+
+    mk = lambda: alloc_tensor_list(numel, torch.float32, dev)
+    Theta, M, th, m, acc = mk(), mk(), mk(), mk(), mk()
+    _upload(Theta, off, theta0)
+    hp = B.paper_hparams(hyper["eta_l"], hyper["beta_l"], hyper["eta_g"], hyper["beta_g"], hyper["alpha"], K)
+    gps = B.halos_gps_create(numel, hp, Theta, M)
+    lps = B.halos_lps_create(gps, 0, n_workers, th, m, acc)
+    bufs = []
+    try:
+        if d_l > 1:
+            bufs.append(mk()); B.halos_lps_set_momentum_delay(lps, d_l, bufs[-1])
+        if d_g > 1:
+            bufs.append(mk()); B.halos_gps_set_momentum_delay(gps, d_g, bufs[-1])
+        start_buf = [mk() for _ in range(n_workers)]       # the worker's start model, written by the server
+        end_buf = [mk() for _ in range(n_workers)]         # where the worker trains
+        # a worker that has no registered buffer cannot send an end model
+        with pytest.raises(B.HalosError) as e:
+            B.halos_lps_push_end_model(lps, 0, end_buf[0])
+        assert e.value.status == B.ESTATE
+        start = []
+        for k in range(n_workers):
+            B.halos_lps_set_worker_model(lps, k, start_buf[k])
+            B.halos_pull_model(lps, False, start_buf[k])                      # first pull: theta_0
+            start.append(oracles[0].get(O.THETA).astype(F32))
+        rng_order = np.random.default_rng(seed)
+        for r in range(rounds):
+            k = int(rng_order.integers(0, n_workers))
+            progress = synth.normal_at(seed, 100 + r, idx, scale_f32(1e-3)).numpy()
+            end = (start[k] - progress).astype(F32)                           # the worker's end model
+            g = (start[k] - end).astype(F32)                                  # what a worker would send (negated delta)
+            _upload(end_buf[k], off, end)
+            B.halos_lps_push_end_model(lps, k, end_buf[k], staleness=r % 5)
+            if r == 4:       # the plain step refuses it and leaves it queued
+                with pytest.raises(B.HalosError) as e:
+                    B.halos_lps_step(lps)
+                assert e.value.status == B.ESTATE
+                assert B.halos_lps_get_counters(lps)["queued"] == 1
+            info = B.halos_lps_step_pull(lps)
+            sent = None
+            for o in oracles:
+                o.arrive_delta(0, k, g)
+                oi = o.lps_step(0)
+                assert (oi.kind, oi.t, oi.t_last, oi.sent, oi.accumulated) == \
+                       (info.kind, info.t, info.t_last, info.delta_ready, info.accumulated)
+                sent = oi.sent
+            start[k] = oracles[0].get(O.THETA).astype(F32)                    # the model handed back in the same pass
+            if sent:
+                B.halos_gps_merge(gps, lps)
+                B.halos_lps_push_global(lps)
+                assert B.halos_lps_step(lps).kind == 2
+                for o in oracles:
+                    o.gps_receive(0)
+                    o.arrive_global(0)
+                    assert o.lps_step(0).kind == 2
+        torch.cuda.synchronize()
+        gpu = {"Theta": _download(Theta), "M": _download(M), "theta0": _download(th), "m0": _download(m),
+               "aux0": _download(acc)}
+        handed_back = [_download(b) for b in start_buf]
+    finally:
+        B.halos_lps_destroy(lps)
+        B.halos_gps_destroy(gps)
+
+    def state(o):
+        names = {"Theta": O.GPS_THETA, "M": O.GPS_MOM, "theta0": O.THETA, "m0": O.MOM, "aux0": O.AUX}
+        return {k: (o.get(w, 0), o.get(w + O.SCALE, 0)) for k, w in names.items()}
+
+    worst, n_diff, name = compare_state(gpu, state(oracles[0]), bitwise=True)
+    assert n_diff == 0, (n_diff, worst, name)
+    for k in range(n_workers):
+        assert np.array_equal(handed_back[k].view(np.uint32), start[k].view(np.uint32)), k
+    worst, _, name = compare_state(gpu, state(oracles[1]), bitwise=False)
+    print(f"[parity] end-model rounds: bit-exact vs fp32 oracle; max rel err vs fp64 reference {worst:.3g} ({name})", flush=True)
+    assert worst <= REL_TOL, (worst, name)
