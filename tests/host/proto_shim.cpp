@@ -41,6 +41,14 @@ int proto_consume(void *p) {
     if (rc == halos::PROTO_OK) s->consume();
     return rc;
 }
+// momentum cycle of the delayed rule
+void *cycle_new() { return new halos::MomentumCycle; }
+void cycle_free(void *p) { delete (halos::MomentumCycle *)p; }
+int cycle_set_d(void *p, int d) { return ((halos::MomentumCycle *)p)->set_d(d); }
+int cycle_next(void *p) { return ((halos::MomentumCycle *)p)->next(); }
+void cycle_commit(void *p) { ((halos::MomentumCycle *)p)->commit(); }
+int cycle_seen(void *p) { return ((halos::MomentumCycle *)p)->seen(); }
+int cycle_d(void *p) { return ((halos::MomentumCycle *)p)->d(); }
 int proto_phase(void *p) { return ((LpsProtocol *)p)->phase(); }
 int proto_queued(void *p) { return ((LpsProtocol *)p)->queued(); }
 }

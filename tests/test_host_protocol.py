@@ -22,6 +22,9 @@ def shim(tmp_path_factory):
               "proto_phase", "proto_queued"):
         getattr(lib, f).argtypes = [ctypes.c_void_p] + {"proto_set_K": [ctypes.c_int], "proto_push_delta": [ctypes.c_int],
                                                          "proto_step": [ctypes.POINTER(ctypes.c_longlong)]}.get(f, [])
+    lib.cycle_new.restype = ctypes.c_void_p
+    for f in ("cycle_free", "cycle_set_d", "cycle_next", "cycle_commit", "cycle_seen", "cycle_d"):
+        getattr(lib, f).argtypes = [ctypes.c_void_p] + ([ctypes.c_int] if f == "cycle_set_d" else [])
     return lib
 
 
@@ -80,3 +83,32 @@ def test_protocol_follows_the_schedule_bookkeeping(shim, name):
                 assert (acc, freezes, worker) == (int(ev["exp_accumulate"]), int(ev["exp_send"]), int(ev["worker"]))
     for p in ps:
         shim.proto_free(p)
+
+
+def test_momentum_cycle_positions(shim):
+    """Delayed momentum (Sec. 5.1, App. D delays): the first update of a cycle restarts the buffer, the d-th refreshes
+    the momentum; d = 1 refreshes every time; the delay changes only between cycles."""
+    FIRST, INNER, REFRESH = 1, 2, 3
+    c = shim.cycle_new()
+    try:
+        assert (shim.cycle_d(c), shim.cycle_seen(c)) == (1, 0)
+        for _ in range(3):                                   # plain rule: every update is a refresh
+            assert shim.cycle_next(c) == REFRESH
+            shim.cycle_commit(c)
+            assert shim.cycle_seen(c) == 0
+        assert shim.cycle_set_d(c, 0) == BAD_ARG and shim.cycle_set_d(c, -2) == BAD_ARG
+        assert shim.cycle_set_d(c, 4) == OK
+        seq = []
+        for _ in range(9):
+            seq.append((shim.cycle_next(c), shim.cycle_seen(c)))
+            shim.cycle_commit(c)
+        assert seq == [(FIRST, 0), (INNER, 1), (INNER, 2), (REFRESH, 3), (FIRST, 0), (INNER, 1), (INNER, 2), (REFRESH, 3),
+                       (FIRST, 0)]
+        assert shim.cycle_seen(c) == 1
+        assert shim.cycle_set_d(c, 2) == BAD_STATE and shim.cycle_d(c) == 4     # in mid-cycle
+        for _ in range(3):
+            shim.cycle_commit(c)
+        assert shim.cycle_seen(c) == 0 and shim.cycle_set_d(c, 2) == OK
+        assert [shim.cycle_next(c), shim.cycle_commit(c), shim.cycle_next(c)][::2] == [FIRST, REFRESH]
+    finally:
+        shim.cycle_free(c)
