@@ -284,8 +284,7 @@ halos_status halos_gps_get_counters(const halos_gps *gps, int64_t *updates);
  *
  * The call copies the pointers into a device table and waits for the device to go idle first: set-up, not
  * event loop.  Allowed only between cycles (before the first update, or when the last update was a refresh):
- * ESTATE otherwise.  ESTATE also for an LPS created under HALOS_FLAG_NORMS with d > 1 (the delayed kernels
- * carry no |g|^2 monitor).  EINVAL for d < 1, or a bad `buffer` with d > 1.  The delayed kernels always use
+ * ESTATE otherwise.  EINVAL for d < 1, or a bad `buffer` with d > 1.  The delayed kernels always use
  * non-temporal accesses (halos_set_launch_config's `nontemporal` does not apply to them).
  */
 halos_status halos_lps_set_momentum_delay(halos_lps *lps, int32_t d, void *const *buffer);

@@ -517,7 +517,7 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
                 const float inv_d = 1.0f / (float)l->cycle.d();
                 e = launch_lps_update_delayed((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_buffer, l->d_acc,
                                               pull_tab, args, g_kind, third_mode, (int)l->cycle.next(),
-                                              l->rule.eta, l->rule.beta, l->rule.cg * inv_d, inv_d, shape);
+                                              l->rule.eta, l->rule.beta, l->rule.cg * inv_d, inv_d, partials, shape);
             } else {
                 e = launch_lps_update((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_acc, pull_tab, args,
                                       g_kind, third_mode, l->rule.eta, l->rule.beta, l->rule.cg, partials, shape);
@@ -698,8 +698,6 @@ static halos_status set_momentum_delay(const halos_gps *g, MomentumCycle &cycle,
 
 halos_status halos_lps_set_momentum_delay(halos_lps *l, int32_t d, void *const *buffer) {
     if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
-    if (d > 1 && l->d_norm_partials)
-        return fail(HALOS_ESTATE, "lps %d was created under HALOS_FLAG_NORMS: no delayed momentum", l->id);
     return set_momentum_delay(l->gps, l->cycle, l->d_buffer, d, buffer, "the local server");
 }
 

@@ -335,18 +335,19 @@ __device__ __forceinline__ f32x4 delayed_update4(f32x4 &x, f32x4 &m, f32x4 &b, f
 }
 
 // S1 under the delayed rule.  THIRD and PULL as in lps_update_kernel; accesses are non-temporal.
-template <typename GT, int THIRD, bool PULL, int RULE, bool FROM_END = false>
+template <typename GT, int THIRD, bool PULL, int RULE, bool FROM_END, bool NORM>
 __global__ void __launch_bounds__(BLOCK_THREADS)
 lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, uint32_t tensor_base,
                           float *const *__restrict__ theta_tab, float *const *__restrict__ m_tab,
                           float *const *__restrict__ buf_tab, float *const *__restrict__ acc_tab,
                           float *const *__restrict__ pull_tab, PtrArgs gargs, float eta, float beta, float cgd,
-                          float inv_d) {
+                          float inv_d, double *__restrict__ partials) {
     static_assert(!FROM_END || (PULL && sizeof(GT) == 4), "an end model is fp32 and needs the worker's start model");
     constexpr bool NT = true;
     constexpr bool LOAD_B = RULE != CYCLE_FIRST, STORE_B = RULE != CYCLE_REFRESH, USE_M = RULE == CYCLE_REFRESH;
     const uint32_t tid = threadIdx.x;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    double norm_acc = 0.0;
     for (uint32_t t = tile_lo + blockIdx.x; t < tile_hi; t += gridDim.x) {
         const Tile tl = tiles[t];
         const uint32_t tensor = tl.tensor;
@@ -367,6 +368,12 @@ lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint
                 tv[u] = ld4<NT>(th + off);
                 if constexpr (THIRD != 0) av[u] = ld4<NT>(ac + off);
             }
+            if constexpr (NORM) {
+                float q = 0.f;
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) q = sumsq4(gv[u], q);
+                norm_acc += static_cast<double>(q);
+            }
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
@@ -384,6 +391,7 @@ lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint
                 if (off + VEC <= len) {
                     f32x4 gv = grad4<FROM_END, NT>(g, pd, off), tv = ld4<NT>(th + off);
                     f32x4 bv = LOAD_B ? ld4<NT>(bb + off) : zero, mv = USE_M ? ld4<NT>(mm + off) : zero;
+                    if constexpr (NORM) norm_acc += static_cast<double>(sumsq4(gv, 0.f));
                     const f32x4 s = delayed_update4<RULE>(tv, mv, bv, gv, eta, beta, cgd, inv_d);
                     if constexpr (STORE_B) st4<NT>(bb + off, bv);
                     if constexpr (USE_M) st4<NT>(mm + off, mv);
@@ -394,7 +402,9 @@ lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint
                 } else {
                     for (uint32_t k = off; k < len; ++k) {      // ragged tail: fewer than 4 elements
                         float tv = th[k], bv = LOAD_B ? bb[k] : 0.f, mv = USE_M ? mm[k] : 0.f;
-                        const float s = delayed_update<RULE>(tv, mv, bv, grad1<FROM_END>(g, pd, k), eta, beta, cgd, inv_d);
+                        const float gk = grad1<FROM_END>(g, pd, k);
+                        if constexpr (NORM) norm_acc += static_cast<double>(__fmul_rn(gk, gk));
+                        const float s = delayed_update<RULE>(tv, mv, bv, gk, eta, beta, cgd, inv_d);
                         if constexpr (STORE_B) bb[k] = bv;
                         if constexpr (USE_M) mm[k] = mv;
                         th[k] = tv;
@@ -406,6 +416,7 @@ lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint
             }
         }
     }
+    if constexpr (NORM) block_sum_store(norm_acc, partials + blockIdx.x);
 }
 
 // S3 under the delayed rule.  G and out may alias.
@@ -692,15 +703,21 @@ hipError_t launch_gps_update(hipStream_t stream, const Tile *tiles, TileRange r,
 hipError_t launch_lps_update_delayed(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
                                      float *const *m, float *const *buffer, float *const *acc, float *const *pull,
                                      const PtrArgs &g, int g_kind, int third_mode, int cycle_pos, float eta,
-                                     float beta, float cgd, float inv_d, LaunchShape shape) {
+                                     float beta, float cgd, float inv_d, double *norm_partials, LaunchShape shape) {
     if (r.hi <= r.lo) return hipSuccess;
     if (cycle_pos < CYCLE_FIRST || cycle_pos > CYCLE_REFRESH || third_mode < 0 || third_mode > 2 ||
         g_kind < GRAD_F32 || g_kind > GRAD_END_MODEL || (g_kind == GRAD_END_MODEL && !pull))
         return hipErrorInvalidValue;
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
 #define HALOS_LAUNCH_DN(GT, THIRD, PULL, RULE, END)                                                                     \
-    lps_update_delayed_kernel<GT, THIRD, PULL, RULE, END><<<grid, block, 0, stream>>>(                                  \
-        tiles, r.lo, r.hi, r.tensor_base, theta, m, buffer, acc, pull, g, eta, beta, cgd, inv_d)
+    do {                                                                                                                \
+        if (norm_partials)                                                                                              \
+            lps_update_delayed_kernel<GT, THIRD, PULL, RULE, END, true><<<grid, block, 0, stream>>>(                    \
+                tiles, r.lo, r.hi, r.tensor_base, theta, m, buffer, acc, pull, g, eta, beta, cgd, inv_d, norm_partials); \
+        else                                                                                                            \
+            lps_update_delayed_kernel<GT, THIRD, PULL, RULE, END, false><<<grid, block, 0, stream>>>(                   \
+                tiles, r.lo, r.hi, r.tensor_base, theta, m, buffer, acc, pull, g, eta, beta, cgd, inv_d, nullptr);      \
+    } while (0)
 #define HALOS_LAUNCH_DN_RULE(GT, THIRD, PULL, END)                                       \
     do {                                                                                 \
         if (cycle_pos == CYCLE_FIRST) HALOS_LAUNCH_DN(GT, THIRD, PULL, CYCLE_FIRST, END); \

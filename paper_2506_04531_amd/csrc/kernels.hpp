@@ -69,11 +69,12 @@ hipError_t launch_gps_update(hipStream_t stream, const Tile *tiles, TileRange r,
 // in its cycle of d updates the server is: CYCLE_FIRST (buffer <- g), CYCLE_INNER (buffer <- buffer + g) or
 // CYCLE_REFRESH (m <- beta m + (buffer + g) * inv_d, then applied; the buffer is left as it is).  Every update
 // steps the model by eta * cgd * g (cgd = cg / d); only a refresh reads or writes m.  Always non-temporal.
+// norm_partials as in launch_lps_update.
 constexpr int CYCLE_FIRST = 1, CYCLE_INNER = 2, CYCLE_REFRESH = 3;
 hipError_t launch_lps_update_delayed(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
                                      float *const *m, float *const *buffer, float *const *acc, float *const *pull,
                                      const PtrArgs &g, int g_kind, int third_mode, int cycle_pos, float eta,
-                                     float beta, float cgd, float inv_d, LaunchShape shape);
+                                     float beta, float cgd, float inv_d, double *norm_partials, LaunchShape shape);
 hipError_t launch_gps_update_delayed(hipStream_t stream, const Tile *tiles, TileRange r, float *const *Theta,
                                      float *const *M, float *const *buffer, float *const *G, float *const *out,
                                      int cycle_pos, float eta, float beta, float cgd, float inv_d, LaunchShape shape);

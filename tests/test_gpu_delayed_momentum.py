@@ -175,21 +175,6 @@ def test_delay_one_is_the_plain_rule_and_errors():
         B.halos_lps_destroy(lps)
         B.halos_gps_destroy(gps)
 
-    # an LPS with the norm monitors refuses a delay > 1
-    hp_n = B.paper_hparams(0.2, 0.9, 0.15, 0.5, 0.25, 4, flags=B.FLAG_NORMS)
-    Th, M, th, m, acc, buf = [Theta[0].clone()], mk(), mk(), mk(), mk(), mk()
-    gps = B.halos_gps_create([n], hp_n, Th, M)
-    lps = B.halos_lps_create(gps, 0, 1, th, m, acc)
-    try:
-        with pytest.raises(B.HalosError) as e:
-            B.halos_lps_set_momentum_delay(lps, 2, buf)
-        assert e.value.status == B.ESTATE
-        B.halos_gps_set_momentum_delay(gps, 2, buf)                           # the GPS has no such monitor
-        torch.cuda.synchronize()
-    finally:
-        B.halos_lps_destroy(lps)
-        B.halos_gps_destroy(gps)
-
 
 def test_buffer_needs_no_initialisation():
     """The first update of a cycle overwrites the gradient buffer without reading it: garbage (even NaN) in it

@@ -234,13 +234,14 @@ def test_step_pull_without_registered_buffer_is_rejected():
         c.close()
 
 
-def test_norm_monitors_match_the_oracle():
+@pytest.mark.parametrize("d_l,d_g", [(1, 1), (3, 2)])
+def test_norm_monitors_match_the_oracle(d_l, d_g):
     """HALOS_FLAG_NORMS: |g|^2 per update and |theta - Theta_i|^2 per merge, against fp64 sums of the oracle, and the
-    state itself is bit-identical to a run without the monitors."""
+    state itself is bit-identical to a run without the monitors.  Also under delayed momentum (d_l, d_g > 1)."""
     from dataclasses import replace
     from paper_2506_04531_amd import binding as B
     from paper_2506_04531_amd.harness import Cluster
-    w = replace(synth.get_workload("410m").scaled(RAGGED, n_updates=80, name="norms"), delta_dtype="bf16")
+    w = replace(synth.get_workload("410m").scaled(RAGGED, n_updates=80, name="norms"), delta_dtype="bf16", d_l=d_l, d_g=d_g)
     trace = synth.make_trace(w, seed=21)
     hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0], flags=B.FLAG_NORMS)
     c = Cluster(w, "cuda:0", k_initial=trace.k_initial, hp=hp)
@@ -254,6 +255,11 @@ def test_norm_monitors_match_the_oracle():
         pool = {s: synth.to_bf16_bits(synth.normal_at(w.seed, 1 + s, idx, scale)).numpy() for s in range(w.pool_slots)}
         ref = HalosOracle(theta0, w.n_lps, eta_l=w.eta_l, beta_l=w.beta_l, eta_g=w.eta_g, beta_g=w.beta_g, alpha=w.alpha,
                           K=trace.k_initial)
+        if d_l > 1:
+            for l in range(w.n_lps):
+                ref.set_delay(l, d_l)
+        if d_g > 1:
+            ref.set_delay(-1, d_g)
         checked = 0
         for ev in trace.events:
             kind, l = int(ev["kind"]), int(ev["lps"])
