@@ -16,7 +16,8 @@
  *                n_tensors device pointers, one per tensor of the layout.
  *   Layout       tensor i is a contiguous array of numel[i] elements; every
  *                non-empty tensor's base address must be 16-byte aligned.
- *                Server state is fp32.  Worker deltas are fp32 or bfloat16.
+ *                Server state is fp32.  Worker deltas are fp32 or bfloat16 (or
+ *                arrive as the worker's fp32 end model, halos_lps_push_end_model).
  *   Ownership    all parameter-sized buffers are allocated by the caller and
  *                only BORROWED: state buffers for the life of the handle, a
  *                pushed delta until the step that consumes it has finished on
@@ -70,7 +71,8 @@ typedef struct {
 /* ModelUpdate(x, g, eta, beta) of Algorithm 1, as defined in Appendix E:
  *     m <- beta * m + g
  *     x <- x - eta * (cg * g + beta * m)
- * The paper's rule has cg = 1 - beta; cg = 1 is the textbook Nesterov step. */
+ * The paper's rule has cg = 1 - beta; cg = 1 is the textbook Nesterov step.
+ * halos_*_set_momentum_delay switches a server to the delayed form of the same rule. */
 typedef struct {
     float eta;
     float beta;
