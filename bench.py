@@ -69,6 +69,12 @@ MEASURED_TRAFFIC: dict = {
     "974e59b8169a3c57fe632fb5100ee3232fb27895e6d1319bf205587b3d6a4726": {
         "1b:lps_update_acc_pull": 30.034,
         "1b:lps_update_noacc_pull": 22.033,
+        "1b-dn:lps_update_acc_first_pull": 26.04,
+        "1b-dn:lps_update_acc_pull": 30.035,
+        "1b-dn:lps_update_acc_refresh_pull": 34.031,
+        "1b-dn:lps_update_noacc_first_pull": 18.042,
+        "1b-dn:lps_update_noacc_pull": 22.036,
+        "1b-dn:lps_update_noacc_refresh_pull": 26.03,
     },
 }
 
