@@ -320,6 +320,21 @@ halos_status halos_set_launch_config(int32_t blocks_per_cu, int32_t nontemporal)
  */
 halos_status halos_probe_pair(void *a, void *b, uint64_t bytes, int32_t reps, void *stream, double *gbps);
 
+/*
+ * Measurement helper (not a step of the algorithm): what the memory system delivers to a kernel that streams
+ * n_read buffers in and n_write other buffers out with the access pattern of the update kernels (tiles of 16 KiB,
+ * 128-bit non-temporal accesses, all loads of a tile issued first) and no arithmetic.  It gives the ceiling that an
+ * update pass with the same mix of read and written streams, placed the same way, can reach on this device.
+ *   read_bufs   host array of n_read device buffers, only read
+ *   write_bufs  host array of n_write device buffers, OVERWRITTEN WITH ZEROS; none may overlap any other buffer
+ *   n_read, n_write   0..4 each, not both 0
+ *   bytes, reps, stream   as for halos_probe_pair (every buffer at least `bytes` long, 16-byte aligned)
+ *   gbps        achieved GB/s, counting (n_read + n_write) x bytes per sweep
+ * Errors: EINVAL, EHIP.
+ */
+halos_status halos_probe_streams(const void *const *read_bufs, int32_t n_read, void *const *write_bufs, int32_t n_write,
+                                 uint64_t bytes, int32_t reps, void *stream, double *gbps);
+
 /* Release the handle's tables (this waits for the device: work that still uses them finishes first).
  * Caller buffers are untouched.  NULL is ignored. */
 void halos_lps_destroy(halos_lps *lps);

@@ -94,6 +94,7 @@ def load_library():
         "halos_gps_get_momentum_delay": [vp, P(i32), P(i32)],
         "halos_set_launch_config": [i32, i32],
         "halos_probe_pair": [vp, vp, ctypes.c_uint64, i32, vp, P(ctypes.c_double)],
+        "halos_probe_streams": [P(vp), i32, P(vp), i32, ctypes.c_uint64, i32, vp, P(ctypes.c_double)],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -256,6 +257,20 @@ def halos_probe_pair(a, b, nbytes: int, reps: int = 2, stream=None) -> float:
     pb = b if isinstance(b, int) else b.data_ptr()
     out = ctypes.c_double()
     _check(load_library().halos_probe_pair(pa, pb, int(nbytes), reps, _stream(stream), ctypes.byref(out)))
+    return out.value
+
+
+def halos_probe_streams(read_bufs, write_bufs, nbytes: int, reps: int = 2, stream=None) -> float:
+    """GB/s of a kernel that only reads `read_bufs` and only writes (zeros to) `write_bufs`: lists of torch tensors or
+    raw addresses, up to four each."""
+    def arr(bufs):
+        a = (ctypes.c_void_p * max(1, len(bufs)))()
+        for i, b in enumerate(bufs):
+            a[i] = b if isinstance(b, int) else b.data_ptr()
+        return a
+    out = ctypes.c_double()
+    _check(load_library().halos_probe_streams(arr(read_bufs), len(read_bufs), arr(write_bufs), len(write_bufs),
+                                              int(nbytes), reps, _stream(stream), ctypes.byref(out)))
     return out.value
 
 

@@ -192,6 +192,45 @@ halos_status upload_tables(void **d_out, const std::vector<const void *const *> 
     return HALOS_OK;
 }
 
+// A probe buffer must be 16-byte aligned device memory with room for `used` bytes.
+halos_status check_probe_buffer(const void *p, uint64_t used) {
+    if (!p) return fail(HALOS_EINVAL, "NULL buffer");
+    if ((reinterpret_cast<uintptr_t>(p) & 15u) != 0) return fail(HALOS_EINVAL, "buffers must be 16-byte aligned");
+    hipPointerAttribute_t attr;
+    hipError_t e = hipPointerGetAttributes(&attr, p);
+    if (e != hipSuccess || (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged)) {
+        (void)hipGetLastError();
+        return fail(HALOS_EINVAL, "not a device pointer");
+    }
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    e = hipMemGetAddressRange(&base, &size, const_cast<void *>(p));
+    if (e != hipSuccess) { (void)hipGetLastError(); return fail(HALOS_EINVAL, "cannot query the allocation"); }
+    if (reinterpret_cast<uintptr_t>(p) + used > reinterpret_cast<uintptr_t>(base) + size)
+        return fail(HALOS_EINVAL, "buffer is smaller than `bytes`");
+    return HALOS_OK;
+}
+
+// Run `launch` once untimed and `reps` times between two events on stream s; *ms = elapsed time of the timed part.
+template <class Launch>
+halos_status time_launches(hipStream_t s, int reps, Launch launch, float *ms) {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    if (e != hipSuccess) { if (e0) (void)hipEventDestroy(e0); return fail_hip(e, "hipEventCreate"); }
+    e = launch();
+    if (e == hipSuccess) e = hipEventRecord(e0, s);
+    for (int r = 0; r < reps && e == hipSuccess; ++r) e = launch();
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    *ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return fail_hip(e, "timing the probe");
+    return HALOS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -220,18 +259,8 @@ halos_status halos_probe_pair(void *a, void *b, uint64_t bytes, int32_t reps, vo
     const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
     if ((pa <= pb && pa + used > pb) || (pb <= pa && pb + used > pa)) return fail(HALOS_EINVAL, "buffers overlap");
     for (void *p : {a, b}) {       // both buffers must be device memory with room for `used` bytes
-        hipPointerAttribute_t attr;
-        hipError_t e = hipPointerGetAttributes(&attr, p);
-        if (e != hipSuccess || (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged)) {
-            (void)hipGetLastError();
-            return fail(HALOS_EINVAL, "not a device pointer");
-        }
-        hipDeviceptr_t base = nullptr;
-        size_t size = 0;
-        e = hipMemGetAddressRange(&base, &size, p);
-        if (e != hipSuccess) { (void)hipGetLastError(); return fail(HALOS_EINVAL, "cannot query the allocation"); }
-        if (reinterpret_cast<uintptr_t>(p) + used > reinterpret_cast<uintptr_t>(base) + size)
-            return fail(HALOS_EINVAL, "buffer is smaller than `bytes`");
+        halos_status st = check_probe_buffer(p, used);
+        if (st != HALOS_OK) return st;
     }
     int dev = 0, n_cu = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -240,22 +269,59 @@ halos_status halos_probe_pair(void *a, void *b, uint64_t bytes, int32_t reps, vo
     LaunchShape shape;
     shape.grid_cap = g_blocks_per_cu.load() * (n_cu > 0 ? n_cu : 1);
     shape.nontemporal = true;
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    e = hipEventCreate(&e0);
-    if (e == hipSuccess) e = hipEventCreate(&e1);
-    if (e != hipSuccess) { if (e0) (void)hipEventDestroy(e0); return fail_hip(e, "hipEventCreate"); }
     hipStream_t s = (hipStream_t)stream;
-    e = launch_probe_pair(s, (float *)a, (float *)b, (uint32_t)n_tiles64, shape);
-    if (e == hipSuccess) e = hipEventRecord(e0, s);
-    for (int r = 0; r < reps && e == hipSuccess; ++r) e = launch_probe_pair(s, (float *)a, (float *)b, (uint32_t)n_tiles64, shape);
-    if (e == hipSuccess) e = hipEventRecord(e1, s);
-    if (e == hipSuccess) e = hipEventSynchronize(e1);
     float ms = 0.f;
-    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
-    if (e != hipSuccess) return fail_hip(e, "timing the probe");
+    halos_status st = time_launches(s, reps, [&] { return launch_probe_pair(s, (float *)a, (float *)b, (uint32_t)n_tiles64, shape); }, &ms);
+    if (st != HALOS_OK) return st;
     *gbps = ms > 0.f ? (double)used * 4.0 * reps / ((double)ms * 1e-3) / 1e9 : 0.0;
+    return HALOS_OK;
+}
+
+halos_status halos_probe_streams(const void *const *read_bufs, int32_t n_read, void *const *write_bufs, int32_t n_write,
+                                 uint64_t bytes, int32_t reps, void *stream, double *gbps) {
+    if (!gbps) return fail(HALOS_EINVAL, "gbps is NULL");
+    if (n_read < 0 || n_read > MAX_PROBE_STREAMS || n_write < 0 || n_write > MAX_PROBE_STREAMS || n_read + n_write == 0)
+        return fail(HALOS_EINVAL, "n_read = %d, n_write = %d: each 0..%d, not both 0", n_read, n_write, MAX_PROBE_STREAMS);
+    if ((n_read > 0 && !read_bufs) || (n_write > 0 && !write_bufs)) return fail(HALOS_EINVAL, "NULL pointer array");
+    const uint64_t tile_bytes = (uint64_t)TILE_ELEMS * sizeof(float);
+    if (bytes < tile_bytes) return fail(HALOS_EINVAL, "bytes = %llu, must be >= %llu", (unsigned long long)bytes,
+                                        (unsigned long long)tile_bytes);
+    if (reps < 1 || reps > 1000) return fail(HALOS_EINVAL, "reps = %d outside 1..1000", reps);
+    const uint64_t n_tiles64 = bytes / tile_bytes;
+    if (n_tiles64 > 0xFFFFFFFFull) return fail(HALOS_EINVAL, "bytes too large");
+    const uint64_t used = n_tiles64 * tile_bytes;
+    ProbeArgs args{};
+    for (int i = 0; i < n_read; ++i) {
+        halos_status st = check_probe_buffer(read_bufs[i], used);
+        if (st != HALOS_OK) return st;
+        args.rd[i] = (const float *)read_bufs[i];
+    }
+    for (int i = 0; i < n_write; ++i) {
+        halos_status st = check_probe_buffer(write_bufs[i], used);
+        if (st != HALOS_OK) return st;
+        args.wr[i] = (float *)write_bufs[i];
+        const uintptr_t w0 = reinterpret_cast<uintptr_t>(write_bufs[i]);     // a written buffer overlaps nothing else
+        for (int j = 0; j < n_read; ++j) {
+            const uintptr_t r0 = reinterpret_cast<uintptr_t>(read_bufs[j]);
+            if (w0 < r0 + used && r0 < w0 + used) return fail(HALOS_EINVAL, "write buffer %d overlaps read buffer %d", i, j);
+        }
+        for (int j = 0; j < i; ++j) {
+            const uintptr_t o0 = reinterpret_cast<uintptr_t>(write_bufs[j]);
+            if (w0 < o0 + used && o0 < w0 + used) return fail(HALOS_EINVAL, "write buffers %d and %d overlap", i, j);
+        }
+    }
+    int dev = 0, n_cu = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return fail_hip(e, "querying the device");
+    LaunchShape shape;
+    shape.grid_cap = g_blocks_per_cu.load() * (n_cu > 0 ? n_cu : 1);
+    shape.nontemporal = true;
+    hipStream_t s = (hipStream_t)stream;
+    float ms = 0.f;
+    halos_status st = time_launches(s, reps, [&] { return launch_probe_streams(s, args, n_read, n_write, (uint32_t)n_tiles64, shape); }, &ms);
+    if (st != HALOS_OK) return st;
+    *gbps = ms > 0.f ? (double)used * (n_read + n_write) * reps / ((double)ms * 1e-3) / 1e9 : 0.0;
     return HALOS_OK;
 }
 

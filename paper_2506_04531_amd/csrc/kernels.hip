@@ -646,6 +646,34 @@ probe_pair_kernel(float *a, float *b, uint32_t n_tiles) {
     }
 }
 
+// Streaming probe: read NR buffers and write NW others, tile by tile with the access pattern of the update kernels
+// (UNROLL 128-bit non-temporal accesses per thread and stream, all loads of a tile issued before anything else).
+// No arithmetic; loaded values are only "used" by an empty asm statement so the loads stay, stores write `fill`.
+template <int NR, int NW>
+__global__ void __launch_bounds__(BLOCK_THREADS)
+probe_streams_kernel(ProbeArgs a, uint32_t n_tiles, float fill) {
+    const uint32_t tid = threadIdx.x;
+    const f32x4 fv = {fill, fill, fill, fill};
+    for (uint32_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const size_t base = static_cast<size_t>(t) * TILE_ELEMS;
+        f32x4 v[NR > 0 ? NR : 1][UNROLL];
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u)
+                v[r][u] = ld4<true>(to_global(a.rd[r]) + base + (u * BLOCK_THREADS + tid) * VEC);
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) asm volatile("" : : "v"(v[r][u]));
+#pragma unroll
+        for (int w = 0; w < NW; ++w)
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u)
+                st4<true>(to_global(a.wr[w]) + base + (u * BLOCK_THREADS + tid) * VEC, fv);
+    }
+}
+
 inline dim3 grid_for(TileRange r, LaunchShape shape) {
     uint32_t n = r.hi - r.lo;
     uint32_t cap = shape.grid_cap > 0 ? (uint32_t)shape.grid_cap : 1u;
@@ -804,6 +832,34 @@ hipError_t launch_probe_pair(hipStream_t stream, float *a, float *b, uint32_t n_
     if (n_tiles == 0) return hipSuccess;
     const uint32_t cap = shape.grid_cap > 0 ? (uint32_t)shape.grid_cap : 1u;
     probe_pair_kernel<<<dim3(n_tiles < cap ? n_tiles : cap), dim3(BLOCK_THREADS), 0, stream>>>(a, b, n_tiles);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_streams(hipStream_t stream, const ProbeArgs &a, int n_read, int n_write, uint32_t n_tiles,
+                                LaunchShape shape) {
+    if (n_tiles == 0) return hipSuccess;
+    if (n_read < 0 || n_read > MAX_PROBE_STREAMS || n_write < 0 || n_write > MAX_PROBE_STREAMS || n_read + n_write == 0)
+        return hipErrorInvalidValue;
+    const uint32_t cap = shape.grid_cap > 0 ? (uint32_t)shape.grid_cap : 1u;
+    const dim3 grid(n_tiles < cap ? n_tiles : cap), block(BLOCK_THREADS);
+#define HALOS_PROBE(NR, NW) probe_streams_kernel<NR, NW><<<grid, block, 0, stream>>>(a, n_tiles, 0.0f)
+#define HALOS_PROBE_W(NR)                            \
+    switch (n_write) {                               \
+        case 0: HALOS_PROBE(NR, 0); break;           \
+        case 1: HALOS_PROBE(NR, 1); break;           \
+        case 2: HALOS_PROBE(NR, 2); break;           \
+        case 3: HALOS_PROBE(NR, 3); break;           \
+        default: HALOS_PROBE(NR, 4); break;          \
+    }
+    switch (n_read) {
+        case 0: HALOS_PROBE_W(0); break;
+        case 1: HALOS_PROBE_W(1); break;
+        case 2: HALOS_PROBE_W(2); break;
+        case 3: HALOS_PROBE_W(3); break;
+        default: HALOS_PROBE_W(4); break;
+    }
+#undef HALOS_PROBE_W
+#undef HALOS_PROBE
     return hipGetLastError();
 }
 

@@ -98,4 +98,14 @@ hipError_t launch_init(hipStream_t stream, const Tile *tiles, TileRange r, float
 // Sweep the first n_tiles * TILE_ELEMS floats of two buffers (read both, write both back unchanged).
 hipError_t launch_probe_pair(hipStream_t stream, float *a, float *b, uint32_t n_tiles, LaunchShape shape);
 
+// Read n_read buffers and write zeros to n_write others (first n_tiles * TILE_ELEMS floats of each), with the access
+// pattern of the update kernels and no arithmetic: what the memory system delivers for that mix of streams.
+constexpr int MAX_PROBE_STREAMS = 4;
+struct ProbeArgs {
+    const float *rd[MAX_PROBE_STREAMS];
+    float *wr[MAX_PROBE_STREAMS];
+};
+hipError_t launch_probe_streams(hipStream_t stream, const ProbeArgs &a, int n_read, int n_write, uint32_t n_tiles,
+                                LaunchShape shape);
+
 }  // namespace halos

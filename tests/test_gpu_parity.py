@@ -191,6 +191,28 @@ def test_probe_pair_reports_bandwidth_and_preserves_contents():
         B.halos_probe_pair(a.data_ptr() + 4, b, n * 2, 2)      # misaligned
 
 
+def test_probe_streams_reads_and_zero_fills():
+    from paper_2506_04531_amd import binding as B
+    n = 1 << 22
+    bufs = [torch.randn(n, device="cuda:0") for _ in range(4)]
+    keep = [b.clone() for b in bufs]
+    for nr, nw in ((1, 0), (2, 0), (0, 1), (2, 2), (1, 3)):
+        for b, k in zip(bufs, keep):
+            b.copy_(k)
+        gbps = B.halos_probe_streams(bufs[:nr], bufs[nr:nr + nw], n * 4, 2)
+        assert 50.0 < gbps < 20000.0, (nr, nw, gbps)
+        for i, (b, k) in enumerate(zip(bufs, keep)):
+            if nr <= i < nr + nw:
+                assert not b.any(), (nr, nw, i)               # written buffers: zeros
+            else:
+                assert torch.equal(b, k), (nr, nw, i)         # everything else untouched
+    for args in (([], [], n * 4), (bufs[:1], bufs[:1], n * 4), ([], [bufs[0], bufs[0]], n * 4), (bufs[:1], [], n * 8),
+                 ([bufs[0].data_ptr() + 4], [], n * 2), (bufs + bufs[:1], [], n * 4)):
+        with pytest.raises(B.HalosError) as e:
+            B.halos_probe_streams(args[0], args[1], args[2], 2)
+        assert e.value.status == B.EINVAL
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_fused_step_pull_equals_step_then_pull(dtype):
     """halos_lps_step_pull = halos_lps_step + halos_pull_model, bit for bit, including the pulled copies."""
