@@ -66,14 +66,14 @@ def bytes_per_param(label: str, delta_dtype: str, delayed: bool) -> int:
 # only for the kernel source it was measured on: {sha256 of kernels.hip: {kernel label: bytes/param}}.
 MEASURED_TRAFFIC: dict = {
     # profiles/lps_update_1b_hbm_traffic.md, profiles/lps_update_delayed_1b_dn.md
-    "974e59b8169a3c57fe632fb5100ee3232fb27895e6d1319bf205587b3d6a4726": {
-        "1b:lps_update_acc_pull": 30.034,
+    "a88c0a6aa60fccf3deb8590183df648b982b595eed0a0592632d53deaaeeeec9": {
+        "1b:lps_update_acc_pull": 30.033,
         "1b:lps_update_noacc_pull": 22.033,
-        "1b-dn:lps_update_acc_first_pull": 26.04,
+        "1b-dn:lps_update_acc_first_pull": 26.039,
         "1b-dn:lps_update_acc_pull": 30.035,
         "1b-dn:lps_update_acc_refresh_pull": 34.031,
-        "1b-dn:lps_update_noacc_first_pull": 18.042,
-        "1b-dn:lps_update_noacc_pull": 22.036,
+        "1b-dn:lps_update_noacc_first_pull": 18.041,
+        "1b-dn:lps_update_noacc_pull": 22.035,
         "1b-dn:lps_update_noacc_refresh_pull": 26.03,
     },
 }
