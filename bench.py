@@ -248,6 +248,69 @@ def end_model_ab(name: str, reps: int = 20, verbose: bool = True):
     return out
 
 
+def graph_ab(reps: int = 300):
+    """Launch-bound case: one accumulation cycle of the Tiny workload's shape (one LPS, two workers, K = 4: four
+    updates with the model handed back, the GPS update, the merge -- six kernels of 7-10 us) issued call by call
+    against the same cycle captured once into a HIP graph and replayed.  Same results (tests/test_gpu_graph.py);
+    the difference is launch overhead."""
+    import torch
+    import synth
+    from paper_2506_04531_amd import binding as B
+    from paper_2506_04531_amd.harness import alloc_tensor_list, fill_delta_slot, fill_initial_model
+
+    w = synth.get_workload("tiny")
+    numel = [int(x) for x in w.layout.numel]
+    N, K, n_workers = w.layout.total, 4, 2
+    dev = torch.device("cuda:0")
+    mk = lambda: alloc_tensor_list(numel, torch.float32, dev)
+    Theta, M, th, m, acc, g = mk(), mk(), mk(), mk(), mk(), mk()
+    wm = [mk() for _ in range(n_workers)]
+    fill_initial_model(w, Theta)
+    fill_delta_slot(w, 0, g)
+    hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, K)
+    gps = B.halos_gps_create(numel, hp, Theta, M)
+    lps = B.halos_lps_create(gps, 0, n_workers, th, m, acc)
+    try:
+        for k in range(n_workers):
+            B.halos_lps_set_worker_model(lps, k, wm[k])
+
+        def cycle():
+            for k in range(K):
+                B.halos_lps_push_update(lps, k % n_workers, g, B.F32)
+                B.halos_lps_step_pull(lps)
+            B.halos_gps_merge(gps, lps)
+            B.halos_lps_push_global(lps)
+            B.halos_lps_step(lps)
+
+        for _ in range(3):
+            cycle()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            cycle()
+        torch.cuda.synchronize()
+        eager = (time.perf_counter() - t0) / reps
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
+            cycle()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        replay = (time.perf_counter() - t0) / reps
+    finally:
+        B.halos_lps_destroy(lps)
+        B.halos_gps_destroy(gps)
+    bytes_per_cycle = N * (K * 32 + 24 + 16)
+    return {"cycle": f"{K} updates with fused pull + GPS update + merge on the tiny layout ({N} parameters, fp32 deltas)",
+            "eager_us_per_cycle": eager * 1e6, "graph_us_per_cycle": replay * 1e6,
+            "eager_GBps": bytes_per_cycle / eager / 1e9, "graph_GBps": bytes_per_cycle / replay / 1e9,
+            "eager_params_per_s": N * (K + 2) / eager, "graph_params_per_s": N * (K + 2) / replay}
+
+
 def cpu_baseline(name: str, budget_elements: int = 1 << 22):
     """Time the CPU oracle (fp64, literal form, single thread) on a bounded sample: every event of one
     workload-sized trace, on `budget_elements` evenly spaced parameters of the workload."""
@@ -311,6 +374,8 @@ def main():
                          "written) instead of keeping a running sum: fewer bytes per update, larger rounding error")
     ap.add_argument("--no-end-model-ab", action="store_true",
                     help="skip the A/B of the update pass fed a delta vs fed the worker's end model")
+    ap.add_argument("--no-graph-ab", action="store_true",
+                    help="skip the call-by-call vs HIP-graph comparison on the launch-bound tiny shape")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
 
@@ -333,6 +398,7 @@ def main():
     for name in [x for x in args.also.split(",") if x and x != args.workload]:
         others.append(run_workload(name, args.steps, args.warmup, not args.quiet, args.placement, not args.no_fuse_pull, args.snapshot))
     ab = None if args.no_end_model_ab else end_model_ab(args.workload, verbose=not args.quiet)
+    gab = None if args.no_graph_ab else graph_ab()
     cpu = None if args.no_cpu_baseline else cpu_baseline(args.workload)
 
     def brief(r):
@@ -355,6 +421,7 @@ def main():
         "kernels": head["kernels"],
         "workloads": [brief(r) for r in others],
         "end_model_ab": ab,
+        "tiny_graph_ab": gab,
     }
     print(json.dumps(line))
 

@@ -28,6 +28,14 @@
  *                work is enqueued there and the call returns; the caller
  *                synchronises.  All calls that touch the same server's state
  *                must be issued on streams that are ordered with each other.
+ *   Graphs       the event-loop calls (push_update / push_end_model with a pointer
+ *                set the worker has used before, push_global, step, step_pull,
+ *                gps_merge, pull_model with a destination used before) only launch
+ *                kernels on `stream`: no allocation, no synchronisation, no memset.
+ *                They may therefore be issued on a capturing stream.  Host-side
+ *                protocol state advances when a call is made, not when a graph is
+ *                replayed, so only a sequence that brings the protocol back to its
+ *                starting state (a whole accumulation cycle) can be replayed as is.
  *   Threads      a handle may be used by one host thread at a time.
  *   Errors       every call returns a halos_status; on anything but HALOS_OK no
  *                host or device state has been modified and halos_last_error()
