@@ -344,7 +344,9 @@ halos_status halos_probe_streams(const void *const *read_bufs, int32_t n_read, v
                                  uint64_t bytes, int32_t reps, void *stream, double *gbps);
 
 /* Release the handle's tables (this waits for the device: work that still uses them finishes first).
- * Caller buffers are untouched.  NULL is ignored. */
+ * Caller buffers are untouched.  NULL is ignored.  A GPS destroyed while local servers are still attached to it
+ * must not be used again, but its layout tables, which those servers launch with, stay alive until the last of
+ * them is destroyed: the order of the destroy calls does not matter. */
 void halos_lps_destroy(halos_lps *lps);
 void halos_gps_destroy(halos_gps *gps);
 

@@ -76,6 +76,7 @@ struct halos_gps {
     halos_hparams hp{};
     int64_t updates = 0;
     int n_lps_attached = 0;
+    bool retired = false;              // halos_gps_destroy was called while local servers were still attached
 };
 
 struct PendingDelta {
@@ -396,19 +397,27 @@ halos_status halos_gps_create(const halos_layout *layout, const halos_hparams *h
     return HALOS_OK;
 }
 
-void halos_gps_destroy(halos_gps *g) {
-    if (!g || g->magic != GPS_MAGIC) return;
+static void gps_release(halos_gps *g) {
     (void)hipFree(g->d_tables);
     (void)hipFree(g->d_tiles);
     g->magic = 0;
     delete g;
 }
 
+void halos_gps_destroy(halos_gps *g) {
+    if (!g || g->magic != GPS_MAGIC || g->retired) return;
+    if (g->n_lps_attached > 0) {        // its local servers still launch with the layout tables: keep them until the last one goes
+        g->retired = true;
+        return;
+    }
+    gps_release(g);
+}
+
 halos_status halos_lps_create(halos_gps *g, int32_t lps_id, int32_t n_workers, void *const *theta, void *const *m,
                               void *const *acc, void *stream, halos_lps **out) {
     if (!out) return fail(HALOS_EINVAL, "out is NULL");
     *out = nullptr;
-    if (!g || g->magic != GPS_MAGIC) return fail(HALOS_EINVAL, "gps is not a valid handle");
+    if (!g || g->magic != GPS_MAGIC || g->retired) return fail(HALOS_EINVAL, "gps is not a valid handle");
     if (lps_id < 0) return fail(HALOS_EINVAL, "lps_id = %d, must be >= 0", lps_id);
     if (n_workers < 1) return fail(HALOS_EINVAL, "n_workers = %d, must be >= 1", n_workers);
     halos_status st = check_device(g);
@@ -469,9 +478,13 @@ void halos_lps_destroy(halos_lps *l) {
     if (!l || l->magic != LPS_MAGIC) return;
     (void)hipFree(l->d_tables);
     if (l->d_norm_partials) (void)hipFree(l->d_norm_partials);
-    if (l->gps && l->gps->magic == GPS_MAGIC) l->gps->n_lps_attached -= 1;
+    halos_gps *g = l->gps;
     l->magic = 0;
     delete l;
+    if (g && g->magic == GPS_MAGIC) {
+        g->n_lps_attached -= 1;
+        if (g->retired && g->n_lps_attached == 0) gps_release(g);
+    }
 }
 
 static halos_status push_delta_impl(halos_lps *l, int32_t worker, const void *const *gptrs, halos_dtype dtype,
@@ -633,7 +646,7 @@ halos_status halos_lps_step_pull(halos_lps *l, void *stream, halos_step_info *in
 }
 
 halos_status halos_gps_merge(halos_gps *g, halos_lps *from, void *stream) {
-    if (!g || g->magic != GPS_MAGIC) return fail(HALOS_EINVAL, "gps is not a valid handle");
+    if (!g || g->magic != GPS_MAGIC || g->retired) return fail(HALOS_EINVAL, "gps is not a valid handle");
     if (!from || from->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "from is not a valid handle");
     if (from->gps != g) return fail(HALOS_EINVAL, "lps %d belongs to another global server", from->id);
     if (from->proto.can_consume() != PROTO_OK)
@@ -667,7 +680,7 @@ halos_status halos_pull_model(const void *server, int32_t is_gps, void *const *d
     halos_lps *l = nullptr;
     if (is_gps) {
         g = static_cast<const halos_gps *>(server);
-        if (g->magic != GPS_MAGIC) return fail(HALOS_EINVAL, "server is not a valid gps handle");
+        if (g->magic != GPS_MAGIC || g->retired) return fail(HALOS_EINVAL, "server is not a valid gps handle");
         src = g->d_Theta;
     } else {
         l = const_cast<halos_lps *>(static_cast<const halos_lps *>(server));
@@ -701,7 +714,7 @@ halos_status halos_set_hparams(void *server, int32_t is_gps, const halos_hparams
     if (st != HALOS_OK) return st;
     if (is_gps) {
         halos_gps *g = static_cast<halos_gps *>(server);
-        if (g->magic != GPS_MAGIC) return fail(HALOS_EINVAL, "server is not a valid gps handle");
+        if (g->magic != GPS_MAGIC || g->retired) return fail(HALOS_EINVAL, "server is not a valid gps handle");
         g->rule = hp->global;
         g->hp.global = hp->global;
     } else {
@@ -768,7 +781,7 @@ halos_status halos_lps_set_momentum_delay(halos_lps *l, int32_t d, void *const *
 }
 
 halos_status halos_gps_set_momentum_delay(halos_gps *g, int32_t d, void *const *buffer) {
-    if (!g || g->magic != GPS_MAGIC) return fail(HALOS_EINVAL, "gps is not a valid handle");
+    if (!g || g->magic != GPS_MAGIC || g->retired) return fail(HALOS_EINVAL, "gps is not a valid handle");
     return set_momentum_delay(g, g->cycle, g->d_buffer, d, buffer, "the global server");
 }
 
@@ -780,14 +793,14 @@ halos_status halos_lps_get_momentum_delay(const halos_lps *l, int32_t *d, int32_
 }
 
 halos_status halos_gps_get_momentum_delay(const halos_gps *g, int32_t *d, int32_t *seen) {
-    if (!g || g->magic != GPS_MAGIC) return fail(HALOS_EINVAL, "gps is not a valid handle");
+    if (!g || g->magic != GPS_MAGIC || g->retired) return fail(HALOS_EINVAL, "gps is not a valid handle");
     if (d) *d = g->cycle.d();
     if (seen) *seen = g->cycle.seen();
     return HALOS_OK;
 }
 
 halos_status halos_gps_get_counters(const halos_gps *g, int64_t *updates) {
-    if (!g || g->magic != GPS_MAGIC) return fail(HALOS_EINVAL, "gps is not a valid handle");
+    if (!g || g->magic != GPS_MAGIC || g->retired) return fail(HALOS_EINVAL, "gps is not a valid handle");
     if (updates) *updates = g->updates;
     return HALOS_OK;
 }

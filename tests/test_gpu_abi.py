@@ -234,3 +234,24 @@ def test_plain_c_client_of_the_abi():
     print(res.stdout, res.stderr)
     assert res.returncode == 0, res.stdout + res.stderr
     assert "all values as derived" in res.stdout
+
+
+def test_gps_may_be_destroyed_before_its_local_servers():
+    """The local servers launch with their GPS's layout tables: those must outlive a GPS handle that is destroyed first."""
+    from paper_2506_04531_amd import binding as B
+    n = 2 * 4096 + 3
+    mk = lambda: [torch.zeros(n, device="cuda:0")]
+    Theta, M, th, m, acc, dst = [torch.randn(n, device="cuda:0")], mk(), mk(), mk(), mk(), mk()
+    g = [torch.full((n,), 0.5, device="cuda:0")]
+    hp = B.paper_hparams(1.0, 0.0, 1.0, 0.0, 0.0, 1 << 20)
+    gps = B.halos_gps_create([n], hp, Theta, M)
+    lps = B.halos_lps_create(gps, 0, 1, th, m, acc)
+    B.halos_gps_destroy(gps)
+    assert _status(B.halos_gps_get_counters, gps) == B.EINVAL            # the handle is gone for the caller
+    assert _status(B.halos_lps_create, gps, 1, 1, th, m, acc) == B.EINVAL
+    B.halos_lps_push_update(lps, 0, g, B.F32)                             # ... but the local server still works
+    assert B.halos_lps_step(lps).kind == 1
+    B.halos_pull_model(lps, False, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[0], Theta[0] - 0.5)
+    B.halos_lps_destroy(lps)                                              # releases the GPS's tables too
