@@ -36,7 +36,8 @@
  *                protocol state advances when a call is made, not when a graph is
  *                replayed, so only a sequence that brings the protocol back to its
  *                starting state (a whole accumulation cycle) can be replayed as is.
- *   Threads      a handle may be used by one host thread at a time.
+ *   Threads      a handle may be used by one host thread at a time; creating or
+ *                destroying an LPS, and halos_gps_merge, also count as a use of its GPS.
  *   Errors       every call returns a halos_status; on anything but HALOS_OK no
  *                host or device state has been modified and halos_last_error()
  *                describes the problem (thread-local string).  The one
