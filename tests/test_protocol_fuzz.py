@@ -29,6 +29,9 @@ def shim(tmp_path_factory):
     lib.proto_consume.argtypes = [ctypes.c_void_p]
     lib.proto_phase.argtypes = [ctypes.c_void_p]
     lib.proto_queued.argtypes = [ctypes.c_void_p]
+    lib.cycle_new.restype = ctypes.c_void_p
+    for f in ("cycle_free", "cycle_set_d", "cycle_commit", "cycle_seen"):
+        getattr(lib, f).argtypes = [ctypes.c_void_p] + ([ctypes.c_int] if f == "cycle_set_d" else [])
     return lib
 
 
@@ -38,11 +41,12 @@ def test_random_sequences_agree_with_the_oracle(shim, seed):
     n_workers = rng.randint(1, 4)
     K = rng.randint(1, 5)
     p = shim.proto_new(n_workers, K)
+    cyc = shim.cycle_new()          # the local server's position in its delayed-momentum cycle
     o = HalosOracle(np.zeros(3, dtype=np.float32), 1, eta_l=0.1, beta_l=0.5, eta_g=0.1, beta_g=0.5, alpha=0.5, K=K)
     g = np.ones(3, dtype=np.float32)
     out = (ctypes.c_longlong * 6)()
     for _ in range(400):
-        op = rng.choice(["delta", "delta", "delta", "step", "step", "step", "global", "consume", "setK"])
+        op = rng.choice(["delta", "delta", "delta", "step", "step", "step", "global", "consume", "setK", "setD"])
         if op == "delta":
             w = rng.randint(0, n_workers - 1)
             rc = shim.proto_push_delta(p, w)
@@ -68,6 +72,15 @@ def test_random_sequences_agree_with_the_oracle(shim, seed):
             except O.OracleError:
                 ok = False
             assert (rc == 0) == ok
+        elif op == "setD":             # the momentum delay may change only between cycles
+            d = rng.randint(1, 4)
+            rc = shim.cycle_set_d(cyc, d)
+            try:
+                o.set_delay(0, d)
+                ok = True
+            except O.OracleError:
+                ok = False
+            assert (rc == 0) == ok
         elif op == "setK":
             k = rng.randint(1, 5)
             assert shim.proto_set_K(p, k) == 0
@@ -79,6 +92,9 @@ def test_random_sequences_agree_with_the_oracle(shim, seed):
             assert (kind, t, t_last) == (info.kind, info.t, info.t_last)
             if kind == 1:
                 assert (worker, acc, freezes) == (info.worker, info.accumulated, info.sent)
+                shim.cycle_commit(cyc)
+            assert shim.cycle_seen(cyc) == o.delay_seen(0)
         c = o.counters(0)
         assert (shim.proto_phase(p), shim.proto_queued(p)) == (c["phase"], c["queued"])
     shim.proto_free(p)
+    shim.cycle_free(cyc)
