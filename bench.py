@@ -68,12 +68,12 @@ MEASURED_TRAFFIC: dict = {
     # profiles/lps_update_1b_hbm_traffic.md, profiles/lps_update_delayed_1b_dn.md
     "a88c0a6aa60fccf3deb8590183df648b982b595eed0a0592632d53deaaeeeec9": {
         "1b:lps_update_acc_pull": 30.033,
-        "1b:lps_update_noacc_pull": 22.033,
+        "1b:lps_update_noacc_pull": 22.034,
         "1b-dn:lps_update_acc_first_pull": 26.039,
         "1b-dn:lps_update_acc_pull": 30.035,
         "1b-dn:lps_update_acc_refresh_pull": 34.031,
         "1b-dn:lps_update_noacc_first_pull": 18.041,
-        "1b-dn:lps_update_noacc_pull": 22.035,
+        "1b-dn:lps_update_noacc_pull": 22.037,
         "1b-dn:lps_update_noacc_refresh_pull": 26.03,
     },
 }
@@ -206,10 +206,11 @@ def end_model_ab(name: str, reps: int = 20, verbose: bool = True):
     N = w.layout.total
     S = sum((n * 4 + 255) // 256 * 256 for n in numel)
     dev = torch.device("cuda:0")
-    ra = RegionArena(dev, [5 * S, S, S], verbose=verbose)
+    ra = RegionArena(dev, [2 * S, 3 * S, 2 * S], verbose=verbose)      # the placement classes of harness.Cluster
     f32 = torch.float32
-    Theta, M, th, m, inp = (ra.alloc_list(0, numel, f32) for _ in range(5))
-    acc, wm = ra.alloc_list(1, numel, f32), ra.alloc_list(2, numel, f32)
+    m, acc = ra.alloc_list(0, numel, f32), ra.alloc_list(0, numel, f32)
+    th, inp, M = (ra.alloc_list(1, numel, f32) for _ in range(3))
+    wm, Theta = ra.alloc_list(2, numel, f32), ra.alloc_list(2, numel, f32)
     fill_initial_model(w, Theta)
     fill_delta_slot(w, 0, inp)
     hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, 1 << 30)
@@ -366,7 +367,7 @@ def main():
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--nontemporal", type=int, default=-1)
     ap.add_argument("--placement", default="regions", choices=["regions", "plain"],
-                    help="regions: models / momenta / third buffers in three different HBM regions; plain: torch allocations")
+                    help="regions: state arrays sorted into three HBM regions (harness.Cluster); plain: torch allocations")
     ap.add_argument("--no-fuse-pull", action="store_true",
                     help="issue every worker pull as its own copy instead of fusing it into the update pass")
     ap.add_argument("--snapshot", action="store_true",

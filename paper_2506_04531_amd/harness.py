@@ -179,8 +179,8 @@ class Cluster:
                  k_initial: Optional[Sequence[int]] = None, pull_buffers: bool = True, placement: str = "plain",
                  verbose: bool = False):
         """placement "plain": every tensor is its own torch allocation (or one arena per list if arena=True).
-        placement "regions": models and momenta / third buffers / worker model buffers are placed in three
-        different HBM regions through a RegionArena (see the comment below for the measured reason)."""
+        placement "regions": momenta and third buffers / local models and deltas / worker model buffers are placed in
+        three different HBM regions through a RegionArena (see the comment below for the measured reason)."""
         self.w = w
         self.device = torch.device(device)
         lay = w.layout
@@ -190,34 +190,33 @@ class Cluster:
         f32 = torch.float32
         self.region_arena = None
         if placement == "regions":
-            # Measured on MI355X (all 243 assignments of g, m, theta, acc, worker model to three regions): the
-            # update pass is fastest when two of its read-modify-write arrays and the delta share one region, the
-            # third read-modify-write array sits in a second region and the worker's model copy in a third
-            # (6.4 TB/s against 6.1 TB/s for an even spread and 5.0 TB/s for everything in one region).
-            #   class 0: models and momenta (Theta, M, theta_l, m_l) and, if it still fits, the delta pool
-            #   class 1: third buffers acc_l (and the delta pool otherwise)
-            #   class 2: worker model buffers (pull destinations)
             ddt_size = 2 if w.delta_dtype == "bf16" else 4
             S = sum((n * 4 + 255) // 256 * 256 for n in self.numel)
             L = w.n_lps
             pool_bytes = w.pool_slots * S * ddt_size // 4
-            cls0 = (2 * L + 2 + (1 if w.d_g > 1 else 0)) * S
-            self._pool_cls = 0 if cls0 + pool_bytes <= (72 << 30) else 1
-            need = [(2 * L + 2) * S, L * S, L * S if pull_buffers else 0]
-            # Delayed momentum: the gradient buffer takes the momentum's place in all but one update of a cycle, so it
-            # goes where the momentum would (class 0) and the momentum, touched once per cycle, moves to class 1.
-            if w.d_l > 1:
-                need[1] += L * S
-            if w.d_g > 1:
-                need[0] += S
-            need[self._pool_cls] += pool_bytes
+            # Measured on MI355X (all 243 assignments of m, theta, third buffer, delta, worker model to three regions,
+            # python -m paper_2506_04531_amd.placement_search): everything in one region 5.0 TB/s, an even spread 6.2,
+            # best (6.35) with the worker's model copy in a region of its own, momentum and third buffer in a second,
+            # model and delta in the third.  That pattern also spreads the three written arrays of an update that leaves
+            # the third buffer alone over three regions (6.3 instead of 6.0 TB/s for those).
+            #   class 0: momenta m_l and third buffers acc_l (delayed momentum: the gradient buffer b_l takes m_l's
+            #            place here, being what all but one update of a cycle read and write, and m_l moves to class 2)
+            #   class 1: local models theta_l, the delta pool, and the GPS's momentum M (and gradient buffer)
+            #   class 2: worker model buffers (pull destinations) and the GPS's model Theta
+            # so that the GPS update (reads G = acc_l, M, Theta; writes M, Theta, acc_l) touches all three as well.
+            cls_of = {"m": 2 if w.d_l > 1 else 0, "b": 0, "acc": 0, "theta": 1, "pool": 1, "M": 1, "B": 1,
+                      "wm": 2, "Theta": 2}
+            size_of = {"Theta": S, "M": S, "B": S if w.d_g > 1 else 0, "theta": L * S, "m": L * S,
+                       "b": L * S if w.d_l > 1 else 0, "acc": L * S, "pool": pool_bytes, "wm": L * S if pull_buffers else 0}
+            need = [0, 0, 0]
+            for role, c in cls_of.items():
+                need[c] += size_of[role]
             self.region_arena = RegionArena(self.device, need, verbose=verbose)
             ra = self.region_arena
-            mk = lambda dt=f32, cls=0: ra.alloc_list(cls, self.numel, dt)
+            mk = lambda dt=f32, role="theta": ra.alloc_list(cls_of[role], self.numel, dt)
         else:
-            self._pool_cls = 0
-            mk = lambda dt=f32, cls=0: alloc_tensor_list(self.numel, dt, self.device, arena)
-        self.Theta, self.M = mk(cls=0), mk(cls=0)
+            mk = lambda dt=f32, role="theta": alloc_tensor_list(self.numel, dt, self.device, arena)
+        self.Theta, self.M = mk(role="Theta"), mk(role="M")
         fill_initial_model(w, self.Theta)
         self.hp = hp if hp is not None else B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0],
                                                                  cg_l=w.cg_l, cg_g=w.cg_g)
@@ -225,15 +224,15 @@ class Cluster:
         self.gps = B.halos_gps_create(self.numel, self.hp, self.Theta, self.M)
         self.gps_buffer = None
         if w.d_g > 1:
-            self.gps_buffer = mk(cls=0)
+            self.gps_buffer = mk(role="B")
             B.halos_gps_set_momentum_delay(self.gps, w.d_g, self.gps_buffer)
         self.theta, self.m, self.acc, self.buffer, self.lps = [], [], [], [], []
         for l in range(w.n_lps):
-            th, m, acc = mk(cls=0), mk(cls=1 if w.d_l > 1 else 0), mk(cls=1)
+            th, m, acc = mk(role="theta"), mk(role="m"), mk(role="acc")
             self.theta.append(th); self.m.append(m); self.acc.append(acc)
             h = B.halos_lps_create(self.gps, l, w.workers_per_lps, th, m, acc)
             if w.d_l > 1:
-                self.buffer.append(mk(cls=0))
+                self.buffer.append(mk(role="b"))
                 B.halos_lps_set_momentum_delay(h, w.d_l, self.buffer[l])
             if k_initial is not None:
                 B.halos_lps_set_threshold(h, int(k_initial[l]))
@@ -242,10 +241,10 @@ class Cluster:
         ddt = torch.bfloat16 if w.delta_dtype == "bf16" else f32
         self.pool = []
         for s in range(w.pool_slots):
-            ts = mk(ddt, cls=self._pool_cls)
+            ts = mk(ddt, role="pool")
             fill_delta_slot(w, s, ts)
             self.pool.append(ts)
-        self.pull_dst = [mk(cls=2) for _ in range(w.n_lps)] if pull_buffers else None
+        self.pull_dst = [mk(role="wm") for _ in range(w.n_lps)] if pull_buffers else None
         # pointer arrays marshalled once: the replay loop then costs a few ctypes calls per event
         self._pool_ptrs = [B._ptrs(ts) for ts in self.pool]
         self._pull_ptrs = [B._ptrs(ts) for ts in self.pull_dst] if pull_buffers else None
