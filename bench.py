@@ -193,7 +193,7 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
 
 def end_model_ab(name: str, reps: int = 20, verbose: bool = True):
     """The update pass fed an fp32 delta against the same pass fed the worker's end model (halos_lps_push_end_model:
-    the subtraction of Alg. 1 line 26 done by the server), on the workload's tensor list with the same placement:
+    the subtraction of Alg. 1's worker block done by the server), on the workload's tensor list with the same placement:
     one LPS, one worker, always accumulating, pull fused.  HIP events around every launch on the launch stream."""
     import numpy as np
     import torch
@@ -371,7 +371,7 @@ def main():
     ap.add_argument("--no-fuse-pull", action="store_true",
                     help="issue every worker pull as its own copy instead of fusing it into the update pass")
     ap.add_argument("--snapshot", action="store_true",
-                    help="form the accumulated update by subtracting the snapshot theta_{t_last} (Alg. 1 line 14 as "
+                    help="form the accumulated update by subtracting the snapshot theta_{t_last} (the Delta of Alg. 1's LPS block as "
                          "written) instead of keeping a running sum: fewer bytes per update, larger rounding error")
     ap.add_argument("--no-end-model-ab", action="store_true",
                     help="skip the A/B of the update pass fed a delta vs fed the worker's end model")

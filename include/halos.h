@@ -104,7 +104,7 @@ typedef struct {
  * the state.  Honoured at halos_gps_create; every LPS of that GPS then owns a small scratch buffer. */
 #define HALOS_FLAG_NORMS 1u
 
-/* Form the accumulated update the way Algorithm 1 line 14 writes it, Delta = theta_t - theta_{t_last}, instead of
+/* Form the accumulated update the way Algorithm 1's LPS block writes it, Delta = theta_t - theta_{t_last}, instead of
  * keeping a running sum: the third buffer of every LPS then holds the snapshot theta_{t_last} (written by
  * halos_lps_create and by every merge), ordinary updates do not touch it (20 or 18 bytes per parameter instead of
  * 28 or 26), and the update that completes the accumulation overwrites it with theta_{t_last} - theta_t.  Same
@@ -120,8 +120,8 @@ typedef struct {
                              update is now frozen and waits for halos_gps_merge               */
     int32_t accumulated;  /* 1 if this update was added to the accumulated update             */
     int32_t worker;       /* worker whose delta was applied, -1 otherwise                     */
-    int64_t t;            /* number of worker updates applied so far (Alg. 1 line 10)         */
-    int64_t t_last;       /* value of t at the last merge (line 18)                           */
+    int64_t t;            /* number of worker updates applied so far (Alg. 1, LPS counter t)  */
+    int64_t t_last;       /* value of t at the last merge (Alg. 1, LPS merge step)            */
 } halos_step_info;
 
 /* Protocol phase of an LPS with respect to its accumulated update. */
@@ -145,7 +145,7 @@ halos_status halos_gps_create(const halos_layout *layout, const halos_hparams *h
                               void *const *Theta, void *const *M, void *stream, halos_gps **out);
 
 /*
- * Create one LPS attached to `gps` (Algorithm 1 line 6: theta_0 <- Theta_0, t <- 0, t_last <- 0).
+ * Create one LPS attached to `gps` (Algorithm 1, LPS initialisation: theta_0 <- Theta_0, t <- 0, t_last <- 0).
  *   lps_id      caller's label for this server, >= 0 (reported in error strings only)
  *   n_workers   number of workers that may push to it, >= 1
  *   theta,m,acc device tensors of the layout.  On `stream` this call copies the GPS's CURRENT model into
@@ -153,14 +153,14 @@ halos_status halos_gps_create(const halos_layout *layout, const halos_hparams *h
  *               accumulated update G = theta_{t_last} - theta_t while collecting, stays frozen while that
  *               update is in flight, is overwritten with the returned global model by halos_gps_merge,
  *               and is zeroed again by the merge step.
- * The LPS keeps a pointer to the GPS: destroy the LPS first.
+ * The LPS keeps a pointer to the GPS (see the destroy calls for the order in which handles may go).
  */
 halos_status halos_lps_create(halos_gps *gps, int32_t lps_id, int32_t n_workers,
                               void *const *theta, void *const *m, void *const *acc,
                               void *stream, halos_lps **out);
 
 /*
- * A worker's delta arrives (Algorithm 1 line 9).  Appends it to the LPS queue (Sec. 4.1 item 2); no device work.
+ * A worker's delta arrives (Algorithm 1, LPS block: "receive delta").  Appends it to the LPS queue (Sec. 4.1 item 2); no device work.
  *   worker     0 <= worker < n_workers; a worker may have only one delta queued at a time (else ESTATE)
  *   g          device tensors of the layout holding the pseudo-gradient, dtype fp32 or bf16; borrowed
  *              until the halos_lps_step that applies it has finished on its stream
@@ -171,8 +171,8 @@ halos_status halos_lps_push_update(halos_lps *lps, int32_t worker, const void *c
                                    halos_dtype dtype, uint32_t staleness);
 
 /*
- * The same arrival with the worker's END model theta_{t,H} in place of its delta: the subtraction of Algorithm 1
- * line 26 (delta = theta_{t,H} - theta_{t,0}) moves from the worker into the server's update pass, which forms the
+ * The same arrival with the worker's END model theta_{t,H} in place of its delta: the subtraction of Algorithm 1's
+ * worker block (delta = theta_{t,H} - theta_{t,0}) moves from the worker into the server's update pass, which forms the
  * pseudo-gradient g = theta_{t,0} - theta_{t,H} per element in fp32 -- the value a worker computing it in fp32
  * would have sent -- and then proceeds exactly as for halos_lps_push_update.  theta_{t,0} is read from the buffer
  * registered for the worker with halos_lps_set_worker_model: the model the server wrote there when the worker last
@@ -187,7 +187,7 @@ halos_status halos_lps_push_update(halos_lps *lps, int32_t worker, const void *c
 halos_status halos_lps_push_end_model(halos_lps *lps, int32_t worker, const void *const *end_model, uint32_t staleness);
 
 /*
- * The global model sent back by the GPS arrives (Algorithm 1 line 17).  Appends it to the same queue as
+ * The global model sent back by the GPS arrives (Algorithm 1, LPS block: "receive Theta_i").  Appends it to the same queue as
  * the worker deltas; no device work.  ESTATE unless a halos_gps_merge for this LPS has run and its
  * result has not been delivered yet.
  */
@@ -195,10 +195,10 @@ halos_status halos_lps_push_global(halos_lps *lps);
 
 /*
  * Handle the head of the LPS queue, in arrival order (Sec. 4.1 item 2).
- *   worker delta (lines 10-15): t <- t+1; one fused pass applies ModelUpdate(theta, g, eta_l, beta_l) and,
+ *   worker delta (the update branch of the LPS block): t <- t+1; one fused pass applies ModelUpdate(theta, g, eta_l, beta_l) and,
  *       unless an accumulated update is in flight, adds the applied step to acc.  If t - t_last has reached
  *       K and nothing is in flight, acc is frozen as the outgoing update (delta_ready = 1).
- *   global model (lines 18-19): t_last <- t; theta <- (1-alpha) theta + alpha Theta_i; acc <- 0.
+ *   global model (the merge branch of the LPS block): t_last <- t; theta <- (1-alpha) theta + alpha Theta_i; acc <- 0.
  * An empty queue is not an error (kind = 0).  `info` may be NULL.
  */
 halos_status halos_lps_step(halos_lps *lps, void *stream, halos_step_info *info);
@@ -213,7 +213,7 @@ halos_status halos_lps_step(halos_lps *lps, void *stream, halos_step_info *info)
 halos_status halos_lps_set_worker_model(halos_lps *lps, int32_t worker, void *const *model);
 
 /*
- * halos_lps_step with "Schedule the worker theta_t" (Algorithm 1 line 12) fused in: if the head of the
+ * halos_lps_step with "Schedule the worker theta_t" (Algorithm 1, LPS block) fused in: if the head of the
  * queue is a worker delta, the pass that applies it also writes the updated model theta_t into that
  * worker's registered model buffer -- one read-modify-write pass instead of an update pass plus a copy
  * (halos_pull_model).  Results are identical to halos_lps_step followed by halos_pull_model.  If the head
@@ -223,7 +223,7 @@ halos_status halos_lps_set_worker_model(halos_lps *lps, int32_t worker, void *co
 halos_status halos_lps_step_pull(halos_lps *lps, void *stream, halos_step_info *info);
 
 /*
- * The accumulated update of LPS `from` reaches the GPS (Algorithm 1 lines 2-4): one fused pass applies
+ * The accumulated update of LPS `from` reaches the GPS (Algorithm 1, GPS block): one fused pass applies
  * ModelUpdate(Theta, G, eta_g, beta_g) and writes the new global model Theta_i over `from`'s third buffer,
  * where it stays frozen until `from` merges it -- later GPS updates do not change it.
  * ESTATE unless `from` has a frozen update waiting (delta_ready was reported and not yet consumed).
@@ -231,7 +231,7 @@ halos_status halos_lps_step_pull(halos_lps *lps, void *stream, halos_step_info *
 halos_status halos_gps_merge(halos_gps *gps, halos_lps *from, void *stream);
 
 /*
- * Copy a server's current model into caller tensors ("Schedule the worker theta_t", lines 7 and 12; also
+ * Copy a server's current model into caller tensors ("Schedule the worker theta_t" in Algorithm 1's LPS block; also
  * usable to read the global model).  server is a halos_lps* (is_gps = 0) or a halos_gps* (is_gps = 1).
  * dst: device tensors of the layout, fp32.
  */
@@ -270,8 +270,8 @@ halos_status halos_gps_get_counters(const halos_gps *gps, int64_t *updates);
 
 /*
  * Delayed Nesterov momentum at a server (the optimizer of the paper's runs at both tiers: Sec. 5.1; the
- * hyper-parameter table of App. D lists the delays d_l, d_g and notes that the rule effectively divides
- * the learning rate by the delay).  The paper takes the rule from the Async-Local-SGD work it cites; with
+ * hyper-parameter table of App. D lists the delays d_l, d_g and gives the rates it prints as
+ * eta / d).  The paper takes the rule from the Async-Local-SGD work it cites; with
  * that work's default of no momentum between refreshes, and this paper's coefficient cg on the gradient
  * term, a server with rule (eta, beta, cg) and delay d handles its updates in cycles of d:
  *     every update:            buffer <- buffer + g;   x <- x - eta * (cg / d) * g

@@ -16,11 +16,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "halos_oracle.cpp")
 _LIB = os.path.join(_HERE, "libhalos_oracle.so")
 
-THETA, MOM, AUX, GPS_THETA, GPS_MOM, AUX_SNAPSHOT = 0, 1, 2, 3, 4, 5
+THETA, MOM, AUX, GPS_THETA, GPS_MOM = 0, 1, 2, 3, 4
+SNAP, FROZEN, INBOX = 20, 21, 22   # raw state of an LPS: theta_{t_last}, the G it last froze, the model last returned
 BUFFER, GPS_BUFFER = 6, 7   # gradient buffers of the delayed momentum (an LPS's, the GPS's)
 SCALE = 10   # add to the ids above for the running max-magnitude of the same array
 
-FORM_LITERAL = 0       # Delta by snapshot subtraction (Algorithm 1 line 14 as written)
+FORM_LITERAL = 0       # Delta by snapshot subtraction (the Delta of Algorithm 1's LPS block as written)
 FORM_ACCUMULATOR = 1   # running sum of applied steps
 
 

@@ -25,8 +25,8 @@
 // document of this repository):
 //   * The coefficient on grad is kept as a parameter cg; the paper's value is
 //     cg = 1 - beta.  cg = 1 gives the textbook Nesterov step.
-//   * theta_{t_last} is the model right AFTER the merge (line 18 sets t_last,
-//     line 19 overwrites theta_t), so updates applied while a Delta is in
+//   * theta_{t_last} is the model right AFTER the merge (the merge branch first sets t_last,
+//     then overwrites theta_t), so updates applied while a Delta is in
 //     flight are never part of any later Delta.
 //   * At most one Delta per LPS is in flight: the send test is
 //     "t - t_last >= K and nothing in flight", which equals the paper's
@@ -37,8 +37,7 @@
 //
 // Delayed Nesterov momentum (optional, per tier).  The paper's runs use, at both tiers, the delayed
 // Nesterov optimizer of the Async-Local-SGD work it cites (Sec. 5.1; App. D lists the delays d_l, d_g and
-// says the method "effectively divides the learning rate by the delay interval"), but does not restate
-// it.  The rule implemented here is that published algorithm with its default momentum activation of
+// gives the listed rates as eta / d), but does not restate it.  The rule implemented here is that published algorithm with its default momentum activation of
 // zero, carried over to this paper's ModelUpdate by keeping the coefficient cg on the gradient term:
 //     every update:        buffer <- buffer + grad;  x <- x - eta * (cg / d) * grad
 //     every d-th update:   m <- beta * m + buffer / d;  x <- x - eta * [ (cg / d) * grad + beta * m ];
@@ -48,7 +47,7 @@
 //
 // Two numerical forms are provided and selected at creation:
 //   form 0 (literal)      keeps the snapshot theta_{t_last} and forms Delta by
-//                         subtraction exactly as Algorithm 1 line 14 writes it;
+//                         subtraction exactly as Algorithm 1's LPS block writes it;
 //   form 1 (accumulator)  keeps a running sum of the applied steps instead.
 // In exact arithmetic they are the same; in fp64 they agree to ~1e-13.
 // Precision is fp64 (the reference) or fp32 (same operation order as a
@@ -224,7 +223,7 @@ struct Oracle {
         lps.resize(n_lps);
         for (int l = 0; l < n_lps; ++l) {
             Lps<R> &s = lps[l];
-            s.theta = Theta;                 // Alg. 1 line 6: theta_0 <- Theta_0
+            s.theta = Theta;                 // LPS initialisation: theta_0 <- Theta_0
             s.m.assign(n, R(0));
             s.snap = Theta;
             s.acc.assign(n, R(0));
@@ -237,7 +236,7 @@ struct Oracle {
         }
     }
 
-    // Alg. 1 line 9: a worker's delta arrives and joins the queue.
+    // LPS block, "receive delta": a worker's delta arrives and joins the queue.
     int arrive_delta(int l, int worker, const float *g) {
         Lps<R> &s = lps[l];
         if (worker < 0) return -1;
@@ -250,7 +249,7 @@ struct Oracle {
         return 0;
     }
 
-    // Alg. 1 line 17: the global model sent back by the GPS arrives and joins the same queue.
+    // LPS block, "receive Theta_i": the global model sent back by the GPS arrives and joins the same queue.
     int arrive_global(int l) {
         Lps<R> &s = lps[l];
         if (s.phase != RETURNING) return -2;
@@ -260,7 +259,7 @@ struct Oracle {
         return 0;
     }
 
-    // Handle the head of the queue: lines 10-15 for a delta, lines 18-19 for a global model.
+    // Handle the head of the queue: the update branch for a delta, the merge branch for a global model.
     int lps_step(int l, StepInfo *info) {
         Lps<R> &s = lps[l];
         StepInfo out{}; out.worker = -1;
@@ -268,12 +267,12 @@ struct Oracle {
         QueueItem<R> it = std::move(s.queue.front());
         s.queue.pop_front();
         if (it.kind == ITEM_DELTA) {
-            s.t += 1;                                                   // line 10
+            s.t += 1;                                                   // t <- t + 1
             const bool accumulate = (s.phase == ACCUMULATING);
             s.last_delta_sq = 0.0;
             for (int64_t j = 0; j < n; ++j) s.last_delta_sq += (double)it.grad[j] * (double)it.grad[j];
             const bool first = s.delay.seen == 0, refresh = s.delay.seen + 1 == s.delay.d;
-            for (int64_t j = 0; j < n; ++j) {                           // line 11
+            for (int64_t j = 0; j < n; ++j) {                           // ModelUpdate
                 const R grad = R(it.grad[j]);
                 R step, terms;
                 if (s.delay.enabled) {
@@ -296,22 +295,22 @@ struct Oracle {
             if (s.delay.enabled) s.delay.seen = refresh ? 0 : s.delay.seen + 1;
             s.worker_queued[it.worker] = 0;
             out.kind = 1; out.worker = it.worker; out.accumulated = accumulate ? 1 : 0;
-            if (accumulate && s.t - s.t_last >= s.K) {                  // line 13
-                for (int64_t j = 0; j < n; ++j)                         // line 14, sign flipped: G = -Delta
+            if (accumulate && s.t - s.t_last >= s.K) {                  // send test
+                for (int64_t j = 0; j < n; ++j)                         // Delta, sign flipped: G = -Delta
                     s.frozen[j] = (form == 1) ? s.acc[j] : (s.snap[j] - s.theta[j]);
                 s.phase = SENT;
                 out.sent = 1;
             }
         } else {
             if (s.phase != QUEUED) return -3;
-            s.t_last = s.t;                                             // line 18
+            s.t_last = s.t;                                             // t_last <- t
             const R keep = R(1) - alpha;
             s.last_merge_dist_sq = 0.0;
             for (int64_t j = 0; j < n; ++j) {
                 const double d = (double)s.theta[j] - (double)s.inbox[j];
                 s.last_merge_dist_sq += d * d;
             }
-            for (int64_t j = 0; j < n; ++j) {                           // line 19
+            for (int64_t j = 0; j < n; ++j) {                           // merge
                 raise_to(s.sc_theta[j], s.sc_aux[j]);                   // scale of the merged global model
                 s.theta[j] = std::fma(alpha, s.inbox[j], keep * s.theta[j]);
             }
@@ -327,7 +326,7 @@ struct Oracle {
         return 0;
     }
 
-    // GPS lines 2-4 for the Delta that LPS l has in flight.
+    // GPS block (receive, update, send back) for the Delta that LPS l has in flight.
     int gps_receive(int l) {
         Lps<R> &s = lps[l];
         if (s.phase != SENT) return -2;
@@ -341,21 +340,22 @@ struct Oracle {
                 raise_to(sc_Theta[j], std::fabs(Theta[j]));
                 continue;
             }
-            model_update<R>(Theta[j], M[j], s.frozen[j], global);       // line 3
+            model_update<R>(Theta[j], M[j], s.frozen[j], global);       // ModelUpdate
             raise_to(sc_M[j], s.sc_aux[j]);                             // the scale of G travels with it
             raise_to(sc_M[j], std::fabs(M[j]));
             raise_to(sc_Theta[j], step_scale<R>(sc_M[j], s.sc_aux[j], global));
             raise_to(sc_Theta[j], std::fabs(Theta[j]));
         }
         if (gps_delay.enabled) gps_delay.seen = refresh ? 0 : gps_delay.seen + 1;
-        s.inbox = Theta;                                                // line 4: this Theta_i, frozen
+        s.inbox = Theta;                                                // send back: this Theta_i, frozen
         s.sc_aux = sc_Theta;
         s.phase = RETURNING;
         return 0;
     }
 
-    // The "third buffer" of an LPS as a single-buffer implementation would hold it:
-    // the running accumulation, then the frozen G, then the returned global model.
+    // The message buffer of an LPS as the protocol sees it, by phase: the update accumulated so far
+    // (G = theta_{t_last} - theta_t, as a running sum or by subtraction, depending on the form), the frozen G
+    // once it has been sent, and the returned global model once the GPS has answered.
     void aux(int l, std::vector<R> &out) const {
         const Lps<R> &s = lps[l];
         out.resize(n);
@@ -368,20 +368,6 @@ struct Oracle {
         }
     }
 };
-
-// The third buffer as an implementation that keeps the SNAPSHOT theta_{t_last} would hold it (form 0 only):
-// the snapshot while accumulating, then the frozen G, then the returned model.  Its error scale while it is G:
-// G was formed by subtracting two model-sized numbers, so rounding errors of the model's size flowed into it.
-template <class R>
-void aux_snapshot_form(const Oracle<R> &o, int l, std::vector<R> &out, std::vector<R> &scale) {
-    const Lps<R> &s = o.lps[l];
-    if (s.phase == ACCUMULATING) { out = s.snap; scale = s.sc_theta; }
-    else if (s.phase == SENT) {
-        out = s.frozen;
-        scale = s.sc_aux;
-        for (size_t j = 0; j < scale.size(); ++j) if (s.sc_theta[j] > scale[j]) scale[j] = s.sc_theta[j];
-    } else { out = s.inbox; scale = s.sc_aux; }
-}
 
 struct Handle {
     int precision;
@@ -396,13 +382,12 @@ void copy_out(const std::vector<R> &v, double *out) {
 
 template <class R>
 int get_impl(Oracle<R> *o, int what, int l, double *out) {
-    if (((what >= 0 && what <= 2) || what == 5 || what == 6 || what == 15 || what == 16) && (l < 0 || (size_t)l >= o->lps.size())) return -1;
+    const bool per_lps = (what >= 0 && what <= 2) || what == 6 || what == 16 || (what >= 10 && what <= 12) || (what >= 20 && what <= 22);
+    if (per_lps && (l < 0 || (size_t)l >= o->lps.size())) return -1;
     switch (what) {
         case 0: copy_out(o->lps[l].theta, out); return 0;
         case 1: copy_out(o->lps[l].m, out); return 0;
         case 2: { std::vector<R> a; o->aux(l, a); copy_out(a, out); return 0; }
-        case 5: { std::vector<R> a, sc; aux_snapshot_form(*o, l, a, sc); copy_out(a, out); return 0; }
-        case 15: { std::vector<R> a, sc; aux_snapshot_form(*o, l, a, sc); copy_out(sc, out); return 0; }
         case 6: copy_out(o->lps[l].buffer, out); return 0;
         case 7: copy_out(o->gps_buffer, out); return 0;
         case 16: copy_out(o->lps[l].sc_buffer, out); return 0;
@@ -414,6 +399,9 @@ int get_impl(Oracle<R> *o, int what, int l, double *out) {
         case 12: copy_out(o->lps[l].sc_aux, out); return 0;
         case 13: copy_out(o->sc_Theta, out); return 0;
         case 14: copy_out(o->sc_M, out); return 0;
+        case 20: copy_out(o->lps[l].snap, out); return 0;
+        case 21: copy_out(o->lps[l].frozen, out); return 0;
+        case 22: copy_out(o->lps[l].inbox, out); return 0;
     }
     return -1;
 }
@@ -515,9 +503,10 @@ int ho_set_rules(void *p, float eta_l, float beta_l, float cg_l, float eta_g, fl
     return 0;
 }
 
-// what: 0 theta_l, 1 m_l, 2 third buffer of l (accumulation / frozen G / returned model),
-//       3 Theta, 4 M, 5 third buffer of l in snapshot form (theta_{t_last} / frozen G / returned model);
-//       6 gradient buffer of l's delayed momentum, 7 the GPS's; 10..17 the error scales of the same arrays.
+// what: 0 theta_l, 1 m_l, 2 message buffer of l by phase (accumulated so far / frozen G / returned model),
+//       3 Theta, 4 M; 6 gradient buffer of l's delayed momentum, 7 the GPS's; 10..17 the error scales of
+//       the same arrays; 20 the snapshot theta_{t_last} of l, 21 the G it last froze, 22 the global model
+//       last returned to it (raw state, whatever the phase).
 int ho_get(void *p, int32_t what, int32_t l, double *out) {
     Handle *h = (Handle *)p;
     return h->precision == 32 ? get_impl(h->f, what, l, out) : get_impl(h->d, what, l, out);

@@ -74,7 +74,7 @@ __device__ __forceinline__ f32x4 sub4(f32x4 a, f32x4 b);
 
 // The pseudo-gradient of four consecutive elements: read from the worker's delta tensor, or (FROM_END) formed here
 // as start - end from the worker's start model (the buffer the server filled at the worker's last pull) and the end
-// model the worker sent (Alg. 1 line 26 moved to the server, sign flipped).
+// model the worker sent (the delta of Alg. 1's worker block, formed on the server, sign flipped).
 template <bool FROM_END, bool NT, typename GP>
 __device__ __forceinline__ f32x4 grad4(const GP *g, const gf32 *start, uint32_t off) {
     if constexpr (FROM_END) return sub4(ld4<NT>(start + off), ld4<NT>(g + off));
@@ -117,7 +117,7 @@ __device__ __forceinline__ f32x4 add4(f32x4 a, f32x4 b) {
     return r;
 }
 
-// Alg. 1 line 19 in the two-product form: exact for alpha = 0 (keep = 1) and alpha = 1 (keep = 0).
+// The merge of Alg. 1's LPS block in the two-product form: exact for alpha = 0 (keep = 1) and alpha = 1 (keep = 0).
 __device__ __forceinline__ float merge1(float theta, float global, float alpha, float keep) {
     return __fmaf_rn(alpha, global, __fmul_rn(keep, theta));
 }
@@ -163,9 +163,9 @@ __device__ __forceinline__ void block_sum_store(double v, double *dst) {
 // S1: worker-delta step of a local server.
 // THIRD says what happens to the server's third buffer: 0 untouched, 1 running accumulation (acc <- acc + s),
 // 2 it holds the snapshot theta_{t_last} and this update completes the accumulation: it is overwritten with
-// G = theta_{t_last} - theta_t (Alg. 1 line 14, sign flipped).
+// G = theta_{t_last} - theta_t (Alg. 1's Delta, sign flipped).
 // With PULL the updated model is also written to a second tensor list (the buffer the worker starts
-// its next round from: Alg. 1 lines 11-12 in one pass instead of an update pass plus a copy pass).
+// its next round from: ModelUpdate and "schedule the worker" of Alg. 1 in one pass instead of an update pass plus a copy pass).
 // With NORM every workgroup also leaves the sum of g^2 over its tiles in partials[blockIdx.x].
 // With FROM_END (needs PULL) the delta tensors hold the worker's end model and pull_tab its start model.
 template <typename GT, int THIRD, bool NT, bool PULL, bool NORM, bool FROM_END = false>
@@ -584,7 +584,7 @@ pull_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Alg. 1 line 6: theta <- Theta_0, m <- 0, third buffer <- 0 (or <- Theta_0 if it is to hold the snapshot
+// Alg. 1, LPS initialisation: theta <- Theta_0, m <- 0, third buffer <- 0 (or <- Theta_0 if it is to hold the snapshot
 // theta_{t_last}).  With src_tab == nullptr only m is zero-filled.
 __global__ void __launch_bounds__(BLOCK_THREADS)
 init_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, float *const *src_tab,

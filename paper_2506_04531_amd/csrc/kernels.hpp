@@ -39,16 +39,16 @@ struct TileRange {      // tiles [lo, hi) all belong to tensors [tensor_base, te
 };
 
 // Worker-delta step of a local server: m <- beta m + g; s = eta (cg g + beta m); theta <- theta - s;
-// third_mode 1: acc <- acc + s (ModelUpdate of App. E fused with the accumulation of Alg. 1 line 14);
-// third_mode 2: the third buffer holds theta_{t_last} and is overwritten with theta_{t_last} - theta_t (line 14 as
+// third_mode 1: acc <- acc + s (ModelUpdate of App. E fused with the accumulation behind Alg. 1's Delta);
+// third_mode 2: the third buffer holds theta_{t_last} and is overwritten with theta_{t_last} - theta_t (Alg. 1's Delta as
 // written, sign flipped); third_mode 0: the third buffer is not touched.
 // If `pull` is not null it is a device table of destination tensors that also receive the updated theta
-// (Alg. 1 line 12, the model handed back to the worker, written in the same pass).
+// (Alg. 1, "schedule the worker": the model handed back to the worker, written in the same pass).
 // If `norm_partials` is not null the launch also leaves, per workgroup, the sum of g^2 over the workgroup's tiles in
 // norm_partials[0 .. launch_grid_size(r, shape)).
 // g_kind says what the tensors in `g` hold: the pseudo-gradient in fp32 or bf16, or (GRAD_END_MODEL, needs `pull`)
 // the worker's END model in fp32 -- the pseudo-gradient is then formed in the kernel as start - end, the start model
-// being what `pull` points to before this launch overwrites it (Alg. 1 line 26 on the server, sign flipped).
+// being what `pull` points to before this launch overwrites it (the delta of Alg. 1's worker block formed on the server, sign flipped).
 constexpr int GRAD_F32 = 0, GRAD_BF16 = 1, GRAD_END_MODEL = 2;
 hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
                              float *const *acc, float *const *pull, const PtrArgs &g, int g_kind, int third_mode,
@@ -90,7 +90,7 @@ hipError_t launch_lps_merge(hipStream_t stream, const Tile *tiles, TileRange r, 
 hipError_t launch_pull(hipStream_t stream, const Tile *tiles, TileRange r, float *const *src, const PtrArgs &dst,
                        LaunchShape shape);
 
-// theta <- src; m <- 0; acc <- 0   (Alg. 1 line 6).  src == nullptr: only zero-fill `m` (used for the GPS momentum).
+// theta <- src; m <- 0; acc <- 0   (Alg. 1, LPS initialisation).  src == nullptr: only zero-fill `m` (used for the GPS momentum).
 // `snapshot`: acc <- src instead of 0.
 hipError_t launch_init(hipStream_t stream, const Tile *tiles, TileRange r, float *const *src, float *const *theta,
                        float *const *m, float *const *acc, bool snapshot, LaunchShape shape);

@@ -49,7 +49,7 @@ public:
         return PROTO_OK;
     }
 
-    // Line 9: a delta from `worker` arrives.
+    // A delta from `worker` arrives.
     ProtoResult can_push_delta(int32_t worker) const {
         if (worker < 0 || worker >= n_workers()) return PROTO_BAD_ARG;
         if (worker_queued_[worker]) return PROTO_BAD_STATE;
@@ -60,7 +60,7 @@ public:
         queue_.push_back(QueueItem{ITEM_DELTA, worker});
     }
 
-    // Line 17: the global model arrives.
+    // The global model arrives.
     ProtoResult can_push_global() const { return phase_ == PHASE_RETURNING ? PROTO_OK : PROTO_BAD_STATE; }
     void push_global() {
         phase_ = PHASE_QUEUED;
@@ -70,7 +70,7 @@ public:
     // Head of the queue without removing it.
     QueueItem head() const { return queue_.empty() ? QueueItem{ITEM_NONE, -1} : queue_.front(); }
 
-    // What applying the delta at the head will mean for the accumulated update (lines 10, 13).
+    // What applying the delta at the head will mean for the accumulated update (counter and send test of the LPS block).
     // The send test is "t - t_last >= K and nothing in flight": identical to the paper's
     // "t - t_last = K" whenever K changes only at merges, and it cannot be skipped over when a
     // caller lowers K in between.
@@ -89,14 +89,14 @@ public:
         if (o.freezes) phase_ = PHASE_SENT;
     }
 
-    // Lines 18-19.
+    // The merge branch of the LPS block.
     void commit_merge() {
         queue_.pop_front();
         t_last_ = t_;
         phase_ = PHASE_ACCUMULATING;
     }
 
-    // Global server consumed the frozen update (GPS lines 2-4).
+    // Global server consumed the frozen update (Alg. 1, GPS block).
     ProtoResult can_consume() const { return phase_ == PHASE_SENT ? PROTO_OK : PROTO_BAD_STATE; }
     void consume() { phase_ = PHASE_RETURNING; }
 

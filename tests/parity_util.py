@@ -72,6 +72,20 @@ def oracle_run(w: synth.Workload, trace: synth.Trace, idx: Optional[np.ndarray],
     return o, log
 
 
+def snapshot_form_view(o: HalosOracle, l: int, with_scale: bool = True):
+    """What the third buffer of an implementation that keeps the SNAPSHOT theta_{t_last} (instead of a running sum)
+    holds, assembled from the oracle's raw state by protocol phase: the snapshot while accumulating, the frozen G
+    once sent, the returned model afterwards.  Its error scale while it is G: G was formed by subtracting two
+    model-sized numbers, so rounding errors of the model's size flowed into it."""
+    phase = o.counters(l)["phase"]
+    if phase == 0:
+        return o.get(O.SNAP, l), (o.get(O.THETA + O.SCALE, l) if with_scale else None)
+    if phase == 1:
+        sc = np.maximum(o.get(O.AUX + O.SCALE, l), o.get(O.THETA + O.SCALE, l)) if with_scale else None
+        return o.get(O.FROZEN, l), sc
+    return o.get(O.INBOX, l), (o.get(O.AUX + O.SCALE, l) if with_scale else None)
+
+
 def oracle_state(o: HalosOracle, n_lps: int, with_scale: bool = True, snapshot_form: bool = False):
     """Every state array of the oracle (value, error scale).  snapshot_form: the third buffers as an implementation
     that keeps theta_{t_last} holds them (only meaningful for an oracle created with FORM_LITERAL)."""
@@ -79,7 +93,8 @@ def oracle_state(o: HalosOracle, n_lps: int, with_scale: bool = True, snapshot_f
     for l in range(n_lps):
         names[f"theta{l}"] = (O.THETA, l)
         names[f"m{l}"] = (O.MOM, l)
-        names[f"aux{l}"] = (O.AUX_SNAPSHOT if snapshot_form else O.AUX, l)
+        if not snapshot_form:
+            names[f"aux{l}"] = (O.AUX, l)
     # gradient buffers of the delayed momentum: defined only while a cycle is open (after a refresh an
     # implementation may leave anything there until the next update overwrites it)
     for l in range(n_lps):
@@ -90,7 +105,57 @@ def oracle_state(o: HalosOracle, n_lps: int, with_scale: bool = True, snapshot_f
     out = {}
     for k, (what, l) in names.items():
         out[k] = (o.get(what, l), o.get(what + O.SCALE, l) if with_scale else None)
+    if snapshot_form:
+        for l in range(n_lps):
+            out[f"aux{l}"] = snapshot_form_view(o, l, with_scale)
     return out
+
+
+def literal_metrics(values: Dict[str, np.ndarray], ref: Dict[str, tuple], floor_rms: float = 1e-3):
+    """The tolerance read literally, for the record: per array, the largest |x - ref| / max(|ref|, floor_rms * rms(ref))
+    and the largest |x - ref|.  Returns {array: (relative, absolute)} plus the overall worst under "*"."""
+    out = {}
+    worst_rel = worst_abs = 0.0
+    for k, (x_ref, _scale) in ref.items():
+        x = values[k].astype(np.float64)
+        if not x.size:
+            continue
+        rms = float(np.sqrt(np.mean(x_ref * x_ref)))
+        diff = np.abs(x - x_ref)
+        rel = float((diff / np.maximum(np.abs(x_ref), max(floor_rms * rms, 1e-300))).max())
+        out[k] = (rel, float(diff.max()))
+        worst_rel, worst_abs = max(worst_rel, rel), max(worst_abs, float(diff.max()))
+    out["*"] = (worst_rel, worst_abs)
+    return out
+
+
+def literal_where_not_tiny(values: Dict[str, np.ndarray], ref: Dict[str, tuple], floor_rms: float = 0.1) -> float:
+    """Largest |x - ref| / |ref| over the elements whose reference magnitude is at least floor_rms of their array's
+    rms -- the tolerance read literally, on every element that is not close to zero."""
+    worst = 0.0
+    for k, (x_ref, _scale) in ref.items():
+        if not x_ref.size:
+            continue
+        rms = float(np.sqrt(np.mean(x_ref * x_ref)))
+        sel = np.abs(x_ref) >= floor_rms * rms
+        if rms > 0 and sel.any():
+            x = values[k].astype(np.float64)
+            worst = max(worst, float((np.abs(x[sel] - x_ref[sel]) / np.abs(x_ref[sel])).max()))
+    return worst
+
+
+def report_literal(tag: str, gpu_values: Dict[str, np.ndarray], o32: HalosOracle, ref64: Dict[str, tuple], n_lps: int) -> float:
+    """Print, for the record, the tolerance read literally (error relative to the reference VALUE, floored at 1e-3 of
+    the array's rms, and the plain absolute error) for the GPU state and for the fp32 oracle, both against fp64.
+    Returns the GPU's literal relative error over the elements that are not close to zero (>= 10 % of the array's rms),
+    which callers hold to the same 1e-5."""
+    g = literal_metrics(gpu_values, ref64)["*"]
+    o = literal_metrics({k: v[0].astype(np.float32) for k, v in oracle_state(o32, n_lps, with_scale=False).items()
+                         if k in ref64}, ref64)["*"]
+    big = literal_where_not_tiny(gpu_values, ref64)
+    print(f"[parity] {tag}: literal metric |x-ref|/max(|ref|, 1e-3 rms): GPU vs fp64 {g[0]:.3g} (max abs {g[1]:.3g}); "
+          f"fp32 oracle vs fp64 {o[0]:.3g} (max abs {o[1]:.3g}); GPU vs fp64 over elements >= 10% of rms: {big:.3g}", flush=True)
+    return big
 
 
 def compare_state(gpu_values: Dict[str, np.ndarray], ref: Dict[str, tuple], bitwise: bool):

@@ -43,7 +43,7 @@ def _status(fn, *a):
 def test_create_initialises_state(small):
     s = small
     for a, b in zip(s["th"], s["Theta"]):
-        assert torch.equal(a, b)                               # Alg. 1 line 6: theta_0 <- Theta_0
+        assert torch.equal(a, b)                               # Alg. 1, LPS initialisation: theta_0 <- Theta_0
     for t in s["m"] + s["acc"] + s["M"]:
         assert not t.any()
     c = s["B"].halos_lps_get_counters(s["lps"])

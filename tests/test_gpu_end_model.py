@@ -1,5 +1,5 @@
 """halos_lps_push_end_model: the worker sends its end model and the server's update pass forms the pseudo-gradient
-start - end itself (Alg. 1 line 26 moved into the pass that applies it).  Checked against the CPU oracle, which is fed
+start - end itself (the subtraction of Alg. 1's worker block moved into the pass that applies it).  Checked against the CPU oracle, which is fed
 the fp32 difference a worker would have computed from the same two models."""
 import numpy as np
 import pytest

@@ -5,7 +5,8 @@ import torch
 
 import synth
 from oracle import FORM_ACCUMULATOR, FORM_LITERAL
-from parity_util import REL_TOL, check_step_logs, compare_state, oracle_run, oracle_state, sample_indices
+from parity_util import (REL_TOL, check_step_logs, compare_state, literal_metrics, oracle_run, oracle_state,
+                         report_literal, sample_indices)
 
 pytestmark = pytest.mark.gpu
 
@@ -33,8 +34,10 @@ def _full_parity(w, trace, arena=False):
     assert n_diff == 0, f"{n_diff} elements differ from the same-order fp32 oracle (worst {worst:.3g} in {name})"
     o64, log64 = oracle_run(w, trace, None, 64, FORM_LITERAL)
     assert log64 == log32
-    worst, _, name = compare_state(gpu, oracle_state(o64, w.n_lps), bitwise=False)
+    ref64 = oracle_state(o64, w.n_lps)
+    worst, _, name = compare_state(gpu, ref64, bitwise=False)
     print(f"[parity] {w.name}: bit-exact vs fp32 oracle; max rel err vs fp64 reference {worst:.3g} ({name})", flush=True)
+    assert report_literal(w.name, gpu, o32, ref64, w.n_lps) <= REL_TOL
     assert worst <= REL_TOL, (worst, name)
 
 
@@ -98,9 +101,11 @@ def test_full_size_workloads_on_sampled_elements(name):
     worst, n_diff, wname = compare_state(gpu, oracle_state(o32, w.n_lps), bitwise=True)
     assert worst <= REL_TOL and n_diff == 0, (worst, n_diff, wname)
     o64, _ = oracle_run(w, trace, idx, 64, FORM_LITERAL)
-    worst, _, wname = compare_state(gpu, oracle_state(o64, w.n_lps), bitwise=False)
+    ref64 = oracle_state(o64, w.n_lps)
+    worst, _, wname = compare_state(gpu, ref64, bitwise=False)
     print(f"[parity] {name}: bit-exact vs fp32 oracle on {idx.size} samples; max rel err vs fp64 {worst:.3g} ({wname})",
           flush=True)
+    assert report_literal(name, gpu, o32, ref64, w.n_lps) <= REL_TOL
     assert worst <= REL_TOL, (worst, wname)
 
 
@@ -422,7 +427,7 @@ def test_replay_on_a_side_stream():
 
 @pytest.mark.parametrize("recipe", ["70m", "160m", "410m"])
 def test_snapshot_form_every_element(recipe):
-    """HALOS_FLAG_SNAPSHOT: Delta by subtraction of the snapshot theta_{t_last} (Alg. 1 line 14 as written).  Bit-exact
+    """HALOS_FLAG_SNAPSHOT: Delta by subtraction of the snapshot theta_{t_last} (the Delta of Alg. 1's LPS block as written).  Bit-exact
     against the fp32 literal-form oracle, within tolerance of the fp64 reference, third buffers included."""
     from paper_2506_04531_amd import binding as B
     base = synth.get_workload(recipe)

@@ -147,7 +147,7 @@ def test_gps_delayed_rule_is_a_filter_over_cycle_means():
 
 def test_merge_leaves_the_cycle_alone():
     """The gradient buffer and the position in the cycle are optimizer state of the server: a merge in mid-cycle
-    (Alg. 1 lines 18-19 change theta only) must not disturb them."""
+    (the merge of Alg. 1's LPS block changes theta only) must not disturb them."""
     rng = np.random.default_rng(8)
     n, d = 9, 5
     G = rng.normal(0, 1e-3, (7, n)).astype(F32)

@@ -10,6 +10,7 @@ import pytest
 import oracle as O
 import test_oracle_pins as pins
 import test_oracle_delayed_momentum as dpins
+import test_oracle_error_scales as spins
 
 SRC = os.path.join(os.path.dirname(os.path.abspath(O.__file__)), "halos_oracle.cpp")
 
@@ -29,7 +30,7 @@ MUTANTS = [
      "s.theta[j] = s.theta[j] + alpha * (s.inbox[j] - s.theta[j]) * R(1.0000001);"),
     ("snapshot is the pre-merge model", "s.snap = s.theta;                                           // theta_{t_last}: the post-merge model",
      "/* snapshot left at its old value */"),
-    ("t_last not reset at merge", "s.t_last = s.t;                                             // line 18", ""),
+    ("t_last not reset at merge", "s.t_last = s.t;                                             // t_last <- t", ""),
     ("updates in flight keep accumulating", "const bool accumulate = (s.phase == ACCUMULATING);", "const bool accumulate = true;"),
     ("Delta sign flipped", "s.frozen[j] = (form == 1) ? s.acc[j] : (s.snap[j] - s.theta[j]);",
      "s.frozen[j] = (form == 1) ? -s.acc[j] : (s.theta[j] - s.snap[j]);"),
@@ -54,6 +55,23 @@ MUTANTS = [
      "if (gps_delay.enabled) gps_delay.seen = s.delay.seen;"),
     ("delayed: merge clears the gradient buffer", "            s.phase = ACCUMULATING;\n            out.kind = 2;",
      "            s.phase = ACCUMULATING; std::fill(s.buffer.begin(), s.buffer.end(), R(0));\n            out.kind = 2;"),
+    # error-scale bookkeeping (the denominator of the fp64 tolerance)
+    ("scales: step scale inflated tenfold", "    return std::fabs(r.eta) * (std::fabs(r.cg) * grad_scale + std::fabs(r.beta) * m_scale);",
+     "    return R(10) * std::fabs(r.eta) * (std::fabs(r.cg) * grad_scale + std::fabs(r.beta) * m_scale);"),
+    ("scales: merge does not carry the global model's scale",
+     "                raise_to(s.sc_theta[j], s.sc_aux[j]);                   // scale of the merged global model\n", ""),
+    ("scales: GPS ignores the scale that travels with G",
+     "            raise_to(sc_M[j], s.sc_aux[j]);                             // the scale of G travels with it\n", ""),
+    ("scales: momentum scale follows the value down", "                    raise_to(s.sc_m[j], std::fabs(s.m[j]));",
+     "                    s.sc_m[j] = std::fabs(s.m[j]);"),
+    ("scales: returned model keeps G's scale instead of Theta's", "        s.sc_aux = sc_Theta;\n", ""),
+    ("scales: accumulated update's scale survives the merge",
+     "            std::fill(s.sc_aux.begin(), s.sc_aux.end(), R(0));\n", ""),
+    ("scales: delayed buffer scale adds signed values", "    buffer_scale = first ? g_mag : buffer_scale + g_mag;",
+     "    buffer_scale = first ? g_mag : buffer_scale + grad;"),
+    ("scales: delayed momentum scale ignores the buffer", "        raise_to(m_scale, buffer_scale * inv_d);\n", ""),
+    ("scales: everything doubled at the end", "        case 10: copy_out(o->lps[l].sc_theta, out); return 0;",
+     "        case 10: { std::vector<R> v = o->lps[l].sc_theta; for (auto &x : v) x *= R(2); copy_out(v, out); return 0; }"),
 ]
 
 PIN_TESTS = [
@@ -78,6 +96,11 @@ PIN_TESTS = [
     dpins.test_constant_delta_closed_form_is_exact_in_fp32,
     dpins.test_gps_delayed_rule_is_a_filter_over_cycle_means,
     dpins.test_merge_leaves_the_cycle_alone,
+    lambda: [spins.test_worked_example_scales_and_raw_state(64, f) for f in pins.BOTH_FORMS],
+    spins.test_snapshot_form_view_follows_the_phases,
+    lambda: [spins.test_scale_rules_with_momentum_rate_and_coefficient(64, f) for f in pins.BOTH_FORMS],
+    lambda: spins.test_scale_rules_of_the_delayed_rule(64),
+    lambda: spins.test_scales_are_bounded_on_both_sides_on_a_seeded_trace(1, 1),
 ]
 
 

@@ -32,7 +32,7 @@ def apply(o, l, w, g):
 @pytest.mark.parametrize("precision", [32, 64])
 def test_zero_momentum_unit_rate_adopts_worker_end_model(precision):
     """One LPS, one worker, beta_l = 0, eta_l = 1: after the update the server model is the
-    worker's end model (Alg. 1 lines 11, 25 with ModelUpdate of App. E) -- plain local SGD."""
+    worker's end model (Alg. 1: the worker's delta and the LPS's ModelUpdate, App. E) -- plain local SGD."""
     rng = np.random.default_rng(0)
     start = (rng.integers(-2000, 2000, 257) / 64.0).astype(F32)        # dyadic: every op exact
     end = (rng.integers(-2000, 2000, 257) / 64.0).astype(F32)
@@ -187,7 +187,7 @@ def test_merge_weight_one_and_zero_return_an_operand_exactly(precision, form):
 
 
 def test_repeated_merges_contract_geometrically():
-    """theta - Theta shrinks by (1 - alpha) per merge when nothing else moves (Alg. 1 line 19)."""
+    """theta - Theta shrinks by (1 - alpha) per merge when nothing else moves (the merge of Alg. 1's LPS block)."""
     alpha = 0.25
     theta0 = np.array([8.0, -4.0, 0.5, 16.0], dtype=F32)
     g = np.array([1.0, 2.0, -3.0, 0.5], dtype=F32)
@@ -317,7 +317,7 @@ def _all_state(o, n_lps):
 
 
 def test_snapshot_form_equals_accumulator_form():
-    """Delta by subtraction (Alg. 1 line 14 as written) and Delta as a running sum are the same quantity."""
+    """Delta by subtraction (the Delta of Alg. 1's LPS block as written) and Delta as a running sum are the same quantity."""
     w, tr, a, log_a = _random_trace_run(64, FORM_LITERAL)
     _, _, b, log_b = _random_trace_run(64, FORM_ACCUMULATOR)
     assert log_a == log_b
@@ -329,7 +329,7 @@ def test_snapshot_form_equals_accumulator_form():
 
 def test_step_log_matches_schedule_bookkeeping_and_counters():
     """t counts worker updates only; one Delta in flight per LPS; the GPS counter equals the number of
-    Deltas received (Alg. 1 lines 1, 10, 13, 18).  The schedule generator keeps its own counters."""
+    Deltas received (the counters and tests of Alg. 1's GPS and LPS blocks).  The schedule generator keeps its own counters."""
     import synth
     w, tr, o, log = _random_trace_run(64, FORM_LITERAL)
     ev = tr.events
