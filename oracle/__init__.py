@@ -52,6 +52,12 @@ def _load():
         lib.ho_destroy.argtypes = [vp]
         lib.ho_arrive_delta_f32.argtypes = [vp, i32, i32, vp]
         lib.ho_arrive_delta_bf16.argtypes = [vp, i32, i32, vp]
+        lib.ho_arrive_delta_weighted.argtypes = [vp, i32, i32, vp, f32]
+        lib.ho_arrive_delta_16.argtypes = [vp, i32, i32, vp, i32, f32]
+        lib.ho_lps_step_average.argtypes = [vp, i32, i32, ctypes.POINTER(StepInfo)]
+        lib.ho_gps_apply_delta.argtypes = [vp, vp, f32]
+        lib.ho_f16_to_f32.restype = f32
+        lib.ho_f16_to_f32.argtypes = [ctypes.c_uint16]
         lib.ho_arrive_global.argtypes = [vp, i32]
         lib.ho_lps_step.argtypes = [vp, i32, ctypes.POINTER(StepInfo)]
         lib.ho_gps_receive.argtypes = [vp, i32]
@@ -111,17 +117,33 @@ class HalosOracle:
         if rc != 0:
             raise OracleError(f"{what}: protocol violation (code {rc})")
 
-    def arrive_delta(self, l: int, worker: int, g: np.ndarray):
-        """g is the pseudo-gradient (start - end model): float32 values, or raw bfloat16 bit patterns as uint16/int16."""
+    def arrive_delta(self, l: int, worker: int, g: np.ndarray, weight: float = 1.0):
+        """g is the pseudo-gradient (start - end model): float32 values, IEEE half values (numpy float16), or raw
+        bfloat16 bit patterns as uint16/int16.  weight: the caller's scalar on this delta (1 = a plain arrival)."""
         g = np.ascontiguousarray(g)
         assert g.size == self.n
+        w = np.float32(weight)
         if g.dtype == np.float32:
-            rc = self._lib.ho_arrive_delta_f32(self._h, l, worker, g.ctypes.data)
+            rc = self._lib.ho_arrive_delta_weighted(self._h, l, worker, g.ctypes.data, w)
+        elif g.dtype == np.float16:
+            rc = self._lib.ho_arrive_delta_16(self._h, l, worker, g.ctypes.data, 2, w)
         elif g.dtype in (np.uint16, np.int16):
-            rc = self._lib.ho_arrive_delta_bf16(self._h, l, worker, g.ctypes.data)
+            rc = self._lib.ho_arrive_delta_16(self._h, l, worker, g.ctypes.data, 1, w)
         else:
             raise TypeError(g.dtype)
         self._chk(rc, "arrive_delta")
+
+    def lps_step_average(self, l: int, count: int) -> StepInfo:
+        """The `count` deltas at the head of LPS l's queue, averaged in arrival order, applied as ONE update."""
+        info = StepInfo()
+        self._chk(self._lib.ho_lps_step_average(self._h, l, count, ctypes.byref(info)), "lps_step_average")
+        return info
+
+    def gps_apply_delta(self, g: np.ndarray, weight: float = 1.0):
+        """Single tier: the GPS applies a worker's pseudo-gradient (float32 values) with its own rule."""
+        g = np.ascontiguousarray(g, dtype=np.float32)
+        assert g.size == self.n
+        self._chk(self._lib.ho_gps_apply_delta(self._h, g.ctypes.data, np.float32(weight)), "gps_apply_delta")
 
     def arrive_global(self, l: int):
         self._chk(self._lib.ho_arrive_global(self._h, l), "arrive_global")
@@ -170,3 +192,7 @@ class HalosOracle:
 
 def bf16_to_f32(bits: int) -> float:
     return float(_load().ho_bf16_to_f32(bits & 0xFFFF))
+
+
+def f16_to_f32(bits: int) -> float:
+    return float(_load().ho_f16_to_f32(bits & 0xFFFF))

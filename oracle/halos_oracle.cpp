@@ -45,6 +45,17 @@
 // With d = 1 every update is a "d-th" one and the rule is exactly ModelUpdate above.  The buffer and the
 // position in the cycle belong to the server; merges do not touch them.
 //
+// Comparison rules on the same servers (Sec. 2 and the ablation of Sec. 5.2 name them; each is a small variation
+// of the steps above, stated here in this file's own terms):
+//   * weighted arrival: a delta may carry a scalar weight w chosen by the caller (a staleness-scaled update as in
+//     the asynchronous-federated baseline of Sec. 5.2; the paper names only the polynomial's exponent, so the
+//     weight's formula stays outside); the server applies ModelUpdate to w * grad.  w = 1 changes nothing.
+//   * averaged step: the n deltas at the head of the queue are averaged, (g_1 + ... + g_n) * (1/n) summed in
+//     arrival order, and applied as ONE update (the synchronous outer step of the Local-SGD methods in Sec. 2).
+//   * single tier: the global server applies a worker's delta itself with its own rule (no local server;
+//     App. D lists this baseline's hyper-parameters), gps_apply_delta below.
+// Deltas may also arrive as IEEE half precision (the workers of Sec. 5.1 train in fp16): upcast exactly.
+//
 // Two numerical forms are provided and selected at creation:
 //   form 0 (literal)      keeps the snapshot theta_{t_last} and forms Delta by
 //                         subtraction exactly as Algorithm 1's LPS block writes it;
@@ -171,6 +182,7 @@ struct QueueItem {
     int kind;
     int worker;
     std::vector<float> grad;     // pseudo-gradient values (exactly representable in fp32)
+    float weight = 1.0f;         // caller's scalar on this delta (1 = plain arrival)
 };
 
 template <class R>
@@ -237,14 +249,14 @@ struct Oracle {
     }
 
     // LPS block, "receive delta": a worker's delta arrives and joins the queue.
-    int arrive_delta(int l, int worker, const float *g) {
+    int arrive_delta(int l, int worker, const float *g, float weight = 1.0f) {
         Lps<R> &s = lps[l];
         if (worker < 0) return -1;
         if ((size_t)worker >= s.worker_queued.size()) s.worker_queued.resize(worker + 1, 0);
         if (s.worker_queued[worker]) return -2;            // one delta per worker at a time
         s.worker_queued[worker] = 1;
         QueueItem<R> it;
-        it.kind = ITEM_DELTA; it.worker = worker; it.grad.assign(g, g + n);
+        it.kind = ITEM_DELTA; it.worker = worker; it.grad.assign(g, g + n); it.weight = weight;
         s.queue.push_back(std::move(it));
         return 0;
     }
@@ -259,6 +271,71 @@ struct Oracle {
         return 0;
     }
 
+    // One worker update of server s with the pseudo-gradient gvec (already weighted or averaged): the counter, ModelUpdate,
+    // the accumulation and the send test of the LPS block.
+    void apply_update(Lps<R> &s, const std::vector<R> &gvec, StepInfo &out) {
+        s.t += 1;                                                       // t <- t + 1
+        const bool accumulate = (s.phase == ACCUMULATING);
+        s.last_delta_sq = 0.0;
+        for (int64_t j = 0; j < n; ++j) s.last_delta_sq += (double)gvec[j] * (double)gvec[j];
+        const bool first = s.delay.seen == 0, refresh = s.delay.seen + 1 == s.delay.d;
+        for (int64_t j = 0; j < n; ++j) {                               // ModelUpdate
+            const R grad = gvec[j];
+            R step, terms;
+            if (s.delay.enabled) {
+                step = delayed_update<R>(s.theta[j], s.m[j], s.buffer[j], grad, local, s.delay.inv_d, first, refresh);
+                terms = delayed_scales<R>(s.sc_m[j], s.sc_buffer[j], s.m[j], grad, local, s.delay.inv_d, first, refresh);
+            } else {
+                step = model_update<R>(s.theta[j], s.m[j], grad, local);
+                raise_to(s.sc_m[j], std::fabs(grad));
+                raise_to(s.sc_m[j], std::fabs(s.m[j]));
+                terms = step_scale<R>(s.sc_m[j], std::fabs(grad), local);
+            }
+            if (form == 1 && accumulate) s.acc[j] = s.acc[j] + step;
+            raise_to(s.sc_theta[j], terms);
+            raise_to(s.sc_theta[j], std::fabs(s.theta[j]));
+            if (accumulate) {
+                raise_to(s.sc_aux[j], terms);
+                raise_to(s.sc_aux[j], std::fabs(form == 1 ? s.acc[j] : s.snap[j] - s.theta[j]));
+            }
+        }
+        if (s.delay.enabled) s.delay.seen = refresh ? 0 : s.delay.seen + 1;
+        out.kind = 1; out.accumulated = accumulate ? 1 : 0;
+        if (accumulate && s.t - s.t_last >= s.K) {                      // send test
+            for (int64_t j = 0; j < n; ++j)                             // Delta, sign flipped: G = -Delta
+                s.frozen[j] = (form == 1) ? s.acc[j] : (s.snap[j] - s.theta[j]);
+            s.phase = SENT;
+            out.sent = 1;
+        }
+    }
+
+    // Averaged step: the `count` deltas at the head of the queue become ONE update with their mean,
+    // (w_1 g_1 + ... + w_n g_n) * (1/n), added up in arrival order.  count = 1 is the plain update.
+    int lps_step_average(int l, int count, StepInfo *info) {
+        Lps<R> &s = lps[l];
+        if (count < 1 || (size_t)count > s.queue.size()) return -2;
+        for (int i = 0; i < count; ++i) if (s.queue[i].kind != ITEM_DELTA) return -2;
+        StepInfo out{}; out.worker = -1;
+        std::vector<R> gvec(n);
+        for (int i = 0; i < count; ++i) {
+            QueueItem<R> it = std::move(s.queue.front());
+            s.queue.pop_front();
+            const R w = R(it.weight);
+            for (int64_t j = 0; j < n; ++j) {
+                const R term = w * R(it.grad[j]);
+                gvec[j] = (i == 0) ? term : gvec[j] + term;
+            }
+            s.worker_queued[it.worker] = 0;
+            out.worker = it.worker;
+        }
+        const R inv_n = R(1) / R(count);
+        for (int64_t j = 0; j < n; ++j) gvec[j] = gvec[j] * inv_n;
+        apply_update(s, gvec, out);
+        out.t = s.t; out.t_last = s.t_last;
+        *info = out;
+        return 0;
+    }
+
     // Handle the head of the queue: the update branch for a delta, the merge branch for a global model.
     int lps_step(int l, StepInfo *info) {
         Lps<R> &s = lps[l];
@@ -267,40 +344,12 @@ struct Oracle {
         QueueItem<R> it = std::move(s.queue.front());
         s.queue.pop_front();
         if (it.kind == ITEM_DELTA) {
-            s.t += 1;                                                   // t <- t + 1
-            const bool accumulate = (s.phase == ACCUMULATING);
-            s.last_delta_sq = 0.0;
-            for (int64_t j = 0; j < n; ++j) s.last_delta_sq += (double)it.grad[j] * (double)it.grad[j];
-            const bool first = s.delay.seen == 0, refresh = s.delay.seen + 1 == s.delay.d;
-            for (int64_t j = 0; j < n; ++j) {                           // ModelUpdate
-                const R grad = R(it.grad[j]);
-                R step, terms;
-                if (s.delay.enabled) {
-                    step = delayed_update<R>(s.theta[j], s.m[j], s.buffer[j], grad, local, s.delay.inv_d, first, refresh);
-                    terms = delayed_scales<R>(s.sc_m[j], s.sc_buffer[j], s.m[j], grad, local, s.delay.inv_d, first, refresh);
-                } else {
-                    step = model_update<R>(s.theta[j], s.m[j], grad, local);
-                    raise_to(s.sc_m[j], std::fabs(grad));
-                    raise_to(s.sc_m[j], std::fabs(s.m[j]));
-                    terms = step_scale<R>(s.sc_m[j], std::fabs(grad), local);
-                }
-                if (form == 1 && accumulate) s.acc[j] = s.acc[j] + step;
-                raise_to(s.sc_theta[j], terms);
-                raise_to(s.sc_theta[j], std::fabs(s.theta[j]));
-                if (accumulate) {
-                    raise_to(s.sc_aux[j], terms);
-                    raise_to(s.sc_aux[j], std::fabs(form == 1 ? s.acc[j] : s.snap[j] - s.theta[j]));
-                }
-            }
-            if (s.delay.enabled) s.delay.seen = refresh ? 0 : s.delay.seen + 1;
+            std::vector<R> gvec(n);
+            const R w = R(it.weight);                                   // the caller's scalar on this delta (1 = none)
+            for (int64_t j = 0; j < n; ++j) gvec[j] = w * R(it.grad[j]);
+            apply_update(s, gvec, out);
             s.worker_queued[it.worker] = 0;
-            out.kind = 1; out.worker = it.worker; out.accumulated = accumulate ? 1 : 0;
-            if (accumulate && s.t - s.t_last >= s.K) {                  // send test
-                for (int64_t j = 0; j < n; ++j)                         // Delta, sign flipped: G = -Delta
-                    s.frozen[j] = (form == 1) ? s.acc[j] : (s.snap[j] - s.theta[j]);
-                s.phase = SENT;
-                out.sent = 1;
-            }
+            out.worker = it.worker;
         } else {
             if (s.phase != QUEUED) return -3;
             s.t_last = s.t;                                             // t_last <- t
@@ -350,6 +399,31 @@ struct Oracle {
         s.inbox = Theta;                                                // send back: this Theta_i, frozen
         s.sc_aux = sc_Theta;
         s.phase = RETURNING;
+        return 0;
+    }
+
+    // Single tier: the global server applies a worker's delta itself, with its own rule (and its own delayed-momentum
+    // cycle if it has one); nothing is sent back -- workers pull the global model.
+    int gps_apply_delta(const float *g, float weight) {
+        gps_updates += 1;
+        const bool first = gps_delay.seen == 0, refresh = gps_delay.seen + 1 == gps_delay.d;
+        const R w = R(weight);
+        for (int64_t j = 0; j < n; ++j) {
+            const R grad = w * R(g[j]);
+            R terms;
+            if (gps_delay.enabled) {
+                delayed_update<R>(Theta[j], M[j], gps_buffer[j], grad, global, gps_delay.inv_d, first, refresh);
+                terms = delayed_scales<R>(sc_M[j], sc_gps_buffer[j], M[j], std::fabs(grad), global, gps_delay.inv_d, first, refresh);
+            } else {
+                model_update<R>(Theta[j], M[j], grad, global);
+                raise_to(sc_M[j], std::fabs(grad));
+                raise_to(sc_M[j], std::fabs(M[j]));
+                terms = step_scale<R>(sc_M[j], std::fabs(grad), global);
+            }
+            raise_to(sc_Theta[j], terms);
+            raise_to(sc_Theta[j], std::fabs(Theta[j]));
+        }
+        if (gps_delay.enabled) { gps_delay.seen = refresh ? 0 : gps_delay.seen + 1; }
         return 0;
     }
 
@@ -452,6 +526,50 @@ int ho_arrive_delta_bf16(void *p, int32_t l, int32_t worker, const uint16_t *g) 
     for (int64_t j = 0; j < n; ++j) up[j] = bf16_to_f32(g[j]);
     return DISPATCH(arrive_delta(l, worker, up.data()));
 }
+
+// IEEE binary16 -> binary32, exact (every half value, subnormals included, is a float).
+inline float f16_to_f32(uint16_t h) {
+    const uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    const uint32_t exp = (h >> 10) & 0x1Fu, frac = h & 0x3FFu;
+    uint32_t u;
+    if (exp == 0x1Fu) u = sign | 0x7F800000u | (frac << 13);                        // infinity, NaN (payload kept)
+    else if (exp != 0) u = sign | ((exp + 112u) << 23) | (frac << 13);              // normal: rebias 15 -> 127
+    else if (frac == 0) u = sign;                                                    // zero
+    else {                                                                          // subnormal: frac * 2^-24
+        float v = (float)frac * 5.9604644775390625e-08f;
+        uint32_t b; std::memcpy(&b, &v, sizeof b);
+        u = sign | b;
+    }
+    float f; std::memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+int ho_arrive_delta_weighted(void *p, int32_t l, int32_t worker, const float *g, float weight) {
+    Handle *h = (Handle *)p;
+    return DISPATCH(arrive_delta(l, worker, g, weight));
+}
+
+// dtype 1: bfloat16 bit patterns, 2: IEEE half bit patterns.
+int ho_arrive_delta_16(void *p, int32_t l, int32_t worker, const uint16_t *g, int32_t dtype, float weight) {
+    Handle *h = (Handle *)p;
+    if (dtype != 1 && dtype != 2) return -1;
+    int64_t n = h->precision == 32 ? h->f->n : h->d->n;
+    std::vector<float> up(n);
+    for (int64_t j = 0; j < n; ++j) up[j] = dtype == 1 ? bf16_to_f32(g[j]) : f16_to_f32(g[j]);
+    return DISPATCH(arrive_delta(l, worker, up.data(), weight));
+}
+
+int ho_lps_step_average(void *p, int32_t l, int32_t count, void *info) {
+    Handle *h = (Handle *)p;
+    return DISPATCH(lps_step_average(l, count, (StepInfo *)info));
+}
+
+int ho_gps_apply_delta(void *p, const float *g, float weight) {
+    Handle *h = (Handle *)p;
+    return DISPATCH(gps_apply_delta(g, weight));
+}
+
+float ho_f16_to_f32(uint16_t bits) { return f16_to_f32(bits); }
 
 int ho_arrive_global(void *p, int32_t l) { Handle *h = (Handle *)p; return DISPATCH(arrive_global(l)); }
 

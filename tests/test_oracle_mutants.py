@@ -11,6 +11,7 @@ import oracle as O
 import test_oracle_pins as pins
 import test_oracle_delayed_momentum as dpins
 import test_oracle_error_scales as spins
+import test_oracle_variants as vpins
 
 SRC = os.path.join(os.path.dirname(os.path.abspath(O.__file__)), "halos_oracle.cpp")
 
@@ -62,14 +63,32 @@ MUTANTS = [
      "                raise_to(s.sc_theta[j], s.sc_aux[j]);                   // scale of the merged global model\n", ""),
     ("scales: GPS ignores the scale that travels with G",
      "            raise_to(sc_M[j], s.sc_aux[j]);                             // the scale of G travels with it\n", ""),
-    ("scales: momentum scale follows the value down", "                    raise_to(s.sc_m[j], std::fabs(s.m[j]));",
-     "                    s.sc_m[j] = std::fabs(s.m[j]);"),
+    ("scales: momentum scale follows the value down", "                raise_to(s.sc_m[j], std::fabs(s.m[j]));",
+     "                s.sc_m[j] = std::fabs(s.m[j]);"),
     ("scales: returned model keeps G's scale instead of Theta's", "        s.sc_aux = sc_Theta;\n", ""),
     ("scales: accumulated update's scale survives the merge",
      "            std::fill(s.sc_aux.begin(), s.sc_aux.end(), R(0));\n", ""),
     ("scales: delayed buffer scale adds signed values", "    buffer_scale = first ? g_mag : buffer_scale + g_mag;",
      "    buffer_scale = first ? g_mag : buffer_scale + grad;"),
     ("scales: delayed momentum scale ignores the buffer", "        raise_to(m_scale, buffer_scale * inv_d);\n", ""),
+    # weighted arrivals, averaged step, single tier, half-precision deltas
+    ("variants: weight ignored", "const R w = R(it.weight);                                   // the caller's scalar on this delta (1 = none)",
+     "const R w = R(1);"),
+    ("variants: average not divided by n", "const R inv_n = R(1) / R(count);", "const R inv_n = R(1);"),
+    ("variants: average keeps only the last delta", "gvec[j] = (i == 0) ? term : gvec[j] + term;", "gvec[j] = term;"),
+    ("variants: average counts n updates", "        apply_update(s, gvec, out);\n        out.t = s.t; out.t_last = s.t_last;",
+     "        apply_update(s, gvec, out); s.t += count - 1;\n        out.t = s.t; out.t_last = s.t_last;"),
+    ("variants: average ignores the weights", "const R term = w * R(it.grad[j]);", "const R term = R(it.grad[j]);"),
+    ("variants: average leaves the senders marked busy", "            s.worker_queued[it.worker] = 0;\n            out.worker = it.worker;\n        }\n        const R inv_n",
+     "            out.worker = it.worker;\n        }\n        const R inv_n"),
+    ("variants: single tier uses the local rule", "model_update<R>(Theta[j], M[j], grad, global);", "model_update<R>(Theta[j], M[j], grad, local);"),
+    ("variants: single tier forgets the weight", "const R grad = w * R(g[j]);", "const R grad = R(g[j]);"),
+    ("variants: single tier never closes its momentum cycle", "if (gps_delay.enabled) { gps_delay.seen = refresh ? 0 : gps_delay.seen + 1; }",
+     "if (gps_delay.enabled) { gps_delay.seen = gps_delay.seen + 1; }"),
+    ("variants: f16 exponent bias off by one", "((exp + 112u) << 23)", "((exp + 111u) << 23)"),
+    ("variants: f16 subnormals flushed", "float v = (float)frac * 5.9604644775390625e-08f;", "float v = 0.0f * (float)frac;"),
+    ("variants: f16 mantissa shifted one bit short", "else if (exp != 0) u = sign | ((exp + 112u) << 23) | (frac << 13);",
+     "else if (exp != 0) u = sign | ((exp + 112u) << 23) | (frac << 12);"),
     ("scales: everything doubled at the end", "        case 10: copy_out(o->lps[l].sc_theta, out); return 0;",
      "        case 10: { std::vector<R> v = o->lps[l].sc_theta; for (auto &x : v) x *= R(2); copy_out(v, out); return 0; }"),
 ]
@@ -101,6 +120,12 @@ PIN_TESTS = [
     lambda: [spins.test_scale_rules_with_momentum_rate_and_coefficient(64, f) for f in pins.BOTH_FORMS],
     lambda: spins.test_scale_rules_of_the_delayed_rule(64),
     lambda: spins.test_scales_are_bounded_on_both_sides_on_a_seeded_trace(1, 1),
+    vpins.test_f16_upcast_matches_torch_for_every_bit_pattern,
+    vpins.test_weighted_delta_is_the_delta_scaled_beforehand,
+    vpins.test_average_is_one_update_with_the_mean,
+    vpins.test_average_adds_in_arrival_order_and_uses_the_weights,
+    lambda: [vpins.test_single_tier_server_is_the_same_rule_one_level_up(64, d) for d in (1, 3)],
+    vpins.test_single_tier_server_matches_the_filter_closed_form,
 ]
 
 
