@@ -241,7 +241,9 @@ def end_model_ab(name: str, reps: int = 20, verbose: bool = True):
     finally:
         B.halos_lps_destroy(lps)
         B.halos_gps_destroy(gps)
-        del ra, Theta, M, th, m, inp, acc, wm
+        torch.cuda.synchronize()
+        del Theta, M, th, m, inp, acc, wm
+        ra.close()
         torch.cuda.empty_cache()
     out["workload"] = name
     out["note"] = ("end_model: the server reads the worker's start and end models (8 B) instead of an fp32 delta (4 B) "
@@ -354,6 +356,158 @@ def cpu_baseline(name: str, budget_elements: int = 1 << 22):
     }
 
 
+def ceilings_mode(gib: float, reps: int):
+    """`bench.py --ceilings`: what this device's memory system delivers to plain streaming kernels, by HBM region.
+
+    Places buffers in each HBM region the library's arena finds, then times halos_probe_streams (read some buffers,
+    write others, no arithmetic, the access pattern of the update kernels) for pure reads, pure writes, copies and the
+    stream mix of the update pass with fused pull (4 read, 4 written) under several placements; then the same mix for
+    other tile sizes (128-bit accesses per thread and stream before anything is consumed: 1 .. 16, tiles of 4 .. 64 KiB),
+    other grid sizes, and with the streams' start addresses staggered inside ONE region.  Prints tables (plain text)."""
+    import torch
+    from paper_2506_04531_amd import binding as B
+    from paper_2506_04531_amd.harness import RegionArena
+
+    nbytes = int(gib * (1 << 30)) // (1 << 16) * (1 << 16)
+    n = nbytes // 4
+    dev = torch.device("cuda:0")
+    per_region = 8
+    pad = 64 << 20                                             # room to shift a buffer's start by up to 64 MiB
+    assert nbytes + pad <= (1 << 31), "a buffer and its padding must fit one 2 GiB slab"
+    slabs_per_buffer = 1 if 2 * (nbytes + pad) > (1 << 31) else 0.5
+    need = int(per_region * slabs_per_buffer * (1 << 31))
+    arena = RegionArena(dev, [need, need, need], verbose=True)
+    if arena.n_regions < 3:
+        print(f"only {arena.n_regions} region(s) found: placements below collapse onto fewer regions")
+    X, Y, Z = ([arena.alloc(r, n + pad // 4, torch.float32).zero_() for _ in range(per_region)] for r in range(3))
+    torch.cuda.synchronize()
+
+    def run(reads, writes, unroll=0, shift=None):
+        """shift: per-stream start offsets in bytes (reads first, then writes)."""
+        bufs = list(reads) + list(writes)
+        ptrs = [b.data_ptr() + (shift[i] if shift else 0) for i, b in enumerate(bufs)]
+        return B.halos_probe_streams(ptrs[:len(reads)], ptrs[len(reads):], nbytes, reps, unroll)
+
+    def table(title, rows):
+        print(f"\n{title}")
+        print(f"{'pattern':104s} {'GB/s':>8s} {'of 8 TB/s':>10s}")
+        for name, v in rows:
+            print(f"{name:104s} {v:8.0f} {v / HBM_PEAK_GBS:10.1%}")
+
+    rows = [("1 read", run([X[0]], [])), ("2 reads, one region", run([X[0], X[1]], [])),
+            ("4 reads, one region", run(X[:4], [])), ("4 reads over three regions", run([X[0], Y[0], Z[0], X[1]], [])),
+            ("1 write", run([], [X[4]])), ("2 writes, one region", run([], [X[4], X[5]])),
+            ("4 writes, one region", run([], X[4:8])), ("4 writes over three regions", run([], [X[4], Y[4], Z[4], X[5]])),
+            ("copy (1 read, 1 write), one region", run([X[0]], [X[4]])), ("copy, two regions", run([X[0]], [Y[4]]))]
+    r4, w4 = max(rows[2][1], rows[3][1]), max(rows[6][1], rows[7][1])
+    mixes = [
+        ("4 reads + 4 writes, all in one region", X[:4], X[4:8]),
+        ("4 reads + 4 writes, spread evenly (reads X Y Z X, writes X Y Z Y)", [X[0], Y[0], Z[0], X[1]], [X[4], Y[4], Z[4], Y[5]]),
+        ("4 reads + 4 writes, as the benchmark places the update pass (reads X X X Y, writes X X Y Z)",
+         [X[0], X[1], X[2], Y[0]], [X[4], X[5], Y[4], Z[4]]),
+        ("4 reads + 4 writes, no region both read and written (reads X X X X, writes Y Z Y Z)", X[:4], [Y[4], Z[4], Y[5], Z[5]]),
+    ]
+    for name, rd, wr in mixes:
+        rows.append((name, run(rd, wr)))
+    table(f"buffers of {nbytes / (1 << 30):.2f} GiB, {reps} timed sweeps each, 16 KiB tiles, default grid", rows)
+    pred = 30.0 / (14.0 / r4 + 16.0 / w4)
+    print(f"best 4-stream read rate {r4:.0f} GB/s, best 4-stream write rate {w4:.0f} GB/s; a pass that reads 14 and writes "
+          f"16 bytes per parameter at those rates, if reads and writes did not disturb each other: {pred:.0f} GB/s = "
+          f"{pred / HBM_PEAK_GBS:.1%} of 8 TB/s")
+
+    # tile size x grid size, for the benchmark's placement of the 4 + 4 mix and for 3 + 3 (GPS update: reads X Y Z, writes X Y Z)
+    bench_mix = ([X[0], X[1], X[2], Y[0]], [X[4], X[5], Y[4], Z[4]])
+    gps_mix = ([X[0], Y[0], Z[0]], [X[4], Y[4], Z[4]])
+    for title, (rd, wr) in (("4 reads + 4 writes in the benchmark's placement", bench_mix), ("3 reads + 3 writes, one per region", gps_mix)):
+        print(f"\n{title}: GB/s by tile size (rows: 128-bit accesses per thread and stream) and workgroups per compute unit (columns)")
+        bpcs = (1, 2, 4, 8, 16, 32)
+        print("unroll  tile " + "".join(f"{b:>8d}" for b in bpcs))
+        for unroll in (1, 2, 4, 8, 16):
+            vals = []
+            for bpc in bpcs:
+                B.halos_set_launch_config(bpc, -1)
+                vals.append(run(rd, wr, unroll))
+            print(f"{unroll:6d} {unroll * 4:3d}KiB " + "".join(f"{v:8.0f}" for v in vals))
+        B.halos_set_launch_config(1, -1)
+
+    # staggered starts inside ONE region: does shifting the streams against each other do what separate regions do?
+    rows = []
+    for label, step in (("no shift", 0), ("256 B", 256), ("4 KiB", 4 << 10), ("68 KiB", 68 << 10), ("1 MiB + 4 KiB", (1 << 20) + (4 << 10)),
+                        ("5 MiB + 20 KiB", (5 << 20) + (20 << 10)), ("7 MiB", 7 << 20)):
+        shift = [k * step for k in range(8)]
+        rows.append((f"4 reads + 4 writes in one region, stream k shifted by k x {label}", run(X[:4], X[4:8], 0, shift)))
+    for label, step in (("no shift", 0), ("68 KiB", 68 << 10), ("5 MiB + 20 KiB", (5 << 20) + (20 << 10))):
+        shift = [k * step for k in range(8)]
+        rows.append((f"benchmark placement, stream k shifted by k x {label}", run(bench_mix[0], bench_mix[1], 0, shift)))
+    table("start addresses staggered", rows)
+    del X, Y, Z
+    arena.close()
+
+
+def placement_search_mode(elements: int, dtype_name: str):
+    """`bench.py --placement-search`: time the library's fused update pass (halos_lps_step_pull: read delta, m, theta,
+    third buffer; write m, theta, third buffer, worker model) for every assignment of those five arrays to the HBM regions
+    the arena finds, and print the assignments grouped by pattern (regions renamed X, Y, Z in order of first use, arrays
+    in the order m, theta, third, delta, worker model).  This is how the benchmark's placement classes were chosen."""
+    import itertools
+    from collections import defaultdict
+    import torch
+    from paper_2506_04531_amd import binding as B
+    from paper_2506_04531_amd.harness import RegionArena
+
+    n = elements
+    dev = torch.device("cuda:0")
+    dtype = B.BF16 if dtype_name == "bf16" else B.F32
+    ddt = torch.bfloat16 if dtype_name == "bf16" else torch.float32
+    need = 7 * n * 4 + (1 << 30)
+    arena = RegionArena(dev, [need, need, need], verbose=True)
+    if arena.n_regions < 3:
+        print(f"only {arena.n_regions} region(s) found: nothing to compare")
+        return
+    pool = []
+    for r in range(3):
+        pool.append({"delta": [arena.alloc(r, n, ddt).zero_()], "m": [arena.alloc(r, n, torch.float32)],
+                     "theta": [arena.alloc(r, n, torch.float32)], "third": [arena.alloc(r, n, torch.float32)],
+                     "model": [arena.alloc(r, n, torch.float32)]})
+    gps_bufs = {"Theta": [arena.alloc(0, n, torch.float32).zero_()], "M": [arena.alloc(0, n, torch.float32)]}
+    bpp = (4 if dtype == B.F32 else 2) + 28
+    roles = ("m", "theta", "third", "delta", "model")
+    hp = B.paper_hparams(0.2, 0.9, 0.15, 0.5, 0.25, 1 << 30)
+    groups = defaultdict(list)
+    for assign in itertools.product(range(3), repeat=5):
+        bufs = dict(gps_bufs)
+        for role, r in zip(roles, assign):
+            bufs[role] = pool[r][role]
+        gps = B.halos_gps_create([n], hp, bufs["Theta"], bufs["M"])
+        lps = B.halos_lps_create(gps, 0, 1, bufs["theta"], bufs["m"], bufs["third"])
+        try:
+            B.halos_lps_set_worker_model(lps, 0, bufs["model"])
+            B.halos_lps_push_update(lps, 0, bufs["delta"], dtype)
+            B.halos_lps_step_pull(lps)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(3):
+                B.halos_lps_push_update(lps, 0, bufs["delta"], dtype)
+                B.halos_lps_step_pull(lps)
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b) / 3
+        finally:
+            B.halos_lps_destroy(lps)
+            B.halos_gps_destroy(gps)
+        rename, pat = {}, []
+        for r in assign:
+            rename.setdefault(r, "XYZ"[len(rename)])
+            pat.append(rename[r])
+        groups["".join(pat)].append(n * bpp / ms / 1e6)
+    print(f"update pass with fused pull, {n} elements per array, {dtype_name} delta, {bpp} B/parameter")
+    print("pattern (m theta third delta model)   mean GB/s    min     max   assignments")
+    for pat, v in sorted(groups.items(), key=lambda kv: -sum(kv[1]) / len(kv[1])):
+        print(f"  {pat}                              {sum(v) / len(v):8.1f} {min(v):7.1f} {max(v):7.1f}   {len(v)}")
+    del pool, gps_bufs
+    arena.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -378,6 +532,15 @@ def main():
     ap.add_argument("--no-graph-ab", action="store_true",
                     help="skip the call-by-call vs HIP-graph comparison on the launch-bound tiny shape")
     ap.add_argument("--quiet", action="store_true")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="instead of the benchmark: print what the memory system delivers to plain streaming kernels "
+                         "(reads, writes, the update pass's mix; by region, tile size, grid size and start offsets)")
+    ap.add_argument("--ceilings-gib", type=float, default=1.0, help="buffer size for --ceilings")
+    ap.add_argument("--ceilings-reps", type=int, default=5)
+    ap.add_argument("--placement-search", action="store_true",
+                    help="instead of the benchmark: time the fused update pass for every assignment of its arrays to the HBM regions")
+    ap.add_argument("--search-elements", type=int, default=1 << 29)
+    ap.add_argument("--search-dtype", default="f32", choices=["f32", "bf16"])
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -393,6 +556,10 @@ def main():
     halos.load_library()
     if args.blocks_per_cu or args.nontemporal >= 0:
         halos.halos_set_launch_config(args.blocks_per_cu, args.nontemporal)
+    if args.ceilings:
+        return ceilings_mode(args.ceilings_gib, args.ceilings_reps)
+    if args.placement_search:
+        return placement_search_mode(args.search_elements, args.search_dtype)
 
     head = run_workload(args.workload, args.steps, args.warmup, not args.quiet, args.placement, not args.no_fuse_pull, args.snapshot)
     others = []

@@ -206,11 +206,12 @@ halos_status halos_lps_step(halos_lps *lps, void *stream, halos_step_info *info)
 /*
  * Register the device tensors in which worker `worker` keeps the model it starts a round from, so that
  * halos_lps_step_pull can hand the updated model back in the same pass that applies the worker's delta.
- * The pointers are copied into a device table; the call waits for the device to go idle first, so it
- * belongs to set-up, not to the event loop.  The buffers are borrowed for the life of the handle (or
- * until re-registered).
+ * The pointers are written into the server's device table by a small kernel on `stream`, i.e. in stream order:
+ * steps issued before this call keep using the old buffers, steps issued after it (on `stream`, or on a stream
+ * ordered after it) use the new ones.  No synchronisation.  The buffers are borrowed for the life of the handle
+ * (or until re-registered).
  */
-halos_status halos_lps_set_worker_model(halos_lps *lps, int32_t worker, void *const *model);
+halos_status halos_lps_set_worker_model(halos_lps *lps, int32_t worker, void *const *model, void *stream);
 
 /*
  * halos_lps_step with "Schedule the worker theta_t" (Algorithm 1, LPS block) fused in: if the head of the
@@ -293,13 +294,13 @@ halos_status halos_gps_get_counters(const halos_gps *gps, int64_t *updates);
  *     x = x - s;  accumulated update as in halos_lps_step.
  * Updates that do not refresh never read or write the momentum, so they move as many bytes as a plain update.
  *
- * The call copies the pointers into a device table and waits for the device to go idle first: set-up, not
- * event loop.  Allowed only between cycles (before the first update, or when the last update was a refresh):
+ * The call writes the pointers into the server's device table in stream order on `stream` (no synchronisation;
+ * see halos_lps_set_worker_model).  Allowed only between cycles (before the first update, or when the last update was a refresh):
  * ESTATE otherwise.  EINVAL for d < 1, or a bad `buffer` with d > 1.  The delayed kernels always use
  * non-temporal accesses (halos_set_launch_config's `nontemporal` does not apply to them).
  */
-halos_status halos_lps_set_momentum_delay(halos_lps *lps, int32_t d, void *const *buffer);
-halos_status halos_gps_set_momentum_delay(halos_gps *gps, int32_t d, void *const *buffer);
+halos_status halos_lps_set_momentum_delay(halos_lps *lps, int32_t d, void *const *buffer, void *stream);
+halos_status halos_gps_set_momentum_delay(halos_gps *gps, int32_t d, void *const *buffer, void *stream);
 
 /* The delay d of a server and the number of updates applied since its last refresh (0 .. d-1).  Either may be NULL. */
 halos_status halos_lps_get_momentum_delay(const halos_lps *lps, int32_t *d, int32_t *seen);
@@ -307,42 +308,47 @@ halos_status halos_gps_get_momentum_delay(const halos_gps *gps, int32_t *d, int3
 
 /*
  * Launch shape for all later kernel launches of the calling process.
- *   blocks_per_cu  persistent workgroups per compute unit, 1..64 (0 = keep)
+ *   blocks_per_cu  persistent workgroups per compute unit, 1..64 (0 = keep; the library starts with 1)
  *   nontemporal    1 = stream state through the caches with non-temporal accesses, 0 = plain, -1 = keep
  * Returns EINVAL for out-of-range values.
  */
 halos_status halos_set_launch_config(int32_t blocks_per_cu, int32_t nontemporal);
 
 /*
- * Memory-placement helper (not a step of the algorithm).  An MI355X serves its 288 GB of HBM from a few
- * independent regions, and a kernel whose read-modify-write streams live in different regions gets
- * noticeably more bandwidth than one whose streams share a region.  This call sweeps the two device
- * buffers `reps` times on `stream` (each element is read and written back unchanged), waits for the
- * sweeps, and reports the achieved GB/s (4 x bytes per sweep).  Two buffers in the same region report a
- * visibly lower figure than two buffers in different regions, which lets a caller that allocates its
- * state in slabs sort the slabs by region and put theta, m and acc of a server into different ones.
- *   a, b    16-byte aligned device buffers of at least `bytes` bytes each; must not overlap; no other
- *           work may write them while the call runs
- *   bytes   >= 16 KiB; rounded down to a multiple of 16 KiB
- *   reps    1..1000 timed sweeps (one untimed sweep runs first)
- * Errors: EINVAL, EHIP.
+ * Device memory sorted by HBM region (a set-up helper, not a step of the algorithm; the one place where this library
+ * owns parameter-sized memory).  An MI355X serves its HBM from a few large regions, handed to a process one after
+ * the other, and an update pass whose arrays lie in different regions runs about a fifth faster than one whose
+ * arrays share a region (halos_probe.h has the measurement call this is built on).  The arena allocates 2 GiB slabs
+ * until it holds, for every placement class, enough slabs from a region of its own, sorts them by timing each new
+ * slab against one slab per region found so far, and releases what it does not need.  Classes are the caller's:
+ * arrays that one pass touches together should go to different classes.  The benchmark uses three: {momenta, third
+ * buffers}, {local models, deltas, GPS momentum}, {worker model buffers, GPS model}.
+ *   n_classes        1..8
+ *   bytes_per_class  host array: bytes the caller will ask for in each class
+ *   max_walk_bytes   upper bound on the memory held DURING the search (0 = all free memory but 8 GiB).  Memory is
+ *                    handed out in region order, so reaching the third region means holding the first two: on an
+ *                    otherwise idle 288 GB device the search holds up to ~230 GiB for a few seconds.
+ * If fewer regions than classes are found (other processes hold memory, a smaller device, a low bound) classes share
+ * regions: slower, still correct.  Errors: EINVAL, ENOMEM, EHIP (from the timing kernel).
+ * The calling thread's current device is used; the search runs on the default stream and waits for it.
  */
-halos_status halos_probe_pair(void *a, void *b, uint64_t bytes, int32_t reps, void *stream, double *gbps);
+typedef struct halos_arena halos_arena;
+halos_status halos_arena_create(int32_t n_classes, const uint64_t *bytes_per_class, uint64_t max_walk_bytes,
+                                halos_arena **out);
 
-/*
- * Measurement helper (not a step of the algorithm): what the memory system delivers to a kernel that streams
- * n_read buffers in and n_write other buffers out with the access pattern of the update kernels (tiles of 16 KiB,
- * 128-bit non-temporal accesses, all loads of a tile issued first) and no arithmetic.  It gives the ceiling that an
- * update pass with the same mix of read and written streams, placed the same way, can reach on this device.
- *   read_bufs   host array of n_read device buffers, only read
- *   write_bufs  host array of n_write device buffers, OVERWRITTEN WITH ZEROS; none may overlap any other buffer
- *   n_read, n_write   0..4 each, not both 0
- *   bytes, reps, stream   as for halos_probe_pair (every buffer at least `bytes` long, 16-byte aligned)
- *   gbps        achieved GB/s, counting (n_read + n_write) x bytes per sweep
- * Errors: EINVAL, EHIP.
- */
-halos_status halos_probe_streams(const void *const *read_bufs, int32_t n_read, void *const *write_bufs, int32_t n_write,
-                                 uint64_t bytes, int32_t reps, void *stream, double *gbps);
+/* Hand out `bytes` (> 0) of device memory from the slabs of class `cls`, 256-byte aligned, uninitialised; it stays
+ * valid until halos_arena_destroy.  An allocation never straddles two slabs.  When a class has used up its region's
+ * slabs, further slabs come from wherever the device has memory left (placement unknown); a request larger than a
+ * slab (2 GiB) gets an allocation of its own, likewise.  ENOMEM when the device is full. */
+halos_status halos_arena_alloc(halos_arena *arena, int32_t cls, uint64_t bytes, void **ptr);
+
+/* What the search found.  Any out pointer may be NULL; region_of_class and slabs_of_class are host arrays of
+ * n_classes entries (region index of each class, -1 if none; slabs it currently holds). */
+halos_status halos_arena_info(const halos_arena *arena, int32_t *n_regions, uint64_t *walked_bytes,
+                              double *same_region_gbps, int32_t *region_of_class, int32_t *slabs_of_class);
+
+/* Wait for the device, then free every slab.  Pointers handed out by the arena die with it.  NULL is ignored. */
+void halos_arena_destroy(halos_arena *arena);
 
 /* Release the handle's tables (this waits for the device: work that still uses them finishes first).
  * Caller buffers are untouched.  NULL is ignored.  A GPS destroyed while local servers are still attached to it

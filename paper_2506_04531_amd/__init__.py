@@ -27,23 +27,25 @@ HIPCC_FLAGS = [
 
 def build(verbose: bool = False) -> str:
     """Compile the kernels and the C ABI for gfx950 (cross-compiles without a GPU)."""
-    srcs = [os.path.join(_CSRC, "kernels.hip"), os.path.join(_CSRC, "halos.cpp")]
+    srcs = [os.path.join(_CSRC, "kernels.hip"), os.path.join(_CSRC, "halos.cpp"), os.path.join(_CSRC, "arena.cpp")]
     cmd = ["hipcc"] + HIPCC_FLAGS + ["-o", LIB_PATH] + srcs
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
     if verbose:
         print(res.stderr)
-    # a client of the ABI written in plain C (tests/host/abi_client.c), linked against the library just built
-    client_src = os.path.join(os.path.dirname(_HERE), "tests", "host", "abi_client.c")
-    if os.path.exists(client_src):
-        client = os.path.join(os.path.dirname(client_src), "abi_client")
-        cmd = ["gcc", "-std=c11", "-O1", "-Wall", "-I/opt/rocm/include", "-D__HIP_PLATFORM_AMD__", "-o", client,
-               client_src, "-L" + _HERE, "-lhalos", "-L/opt/rocm/lib", "-lamdhip64",
+    # clients of the ABI written in plain C (tests/host/*.c), linked against the library just built
+    host_dir = os.path.join(os.path.dirname(_HERE), "tests", "host")
+    for name in ("abi_client", "arena_client"):
+        client_src = os.path.join(host_dir, name + ".c")
+        if not os.path.exists(client_src):
+            continue
+        cmd = ["gcc", "-std=c11", "-O1", "-Wall", "-I/opt/rocm/include", "-D__HIP_PLATFORM_AMD__", "-o",
+               os.path.join(host_dir, name), client_src, "-L" + _HERE, "-lhalos", "-L/opt/rocm/lib", "-lamdhip64",
                "-Wl,-rpath,$ORIGIN/../../paper_2506_04531_amd", "-Wl,-rpath,/opt/rocm/lib"]
         res = subprocess.run(cmd, capture_output=True, text=True)
         if res.returncode != 0:
-            raise RuntimeError("gcc failed on the C client:\n" + res.stdout + res.stderr)
+            raise RuntimeError(f"gcc failed on {name}.c:\n" + res.stdout + res.stderr)
     return LIB_PATH
 
 

@@ -69,6 +69,7 @@ def load_library():
     from . import LIB_PATH, build
     if not os.path.exists(LIB_PATH):
         build()
+    import torch  # noqa: F401  -- first, so that the process uses the one HIP runtime torch brings with it
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, i64, u32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32
     P = ctypes.POINTER
@@ -80,7 +81,7 @@ def load_library():
         "halos_lps_push_global": [vp],
         "halos_lps_step": [vp, vp, P(StepInfo)],
         "halos_lps_step_pull": [vp, vp, P(StepInfo)],
-        "halos_lps_set_worker_model": [vp, i32, P(vp)],
+        "halos_lps_set_worker_model": [vp, i32, P(vp), vp],
         "halos_gps_merge": [vp, vp, vp],
         "halos_pull_model": [vp, i32, P(vp), vp],
         "halos_set_hparams": [vp, i32, P(HParams)],
@@ -88,13 +89,16 @@ def load_library():
         "halos_lps_get_counters": [vp, P(i64), P(i64), P(i32), P(i32), P(u32)],
         "halos_gps_get_counters": [vp, P(i64)],
         "halos_lps_get_norms": [vp, vp, P(ctypes.c_double)],
-        "halos_lps_set_momentum_delay": [vp, i32, P(vp)],
-        "halos_gps_set_momentum_delay": [vp, i32, P(vp)],
+        "halos_lps_set_momentum_delay": [vp, i32, P(vp), vp],
+        "halos_gps_set_momentum_delay": [vp, i32, P(vp), vp],
         "halos_lps_get_momentum_delay": [vp, P(i32), P(i32)],
         "halos_gps_get_momentum_delay": [vp, P(i32), P(i32)],
         "halos_set_launch_config": [i32, i32],
+        "halos_arena_create": [i32, P(ctypes.c_uint64), ctypes.c_uint64, P(vp)],
+        "halos_arena_alloc": [vp, i32, ctypes.c_uint64, P(vp)],
+        "halos_arena_info": [vp, P(i32), P(ctypes.c_uint64), P(ctypes.c_double), P(i32), P(i32)],
         "halos_probe_pair": [vp, vp, ctypes.c_uint64, i32, vp, P(ctypes.c_double)],
-        "halos_probe_streams": [P(vp), i32, P(vp), i32, ctypes.c_uint64, i32, vp, P(ctypes.c_double)],
+        "halos_probe_streams": [P(vp), i32, P(vp), i32, ctypes.c_uint64, i32, i32, vp, P(ctypes.c_double)],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -104,6 +108,8 @@ def load_library():
     lib.halos_lps_destroy.restype = None
     lib.halos_gps_destroy.argtypes = [vp]
     lib.halos_gps_destroy.restype = None
+    lib.halos_arena_destroy.argtypes = [vp]
+    lib.halos_arena_destroy.restype = None
     lib.halos_last_error.argtypes = []
     lib.halos_last_error.restype = ctypes.c_char_p
     _lib = lib
@@ -186,8 +192,8 @@ def halos_lps_step_pull(lps: int, stream=None) -> StepInfo:
     return info
 
 
-def halos_lps_set_worker_model(lps: int, worker: int, model) -> None:
-    _check(load_library().halos_lps_set_worker_model(lps, worker, _ptrs(model)))
+def halos_lps_set_worker_model(lps: int, worker: int, model, stream=None) -> None:
+    _check(load_library().halos_lps_set_worker_model(lps, worker, _ptrs(model), _stream(stream)))
 
 
 def halos_gps_merge(gps: int, from_lps: int, stream=None) -> None:
@@ -227,12 +233,12 @@ def halos_gps_get_counters(gps: int) -> dict:
     return {"updates": u.value}
 
 
-def halos_lps_set_momentum_delay(lps: int, d: int, buffer=None) -> None:
-    _check(load_library().halos_lps_set_momentum_delay(lps, d, _ptrs(buffer) if buffer is not None else None))
+def halos_lps_set_momentum_delay(lps: int, d: int, buffer=None, stream=None) -> None:
+    _check(load_library().halos_lps_set_momentum_delay(lps, d, _ptrs(buffer) if buffer is not None else None, _stream(stream)))
 
 
-def halos_gps_set_momentum_delay(gps: int, d: int, buffer=None) -> None:
-    _check(load_library().halos_gps_set_momentum_delay(gps, d, _ptrs(buffer) if buffer is not None else None))
+def halos_gps_set_momentum_delay(gps: int, d: int, buffer=None, stream=None) -> None:
+    _check(load_library().halos_gps_set_momentum_delay(gps, d, _ptrs(buffer) if buffer is not None else None, _stream(stream)))
 
 
 def halos_lps_get_momentum_delay(lps: int) -> dict:
@@ -260,9 +266,9 @@ def halos_probe_pair(a, b, nbytes: int, reps: int = 2, stream=None) -> float:
     return out.value
 
 
-def halos_probe_streams(read_bufs, write_bufs, nbytes: int, reps: int = 2, stream=None) -> float:
+def halos_probe_streams(read_bufs, write_bufs, nbytes: int, reps: int = 2, unroll: int = 0, stream=None) -> float:
     """GB/s of a kernel that only reads `read_bufs` and only writes (zeros to) `write_bufs`: lists of torch tensors or
-    raw addresses, up to four each."""
+    raw addresses, up to four each.  unroll: 128-bit accesses per thread, stream and tile (0 = the update kernels' own)."""
     def arr(bufs):
         a = (ctypes.c_void_p * max(1, len(bufs)))()
         for i, b in enumerate(bufs):
@@ -270,8 +276,36 @@ def halos_probe_streams(read_bufs, write_bufs, nbytes: int, reps: int = 2, strea
         return a
     out = ctypes.c_double()
     _check(load_library().halos_probe_streams(arr(read_bufs), len(read_bufs), arr(write_bufs), len(write_bufs),
-                                              int(nbytes), reps, _stream(stream), ctypes.byref(out)))
+                                              int(nbytes), reps, unroll, _stream(stream), ctypes.byref(out)))
     return out.value
+
+
+def halos_arena_create(bytes_per_class: Sequence[int], max_walk_bytes: int = 0) -> int:
+    n = len(bytes_per_class)
+    arr = (ctypes.c_uint64 * max(1, n))(*[int(b) for b in bytes_per_class])
+    out = ctypes.c_void_p()
+    _check(load_library().halos_arena_create(n, arr, int(max_walk_bytes), ctypes.byref(out)))
+    return out.value
+
+
+def halos_arena_alloc(arena: int, cls: int, nbytes: int) -> int:
+    """Raw device address of `nbytes` bytes in placement class `cls`."""
+    out = ctypes.c_void_p()
+    _check(load_library().halos_arena_alloc(arena, cls, int(nbytes), ctypes.byref(out)))
+    return out.value
+
+
+def halos_arena_info(arena: int, n_classes: int) -> dict:
+    nr, walked, same = ctypes.c_int32(), ctypes.c_uint64(), ctypes.c_double()
+    roc, soc = (ctypes.c_int32 * max(1, n_classes))(), (ctypes.c_int32 * max(1, n_classes))()
+    _check(load_library().halos_arena_info(arena, ctypes.byref(nr), ctypes.byref(walked), ctypes.byref(same), roc, soc))
+    return {"n_regions": nr.value, "walked_bytes": walked.value, "same_region_gbps": same.value,
+            "region_of_class": list(roc)[:n_classes], "slabs_of_class": list(soc)[:n_classes]}
+
+
+def halos_arena_destroy(arena: Optional[int]) -> None:
+    if arena:
+        load_library().halos_arena_destroy(arena)
 
 
 def halos_lps_destroy(lps: Optional[int]) -> None:

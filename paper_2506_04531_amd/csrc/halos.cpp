@@ -2,6 +2,7 @@
 // This file is host logic only: argument checking, the protocol state machine, the small device
 // tables, and the decision which kernel to launch.  All parameter arithmetic is in kernels.hip.
 #include "../../include/halos.h"
+#include "../../include/halos_probe.h"
 
 #include <hip/hip_runtime_api.h>
 
@@ -10,8 +11,10 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
+#include <unordered_set>
 #include <vector>
 
 #include "kernels.hpp"
@@ -20,10 +23,12 @@
 using namespace halos;
 
 namespace {
-
 thread_local std::string g_last_error;
+}
 
-halos_status fail(halos_status code, const char *fmt, ...) {
+namespace halos {
+// Shared with the other translation units of the library: record the calling thread's error text, return `code`.
+halos_status set_error(halos_status code, const char *fmt, ...) {
     char buf[512];
     va_list ap;
     va_start(ap, fmt);
@@ -32,16 +37,36 @@ halos_status fail(halos_status code, const char *fmt, ...) {
     g_last_error = buf;
     return code;
 }
+}  // namespace halos
+
+namespace {
+
+#define fail(...) halos::set_error(__VA_ARGS__)
 
 halos_status fail_hip(hipError_t e, const char *what) {
     return fail(HALOS_EHIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-std::atomic<int> g_blocks_per_cu{8};
+// One workgroup per compute unit = one wavefront per SIMD: measured best on MI355X (more resident wavefronts only
+// deepen the queues in front of the memory controllers; 1-4 % slower at 2..32 per compute unit on every workload).
+std::atomic<int> g_blocks_per_cu{1};
 std::atomic<int> g_nontemporal{1};
 
 constexpr uint32_t GPS_MAGIC = 0x48475053u;   // "HGPS"
 constexpr uint32_t LPS_MAGIC = 0x484c5053u;   // "HLPS"
+
+// Handles are validated against a registry of live ones, so that a stale or foreign pointer is rejected without
+// being dereferenced.
+std::mutex g_registry_mutex;
+std::unordered_set<const void *> g_live_handles;
+
+void register_handle(const void *h) { std::lock_guard<std::mutex> lk(g_registry_mutex); g_live_handles.insert(h); }
+void unregister_handle(const void *h) { std::lock_guard<std::mutex> lk(g_registry_mutex); g_live_handles.erase(h); }
+bool is_registered(const void *h) {
+    if (!h) return false;
+    std::lock_guard<std::mutex> lk(g_registry_mutex);
+    return g_live_handles.count(h) != 0;
+}
 
 bool rule_ok(const halos_rule &r) {
     return std::isfinite(r.eta) && std::isfinite(r.beta) && std::isfinite(r.cg);
@@ -114,6 +139,9 @@ struct halos_lps {
 };
 
 namespace {
+
+bool live_gps(const halos_gps *g) { return is_registered(g) && g->magic == GPS_MAGIC && !g->retired; }
+bool live_lps(const halos_lps *l) { return is_registered(l) && l->magic == LPS_MAGIC; }
 
 static_assert(POS_FIRST == CYCLE_FIRST && POS_INNER == CYCLE_INNER && POS_REFRESH == CYCLE_REFRESH,
               "the protocol's cycle positions are the kernels' rule selectors");
@@ -279,12 +307,15 @@ halos_status halos_probe_pair(void *a, void *b, uint64_t bytes, int32_t reps, vo
 }
 
 halos_status halos_probe_streams(const void *const *read_bufs, int32_t n_read, void *const *write_bufs, int32_t n_write,
-                                 uint64_t bytes, int32_t reps, void *stream, double *gbps) {
+                                 uint64_t bytes, int32_t reps, int32_t unroll, void *stream, double *gbps) {
     if (!gbps) return fail(HALOS_EINVAL, "gbps is NULL");
+    if (unroll == 0) unroll = UNROLL;
+    if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8 && unroll != 16)
+        return fail(HALOS_EINVAL, "unroll = %d, must be 0 (the update kernels' own), 1, 2, 4, 8 or 16", unroll);
     if (n_read < 0 || n_read > MAX_PROBE_STREAMS || n_write < 0 || n_write > MAX_PROBE_STREAMS || n_read + n_write == 0)
         return fail(HALOS_EINVAL, "n_read = %d, n_write = %d: each 0..%d, not both 0", n_read, n_write, MAX_PROBE_STREAMS);
     if ((n_read > 0 && !read_bufs) || (n_write > 0 && !write_bufs)) return fail(HALOS_EINVAL, "NULL pointer array");
-    const uint64_t tile_bytes = (uint64_t)TILE_ELEMS * sizeof(float);
+    const uint64_t tile_bytes = (uint64_t)probe_tile_elems(unroll) * sizeof(float);
     if (bytes < tile_bytes) return fail(HALOS_EINVAL, "bytes = %llu, must be >= %llu", (unsigned long long)bytes,
                                         (unsigned long long)tile_bytes);
     if (reps < 1 || reps > 1000) return fail(HALOS_EINVAL, "reps = %d outside 1..1000", reps);
@@ -320,7 +351,7 @@ halos_status halos_probe_streams(const void *const *read_bufs, int32_t n_read, v
     shape.nontemporal = true;
     hipStream_t s = (hipStream_t)stream;
     float ms = 0.f;
-    halos_status st = time_launches(s, reps, [&] { return launch_probe_streams(s, args, n_read, n_write, (uint32_t)n_tiles64, shape); }, &ms);
+    halos_status st = time_launches(s, reps, [&] { return launch_probe_streams(s, args, n_read, n_write, unroll, (uint32_t)n_tiles64, shape); }, &ms);
     if (st != HALOS_OK) return st;
     *gbps = ms > 0.f ? (double)used * (n_read + n_write) * reps / ((double)ms * 1e-3) / 1e9 : 0.0;
     return HALOS_OK;
@@ -393,11 +424,13 @@ halos_status halos_gps_create(const halos_layout *layout, const halos_hparams *h
             return fail_hip(e, "zero-filling M");
         }
     }
+    register_handle(g);
     *out = g;
     return HALOS_OK;
 }
 
 static void gps_release(halos_gps *g) {
+    unregister_handle(g);
     (void)hipFree(g->d_tables);
     (void)hipFree(g->d_tiles);
     g->magic = 0;
@@ -405,7 +438,7 @@ static void gps_release(halos_gps *g) {
 }
 
 void halos_gps_destroy(halos_gps *g) {
-    if (!g || g->magic != GPS_MAGIC || g->retired) return;
+    if (!live_gps(g)) return;
     if (g->n_lps_attached > 0) {        // its local servers still launch with the layout tables: keep them until the last one goes
         g->retired = true;
         return;
@@ -417,7 +450,7 @@ halos_status halos_lps_create(halos_gps *g, int32_t lps_id, int32_t n_workers, v
                               void *const *acc, void *stream, halos_lps **out) {
     if (!out) return fail(HALOS_EINVAL, "out is NULL");
     *out = nullptr;
-    if (!g || g->magic != GPS_MAGIC || g->retired) return fail(HALOS_EINVAL, "gps is not a valid handle");
+    if (!live_gps(g)) return fail(HALOS_EINVAL, "gps is not a valid handle");
     if (lps_id < 0) return fail(HALOS_EINVAL, "lps_id = %d, must be >= 0", lps_id);
     if (n_workers < 1) return fail(HALOS_EINVAL, "n_workers = %d, must be >= 1", n_workers);
     halos_status st = check_device(g);
@@ -470,18 +503,19 @@ halos_status halos_lps_create(halos_gps *g, int32_t lps_id, int32_t n_workers, v
         }
     }
     g->n_lps_attached += 1;
+    register_handle(l);
     *out = l;
     return HALOS_OK;
 }
 
 void halos_lps_destroy(halos_lps *l) {
-    if (!l || l->magic != LPS_MAGIC) return;
+    if (!live_lps(l)) return;
     (void)hipFree(l->d_tables);
     if (l->d_norm_partials) (void)hipFree(l->d_norm_partials);
     halos_gps *g = l->gps;
     l->magic = 0;
     delete l;
-    if (g && g->magic == GPS_MAGIC) {
+    if (is_registered(g) && g->magic == GPS_MAGIC) {
         g->n_lps_attached -= 1;
         if (g->retired && g->n_lps_attached == 0) gps_release(g);
     }
@@ -489,7 +523,7 @@ void halos_lps_destroy(halos_lps *l) {
 
 static halos_status push_delta_impl(halos_lps *l, int32_t worker, const void *const *gptrs, halos_dtype dtype,
                                     uint32_t staleness, bool end_model) {
-    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    if (!live_lps(l)) return fail(HALOS_EINVAL, "lps is not a valid handle");
     if (dtype != HALOS_F32 && dtype != HALOS_BF16) return fail(HALOS_EINVAL, "unknown delta dtype %d", (int)dtype);
     ProtoResult pr = l->proto.can_push_delta(worker);
     if (pr == PROTO_BAD_ARG) return fail(HALOS_EINVAL, "worker %d outside 0..%d", worker, l->proto.n_workers() - 1);
@@ -530,15 +564,27 @@ halos_status halos_lps_push_end_model(halos_lps *l, int32_t worker, const void *
 }
 
 halos_status halos_lps_push_global(halos_lps *l) {
-    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    if (!live_lps(l)) return fail(HALOS_EINVAL, "lps is not a valid handle");
     if (l->proto.can_push_global() != PROTO_OK)
         return fail(HALOS_ESTATE, "lps %d: no global model is on its way back (phase %d)", l->id, l->proto.phase());
     l->proto.push_global();
     return HALOS_OK;
 }
 
-halos_status halos_lps_set_worker_model(halos_lps *l, int32_t worker, void *const *model) {
-    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
+// Rewrite one pointer table of n_tensors entries in stream order (the entries travel in kernel-argument blocks).
+static halos_status store_table(hipStream_t stream, float **d_table, const void *const *host_ptrs, size_t n_tensors) {
+    for (size_t base = 0; base < n_tensors; base += MAX_ARG_TENSORS) {
+        PtrArgs args;
+        const size_t count = n_tensors - base < (size_t)MAX_ARG_TENSORS ? n_tensors - base : (size_t)MAX_ARG_TENSORS;
+        for (size_t i = 0; i < (size_t)MAX_ARG_TENSORS; ++i) args.p[i] = i < count ? host_ptrs[base + i] : nullptr;
+        hipError_t e = launch_store_pointers(stream, d_table, args, (uint32_t)base, (uint32_t)count);
+        if (e != hipSuccess) return fail_hip(e, "rewriting a pointer table");
+    }
+    return HALOS_OK;
+}
+
+halos_status halos_lps_set_worker_model(halos_lps *l, int32_t worker, void *const *model, void *stream) {
+    if (!live_lps(l)) return fail(HALOS_EINVAL, "lps is not a valid handle");
     if (worker < 0 || worker >= l->proto.n_workers())
         return fail(HALOS_EINVAL, "worker %d outside 0..%d", worker, l->proto.n_workers() - 1);
     const halos_gps *g = l->gps;
@@ -546,17 +592,21 @@ halos_status halos_lps_set_worker_model(halos_lps *l, int32_t worker, void *cons
     if (st == HALOS_OK) st = check_tensors(g, (const void *const *)model, sizeof(float), "model");
     if (st != HALOS_OK) return st;
     const size_t nt = g->numel.size();
-    hipError_t e = hipDeviceSynchronize();      // no launch that still reads the old table may be in flight
-    if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
-    e = hipMemcpy(l->d_worker_model + (size_t)worker * nt, model, nt * sizeof(void *), hipMemcpyHostToDevice);
-    if (e != hipSuccess) return fail_hip(e, "uploading the worker's pointer table");
+    // in stream order: launches already issued on the stream keep the old table, later ones see the new
+    st = store_table((hipStream_t)stream, l->d_worker_model + (size_t)worker * nt, (const void *const *)model, nt);
+    if (st != HALOS_OK) return st;
     l->worker_has_model[worker] = 1;
     return HALOS_OK;
 }
 
-static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *info, bool pull) {
-    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
+// ext_partials / ext_results: where the norm monitors of this step go instead of the server's own scratch (both null:
+// the server's own, if it has one).
+static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *info, bool pull,
+                                  double *ext_partials = nullptr, double *ext_results = nullptr) {
+    if (!live_lps(l)) return fail(HALOS_EINVAL, "lps is not a valid handle");
     halos_gps *g = l->gps;
+    double *const norm_partials = ext_partials ? ext_partials : l->d_norm_partials;
+    double *const norm_results = ext_partials ? ext_results : l->d_norm_results;
     halos_step_info out{};
     out.worker = -1;
     const QueueItem head = l->proto.head();
@@ -590,7 +640,7 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
         for (const TileRange &r : g->ranges) {
             PtrArgs args;
             fill_args(args, p.ptrs.data(), r, g->numel.size());
-            double *partials = l->d_norm_partials ? l->d_norm_partials + n_partials : nullptr;
+            double *partials = norm_partials ? norm_partials + n_partials : nullptr;
             hipError_t e;
             if (l->cycle.d() > 1) {
                 const float inv_d = 1.0f / (float)l->cycle.d();
@@ -604,8 +654,8 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
             if (e != hipSuccess) return fail_hip(e, "launching the local update");
             n_partials += launch_grid_size(r, shape);
         }
-        if (l->d_norm_partials) {
-            hipError_t e = launch_norm_finalize((hipStream_t)stream, l->d_norm_partials, n_partials, l->d_norm_results + 0);
+        if (norm_partials) {
+            hipError_t e = launch_norm_finalize((hipStream_t)stream, norm_partials, n_partials, norm_results + 0);
             if (e != hipSuccess) return fail_hip(e, "launching the norm reduction");
         }
         l->proto.commit_update();
@@ -618,14 +668,14 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
         const float keep = 1.0f - l->alpha;
         uint32_t n_partials = 0;
         for (const TileRange &r : g->ranges) {
-            double *partials = l->d_norm_partials ? l->d_norm_partials + n_partials : nullptr;
+            double *partials = norm_partials ? norm_partials + n_partials : nullptr;
             hipError_t e = launch_lps_merge((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_acc, l->alpha, keep,
                                             l->snapshot, partials, shape);
             if (e != hipSuccess) return fail_hip(e, "launching the merge");
             n_partials += launch_grid_size(r, shape);
         }
-        if (l->d_norm_partials) {
-            hipError_t e = launch_norm_finalize((hipStream_t)stream, l->d_norm_partials, n_partials, l->d_norm_results + 1);
+        if (norm_partials) {
+            hipError_t e = launch_norm_finalize((hipStream_t)stream, norm_partials, n_partials, norm_results + 1);
             if (e != hipSuccess) return fail_hip(e, "launching the norm reduction");
         }
         l->proto.commit_merge();
@@ -646,8 +696,8 @@ halos_status halos_lps_step_pull(halos_lps *l, void *stream, halos_step_info *in
 }
 
 halos_status halos_gps_merge(halos_gps *g, halos_lps *from, void *stream) {
-    if (!g || g->magic != GPS_MAGIC || g->retired) return fail(HALOS_EINVAL, "gps is not a valid handle");
-    if (!from || from->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "from is not a valid handle");
+    if (!live_gps(g)) return fail(HALOS_EINVAL, "gps is not a valid handle");
+    if (!live_lps(from)) return fail(HALOS_EINVAL, "from is not a valid handle");
     if (from->gps != g) return fail(HALOS_EINVAL, "lps %d belongs to another global server", from->id);
     if (from->proto.can_consume() != PROTO_OK)
         return fail(HALOS_ESTATE, "lps %d has no accumulated update waiting (phase %d)", from->id, from->proto.phase());
@@ -680,11 +730,11 @@ halos_status halos_pull_model(const void *server, int32_t is_gps, void *const *d
     halos_lps *l = nullptr;
     if (is_gps) {
         g = static_cast<const halos_gps *>(server);
-        if (g->magic != GPS_MAGIC || g->retired) return fail(HALOS_EINVAL, "server is not a valid gps handle");
+        if (!live_gps(g)) return fail(HALOS_EINVAL, "server is not a valid gps handle");
         src = g->d_Theta;
     } else {
         l = const_cast<halos_lps *>(static_cast<const halos_lps *>(server));
-        if (l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "server is not a valid lps handle");
+        if (!live_lps(l)) return fail(HALOS_EINVAL, "server is not a valid lps handle");
         g = l->gps;
         src = l->d_theta;
     }
@@ -714,12 +764,12 @@ halos_status halos_set_hparams(void *server, int32_t is_gps, const halos_hparams
     if (st != HALOS_OK) return st;
     if (is_gps) {
         halos_gps *g = static_cast<halos_gps *>(server);
-        if (g->magic != GPS_MAGIC || g->retired) return fail(HALOS_EINVAL, "server is not a valid gps handle");
+        if (!live_gps(g)) return fail(HALOS_EINVAL, "server is not a valid gps handle");
         g->rule = hp->global;
         g->hp.global = hp->global;
     } else {
         halos_lps *l = static_cast<halos_lps *>(server);
-        if (l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "server is not a valid lps handle");
+        if (!live_lps(l)) return fail(HALOS_EINVAL, "server is not a valid lps handle");
         l->rule = hp->local;
         l->alpha = hp->alpha;
         l->proto.set_K(hp->K);
@@ -728,14 +778,14 @@ halos_status halos_set_hparams(void *server, int32_t is_gps, const halos_hparams
 }
 
 halos_status halos_lps_set_threshold(halos_lps *l, int32_t K) {
-    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    if (!live_lps(l)) return fail(HALOS_EINVAL, "lps is not a valid handle");
     if (l->proto.set_K(K) != PROTO_OK) return fail(HALOS_EINVAL, "K = %d, must be >= 1", K);
     return HALOS_OK;
 }
 
 halos_status halos_lps_get_counters(const halos_lps *l, int64_t *t, int64_t *t_last, int32_t *phase, int32_t *queued,
                                     uint32_t *max_staleness) {
-    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    if (!live_lps(l)) return fail(HALOS_EINVAL, "lps is not a valid handle");
     if (t) *t = l->proto.t();
     if (t_last) *t_last = l->proto.t_last();
     if (phase) *phase = l->proto.phase();
@@ -745,7 +795,7 @@ halos_status halos_lps_get_counters(const halos_lps *l, int64_t *t, int64_t *t_l
 }
 
 halos_status halos_lps_get_norms(const halos_lps *l, void *stream, double *out) {
-    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    if (!live_lps(l)) return fail(HALOS_EINVAL, "lps is not a valid handle");
     if (!out) return fail(HALOS_EINVAL, "out is NULL");
     if (!l->d_norm_results) return fail(HALOS_ESTATE, "lps %d was created without HALOS_FLAG_NORMS", l->id);
     hipError_t e = hipMemcpyAsync(out, l->d_norm_results, 2 * sizeof(double), hipMemcpyDeviceToHost, (hipStream_t)stream);
@@ -756,7 +806,7 @@ halos_status halos_lps_get_norms(const halos_lps *l, void *stream, double *out) 
 
 // Shared by both tiers: check, wait for the device, store the buffer's pointers in the server's table slot.
 static halos_status set_momentum_delay(const halos_gps *g, MomentumCycle &cycle, float **d_slot, int32_t d,
-                                       void *const *buffer, const char *who) {
+                                       void *const *buffer, void *stream, const char *who) {
     if (d < 1) return fail(HALOS_EINVAL, "d = %d, must be >= 1", d);
     if (cycle.seen() != 0)
         return fail(HALOS_ESTATE, "%s is %d updates into a cycle of %d: the delay can change only between cycles", who,
@@ -765,42 +815,39 @@ static halos_status set_momentum_delay(const halos_gps *g, MomentumCycle &cycle,
         halos_status st = check_device(g);
         if (st == HALOS_OK) st = check_tensors(g, (const void *const *)buffer, sizeof(float), "buffer");
         if (st != HALOS_OK) return st;
-        const size_t nt = g->numel.size();
-        hipError_t e = hipDeviceSynchronize();      // no launch that still reads the old table may be in flight
-        if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
-        e = hipMemcpy(d_slot, buffer, nt * sizeof(void *), hipMemcpyHostToDevice);
-        if (e != hipSuccess) return fail_hip(e, "uploading the buffer's pointer table");
+        st = store_table((hipStream_t)stream, d_slot, (const void *const *)buffer, g->numel.size());
+        if (st != HALOS_OK) return st;
     }
     cycle.set_d(d);
     return HALOS_OK;
 }
 
-halos_status halos_lps_set_momentum_delay(halos_lps *l, int32_t d, void *const *buffer) {
-    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
-    return set_momentum_delay(l->gps, l->cycle, l->d_buffer, d, buffer, "the local server");
+halos_status halos_lps_set_momentum_delay(halos_lps *l, int32_t d, void *const *buffer, void *stream) {
+    if (!live_lps(l)) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    return set_momentum_delay(l->gps, l->cycle, l->d_buffer, d, buffer, stream, "the local server");
 }
 
-halos_status halos_gps_set_momentum_delay(halos_gps *g, int32_t d, void *const *buffer) {
-    if (!g || g->magic != GPS_MAGIC || g->retired) return fail(HALOS_EINVAL, "gps is not a valid handle");
-    return set_momentum_delay(g, g->cycle, g->d_buffer, d, buffer, "the global server");
+halos_status halos_gps_set_momentum_delay(halos_gps *g, int32_t d, void *const *buffer, void *stream) {
+    if (!live_gps(g)) return fail(HALOS_EINVAL, "gps is not a valid handle");
+    return set_momentum_delay(g, g->cycle, g->d_buffer, d, buffer, stream, "the global server");
 }
 
 halos_status halos_lps_get_momentum_delay(const halos_lps *l, int32_t *d, int32_t *seen) {
-    if (!l || l->magic != LPS_MAGIC) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    if (!live_lps(l)) return fail(HALOS_EINVAL, "lps is not a valid handle");
     if (d) *d = l->cycle.d();
     if (seen) *seen = l->cycle.seen();
     return HALOS_OK;
 }
 
 halos_status halos_gps_get_momentum_delay(const halos_gps *g, int32_t *d, int32_t *seen) {
-    if (!g || g->magic != GPS_MAGIC || g->retired) return fail(HALOS_EINVAL, "gps is not a valid handle");
+    if (!live_gps(g)) return fail(HALOS_EINVAL, "gps is not a valid handle");
     if (d) *d = g->cycle.d();
     if (seen) *seen = g->cycle.seen();
     return HALOS_OK;
 }
 
 halos_status halos_gps_get_counters(const halos_gps *g, int64_t *updates) {
-    if (!g || g->magic != GPS_MAGIC || g->retired) return fail(HALOS_EINVAL, "gps is not a valid handle");
+    if (!live_gps(g)) return fail(HALOS_EINVAL, "gps is not a valid handle");
     if (updates) *updates = g->updates;
     return HALOS_OK;
 }

@@ -646,30 +646,37 @@ probe_pair_kernel(float *a, float *b, uint32_t n_tiles) {
     }
 }
 
+__global__ void __launch_bounds__(BLOCK_THREADS)
+store_pointers_kernel(float **table, PtrArgs src, uint32_t first, uint32_t count) {
+    for (uint32_t i = threadIdx.x; i < count; i += BLOCK_THREADS)
+        table[first + i] = static_cast<float *>(const_cast<void *>(src.p[i]));
+}
+
 // Streaming probe: read NR buffers and write NW others, tile by tile with the access pattern of the update kernels
-// (UNROLL 128-bit non-temporal accesses per thread and stream, all loads of a tile issued before anything else).
+// (UNR 128-bit non-temporal accesses per thread and stream, all loads of a tile issued before anything else).
 // No arithmetic; loaded values are only "used" by an empty asm statement so the loads stay, stores write `fill`.
-template <int NR, int NW>
+template <int NR, int NW, int UNR>
 __global__ void __launch_bounds__(BLOCK_THREADS)
 probe_streams_kernel(ProbeArgs a, uint32_t n_tiles, float fill) {
     const uint32_t tid = threadIdx.x;
     const f32x4 fv = {fill, fill, fill, fill};
+    constexpr size_t TILE = (size_t)BLOCK_THREADS * VEC * UNR;
     for (uint32_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-        const size_t base = static_cast<size_t>(t) * TILE_ELEMS;
-        f32x4 v[NR > 0 ? NR : 1][UNROLL];
+        const size_t base = static_cast<size_t>(t) * TILE;
+        f32x4 v[NR > 0 ? NR : 1][UNR];
 #pragma unroll
         for (int r = 0; r < NR; ++r)
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u)
+            for (int u = 0; u < UNR; ++u)
                 v[r][u] = ld4<true>(to_global(a.rd[r]) + base + (u * BLOCK_THREADS + tid) * VEC);
 #pragma unroll
         for (int r = 0; r < NR; ++r)
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) asm volatile("" : : "v"(v[r][u]));
+            for (int u = 0; u < UNR; ++u) asm volatile("" : : "v"(v[r][u]));
 #pragma unroll
         for (int w = 0; w < NW; ++w)
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u)
+            for (int u = 0; u < UNR; ++u)
                 st4<true>(to_global(a.wr[w]) + base + (u * BLOCK_THREADS + tid) * VEC, fv);
     }
 }
@@ -820,6 +827,13 @@ hipError_t launch_pull(hipStream_t stream, const Tile *tiles, TileRange r, float
     return hipGetLastError();
 }
 
+hipError_t launch_store_pointers(hipStream_t stream, float **table, const PtrArgs &src, uint32_t first, uint32_t count) {
+    if (count == 0) return hipSuccess;
+    if (count > (uint32_t)MAX_ARG_TENSORS) return hipErrorInvalidValue;
+    store_pointers_kernel<<<dim3(1), dim3(BLOCK_THREADS), 0, stream>>>(table, src, first, count);
+    return hipGetLastError();
+}
+
 hipError_t launch_init(hipStream_t stream, const Tile *tiles, TileRange r, float *const *src, float *const *theta,
                        float *const *m, float *const *acc, bool snapshot, LaunchShape shape) {
     if (r.hi <= r.lo) return hipSuccess;
@@ -835,31 +849,45 @@ hipError_t launch_probe_pair(hipStream_t stream, float *a, float *b, uint32_t n_
     return hipGetLastError();
 }
 
-hipError_t launch_probe_streams(hipStream_t stream, const ProbeArgs &a, int n_read, int n_write, uint32_t n_tiles,
-                                LaunchShape shape) {
+namespace {
+template <int NR, int NW>
+void probe_dispatch_unroll(hipStream_t stream, dim3 grid, const ProbeArgs &a, int unroll, uint32_t n_tiles) {
+    const dim3 block(BLOCK_THREADS);
+    switch (unroll) {
+        case 1: probe_streams_kernel<NR, NW, 1><<<grid, block, 0, stream>>>(a, n_tiles, 0.0f); break;
+        case 2: probe_streams_kernel<NR, NW, 2><<<grid, block, 0, stream>>>(a, n_tiles, 0.0f); break;
+        case 4: probe_streams_kernel<NR, NW, 4><<<grid, block, 0, stream>>>(a, n_tiles, 0.0f); break;
+        case 8: probe_streams_kernel<NR, NW, 8><<<grid, block, 0, stream>>>(a, n_tiles, 0.0f); break;
+        default: probe_streams_kernel<NR, NW, 16><<<grid, block, 0, stream>>>(a, n_tiles, 0.0f); break;
+    }
+}
+template <int NR>
+void probe_dispatch_writes(hipStream_t stream, dim3 grid, const ProbeArgs &a, int n_write, int unroll, uint32_t n_tiles) {
+    switch (n_write) {
+        case 0: if constexpr (NR > 0) probe_dispatch_unroll<NR, 0>(stream, grid, a, unroll, n_tiles); break;
+        case 1: probe_dispatch_unroll<NR, 1>(stream, grid, a, unroll, n_tiles); break;
+        case 2: probe_dispatch_unroll<NR, 2>(stream, grid, a, unroll, n_tiles); break;
+        case 3: probe_dispatch_unroll<NR, 3>(stream, grid, a, unroll, n_tiles); break;
+        default: probe_dispatch_unroll<NR, 4>(stream, grid, a, unroll, n_tiles); break;
+    }
+}
+}  // namespace
+
+hipError_t launch_probe_streams(hipStream_t stream, const ProbeArgs &a, int n_read, int n_write, int unroll,
+                                uint32_t n_tiles, LaunchShape shape) {
     if (n_tiles == 0) return hipSuccess;
     if (n_read < 0 || n_read > MAX_PROBE_STREAMS || n_write < 0 || n_write > MAX_PROBE_STREAMS || n_read + n_write == 0)
         return hipErrorInvalidValue;
+    if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8 && unroll != 16) return hipErrorInvalidValue;
     const uint32_t cap = shape.grid_cap > 0 ? (uint32_t)shape.grid_cap : 1u;
-    const dim3 grid(n_tiles < cap ? n_tiles : cap), block(BLOCK_THREADS);
-#define HALOS_PROBE(NR, NW) probe_streams_kernel<NR, NW><<<grid, block, 0, stream>>>(a, n_tiles, 0.0f)
-#define HALOS_PROBE_W(NR)                            \
-    switch (n_write) {                               \
-        case 0: HALOS_PROBE(NR, 0); break;           \
-        case 1: HALOS_PROBE(NR, 1); break;           \
-        case 2: HALOS_PROBE(NR, 2); break;           \
-        case 3: HALOS_PROBE(NR, 3); break;           \
-        default: HALOS_PROBE(NR, 4); break;          \
-    }
+    const dim3 grid(n_tiles < cap ? n_tiles : cap);
     switch (n_read) {
-        case 0: HALOS_PROBE_W(0); break;
-        case 1: HALOS_PROBE_W(1); break;
-        case 2: HALOS_PROBE_W(2); break;
-        case 3: HALOS_PROBE_W(3); break;
-        default: HALOS_PROBE_W(4); break;
+        case 0: probe_dispatch_writes<0>(stream, grid, a, n_write, unroll, n_tiles); break;
+        case 1: probe_dispatch_writes<1>(stream, grid, a, n_write, unroll, n_tiles); break;
+        case 2: probe_dispatch_writes<2>(stream, grid, a, n_write, unroll, n_tiles); break;
+        case 3: probe_dispatch_writes<3>(stream, grid, a, n_write, unroll, n_tiles); break;
+        default: probe_dispatch_writes<4>(stream, grid, a, n_write, unroll, n_tiles); break;
     }
-#undef HALOS_PROBE_W
-#undef HALOS_PROBE
     return hipGetLastError();
 }
 

@@ -12,7 +12,10 @@ namespace halos {
 // in device memory; a persistent grid walks it with a grid stride.
 constexpr int BLOCK_THREADS = 256;      // 4 wavefronts of 64
 constexpr int VEC = 4;                  // fp32 elements per 128-bit access
-constexpr int UNROLL = 4;               // 128-bit accesses per thread per stream and tile
+#ifndef HALOS_UNROLL
+#define HALOS_UNROLL 4                  // compile-time knob, for measuring other tile sizes (2, 8, 16)
+#endif
+constexpr int UNROLL = HALOS_UNROLL;    // 128-bit accesses per thread per stream and tile
 constexpr int TILE_ELEMS = BLOCK_THREADS * VEC * UNROLL;   // 4096
 
 struct Tile {
@@ -86,6 +89,10 @@ hipError_t launch_lps_merge(hipStream_t stream, const Tile *tiles, TileRange r, 
                             float *const *inbox, float alpha, float keep, bool snapshot, double *norm_partials,
                             LaunchShape shape);
 
+// table[first + i] <- src.p[i] for i < count (count <= MAX_ARG_TENSORS): rewrites part of a device pointer table in
+// stream order, so that launches issued earlier on the stream still see the old entries and later ones the new.
+hipError_t launch_store_pointers(hipStream_t stream, float **table, const PtrArgs &src, uint32_t first, uint32_t count);
+
 // dst <- src (fp32), dst pointers in the argument block.
 hipError_t launch_pull(hipStream_t stream, const Tile *tiles, TileRange r, float *const *src, const PtrArgs &dst,
                        LaunchShape shape);
@@ -98,14 +105,17 @@ hipError_t launch_init(hipStream_t stream, const Tile *tiles, TileRange r, float
 // Sweep the first n_tiles * TILE_ELEMS floats of two buffers (read both, write both back unchanged).
 hipError_t launch_probe_pair(hipStream_t stream, float *a, float *b, uint32_t n_tiles, LaunchShape shape);
 
-// Read n_read buffers and write zeros to n_write others (first n_tiles * TILE_ELEMS floats of each), with the access
-// pattern of the update kernels and no arithmetic: what the memory system delivers for that mix of streams.
+// Read n_read buffers and write zeros to n_write others, with the access pattern of the update kernels and no
+// arithmetic: what the memory system delivers for that mix of streams.  `unroll` (1, 2, 4, 8 or 16) is the number of
+// 128-bit accesses per thread, stream and tile: a probe tile is BLOCK_THREADS * VEC * unroll floats (probe_tile_elems),
+// and the first n_tiles of them are swept in every buffer.
 constexpr int MAX_PROBE_STREAMS = 4;
 struct ProbeArgs {
     const float *rd[MAX_PROBE_STREAMS];
     float *wr[MAX_PROBE_STREAMS];
 };
-hipError_t launch_probe_streams(hipStream_t stream, const ProbeArgs &a, int n_read, int n_write, uint32_t n_tiles,
-                                LaunchShape shape);
+constexpr uint32_t probe_tile_elems(int unroll) { return (uint32_t)(BLOCK_THREADS * VEC * unroll); }
+hipError_t launch_probe_streams(hipStream_t stream, const ProbeArgs &a, int n_read, int n_write, int unroll,
+                                uint32_t n_tiles, LaunchShape shape);
 
 }  // namespace halos

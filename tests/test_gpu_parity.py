@@ -149,7 +149,7 @@ def test_launch_shapes_give_identical_results():
             finally:
                 c.close()
     finally:
-        B.halos_set_launch_config(8, 1)
+        B.halos_set_launch_config(1, 1)             # back to the defaults
     for r in results[1:]:
         for k in results[0]:
             assert np.array_equal(results[0][k].view(np.uint32), r[k].view(np.uint32)), k
