@@ -266,6 +266,27 @@ halos_status halos_lps_get_counters(const halos_lps *lps, int64_t *t, int64_t *t
  */
 halos_status halos_lps_get_norms(const halos_lps *lps, void *stream, double *out);
 
+/*
+ * halos_lps_step for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid it) and still want the monitors of HALOS_FLAG_NORMS: works on ANY local server, with
+ * or without that flag, and never calls hipMalloc / hipFree.  The per-workgroup partial sums go to a fixed array in
+ * the library's device image (one copy per GPU, 16384 doubles = 128 KiB, held until the process ends) instead of a
+ * buffer owned by the server.
+ *   norms_out  device pointer, 8-byte aligned, to two doubles owned by the caller: a step that applies a worker
+ *              delta writes the sum of g^2 to norms_out[0], a step that merges a global model writes the sum of
+ *              (theta - Theta_i)^2 before the merge to norms_out[1]; the other element is left as it is, and an empty
+ *              queue writes nothing.  Written on `stream`; same values, bit for bit, as halos_lps_get_norms reports
+ *              after halos_lps_step on a server created under the flag.
+ * Everything else (state, counters, `info`, errors) is exactly halos_lps_step.  The server's own monitors, if it has
+ * any, are not updated by this call.
+ * Limit: one partial sum per workgroup per launch, i.e. blocks_per_cu x compute units per 384 tensors of the
+ * layout; EINVAL (nothing modified) if that exceeds 16384.  With the default launch shape (one workgroup per compute
+ * unit) a layout of up to 24,576 tensors fits on a 256-unit device.
+ * Every call on a GPU shares that GPU's array: calls that may run concurrently on one GPU (different streams, different
+ * servers) race on it and give wrong NORMS (state is unaffected); issue them on one stream or order the streams.
+ */
+halos_status halos_lps_step_norms(halos_lps *lps, void *stream, halos_step_info *info, double *norms_out);
+
 /* Number of accumulated updates the GPS has applied (the index i of Algorithm 1's GPS loop). */
 halos_status halos_gps_get_counters(const halos_gps *gps, int64_t *updates);
 

@@ -81,6 +81,7 @@ def load_library():
         "halos_lps_push_global": [vp],
         "halos_lps_step": [vp, vp, P(StepInfo)],
         "halos_lps_step_pull": [vp, vp, P(StepInfo)],
+        "halos_lps_step_norms": [vp, vp, P(StepInfo), vp],
         "halos_lps_set_worker_model": [vp, i32, P(vp), vp],
         "halos_gps_merge": [vp, vp, vp],
         "halos_pull_model": [vp, i32, P(vp), vp],
@@ -189,6 +190,14 @@ def halos_lps_step(lps: int, stream=None) -> StepInfo:
 def halos_lps_step_pull(lps: int, stream=None) -> StepInfo:
     info = StepInfo()
     _check(load_library().halos_lps_step_pull(lps, _stream(stream), ctypes.byref(info)))
+    return info
+
+
+def halos_lps_step_norms(lps: int, norms_out, stream=None) -> StepInfo:
+    """norms_out: a torch CUDA tensor of two float64 (or a raw device address)."""
+    info = StepInfo()
+    p = norms_out if isinstance(norms_out, int) else norms_out.data_ptr()
+    _check(load_library().halos_lps_step_norms(lps, _stream(stream), ctypes.byref(info), p))
     return info
 
 

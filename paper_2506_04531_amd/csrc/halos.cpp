@@ -134,6 +134,7 @@ struct halos_lps {
     std::vector<std::vector<const void *>> validated;   // per worker: last pointer set whose ranges were checked
     std::vector<halos_dtype> validated_dtype;
     std::vector<const void *> validated_pull;
+    const void *validated_norm_out = nullptr;    // last device pointer accepted by halos_lps_step_norms
     uint32_t max_staleness = 0;
     halos_lps(int32_t n_workers, int32_t K) : proto(n_workers, K) {}
 };
@@ -693,6 +694,42 @@ halos_status halos_lps_step(halos_lps *l, void *stream, halos_step_info *info) {
 
 halos_status halos_lps_step_pull(halos_lps *l, void *stream, halos_step_info *info) {
     return lps_step_impl(l, stream, info, true);
+}
+
+halos_status halos_lps_step_norms(halos_lps *l, void *stream, halos_step_info *info, double *norms_out) {
+    if (!live_lps(l)) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    if (!norms_out) return fail(HALOS_EINVAL, "norms_out is NULL");
+    if ((reinterpret_cast<uintptr_t>(norms_out) & 7u) != 0) return fail(HALOS_EINVAL, "norms_out is not 8-byte aligned");
+    const halos_gps *g = l->gps;
+    halos_status st = check_device(g);
+    if (st != HALOS_OK) return st;
+    if (l->validated_norm_out != norms_out) {
+        hipPointerAttribute_t attr;
+        hipError_t e = hipPointerGetAttributes(&attr, norms_out);
+        if (e != hipSuccess || (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged)) {
+            (void)hipGetLastError();
+            return fail(HALOS_EINVAL, "norms_out is not a device pointer");
+        }
+        hipDeviceptr_t base = nullptr;
+        size_t size = 0;
+        e = hipMemGetAddressRange(&base, &size, norms_out);
+        if (e != hipSuccess) { (void)hipGetLastError(); return fail(HALOS_EINVAL, "norms_out: cannot query its allocation"); }
+        if (reinterpret_cast<uintptr_t>(norms_out) + 2 * sizeof(double) > reinterpret_cast<uintptr_t>(base) + size)
+            return fail(HALOS_EINVAL, "norms_out has no room for two doubles");
+        l->validated_norm_out = norms_out;
+    }
+    // one partial sum per workgroup of every launch of the step: they must fit the fixed array
+    const LaunchShape shape = current_shape(g);
+    uint64_t need = 0;
+    for (const TileRange &r : g->ranges) need += launch_grid_size(r, shape);
+    if (need > STATIC_SCRATCH_DOUBLES)
+        return fail(HALOS_EINVAL, "this layout and launch shape need %llu partial sums; the fixed scratch array holds %u "
+                    "(lower blocks_per_cu, or use a server created under HALOS_FLAG_NORMS)", (unsigned long long)need,
+                    STATIC_SCRATCH_DOUBLES);
+    double *partials = nullptr;
+    hipError_t e = static_scratch(&partials);
+    if (e != hipSuccess) return fail_hip(e, "locating the fixed scratch array");
+    return lps_step_impl(l, stream, info, false, partials, norms_out);
 }
 
 halos_status halos_gps_merge(halos_gps *g, halos_lps *from, void *stream) {

@@ -14,6 +14,8 @@
 //                       m1 = fma(beta, m, b1 * (1/d));  s = eta * fma(beta, m1, gp)
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "kernels.hpp"
 
 namespace halos {
@@ -681,6 +683,10 @@ probe_streams_kernel(ProbeArgs a, uint32_t n_tiles, float fill) {
     }
 }
 
+// Partial sums of the norm monitors for the entry point that allocates nothing.  In host code this name is only a
+// handle for hipGetSymbolAddress; kernels receive the address that call returns.
+static __device__ __align__(256) double scratch[STATIC_SCRATCH_DOUBLES];
+
 inline dim3 grid_for(TileRange r, LaunchShape shape) {
     uint32_t n = r.hi - r.lo;
     uint32_t cap = shape.grid_cap > 0 ? (uint32_t)shape.grid_cap : 1u;
@@ -688,6 +694,27 @@ inline dim3 grid_for(TileRange r, LaunchShape shape) {
 }
 
 }  // namespace
+
+hipError_t static_scratch(double **ptr) {
+    constexpr int MAX_DEVICES = 64;
+    static std::atomic<double *> per_device[MAX_DEVICES];      // zero-initialised: "not looked up yet"
+    *ptr = nullptr;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    double *p = per_device[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void *sym = nullptr;
+        e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));     // this device's copy of the array
+        if (e != hipSuccess) return e;
+        if (!sym) return hipErrorInvalidSymbol;
+        p = static_cast<double *>(sym);
+        per_device[dev].store(p, std::memory_order_release);
+    }
+    *ptr = p;
+    return hipSuccess;
+}
 
 uint32_t launch_grid_size(TileRange r, LaunchShape shape) { return r.hi > r.lo ? grid_for(r, shape).x : 0u; }
 

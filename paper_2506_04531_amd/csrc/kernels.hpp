@@ -93,6 +93,12 @@ hipError_t launch_lps_merge(hipStream_t stream, const Tile *tiles, TileRange r, 
 // stream order, so that launches issued earlier on the stream still see the old entries and later ones the new.
 hipError_t launch_store_pointers(hipStream_t stream, float **table, const PtrArgs &src, uint32_t first, uint32_t count);
 
+// Per-workgroup partial sums for callers that may not allocate: a fixed array in the library's device image, one copy
+// per GPU, STATIC_SCRATCH_DOUBLES doubles long.  *ptr receives its address on the CURRENT device (looked up once per
+// device and remembered).  Whatever an earlier launch left there stays there; launches that use it must not overlap.
+constexpr uint32_t STATIC_SCRATCH_DOUBLES = 16384;      // 128 KiB
+hipError_t static_scratch(double **ptr);
+
 // dst <- src (fp32), dst pointers in the argument block.
 hipError_t launch_pull(hipStream_t stream, const Tile *tiles, TileRange r, float *const *src, const PtrArgs &dst,
                        LaunchShape shape);
