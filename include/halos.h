@@ -16,7 +16,7 @@
  *                n_tensors device pointers, one per tensor of the layout.
  *   Layout       tensor i is a contiguous array of numel[i] elements; every
  *                non-empty tensor's base address must be 16-byte aligned.
- *                Server state is fp32.  Worker deltas are fp32 or bfloat16 (or
+ *                Server state is fp32.  Worker deltas are fp32, bfloat16 or IEEE half (or
  *                arrive as the worker's fp32 end model, halos_lps_push_end_model).
  *   Ownership    all parameter-sized buffers are allocated by the caller and
  *                only BORROWED: state buffers for the life of the handle, a
@@ -69,7 +69,9 @@ typedef enum {
     HALOS_EHIP = 4      /* the HIP runtime reported an error */
 } halos_status;
 
-typedef enum { HALOS_F32 = 0, HALOS_BF16 = 1 } halos_dtype;
+/* Element type of a worker delta.  bfloat16 and IEEE half (the paper's workers train in fp16, Sec. 5.1) are upcast
+ * exactly inside the update pass. */
+typedef enum { HALOS_F32 = 0, HALOS_BF16 = 1, HALOS_F16 = 2 } halos_dtype;
 
 /* Tensor list.  numel is a host array, copied by the create call. */
 typedef struct {
@@ -87,6 +89,9 @@ typedef struct {
     float beta;
     float cg;
 } halos_rule;
+
+/* The paper's rule for a rate and a momentum coefficient: cg = 1 - beta, formed in fp32 (App. E). */
+halos_rule halos_paper_rule(float eta, float beta);
 
 /* Hyper-parameters of Algorithm 1 (its REQUIRE line). */
 typedef struct {
@@ -113,6 +118,18 @@ typedef struct {
  * accumulated update, against 1e-7 for the running sum.  Honoured at halos_gps_create. */
 #define HALOS_FLAG_SNAPSHOT 2u
 
+/* The global server keeps no momentum: beta_g = 0, the setting the paper uses for non-i.i.d. data (Sec. 5.4).  `M` of
+ * halos_gps_create may be NULL and is never touched; a GPS update moves 16 bytes per parameter instead of 24 and gives
+ * the model the general rule gives at beta = 0 (up to the sign of an exact zero).  global.beta must be 0 and stay 0;
+ * halos_gps_push_update and a momentum delay are refused (ESTATE).  Honoured at halos_gps_create. */
+#define HALOS_FLAG_GPS_NO_MOMENTUM 4u
+
+/* Merges do not clear the third buffer (12 bytes per parameter instead of 16): the returned global model stays there
+ * and the first update that accumulates afterwards overwrites it with 0 + its step instead of adding to it (4 bytes
+ * less, once per accumulation).  Every result is the same, bit for bit; only the buffer's contents between a merge
+ * and the next update are unspecified (logically zero).  Not with HALOS_FLAG_SNAPSHOT.  Honoured at halos_gps_create. */
+#define HALOS_FLAG_DEFER_CLEAR 8u
+
 /* What one halos_lps_step did. */
 typedef struct {
     int32_t kind;         /* 0 queue was empty, 1 applied a worker delta, 2 merged a global model */
@@ -137,7 +154,7 @@ enum {
  *   layout   tensor list (copied).  Tensors with numel 0 are allowed and skipped.
  *   hp       hyper-parameters (copied); hp->global is the GPS rule.
  *   Theta    device tensors holding the initial model Theta_0 (read and later updated in place).
- *   M        device tensors for the GPS momentum; zero-filled on `stream` by this call.
+ *   M        device tensors for the GPS momentum; zero-filled on `stream` by this call (NULL under HALOS_FLAG_GPS_NO_MOMENTUM).
  * Errors: EINVAL (null/misaligned pointers, n_tensors < 1, negative numel, more than 2^32-1 elements
  * in one tensor, non-finite or out-of-range hyper-parameters), ENOMEM, EHIP.
  */
@@ -169,6 +186,16 @@ halos_status halos_lps_create(halos_gps *gps, int32_t lps_id, int32_t n_workers,
  */
 halos_status halos_lps_push_update(halos_lps *lps, int32_t worker, const void *const *g,
                                    halos_dtype dtype, uint32_t staleness);
+
+/*
+ * The same arrival with a scalar weight on the delta: the server applies ModelUpdate to weight * g (one fp32 product per
+ * element inside the pass; weight = 1 is halos_lps_push_update exactly).  This is the hook for staleness-scaled
+ * updates, the rule of the asynchronous-federated baseline in the paper's ablation (Sec. 5.2); the paper names only the
+ * exponent of that method's polynomial, so the weight's formula is the caller's.  HALoS itself uses weight 1.
+ *   weight   finite (EINVAL otherwise); the |g|^2 monitor sees the weighted delta
+ */
+halos_status halos_lps_push_update_weighted(halos_lps *lps, int32_t worker, const void *const *g, halos_dtype dtype,
+                                            uint32_t staleness, float weight);
 
 /*
  * The same arrival with the worker's END model theta_{t,H} in place of its delta: the subtraction of Algorithm 1's
@@ -230,6 +257,17 @@ halos_status halos_lps_step_pull(halos_lps *lps, void *stream, halos_step_info *
  * ESTATE unless `from` has a frozen update waiting (delta_ready was reported and not yet consumed).
  */
 halos_status halos_gps_merge(halos_gps *gps, halos_lps *from, void *stream);
+
+/*
+ * Single tier: the global server applies a worker's delta itself, Theta <- ModelUpdate(Theta, weight * g, eta_g, beta_g),
+ * with its own momentum (and its delayed-momentum cycle, if one is set): the server of the single-level asynchronous
+ * baseline that the paper compares with (Sec. 2; App. D lists its hyper-parameters).  One fused pass, 20 bytes per
+ * parameter for an fp32 delta (18 for a 16-bit one); nothing is sent back -- workers read the model with
+ * halos_pull_model.  Counts as one update of the GPS.  Local servers attached to the same GPS are unaffected.
+ *   g, dtype   as for halos_lps_push_update; borrowed until the pass has finished on `stream`
+ * ESTATE under HALOS_FLAG_GPS_NO_MOMENTUM; EINVAL as for halos_lps_push_update.
+ */
+halos_status halos_gps_push_update(halos_gps *gps, const void *const *g, halos_dtype dtype, float weight, void *stream);
 
 /*
  * Copy a server's current model into caller tensors ("Schedule the worker theta_t" in Algorithm 1's LPS block; also

@@ -14,9 +14,11 @@ from typing import Optional, Sequence
 import numpy as np
 
 OK, EINVAL, ESTATE, ENOMEM, EHIP = 0, 1, 2, 3, 4
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 FLAG_NORMS = 1
 FLAG_SNAPSHOT = 2
+FLAG_GPS_NO_MOMENTUM = 4
+FLAG_DEFER_CLEAR = 8
 PHASE_ACCUMULATING, PHASE_SENT, PHASE_RETURNING, PHASE_QUEUED = 0, 1, 2, 3
 
 
@@ -47,11 +49,12 @@ class HalosError(RuntimeError):
 
 def paper_hparams(eta_l: float, beta_l: float, eta_g: float, beta_g: float, alpha: float, K: int,
                   cg_l: Optional[float] = None, cg_g: Optional[float] = None, flags: int = 0) -> HParams:
-    """Hyper-parameter block with the paper's coefficient cg = 1 - beta (formed in fp32) unless given."""
+    """Hyper-parameter block with the paper's coefficient cg = 1 - beta (halos_paper_rule) unless given."""
     f = np.float32
+    lib = load_library()
     hp = HParams()
-    hp.local = Rule(f(eta_l), f(beta_l), f(f(1) - f(beta_l)) if cg_l is None else f(cg_l))
-    hp.glob = Rule(f(eta_g), f(beta_g), f(f(1) - f(beta_g)) if cg_g is None else f(cg_g))
+    hp.local = lib.halos_paper_rule(f(eta_l), f(beta_l)) if cg_l is None else Rule(f(eta_l), f(beta_l), f(cg_l))
+    hp.glob = lib.halos_paper_rule(f(eta_g), f(beta_g)) if cg_g is None else Rule(f(eta_g), f(beta_g), f(cg_g))
     hp.alpha = f(alpha)
     hp.K = int(K)
     hp.flags = int(flags)
@@ -77,6 +80,8 @@ def load_library():
         "halos_gps_create": [P(_Layout), P(HParams), P(vp), P(vp), vp, P(vp)],
         "halos_lps_create": [vp, i32, i32, P(vp), P(vp), P(vp), vp, P(vp)],
         "halos_lps_push_update": [vp, i32, P(vp), i32, u32],
+        "halos_lps_push_update_weighted": [vp, i32, P(vp), i32, u32, ctypes.c_float],
+        "halos_gps_push_update": [vp, P(vp), i32, ctypes.c_float, vp],
         "halos_lps_push_end_model": [vp, i32, P(vp), u32],
         "halos_lps_push_global": [vp],
         "halos_lps_step": [vp, vp, P(StepInfo)],
@@ -111,6 +116,8 @@ def load_library():
     lib.halos_gps_destroy.restype = None
     lib.halos_arena_destroy.argtypes = [vp]
     lib.halos_arena_destroy.restype = None
+    lib.halos_paper_rule.argtypes = [ctypes.c_float, ctypes.c_float]
+    lib.halos_paper_rule.restype = Rule
     lib.halos_last_error.argtypes = []
     lib.halos_last_error.restype = ctypes.c_char_p
     _lib = lib
@@ -171,6 +178,14 @@ def halos_lps_create(gps: int, lps_id: int, n_workers: int, theta, m, acc, strea
 
 def halos_lps_push_update(lps: int, worker: int, g, dtype: int, staleness: int = 0) -> None:
     _check(load_library().halos_lps_push_update(lps, worker, _ptrs(g), dtype, staleness))
+
+
+def halos_lps_push_update_weighted(lps: int, worker: int, g, dtype: int, staleness: int, weight: float) -> None:
+    _check(load_library().halos_lps_push_update_weighted(lps, worker, _ptrs(g), dtype, staleness, weight))
+
+
+def halos_gps_push_update(gps: int, g, dtype: int, weight: float = 1.0, stream=None) -> None:
+    _check(load_library().halos_gps_push_update(gps, _ptrs(g), dtype, weight, _stream(stream)))
 
 
 def halos_lps_push_end_model(lps: int, worker: int, end_model, staleness: int = 0) -> None:

@@ -77,8 +77,12 @@ halos_status check_hparams(const halos_hparams *hp) {
     if (!rule_ok(hp->local) || !rule_ok(hp->global)) return fail(HALOS_EINVAL, "non-finite eta/beta/cg");
     if (!(hp->alpha >= 0.0f && hp->alpha <= 1.0f)) return fail(HALOS_EINVAL, "alpha %g outside [0,1]", (double)hp->alpha);
     if (hp->K < 1) return fail(HALOS_EINVAL, "K = %d, must be >= 1", hp->K);
-    if ((hp->flags & ~(uint32_t)(HALOS_FLAG_NORMS | HALOS_FLAG_SNAPSHOT)) != 0)
+    if ((hp->flags & ~(uint32_t)(HALOS_FLAG_NORMS | HALOS_FLAG_SNAPSHOT | HALOS_FLAG_GPS_NO_MOMENTUM | HALOS_FLAG_DEFER_CLEAR)) != 0)
         return fail(HALOS_EINVAL, "unknown bits in flags");
+    if ((hp->flags & HALOS_FLAG_SNAPSHOT) && (hp->flags & HALOS_FLAG_DEFER_CLEAR))
+        return fail(HALOS_EINVAL, "HALOS_FLAG_DEFER_CLEAR has no meaning under HALOS_FLAG_SNAPSHOT (the merge writes the snapshot)");
+    if ((hp->flags & HALOS_FLAG_GPS_NO_MOMENTUM) && hp->global.beta != 0.0f)
+        return fail(HALOS_EINVAL, "HALOS_FLAG_GPS_NO_MOMENTUM needs global.beta = 0, got %g", (double)hp->global.beta);
     return HALOS_OK;
 }
 
@@ -101,6 +105,9 @@ struct halos_gps {
     halos_hparams hp{};
     int64_t updates = 0;
     int n_lps_attached = 0;
+    bool no_momentum = false;          // HALOS_FLAG_GPS_NO_MOMENTUM: there is no M; beta stays 0
+    std::vector<const void *> validated_delta;   // last pointer set accepted by halos_gps_push_update
+    halos_dtype validated_delta_dtype = HALOS_F32;
     bool retired = false;              // halos_gps_destroy was called while local servers were still attached
 };
 
@@ -109,6 +116,7 @@ struct PendingDelta {
     halos_dtype dtype = HALOS_F32;
     bool end_model = false;            // ptrs hold the worker's end model, not a pseudo-gradient
     uint32_t staleness = 0;
+    float weight = 1.0f;               // the caller's scalar on this delta
 };
 
 struct halos_lps {
@@ -129,6 +137,8 @@ struct halos_lps {
     halos_rule rule{};
     float alpha = 0.f;
     bool snapshot = false;             // third buffer holds theta_{t_last}; Delta is formed by subtraction at the send
+    bool defer_clear = false;          // HALOS_FLAG_DEFER_CLEAR: merges leave the third buffer as it is ...
+    bool third_stale = false;          // ... and the next accumulating update restarts it (set by a merge, cleared by that update)
     LpsProtocol proto;
     std::vector<PendingDelta> pending;           // per worker: the delta it has queued
     std::vector<std::vector<const void *>> validated;   // per worker: last pointer set whose ranges were checked
@@ -267,6 +277,14 @@ extern "C" {
 
 const char *halos_last_error(void) { return g_last_error.c_str(); }
 
+halos_rule halos_paper_rule(float eta, float beta) {
+    halos_rule r;
+    r.eta = eta;
+    r.beta = beta;
+    r.cg = 1.0f - beta;
+    return r;
+}
+
 halos_status halos_set_launch_config(int32_t blocks_per_cu, int32_t nontemporal) {
     if (blocks_per_cu < 0 || blocks_per_cu > 64) return fail(HALOS_EINVAL, "blocks_per_cu %d outside 0..64", blocks_per_cu);
     if (nontemporal < -1 || nontemporal > 1) return fail(HALOS_EINVAL, "nontemporal %d outside -1..1", nontemporal);
@@ -383,8 +401,9 @@ halos_status halos_gps_create(const halos_layout *layout, const halos_hparams *h
     g->hp = *hp;
     g->rule = hp->global;
 
+    g->no_momentum = (hp->flags & HALOS_FLAG_GPS_NO_MOMENTUM) != 0;
     st = check_tensors(g, Theta, sizeof(float), "Theta");
-    if (st == HALOS_OK) st = check_tensors(g, M, sizeof(float), "M");
+    if (st == HALOS_OK && !g->no_momentum) st = check_tensors(g, M, sizeof(float), "M");
     if (st != HALOS_OK) { delete g; return st; }
 
     // tile table and launch ranges
@@ -412,13 +431,15 @@ halos_status halos_gps_create(const halos_layout *layout, const halos_hparams *h
         e = hipMemcpy(g->d_tiles, tiles.data(), tiles.size() * sizeof(Tile), hipMemcpyHostToDevice);
         if (e != hipSuccess) { (void)hipFree(g->d_tiles); delete g; return fail_hip(e, "uploading the tile table"); }
     }
-    st = upload_tables(&g->d_tables, {(const void *const *)Theta, (const void *const *)M}, nt, 1);
+    const std::vector<const void *> no_M(nt, nullptr);
+    st = upload_tables(&g->d_tables, {(const void *const *)Theta, g->no_momentum ? no_M.data() : (const void *const *)M}, nt, 1);
     if (st != HALOS_OK) { (void)hipFree(g->d_tiles); delete g; return st; }
     g->d_Theta = (float **)g->d_tables;
     g->d_M = g->d_Theta + nt;
     g->d_buffer = g->d_M + nt;
 
     for (const TileRange &r : g->ranges) {       // M <- 0
+        if (g->no_momentum) break;
         e = launch_init((hipStream_t)stream, g->d_tiles, r, nullptr, nullptr, g->d_M, nullptr, false, current_shape(g));
         if (e != hipSuccess) {
             (void)hipFree(g->d_tables); (void)hipFree(g->d_tiles); delete g;
@@ -464,6 +485,7 @@ halos_status halos_lps_create(halos_gps *g, int32_t lps_id, int32_t n_workers, v
     l->gps = g;
     l->id = lps_id;
     l->snapshot = (g->hp.flags & HALOS_FLAG_SNAPSHOT) != 0;
+    l->defer_clear = (g->hp.flags & HALOS_FLAG_DEFER_CLEAR) != 0;
     l->rule = g->hp.local;
     l->alpha = g->hp.alpha;
     l->pending.resize(n_workers);
@@ -523,9 +545,10 @@ void halos_lps_destroy(halos_lps *l) {
 }
 
 static halos_status push_delta_impl(halos_lps *l, int32_t worker, const void *const *gptrs, halos_dtype dtype,
-                                    uint32_t staleness, bool end_model) {
+                                    uint32_t staleness, bool end_model, float weight) {
     if (!live_lps(l)) return fail(HALOS_EINVAL, "lps is not a valid handle");
-    if (dtype != HALOS_F32 && dtype != HALOS_BF16) return fail(HALOS_EINVAL, "unknown delta dtype %d", (int)dtype);
+    if (dtype != HALOS_F32 && dtype != HALOS_BF16 && dtype != HALOS_F16) return fail(HALOS_EINVAL, "unknown delta dtype %d", (int)dtype);
+    if (!std::isfinite(weight)) return fail(HALOS_EINVAL, "weight is not finite");
     ProtoResult pr = l->proto.can_push_delta(worker);
     if (pr == PROTO_BAD_ARG) return fail(HALOS_EINVAL, "worker %d outside 0..%d", worker, l->proto.n_workers() - 1);
     if (pr == PROTO_BAD_STATE) return fail(HALOS_ESTATE, "worker %d of lps %d already has a delta queued", worker, l->id);
@@ -540,7 +563,7 @@ static halos_status push_delta_impl(halos_lps *l, int32_t worker, const void *co
                       std::memcmp(seen.data(), gptrs, nt * sizeof(void *)) == 0;
     if (!same) {      // a worker normally reuses its receive buffers: their ranges are checked once
         halos_status st = check_device(g);
-        if (st == HALOS_OK) st = check_tensors(g, gptrs, dtype == HALOS_BF16 ? 2 : 4, what);
+        if (st == HALOS_OK) st = check_tensors(g, gptrs, dtype == HALOS_F32 ? 4 : 2, what);
         if (st != HALOS_OK) return st;
         seen.assign(gptrs, gptrs + nt);
         l->validated_dtype[worker] = dtype;
@@ -550,6 +573,7 @@ static halos_status push_delta_impl(halos_lps *l, int32_t worker, const void *co
     p.dtype = dtype;
     p.end_model = end_model;
     p.staleness = staleness;
+    p.weight = weight;
     if (staleness > l->max_staleness) l->max_staleness = staleness;
     l->proto.push_delta(worker);
     return HALOS_OK;
@@ -557,11 +581,16 @@ static halos_status push_delta_impl(halos_lps *l, int32_t worker, const void *co
 
 halos_status halos_lps_push_update(halos_lps *l, int32_t worker, const void *const *gptrs, halos_dtype dtype,
                                    uint32_t staleness) {
-    return push_delta_impl(l, worker, gptrs, dtype, staleness, false);
+    return push_delta_impl(l, worker, gptrs, dtype, staleness, false, 1.0f);
+}
+
+halos_status halos_lps_push_update_weighted(halos_lps *l, int32_t worker, const void *const *gptrs, halos_dtype dtype,
+                                            uint32_t staleness, float weight) {
+    return push_delta_impl(l, worker, gptrs, dtype, staleness, false, weight);
 }
 
 halos_status halos_lps_push_end_model(halos_lps *l, int32_t worker, const void *const *end_model, uint32_t staleness) {
-    return push_delta_impl(l, worker, end_model, HALOS_F32, staleness, true);
+    return push_delta_impl(l, worker, end_model, HALOS_F32, staleness, true, 1.0f);
 }
 
 halos_status halos_lps_push_global(halos_lps *l) {
@@ -627,7 +656,8 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
         if (p.end_model && !pull)
             return fail(HALOS_ESTATE, "lps %d: worker %d sent its end model; halos_lps_step_pull applies it (the pass "
                         "that reads the worker's start model also replaces it)", l->id, head.worker);
-        const int g_kind = p.end_model ? GRAD_END_MODEL : (p.dtype == HALOS_BF16 ? GRAD_BF16 : GRAD_F32);
+        const int g_kind = p.end_model ? GRAD_END_MODEL
+                         : (p.dtype == HALOS_BF16 ? GRAD_BF16 : (p.dtype == HALOS_F16 ? GRAD_F16 : GRAD_F32));
         if (pull) {
             if (!l->worker_has_model[head.worker])
                 return fail(HALOS_ESTATE, "worker %d of lps %d has no model buffer registered", head.worker, l->id);
@@ -636,7 +666,9 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
         // what this update does to the third buffer: add its step (running accumulation), or nothing (an accumulated
         // update is in flight, or the buffer holds the snapshot), or -- snapshot form, accumulation complete --
         // turn the snapshot into theta_{t_last} - theta_t
-        const int third_mode = l->snapshot ? (oc.freezes ? 2 : 0) : (oc.accumulate ? 1 : 0);
+        // (or, after a merge that did not clear the buffer, restart the accumulation from this update's step)
+        const int third_mode = l->snapshot ? (oc.freezes ? THIRD_FREEZE_SNAPSHOT : THIRD_NONE)
+                             : (oc.accumulate ? (l->third_stale ? THIRD_RESTART : THIRD_ADD) : THIRD_NONE);
         uint32_t n_partials = 0;
         for (const TileRange &r : g->ranges) {
             PtrArgs args;
@@ -647,10 +679,10 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
                 const float inv_d = 1.0f / (float)l->cycle.d();
                 e = launch_lps_update_delayed((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_buffer, l->d_acc,
                                               pull_tab, args, g_kind, third_mode, (int)l->cycle.next(),
-                                              l->rule.eta, l->rule.beta, l->rule.cg * inv_d, inv_d, partials, shape);
+                                              l->rule.eta, l->rule.beta, l->rule.cg * inv_d, inv_d, p.weight, partials, shape);
             } else {
                 e = launch_lps_update((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_acc, pull_tab, args,
-                                      g_kind, third_mode, l->rule.eta, l->rule.beta, l->rule.cg, partials, shape);
+                                      g_kind, third_mode, l->rule.eta, l->rule.beta, l->rule.cg, p.weight, partials, shape);
             }
             if (e != hipSuccess) return fail_hip(e, "launching the local update");
             n_partials += launch_grid_size(r, shape);
@@ -661,6 +693,7 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
         }
         l->proto.commit_update();
         l->cycle.commit();
+        if (third_mode == THIRD_RESTART) l->third_stale = false;
         out.kind = 1;
         out.worker = head.worker;
         out.accumulated = oc.accumulate ? 1 : 0;
@@ -671,7 +704,8 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
         for (const TileRange &r : g->ranges) {
             double *partials = norm_partials ? norm_partials + n_partials : nullptr;
             hipError_t e = launch_lps_merge((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_acc, l->alpha, keep,
-                                            l->snapshot, partials, shape);
+                                            l->snapshot ? MERGE_SNAPSHOT : (l->defer_clear ? MERGE_LEAVE : MERGE_CLEAR),
+                                            partials, shape);
             if (e != hipSuccess) return fail_hip(e, "launching the merge");
             n_partials += launch_grid_size(r, shape);
         }
@@ -680,6 +714,7 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
             if (e != hipSuccess) return fail_hip(e, "launching the norm reduction");
         }
         l->proto.commit_merge();
+        if (l->defer_clear) l->third_stale = true;
         out.kind = 2;
     }
     out.t = l->proto.t();
@@ -748,6 +783,9 @@ halos_status halos_gps_merge(halos_gps *g, halos_lps *from, void *stream) {
             e = launch_gps_update_delayed((hipStream_t)stream, g->d_tiles, r, g->d_Theta, g->d_M, g->d_buffer, from->d_acc,
                                           from->d_acc, (int)g->cycle.next(), g->rule.eta, g->rule.beta, g->rule.cg * inv_d,
                                           inv_d, shape);
+        } else if (g->no_momentum) {
+            e = launch_gps_update_nomom((hipStream_t)stream, g->d_tiles, r, g->d_Theta, from->d_acc, from->d_acc,
+                                        g->rule.eta, g->rule.cg, shape);
         } else {
             e = launch_gps_update((hipStream_t)stream, g->d_tiles, r, g->d_Theta, g->d_M, from->d_acc, from->d_acc,
                                   g->rule.eta, g->rule.beta, g->rule.cg, shape);
@@ -756,6 +794,46 @@ halos_status halos_gps_merge(halos_gps *g, halos_lps *from, void *stream) {
     }
     g->cycle.commit();
     from->proto.consume();
+    g->updates += 1;
+    return HALOS_OK;
+}
+
+halos_status halos_gps_push_update(halos_gps *g, const void *const *gptrs, halos_dtype dtype, float weight, void *stream) {
+    if (!live_gps(g)) return fail(HALOS_EINVAL, "gps is not a valid handle");
+    if (dtype != HALOS_F32 && dtype != HALOS_BF16 && dtype != HALOS_F16) return fail(HALOS_EINVAL, "unknown delta dtype %d", (int)dtype);
+    if (!std::isfinite(weight)) return fail(HALOS_EINVAL, "weight is not finite");
+    if (g->no_momentum)
+        return fail(HALOS_ESTATE, "this global server was created without a momentum array (HALOS_FLAG_GPS_NO_MOMENTUM)");
+    if (!gptrs) return fail(HALOS_EINVAL, "g: pointer array is NULL");
+    halos_status st = check_device(g);
+    if (st != HALOS_OK) return st;
+    const size_t nt = g->numel.size();
+    const bool same = g->validated_delta.size() == nt && g->validated_delta_dtype == dtype &&
+                      std::memcmp(g->validated_delta.data(), gptrs, nt * sizeof(void *)) == 0;
+    if (!same) {
+        st = check_tensors(g, gptrs, dtype == HALOS_F32 ? 4 : 2, "g");
+        if (st != HALOS_OK) return st;
+        g->validated_delta.assign(gptrs, gptrs + nt);
+        g->validated_delta_dtype = dtype;
+    }
+    const LaunchShape shape = current_shape(g);
+    const int g_kind = dtype == HALOS_BF16 ? GRAD_BF16 : (dtype == HALOS_F16 ? GRAD_F16 : GRAD_F32);
+    for (const TileRange &r : g->ranges) {
+        PtrArgs args;
+        fill_args(args, gptrs, r, nt);
+        hipError_t e;
+        if (g->cycle.d() > 1) {
+            const float inv_d = 1.0f / (float)g->cycle.d();
+            e = launch_lps_update_delayed((hipStream_t)stream, g->d_tiles, r, g->d_Theta, g->d_M, g->d_buffer, nullptr, nullptr,
+                                          args, g_kind, THIRD_NONE, (int)g->cycle.next(), g->rule.eta, g->rule.beta,
+                                          g->rule.cg * inv_d, inv_d, weight, nullptr, shape);
+        } else {
+            e = launch_lps_update((hipStream_t)stream, g->d_tiles, r, g->d_Theta, g->d_M, nullptr, nullptr, args, g_kind,
+                                  THIRD_NONE, g->rule.eta, g->rule.beta, g->rule.cg, weight, nullptr, shape);
+        }
+        if (e != hipSuccess) return fail_hip(e, "launching the global server's update");
+    }
+    g->cycle.commit();
     g->updates += 1;
     return HALOS_OK;
 }
@@ -802,6 +880,8 @@ halos_status halos_set_hparams(void *server, int32_t is_gps, const halos_hparams
     if (is_gps) {
         halos_gps *g = static_cast<halos_gps *>(server);
         if (!live_gps(g)) return fail(HALOS_EINVAL, "server is not a valid gps handle");
+        if (g->no_momentum && hp->global.beta != 0.0f)
+            return fail(HALOS_EINVAL, "this global server keeps no momentum (HALOS_FLAG_GPS_NO_MOMENTUM): global.beta must stay 0");
         g->rule = hp->global;
         g->hp.global = hp->global;
     } else {
@@ -866,6 +946,8 @@ halos_status halos_lps_set_momentum_delay(halos_lps *l, int32_t d, void *const *
 
 halos_status halos_gps_set_momentum_delay(halos_gps *g, int32_t d, void *const *buffer, void *stream) {
     if (!live_gps(g)) return fail(HALOS_EINVAL, "gps is not a valid handle");
+    if (g->no_momentum && d > 1)
+        return fail(HALOS_ESTATE, "this global server keeps no momentum (HALOS_FLAG_GPS_NO_MOMENTUM): nothing to delay");
     return set_momentum_delay(g, g->cycle, g->d_buffer, d, buffer, stream, "the global server");
 }
 

@@ -27,14 +27,18 @@ typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
 // Pointers read from a table in memory are generic ("flat") to the compiler.  Everything this
 // library touches is global device memory, so say so: global_load/global_store instead of flat_*.
 #define HALOS_GLOBAL __attribute__((address_space(1)))
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef HALOS_GLOBAL float gf32;
-typedef HALOS_GLOBAL unsigned short gu16;
+typedef HALOS_GLOBAL unsigned short gu16;       // bfloat16 bit patterns
+typedef HALOS_GLOBAL _Float16 gf16;             // IEEE half
 typedef HALOS_GLOBAL f32x4 gf32x4;
 typedef HALOS_GLOBAL u16x4 gu16x4;
+typedef HALOS_GLOBAL f16x4 gf16x4;
 
 __device__ __forceinline__ gf32 *to_global(float *p) { return (gf32 *)p; }
 __device__ __forceinline__ const gf32 *to_global(const float *p) { return (const gf32 *)p; }
 __device__ __forceinline__ const gu16 *to_global(const unsigned short *p) { return (const gu16 *)p; }
+__device__ __forceinline__ const gf16 *to_global(const _Float16 *p) { return (const gf16 *)p; }
 
 template <bool NT>
 __device__ __forceinline__ f32x4 ld4(const gf32 *p) {
@@ -69,24 +73,39 @@ __device__ __forceinline__ f32x4 ldg4(const gu16 *p) {
     return r;
 }
 
+template <bool NT>
+__device__ __forceinline__ f32x4 ldg4(const gf16 *p) {          // half -> float is exact for every half value
+    const gf16x4 *q = (const gf16x4 *)p;
+    f16x4 h;
+    if constexpr (NT) h = __builtin_nontemporal_load(q);
+    else h = *q;
+    f32x4 r;
+    r[0] = static_cast<float>(h[0]); r[1] = static_cast<float>(h[1]); r[2] = static_cast<float>(h[2]); r[3] = static_cast<float>(h[3]);
+    return r;
+}
+
 __device__ __forceinline__ float ldg1(const gf32 *p) { return *p; }
 __device__ __forceinline__ float ldg1(const gu16 *p) { return bf16_up(*p); }
+__device__ __forceinline__ float ldg1(const gf16 *p) { return static_cast<float>(*p); }
 
 __device__ __forceinline__ f32x4 sub4(f32x4 a, f32x4 b);
 
 // The pseudo-gradient of four consecutive elements: read from the worker's delta tensor, or (FROM_END) formed here
 // as start - end from the worker's start model (the buffer the server filled at the worker's last pull) and the end
 // model the worker sent (the delta of Alg. 1's worker block, formed on the server, sign flipped).
+// ... times the caller's scalar on this delta (gw = 1 is exact and changes nothing).
+__device__ __forceinline__ f32x4 scale4(float w, f32x4 v);
+
 template <bool FROM_END, bool NT, typename GP>
-__device__ __forceinline__ f32x4 grad4(const GP *g, const gf32 *start, uint32_t off) {
-    if constexpr (FROM_END) return sub4(ld4<NT>(start + off), ld4<NT>(g + off));
-    else return ldg4<NT>(g + off);
+__device__ __forceinline__ f32x4 grad4(const GP *g, const gf32 *start, uint32_t off, float gw) {
+    if constexpr (FROM_END) return scale4(gw, sub4(ld4<NT>(start + off), ld4<NT>(g + off)));
+    else return scale4(gw, ldg4<NT>(g + off));
 }
 
 template <bool FROM_END, typename GP>
-__device__ __forceinline__ float grad1(const GP *g, const gf32 *start, uint32_t k) {
-    if constexpr (FROM_END) return __fsub_rn(start[k], ldg1(g + k));
-    else return ldg1(g + k);
+__device__ __forceinline__ float grad1(const GP *g, const gf32 *start, uint32_t k, float gw) {
+    if constexpr (FROM_END) return __fmul_rn(gw, __fsub_rn(start[k], ldg1(g + k)));
+    else return __fmul_rn(gw, ldg1(g + k));
 }
 
 // ModelUpdate (App. E) on one element; returns the step that was subtracted from x.
@@ -145,6 +164,13 @@ __device__ __forceinline__ f32x4 sub4(f32x4 a, f32x4 b) {
     return r;
 }
 
+__device__ __forceinline__ f32x4 scale4(float w, f32x4 v) {
+    f32x4 r;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) r[i] = __fmul_rn(w, v[i]);
+    return r;
+}
+
 // Wavefront reduction (64 lanes, shuffles), then the four wavefronts of the workgroup through LDS.
 // Every thread of the workgroup must call it.  Thread 0 stores the workgroup's total.
 __device__ __forceinline__ void block_sum_store(double v, double *dst) {
@@ -165,7 +191,9 @@ __device__ __forceinline__ void block_sum_store(double v, double *dst) {
 // S1: worker-delta step of a local server.
 // THIRD says what happens to the server's third buffer: 0 untouched, 1 running accumulation (acc <- acc + s),
 // 2 it holds the snapshot theta_{t_last} and this update completes the accumulation: it is overwritten with
-// G = theta_{t_last} - theta_t (Alg. 1's Delta, sign flipped).
+// G = theta_{t_last} - theta_t (Alg. 1's Delta, sign flipped), 3 the accumulation restarts here: acc <- 0 + s without
+// reading what the buffer held (the merge before it did not clear it).
+// gw is the caller's scalar on this delta: the update is applied to gw * g.
 // With PULL the updated model is also written to a second tensor list (the buffer the worker starts
 // its next round from: ModelUpdate and "schedule the worker" of Alg. 1 in one pass instead of an update pass plus a copy pass).
 // With NORM every workgroup also leaves the sum of g^2 over its tiles in partials[blockIdx.x].
@@ -175,9 +203,11 @@ __global__ void __launch_bounds__(BLOCK_THREADS)
 lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, uint32_t tensor_base,
                   float *const *__restrict__ theta_tab, float *const *__restrict__ m_tab,
                   float *const *__restrict__ acc_tab, float *const *__restrict__ pull_tab, PtrArgs gargs,
-                  float eta, float beta, float cg, double *__restrict__ partials) {
+                  float eta, float beta, float cg, float gw, double *__restrict__ partials) {
     static_assert(!FROM_END || (PULL && sizeof(GT) == 4), "an end model is fp32 and needs the worker's start model");
+    constexpr bool LOAD_THIRD = THIRD == 1 || THIRD == 2;
     const uint32_t tid = threadIdx.x;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
     double norm_acc = 0.0;
     for (uint32_t t = tile_lo + blockIdx.x; t < tile_hi; t += gridDim.x) {
         const Tile tl = tiles[t];
@@ -192,10 +222,10 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
-                gv[u] = grad4<FROM_END, NT>(g, pd, off);
+                gv[u] = grad4<FROM_END, NT>(g, pd, off, gw);
                 mv[u] = ld4<NT>(mm + off);
                 tv[u] = ld4<NT>(th + off);
-                if constexpr (THIRD != 0) av[u] = ld4<NT>(ac + off);
+                if constexpr (LOAD_THIRD) av[u] = ld4<NT>(ac + off);
             }
             if constexpr (NORM) {
                 float q = 0.f;
@@ -212,12 +242,13 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
                 if constexpr (PULL) st4<NT>(pd + off, tv[u]);
                 if constexpr (THIRD == 1) st4<NT>(ac + off, add4(av[u], s));
                 if constexpr (THIRD == 2) st4<NT>(ac + off, sub4(av[u], tv[u]));
+                if constexpr (THIRD == 3) st4<NT>(ac + off, add4(zero, s));
             }
         } else {
             const uint32_t len = tl.len;
             for (uint32_t off = tid * VEC; off < len; off += BLOCK_THREADS * VEC) {
                 if (off + VEC <= len) {
-                    f32x4 gv = grad4<FROM_END, NT>(g, pd, off), mv = ld4<NT>(mm + off), tv = ld4<NT>(th + off);
+                    f32x4 gv = grad4<FROM_END, NT>(g, pd, off, gw), mv = ld4<NT>(mm + off), tv = ld4<NT>(th + off);
                     if constexpr (NORM) norm_acc += static_cast<double>(sumsq4(gv, 0.f));
                     const f32x4 s = model_update4(tv, mv, gv, eta, beta, cg);
                     st4<NT>(mm + off, mv);
@@ -225,16 +256,18 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
                     if constexpr (PULL) st4<NT>(pd + off, tv);
                     if constexpr (THIRD == 1) st4<NT>(ac + off, add4(ld4<NT>(ac + off), s));
                     if constexpr (THIRD == 2) st4<NT>(ac + off, sub4(ld4<NT>(ac + off), tv));
+                    if constexpr (THIRD == 3) st4<NT>(ac + off, add4(zero, s));
                 } else {
                     for (uint32_t k = off; k < len; ++k) {      // ragged tail: fewer than 4 elements
                         float mv = mm[k], tv = th[k];
-                        const float gk = grad1<FROM_END>(g, pd, k);
+                        const float gk = grad1<FROM_END>(g, pd, k, gw);
                         if constexpr (NORM) norm_acc += static_cast<double>(__fmul_rn(gk, gk));
                         const float s = model_update(tv, mv, gk, eta, beta, cg);
                         mm[k] = mv; th[k] = tv;
                         if constexpr (PULL) pd[k] = tv;
                         if constexpr (THIRD == 1) ac[k] = __fadd_rn(ac[k], s);
                         if constexpr (THIRD == 2) ac[k] = __fsub_rn(ac[k], tv);
+                        if constexpr (THIRD == 3) ac[k] = __fadd_rn(0.f, s);
                     }
                 }
             }
@@ -296,6 +329,53 @@ gps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
     }
 }
 
+// S3 without global momentum (beta_g = 0, the setting of Sec. 5.4 for non-i.i.d. data): the momentum array is neither
+// read nor written, Theta <- Theta - eta (cg G).  Same bits as gps_update_kernel at beta = 0 (where m = G and the
+// momentum term is an exact zero), up to the sign of an exact zero.  G and out may alias.
+template <bool NT>
+__global__ void __launch_bounds__(BLOCK_THREADS)
+gps_update_nomom_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi,
+                        float *const *__restrict__ Theta_tab, float *const *G_tab, float *const *out_tab, float eta, float cg) {
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t t = tile_lo + blockIdx.x; t < tile_hi; t += gridDim.x) {
+        const Tile tl = tiles[t];
+        const uint32_t tensor = tl.tensor;
+        gf32 *Th = to_global(Theta_tab[tensor]) + tl.start;
+        const gf32 *G = to_global(G_tab[tensor]) + tl.start;
+        gf32 *out = to_global(out_tab[tensor]) + tl.start;
+        if (tl.len == TILE_ELEMS) {
+            f32x4 gv[UNROLL], tv[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
+                gv[u] = ld4<NT>(G + off);
+                tv[u] = ld4<NT>(Th + off);
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
+                const f32x4 nt = sub4(tv[u], scale4(eta, scale4(cg, gv[u])));
+                st4<NT>(Th + off, nt);
+                st4<NT>(out + off, nt);
+            }
+        } else {
+            const uint32_t len = tl.len;
+            for (uint32_t off = tid * VEC; off < len; off += BLOCK_THREADS * VEC) {
+                if (off + VEC <= len) {
+                    const f32x4 nt = sub4(ld4<NT>(Th + off), scale4(eta, scale4(cg, ld4<NT>(G + off))));
+                    st4<NT>(Th + off, nt);
+                    st4<NT>(out + off, nt);
+                } else {
+                    for (uint32_t k = off; k < len; ++k) {
+                        const float nt = __fsub_rn(Th[k], __fmul_rn(eta, __fmul_rn(cg, G[k])));
+                        Th[k] = nt; out[k] = nt;
+                    }
+                }
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Delayed Nesterov momentum (Sec. 5.1; App. D, delays d_l and d_g).  A server handles its updates in cycles
 // of d: every update adds g to a buffer and steps the model by eta (cg/d) g; the last one of a cycle also
@@ -343,9 +423,10 @@ lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint
                           float *const *__restrict__ theta_tab, float *const *__restrict__ m_tab,
                           float *const *__restrict__ buf_tab, float *const *__restrict__ acc_tab,
                           float *const *__restrict__ pull_tab, PtrArgs gargs, float eta, float beta, float cgd,
-                          float inv_d, double *__restrict__ partials) {
+                          float inv_d, float gw, double *__restrict__ partials) {
     static_assert(!FROM_END || (PULL && sizeof(GT) == 4), "an end model is fp32 and needs the worker's start model");
     constexpr bool NT = true;
+    constexpr bool LOAD_THIRD = THIRD == 1 || THIRD == 2;
     constexpr bool LOAD_B = RULE != CYCLE_FIRST, STORE_B = RULE != CYCLE_REFRESH, USE_M = RULE == CYCLE_REFRESH;
     const uint32_t tid = threadIdx.x;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
@@ -364,11 +445,11 @@ lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
-                gv[u] = grad4<FROM_END, NT>(g, pd, off);
+                gv[u] = grad4<FROM_END, NT>(g, pd, off, gw);
                 bv[u] = LOAD_B ? ld4<NT>(bb + off) : zero;
                 mv[u] = USE_M ? ld4<NT>(mm + off) : zero;
                 tv[u] = ld4<NT>(th + off);
-                if constexpr (THIRD != 0) av[u] = ld4<NT>(ac + off);
+                if constexpr (LOAD_THIRD) av[u] = ld4<NT>(ac + off);
             }
             if constexpr (NORM) {
                 float q = 0.f;
@@ -386,12 +467,13 @@ lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint
                 if constexpr (PULL) st4<NT>(pd + off, tv[u]);
                 if constexpr (THIRD == 1) st4<NT>(ac + off, add4(av[u], s));
                 if constexpr (THIRD == 2) st4<NT>(ac + off, sub4(av[u], tv[u]));
+                if constexpr (THIRD == 3) st4<NT>(ac + off, add4(zero, s));
             }
         } else {
             const uint32_t len = tl.len;
             for (uint32_t off = tid * VEC; off < len; off += BLOCK_THREADS * VEC) {
                 if (off + VEC <= len) {
-                    f32x4 gv = grad4<FROM_END, NT>(g, pd, off), tv = ld4<NT>(th + off);
+                    f32x4 gv = grad4<FROM_END, NT>(g, pd, off, gw), tv = ld4<NT>(th + off);
                     f32x4 bv = LOAD_B ? ld4<NT>(bb + off) : zero, mv = USE_M ? ld4<NT>(mm + off) : zero;
                     if constexpr (NORM) norm_acc += static_cast<double>(sumsq4(gv, 0.f));
                     const f32x4 s = delayed_update4<RULE>(tv, mv, bv, gv, eta, beta, cgd, inv_d);
@@ -401,10 +483,11 @@ lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint
                     if constexpr (PULL) st4<NT>(pd + off, tv);
                     if constexpr (THIRD == 1) st4<NT>(ac + off, add4(ld4<NT>(ac + off), s));
                     if constexpr (THIRD == 2) st4<NT>(ac + off, sub4(ld4<NT>(ac + off), tv));
+                    if constexpr (THIRD == 3) st4<NT>(ac + off, add4(zero, s));
                 } else {
                     for (uint32_t k = off; k < len; ++k) {      // ragged tail: fewer than 4 elements
                         float tv = th[k], bv = LOAD_B ? bb[k] : 0.f, mv = USE_M ? mm[k] : 0.f;
-                        const float gk = grad1<FROM_END>(g, pd, k);
+                        const float gk = grad1<FROM_END>(g, pd, k, gw);
                         if constexpr (NORM) norm_acc += static_cast<double>(__fmul_rn(gk, gk));
                         const float s = delayed_update<RULE>(tv, mv, bv, gk, eta, beta, cgd, inv_d);
                         if constexpr (STORE_B) bb[k] = bv;
@@ -413,6 +496,7 @@ lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint
                         if constexpr (PULL) pd[k] = tv;
                         if constexpr (THIRD == 1) ac[k] = __fadd_rn(ac[k], s);
                         if constexpr (THIRD == 2) ac[k] = __fsub_rn(ac[k], tv);
+                        if constexpr (THIRD == 3) ac[k] = __fadd_rn(0.f, s);
                     }
                 }
             }
@@ -487,8 +571,9 @@ gps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint
 // ---------------------------------------------------------------------------------------------
 // S4: merge the returned global model into the local model and restart the accumulation.
 // With NORM every workgroup also leaves the sum of (theta - Theta_i)^2 before the merge in partials[blockIdx.x].
-// With SNAP the third buffer receives the merged model (the new snapshot theta_{t_last}) instead of zeros.
-template <bool NT, bool NORM, bool SNAP>
+// OUT says what the third buffer receives: MERGE_CLEAR zeros (the accumulation restarts), MERGE_SNAPSHOT the merged model
+// (the new snapshot theta_{t_last}), MERGE_LEAVE nothing -- the first update that accumulates afterwards overwrites it.
+template <bool NT, bool NORM, int OUT>
 __global__ void __launch_bounds__(BLOCK_THREADS)
 lps_merge_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi,
                  float *const *__restrict__ theta_tab, float *const *__restrict__ inbox_tab, float alpha, float keep,
@@ -520,7 +605,7 @@ lps_merge_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile
                 const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
                 const f32x4 merged = merge4(tv[u], iv[u], alpha, keep);
                 st4<NT>(th + off, merged);
-                st4<NT>(in + off, SNAP ? merged : zero);
+                if constexpr (OUT != MERGE_LEAVE) st4<NT>(in + off, OUT == MERGE_SNAPSHOT ? merged : zero);
             }
         } else {
             const uint32_t len = tl.len;
@@ -530,7 +615,7 @@ lps_merge_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile
                     if constexpr (NORM) norm_acc += static_cast<double>(sumsq4(sub4(tv, iv), 0.f));
                     const f32x4 merged = merge4(tv, iv, alpha, keep);
                     st4<NT>(th + off, merged);
-                    st4<NT>(in + off, SNAP ? merged : zero);
+                    if constexpr (OUT != MERGE_LEAVE) st4<NT>(in + off, OUT == MERGE_SNAPSHOT ? merged : zero);
                 } else {
                     for (uint32_t k = off; k < len; ++k) {
                         const float tk = th[k], ik = in[k];
@@ -540,7 +625,7 @@ lps_merge_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile
                         }
                         const float merged = merge1(tk, ik, alpha, keep);
                         th[k] = merged;
-                        in[k] = SNAP ? merged : 0.f;
+                        if constexpr (OUT != MERGE_LEAVE) in[k] = OUT == MERGE_SNAPSHOT ? merged : 0.f;
                     }
                 }
             }
@@ -720,31 +805,37 @@ uint32_t launch_grid_size(TileRange r, LaunchShape shape) { return r.hi > r.lo ?
 
 hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
                              float *const *acc, float *const *pull, const PtrArgs &g, int g_kind, int third_mode,
-                             float eta, float beta, float cg, double *norm_partials, LaunchShape shape) {
+                             float eta, float beta, float cg, float gw, double *norm_partials, LaunchShape shape) {
     if (r.hi <= r.lo) return hipSuccess;
-    if (g_kind < GRAD_F32 || g_kind > GRAD_END_MODEL || third_mode < 0 || third_mode > 2 || (g_kind == GRAD_END_MODEL && !pull))
+    if (g_kind < GRAD_F32 || g_kind > GRAD_F16 || third_mode < THIRD_NONE || third_mode > THIRD_RESTART ||
+        (g_kind == GRAD_END_MODEL && !pull))
         return hipErrorInvalidValue;
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
 #define HALOS_LAUNCH_UPD(GT, THIRD, NT, PULL, END)                                                                         \
     do {                                                                                                                 \
         if (norm_partials)                                                                                               \
             lps_update_kernel<GT, THIRD, NT, PULL, true, END><<<grid, block, 0, stream>>>(                               \
-                tiles, r.lo, r.hi, r.tensor_base, theta, m, acc, pull, g, eta, beta, cg, norm_partials);                 \
+                tiles, r.lo, r.hi, r.tensor_base, theta, m, acc, pull, g, eta, beta, cg, gw, norm_partials);             \
         else                                                                                                             \
             lps_update_kernel<GT, THIRD, NT, PULL, false, END><<<grid, block, 0, stream>>>(                              \
-                tiles, r.lo, r.hi, r.tensor_base, theta, m, acc, pull, g, eta, beta, cg, nullptr);                       \
+                tiles, r.lo, r.hi, r.tensor_base, theta, m, acc, pull, g, eta, beta, cg, gw, nullptr);                   \
     } while (0)
 #define HALOS_LAUNCH_UPD_NT(GT, THIRD, PULL, END) \
     do { if (shape.nontemporal) HALOS_LAUNCH_UPD(GT, THIRD, true, PULL, END); else HALOS_LAUNCH_UPD(GT, THIRD, false, PULL, END); } while (0)
 #define HALOS_LAUNCH_UPD_THIRD(GT, PULL, END)                                  \
     do {                                                                       \
-        if (third_mode == 0) HALOS_LAUNCH_UPD_NT(GT, 0, PULL, END);            \
-        else if (third_mode == 1) HALOS_LAUNCH_UPD_NT(GT, 1, PULL, END);       \
-        else HALOS_LAUNCH_UPD_NT(GT, 2, PULL, END);                            \
+        if (third_mode == THIRD_NONE) HALOS_LAUNCH_UPD_NT(GT, 0, PULL, END);   \
+        else if (third_mode == THIRD_ADD) HALOS_LAUNCH_UPD_NT(GT, 1, PULL, END); \
+        else if (third_mode == THIRD_FREEZE_SNAPSHOT) HALOS_LAUNCH_UPD_NT(GT, 2, PULL, END); \
+        else HALOS_LAUNCH_UPD_NT(GT, 3, PULL, END);                            \
     } while (0)
+#define HALOS_LAUNCH_UPD_PULL(GT) \
+    do { if (pull) HALOS_LAUNCH_UPD_THIRD(GT, true, false); else HALOS_LAUNCH_UPD_THIRD(GT, false, false); } while (0)
     if (g_kind == GRAD_END_MODEL) HALOS_LAUNCH_UPD_THIRD(float, true, true);
-    else if (g_kind == GRAD_BF16) { if (pull) HALOS_LAUNCH_UPD_THIRD(unsigned short, true, false); else HALOS_LAUNCH_UPD_THIRD(unsigned short, false, false); }
-    else { if (pull) HALOS_LAUNCH_UPD_THIRD(float, true, false); else HALOS_LAUNCH_UPD_THIRD(float, false, false); }
+    else if (g_kind == GRAD_BF16) HALOS_LAUNCH_UPD_PULL(unsigned short);
+    else if (g_kind == GRAD_F16) HALOS_LAUNCH_UPD_PULL(_Float16);
+    else HALOS_LAUNCH_UPD_PULL(float);
+#undef HALOS_LAUNCH_UPD_PULL
 #undef HALOS_LAUNCH_UPD_THIRD
 #undef HALOS_LAUNCH_UPD_NT
 #undef HALOS_LAUNCH_UPD
@@ -762,23 +853,34 @@ hipError_t launch_gps_update(hipStream_t stream, const Tile *tiles, TileRange r,
     return hipGetLastError();
 }
 
+hipError_t launch_gps_update_nomom(hipStream_t stream, const Tile *tiles, TileRange r, float *const *Theta,
+                                   float *const *G, float *const *out, float eta, float cg, LaunchShape shape) {
+    if (r.hi <= r.lo) return hipSuccess;
+    const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
+    if (shape.nontemporal)
+        gps_update_nomom_kernel<true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, Theta, G, out, eta, cg);
+    else
+        gps_update_nomom_kernel<false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, Theta, G, out, eta, cg);
+    return hipGetLastError();
+}
+
 hipError_t launch_lps_update_delayed(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
                                      float *const *m, float *const *buffer, float *const *acc, float *const *pull,
                                      const PtrArgs &g, int g_kind, int third_mode, int cycle_pos, float eta,
-                                     float beta, float cgd, float inv_d, double *norm_partials, LaunchShape shape) {
+                                     float beta, float cgd, float inv_d, float gw, double *norm_partials, LaunchShape shape) {
     if (r.hi <= r.lo) return hipSuccess;
-    if (cycle_pos < CYCLE_FIRST || cycle_pos > CYCLE_REFRESH || third_mode < 0 || third_mode > 2 ||
-        g_kind < GRAD_F32 || g_kind > GRAD_END_MODEL || (g_kind == GRAD_END_MODEL && !pull))
+    if (cycle_pos < CYCLE_FIRST || cycle_pos > CYCLE_REFRESH || third_mode < THIRD_NONE || third_mode > THIRD_RESTART ||
+        g_kind < GRAD_F32 || g_kind > GRAD_F16 || (g_kind == GRAD_END_MODEL && !pull))
         return hipErrorInvalidValue;
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
 #define HALOS_LAUNCH_DN(GT, THIRD, PULL, RULE, END)                                                                     \
     do {                                                                                                                \
         if (norm_partials)                                                                                              \
             lps_update_delayed_kernel<GT, THIRD, PULL, RULE, END, true><<<grid, block, 0, stream>>>(                    \
-                tiles, r.lo, r.hi, r.tensor_base, theta, m, buffer, acc, pull, g, eta, beta, cgd, inv_d, norm_partials); \
+                tiles, r.lo, r.hi, r.tensor_base, theta, m, buffer, acc, pull, g, eta, beta, cgd, inv_d, gw, norm_partials); \
         else                                                                                                            \
             lps_update_delayed_kernel<GT, THIRD, PULL, RULE, END, false><<<grid, block, 0, stream>>>(                   \
-                tiles, r.lo, r.hi, r.tensor_base, theta, m, buffer, acc, pull, g, eta, beta, cgd, inv_d, nullptr);      \
+                tiles, r.lo, r.hi, r.tensor_base, theta, m, buffer, acc, pull, g, eta, beta, cgd, inv_d, gw, nullptr);  \
     } while (0)
 #define HALOS_LAUNCH_DN_RULE(GT, THIRD, PULL, END)                                       \
     do {                                                                                 \
@@ -788,13 +890,18 @@ hipError_t launch_lps_update_delayed(hipStream_t stream, const Tile *tiles, Tile
     } while (0)
 #define HALOS_LAUNCH_DN_THIRD(GT, PULL, END)                                   \
     do {                                                                       \
-        if (third_mode == 0) HALOS_LAUNCH_DN_RULE(GT, 0, PULL, END);           \
-        else if (third_mode == 1) HALOS_LAUNCH_DN_RULE(GT, 1, PULL, END);      \
-        else HALOS_LAUNCH_DN_RULE(GT, 2, PULL, END);                           \
+        if (third_mode == THIRD_NONE) HALOS_LAUNCH_DN_RULE(GT, 0, PULL, END);  \
+        else if (third_mode == THIRD_ADD) HALOS_LAUNCH_DN_RULE(GT, 1, PULL, END); \
+        else if (third_mode == THIRD_FREEZE_SNAPSHOT) HALOS_LAUNCH_DN_RULE(GT, 2, PULL, END); \
+        else HALOS_LAUNCH_DN_RULE(GT, 3, PULL, END);                           \
     } while (0)
+#define HALOS_LAUNCH_DN_PULL(GT) \
+    do { if (pull) HALOS_LAUNCH_DN_THIRD(GT, true, false); else HALOS_LAUNCH_DN_THIRD(GT, false, false); } while (0)
     if (g_kind == GRAD_END_MODEL) HALOS_LAUNCH_DN_THIRD(float, true, true);
-    else if (g_kind == GRAD_BF16) { if (pull) HALOS_LAUNCH_DN_THIRD(unsigned short, true, false); else HALOS_LAUNCH_DN_THIRD(unsigned short, false, false); }
-    else { if (pull) HALOS_LAUNCH_DN_THIRD(float, true, false); else HALOS_LAUNCH_DN_THIRD(float, false, false); }
+    else if (g_kind == GRAD_BF16) HALOS_LAUNCH_DN_PULL(unsigned short);
+    else if (g_kind == GRAD_F16) HALOS_LAUNCH_DN_PULL(_Float16);
+    else HALOS_LAUNCH_DN_PULL(float);
+#undef HALOS_LAUNCH_DN_PULL
 #undef HALOS_LAUNCH_DN_THIRD
 #undef HALOS_LAUNCH_DN_RULE
 #undef HALOS_LAUNCH_DN
@@ -817,23 +924,22 @@ hipError_t launch_gps_update_delayed(hipStream_t stream, const Tile *tiles, Tile
 }
 
 hipError_t launch_lps_merge(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
-                            float *const *inbox, float alpha, float keep, bool snapshot, double *norm_partials,
+                            float *const *inbox, float alpha, float keep, int third_out, double *norm_partials,
                             LaunchShape shape) {
     if (r.hi <= r.lo) return hipSuccess;
+    if (third_out < MERGE_CLEAR || third_out > MERGE_LEAVE) return hipErrorInvalidValue;
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
-#define HALOS_LAUNCH_MERGE(NT, NORM, SNAP) \
-    lps_merge_kernel<NT, NORM, SNAP><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, inbox, alpha, keep, norm_partials)
-    const int variant = (shape.nontemporal ? 4 : 0) | (norm_partials ? 2 : 0) | (snapshot ? 1 : 0);
-    switch (variant) {
-        case 0: HALOS_LAUNCH_MERGE(false, false, false); break;
-        case 1: HALOS_LAUNCH_MERGE(false, false, true); break;
-        case 2: HALOS_LAUNCH_MERGE(false, true, false); break;
-        case 3: HALOS_LAUNCH_MERGE(false, true, true); break;
-        case 4: HALOS_LAUNCH_MERGE(true, false, false); break;
-        case 5: HALOS_LAUNCH_MERGE(true, false, true); break;
-        case 6: HALOS_LAUNCH_MERGE(true, true, false); break;
-        default: HALOS_LAUNCH_MERGE(true, true, true); break;
-    }
+#define HALOS_LAUNCH_MERGE(NT, NORM, OUT) \
+    lps_merge_kernel<NT, NORM, OUT><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, inbox, alpha, keep, norm_partials)
+#define HALOS_LAUNCH_MERGE_OUT(NT, NORM)                                              \
+    do {                                                                              \
+        if (third_out == MERGE_CLEAR) HALOS_LAUNCH_MERGE(NT, NORM, MERGE_CLEAR);      \
+        else if (third_out == MERGE_SNAPSHOT) HALOS_LAUNCH_MERGE(NT, NORM, MERGE_SNAPSHOT); \
+        else HALOS_LAUNCH_MERGE(NT, NORM, MERGE_LEAVE);                               \
+    } while (0)
+    if (shape.nontemporal) { if (norm_partials) HALOS_LAUNCH_MERGE_OUT(true, true); else HALOS_LAUNCH_MERGE_OUT(true, false); }
+    else { if (norm_partials) HALOS_LAUNCH_MERGE_OUT(false, true); else HALOS_LAUNCH_MERGE_OUT(false, false); }
+#undef HALOS_LAUNCH_MERGE_OUT
 #undef HALOS_LAUNCH_MERGE
     return hipGetLastError();
 }

@@ -42,6 +42,7 @@ struct TileRange {      // tiles [lo, hi) all belong to tensors [tensor_base, te
 };
 
 // Worker-delta step of a local server: m <- beta m + g; s = eta (cg g + beta m); theta <- theta - s;
+// The update is applied to gw * g, gw being the caller's scalar on this delta (1 changes nothing).
 // third_mode 1: acc <- acc + s (ModelUpdate of App. E fused with the accumulation behind Alg. 1's Delta);
 // third_mode 2: the third buffer holds theta_{t_last} and is overwritten with theta_{t_last} - theta_t (Alg. 1's Delta as
 // written, sign flipped); third_mode 0: the third buffer is not touched.
@@ -52,10 +53,14 @@ struct TileRange {      // tiles [lo, hi) all belong to tensors [tensor_base, te
 // g_kind says what the tensors in `g` hold: the pseudo-gradient in fp32 or bf16, or (GRAD_END_MODEL, needs `pull`)
 // the worker's END model in fp32 -- the pseudo-gradient is then formed in the kernel as start - end, the start model
 // being what `pull` points to before this launch overwrites it (the delta of Alg. 1's worker block formed on the server, sign flipped).
-constexpr int GRAD_F32 = 0, GRAD_BF16 = 1, GRAD_END_MODEL = 2;
+// third_mode 3: the accumulation restarts with this update, acc <- 0 + s, without reading the buffer (used after a merge
+// that left the returned model there instead of clearing it).
+// GRAD_F16: the tensors in `g` hold IEEE half values (upcast exactly).
+constexpr int GRAD_F32 = 0, GRAD_BF16 = 1, GRAD_END_MODEL = 2, GRAD_F16 = 3;
+constexpr int THIRD_NONE = 0, THIRD_ADD = 1, THIRD_FREEZE_SNAPSHOT = 2, THIRD_RESTART = 3;
 hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
                              float *const *acc, float *const *pull, const PtrArgs &g, int g_kind, int third_mode,
-                             float eta, float beta, float cg, double *norm_partials, LaunchShape shape);
+                             float eta, float beta, float cg, float gw, double *norm_partials, LaunchShape shape);
 
 // Number of workgroups a launch over range r uses (0 for an empty range).
 uint32_t launch_grid_size(TileRange r, LaunchShape shape);
@@ -68,6 +73,11 @@ hipError_t launch_norm_finalize(hipStream_t stream, const double *partials, uint
 hipError_t launch_gps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *Theta, float *const *M,
                              float *const *G, float *const *out, float eta, float beta, float cg, LaunchShape shape);
 
+// The global-server step without momentum (beta_g = 0, Sec. 5.4): Theta <- Theta - eta (cg G); out <- Theta.  No
+// momentum array is touched.
+hipError_t launch_gps_update_nomom(hipStream_t stream, const Tile *tiles, TileRange r, float *const *Theta,
+                                   float *const *G, float *const *out, float eta, float cg, LaunchShape shape);
+
 // The same two steps under delayed Nesterov momentum (Sec. 5.1; App. D, delays d_l and d_g).  cycle_pos says where
 // in its cycle of d updates the server is: CYCLE_FIRST (buffer <- g), CYCLE_INNER (buffer <- buffer + g) or
 // CYCLE_REFRESH (m <- beta m + (buffer + g) * inv_d, then applied; the buffer is left as it is).  Every update
@@ -77,16 +87,18 @@ constexpr int CYCLE_FIRST = 1, CYCLE_INNER = 2, CYCLE_REFRESH = 3;
 hipError_t launch_lps_update_delayed(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
                                      float *const *m, float *const *buffer, float *const *acc, float *const *pull,
                                      const PtrArgs &g, int g_kind, int third_mode, int cycle_pos, float eta,
-                                     float beta, float cgd, float inv_d, double *norm_partials, LaunchShape shape);
+                                     float beta, float cgd, float inv_d, float gw, double *norm_partials, LaunchShape shape);
 hipError_t launch_gps_update_delayed(hipStream_t stream, const Tile *tiles, TileRange r, float *const *Theta,
                                      float *const *M, float *const *buffer, float *const *G, float *const *out,
                                      int cycle_pos, float eta, float beta, float cgd, float inv_d, LaunchShape shape);
 
-// Merge step of a local server: theta <- alpha * inbox + keep * theta (keep = 1 - alpha); inbox buffer <- 0.
+// Merge step of a local server: theta <- alpha * inbox + keep * theta (keep = 1 - alpha).
+// third_out: what the inbox buffer receives -- MERGE_CLEAR zeros, MERGE_SNAPSHOT the merged model (the new
+// theta_{t_last}), MERGE_LEAVE nothing (the next accumulating update must then run with THIRD_RESTART).
 // With `norm_partials`: per workgroup, the sum of (theta - inbox)^2 before the merge (same layout as above).
-// `snapshot`: the inbox buffer receives the merged model (the new theta_{t_last}) instead of zeros.
+constexpr int MERGE_CLEAR = 0, MERGE_SNAPSHOT = 1, MERGE_LEAVE = 2;
 hipError_t launch_lps_merge(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
-                            float *const *inbox, float alpha, float keep, bool snapshot, double *norm_partials,
+                            float *const *inbox, float alpha, float keep, int third_out, double *norm_partials,
                             LaunchShape shape);
 
 // table[first + i] <- src.p[i] for i < count (count <= MAX_ARG_TENSORS): rewrites part of a device pointer table in

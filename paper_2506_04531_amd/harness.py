@@ -131,7 +131,7 @@ class Cluster:
         f32 = torch.float32
         self.region_arena = None
         if placement == "regions":
-            ddt_size = 2 if w.delta_dtype == "bf16" else 4
+            ddt_size = 4 if w.delta_dtype == "f32" else 2
             S = sum((n * 4 + 255) // 256 * 256 for n in self.numel)
             L = w.n_lps
             pool_bytes = w.pool_slots * S * ddt_size // 4
@@ -157,11 +157,12 @@ class Cluster:
             mk = lambda dt=f32, role="theta": ra.alloc_list(cls_of[role], self.numel, dt)
         else:
             mk = lambda dt=f32, role="theta": alloc_tensor_list(self.numel, dt, self.device, arena)
-        self.Theta, self.M = mk(role="Theta"), mk(role="M")
-        fill_initial_model(w, self.Theta)
         self.hp = hp if hp is not None else B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0],
                                                                  cg_l=w.cg_l, cg_g=w.cg_g)
         self.snapshot = bool(self.hp.flags & B.FLAG_SNAPSHOT)
+        self.Theta = mk(role="Theta")
+        self.M = None if self.hp.flags & B.FLAG_GPS_NO_MOMENTUM else mk(role="M")      # a momentum-free GPS has no M at all
+        fill_initial_model(w, self.Theta)
         self.gps = B.halos_gps_create(self.numel, self.hp, self.Theta, self.M)
         self.gps_buffer = None
         if w.d_g > 1:
@@ -178,8 +179,8 @@ class Cluster:
             if k_initial is not None:
                 B.halos_lps_set_threshold(h, int(k_initial[l]))
             self.lps.append(h)
-        self.delta_dtype = B.BF16 if w.delta_dtype == "bf16" else B.F32
-        ddt = torch.bfloat16 if w.delta_dtype == "bf16" else f32
+        self.delta_dtype = {"f32": B.F32, "bf16": B.BF16, "f16": B.F16}[w.delta_dtype]
+        ddt = {"f32": f32, "bf16": torch.bfloat16, "f16": torch.float16}[w.delta_dtype]
         self.pool = []
         for s in range(w.pool_slots):
             ts = mk(ddt, role="pool")
@@ -227,6 +228,7 @@ class Cluster:
         from collections import defaultdict
         timings: Dict[str, list] = defaultdict(list)
         fuse_pull = fuse_pull and self._pull_ptrs is not None
+        weighted = self.w.staleness_exponent > 0.0
         skip = -1
         info = B.StepInfo()
         k_now = [None] * len(self.lps)
@@ -251,8 +253,12 @@ class Cluster:
             kind, l = int(ev["kind"]), int(ev["lps"])
             h = self.lps[l]
             if kind == _ARRIVE_DELTA:
-                chk(lib.halos_lps_push_update(h, int(ev["worker"]), self._pool_ptrs[int(ev["slot"])],
-                                              self.delta_dtype, int(ev["staleness"])))
+                if weighted:
+                    chk(lib.halos_lps_push_update_weighted(h, int(ev["worker"]), self._pool_ptrs[int(ev["slot"])], self.delta_dtype,
+                                                           int(ev["staleness"]), synth.staleness_weight(self.w, int(ev["staleness"]))))
+                else:
+                    chk(lib.halos_lps_push_update(h, int(ev["worker"]), self._pool_ptrs[int(ev["slot"])],
+                                                  self.delta_dtype, int(ev["staleness"])))
             elif kind == _LPS_STEP:
                 k = int(ev["k_cur"])
                 if k_now[l] != k:
@@ -296,7 +302,9 @@ class Cluster:
 
     # ------------------------------------------------------------------ inspection
     def state_lists(self) -> Dict[str, List[torch.Tensor]]:
-        out = {"Theta": self.Theta, "M": self.M}
+        out = {"Theta": self.Theta}
+        if self.M is not None:
+            out["M"] = self.M
         for l in range(len(self.theta)):
             out[f"theta{l}"] = self.theta[l]
             out[f"m{l}"] = self.m[l]

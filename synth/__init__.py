@@ -7,8 +7,8 @@ the one module that both the CPU oracle's tests and the HIP path's tests
 are allowed to share.
 """
 from .layouts import Layout, gpt_layout, flat_layout
-from .configs import Workload, WORKLOADS, get_workload, delta_scales
-from .tensors import normal_at, normal_flat, to_bf16_bits
+from .configs import Workload, WORKLOADS, get_workload, delta_scales, staleness_weight
+from .tensors import normal_at, normal_flat, to_bf16_bits, to_f16
 from .schedule import Trace, EV_ARRIVE_DELTA, EV_ARRIVE_GLOBAL, EV_LPS_STEP, EV_GPS_MERGE, EV_PULL
 from .schedule import make_trace as make_seeded_trace
 from .paper_cluster import PaperClusterSpec, make_paper_trace
@@ -25,7 +25,7 @@ def make_trace(w: Workload, seed=None, with_pulls: bool = True) -> Trace:
 
 __all__ = [
     "Layout", "gpt_layout", "flat_layout", "Workload", "WORKLOADS", "get_workload", "delta_scales",
-    "normal_at", "normal_flat", "to_bf16_bits", "Trace", "make_trace", "make_seeded_trace", "make_paper_trace",
+    "normal_at", "normal_flat", "to_bf16_bits", "to_f16", "staleness_weight", "Trace", "make_trace", "make_seeded_trace", "make_paper_trace",
     "PaperClusterSpec",
     "EV_ARRIVE_DELTA", "EV_ARRIVE_GLOBAL", "EV_LPS_STEP", "EV_GPS_MERGE", "EV_PULL",
 ]

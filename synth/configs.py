@@ -23,7 +23,7 @@ class Workload:
     n_lps: int
     workers_per_lps: int
     n_updates: int                 # number of worker-delta arrivals in the trace
-    delta_dtype: str               # "f32" or "bf16"
+    delta_dtype: str               # "f32", "bf16" or "f16"
     delta_sigma: float = 1e-3      # base standard deviation of a worker delta
     scale_by_fan_in: bool = True   # multiply sigma by 1/sqrt(fan_in) per tensor
     init_sigma: float = 0.02
@@ -40,6 +40,8 @@ class Workload:
     cg_g: float | None = None      # same for the GPS rule
     d_l: int = 1                   # momentum update delay of the LPS rule (delayed Nesterov momentum); 1 = plain rule
     d_g: int = 1                   # same for the GPS rule
+    staleness_exponent: float = 0.0    # a > 0: every arriving delta carries the weight (1 + staleness)^-a (a caller-side
+                                       # staleness scaling; 0 = HALoS itself, every weight 1)
     seed: int = 0
     pool_slots: int = 8            # number of distinct resident delta buffers
     schedule: str = "seeded"       # "seeded": synth.schedule; "paper": the paper's own cluster model (synth.paper_cluster)
@@ -61,6 +63,15 @@ def delta_scales(w: Workload):
         sigma = w.delta_sigma / (float(fan) ** 0.5 if w.scale_by_fan_in else 1.0)
         out[i] = scale_f32(sigma)
     return out
+
+
+def staleness_weight(w: Workload, staleness: int):
+    """The fp32 weight a caller applying polynomial staleness scaling would hand over with a delta (an INPUT of the
+    update path, like the delta itself; 1 when the workload uses none)."""
+    import numpy as np
+    if w.staleness_exponent <= 0.0:
+        return np.float32(1.0)
+    return np.float32((1.0 + float(staleness)) ** (-float(w.staleness_exponent)))
 
 
 def _mk() -> Dict[str, Workload]:

@@ -93,8 +93,8 @@ def normal_flat(seed: int, stream: int, start: int, count: int, scale: Union[flo
                 chunk: int = 1 << 24) -> torch.Tensor:
     """Values for the contiguous index range [start, start+count), generated in chunks.
 
-    If `out` is given (float32 or bfloat16, `count` elements) it is filled in
-    place; bfloat16 output is the fp32 value rounded to nearest-even.
+    If `out` is given (float32, bfloat16 or float16, `count` elements) it is filled in
+    place; 16-bit output is the fp32 value rounded to nearest-even.
     """
     if out is None:
         out = torch.empty(count, dtype=torch.float32, device=device)
@@ -110,3 +110,8 @@ def normal_flat(seed: int, stream: int, start: int, count: int, scale: Union[flo
 def to_bf16_bits(x: torch.Tensor) -> torch.Tensor:
     """Round an fp32 tensor to bfloat16 (nearest-even) and return the raw 16-bit patterns as int16."""
     return x.to(torch.bfloat16).view(torch.int16)
+
+
+def to_f16(x: torch.Tensor) -> torch.Tensor:
+    """Round an fp32 tensor to IEEE half (nearest-even, subnormals kept)."""
+    return x.to(torch.float16)

@@ -58,7 +58,8 @@ def oracle_run(w: synth.Workload, trace: synth.Trace, idx: Optional[np.ndarray],
     def delta(slot: int) -> np.ndarray:
         if slot not in cache:
             g = synth.normal_at(w.seed, 1 + slot, tidx, scale)
-            cache[slot] = synth.to_bf16_bits(g).numpy() if w.delta_dtype == "bf16" else g.numpy()
+            cache[slot] = (synth.to_bf16_bits(g).numpy() if w.delta_dtype == "bf16" else
+                           synth.to_f16(g).numpy() if w.delta_dtype == "f16" else g.numpy())
         return cache[slot]
 
     o = HalosOracle(theta0, w.n_lps, eta_l=w.eta_l, beta_l=w.beta_l, eta_g=w.eta_g, beta_g=w.beta_g,
@@ -68,7 +69,7 @@ def oracle_run(w: synth.Workload, trace: synth.Trace, idx: Optional[np.ndarray],
             o.set_delay(l, w.d_l)
     if w.d_g > 1:
         o.set_delay(-1, w.d_g)
-    log = oracle_replay(o, trace.events, delta)
+    log = oracle_replay(o, trace.events, delta, weight_of=lambda st: synth.staleness_weight(w, st))
     return o, log
 
 

@@ -1,0 +1,238 @@
+"""GPU parity of the variants next to the base path: IEEE-half deltas, weighted arrivals, the momentum-free global
+server, merges that do not clear the third buffer, and the single-tier server -- each through the C ABI against the
+CPU oracle on the same seeded inputs."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import synth
+from oracle import FORM_ACCUMULATOR, FORM_LITERAL, HalosOracle
+from parity_util import REL_TOL, check_step_logs, compare_state, oracle_run, oracle_state
+from test_gpu_parity import RAGGED, _cluster, _full_parity
+
+pytestmark = pytest.mark.gpu
+
+
+# ---------------------------------------------------------------- IEEE-half deltas
+@pytest.mark.parametrize("layout", ["ragged", "gpt"])
+def test_half_precision_deltas_every_element(layout):
+    """fp16 deltas (many of them subnormal at these magnitudes) upcast in the update pass."""
+    lay = RAGGED if layout == "ragged" else synth.gpt_layout(96, 2, vocab=1031)
+    w = replace(synth.get_workload("160m").scaled(lay, n_updates=96, name="f16-" + layout), delta_dtype="f16")
+    _full_parity(w, synth.make_trace(w, seed=71))
+
+
+def test_every_half_bit_pattern_goes_through_the_update_exactly():
+    """theta_0 = 0, beta = 0, eta = cg = 1: theta = -g, so the updated model shows the upcast of every one of the 65,536
+    half patterns (NaNs and infinities replaced by zeros: they would poison the state by design)."""
+    from paper_2506_04531_amd import binding as B
+    dev = torch.device("cuda:0")
+    bits = np.arange(65536, dtype=np.uint16)
+    h = bits.view(np.float16).copy()
+    h[~np.isfinite(h)] = 0.0
+    n = h.size + 3                                       # not a multiple of the vector width: the scalar tail sees halves too
+    g = torch.zeros(n, dtype=torch.float16, device=dev)
+    g[:h.size] = torch.from_numpy(h).to(dev)
+    Theta, M, th, m, acc = (torch.zeros(n, device=dev) for _ in range(5))
+    hp = B.paper_hparams(1.0, 0.0, 1.0, 0.0, 0.0, 1 << 30, cg_l=1.0, cg_g=1.0)
+    gps = B.halos_gps_create([n], hp, [Theta], [M])
+    lps = B.halos_lps_create(gps, 0, 1, [th], [m], [acc])
+    try:
+        B.halos_lps_push_update(lps, 0, [g], B.F16)
+        B.halos_lps_step(lps)
+        torch.cuda.synchronize()
+        got = th.cpu().numpy()[:h.size]
+    finally:
+        B.halos_lps_destroy(lps)
+        B.halos_gps_destroy(gps)
+    want = np.array([O.f16_to_f32(int(b)) for b in h.view(np.uint16)], dtype=np.float32)
+    o = HalosOracle(np.zeros(h.size, dtype=np.float32), 1, eta_l=1.0, beta_l=0.0, eta_g=1.0, beta_g=0.0, alpha=0.0,
+                    K=1 << 30, cg_l=1.0, cg_g=1.0, precision=32, form=FORM_ACCUMULATOR)
+    o.arrive_delta(0, 0, h); o.lps_step(0)
+    ref = o.get(O.THETA).astype(np.float32)
+    assert np.array_equal(ref, np.float32(0.0) - want)                 # the oracle's model is minus the upcast delta
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+
+
+# ---------------------------------------------------------------- weighted arrivals
+@pytest.mark.parametrize("dtype,d_l", [("f32", 1), ("bf16", 1), ("f32", 4)])
+def test_staleness_weighted_arrivals_every_element(dtype, d_l):
+    """Every delta carries the weight (1 + staleness)^-0.5 (the caller's polynomial; halos_lps_push_update_weighted)."""
+    base = synth.get_workload("410m").scaled(RAGGED, n_updates=96, name=f"weighted-{dtype}-d{d_l}")
+    w = replace(base, delta_dtype=dtype, staleness_exponent=0.5, d_l=d_l, eta_l=0.2 * d_l)
+    trace = synth.make_trace(w, seed=81)
+    st = trace.events[trace.events["kind"] == synth.EV_ARRIVE_DELTA]["staleness"]
+    assert st.max() > 0, "the schedule must produce stale arrivals for this test to mean anything"
+    _full_parity(w, trace)
+
+
+def test_weight_must_be_finite():
+    from paper_2506_04531_amd import binding as B
+    w = synth.get_workload("tiny").scaled(synth.flat_layout(5000), n_updates=4, name="badweight")
+    trace = synth.make_trace(w)
+    c = _cluster(w, trace)
+    try:
+        for bad in (float("nan"), float("inf")):
+            with pytest.raises(B.HalosError) as e:
+                B.halos_lps_push_update_weighted(c.lps[0], 0, c.pool[0], c.delta_dtype, 0, bad)
+            assert e.value.status == B.EINVAL
+            with pytest.raises(B.HalosError) as e:
+                B.halos_gps_push_update(c.gps, c.pool[0], c.delta_dtype, bad)
+            assert e.value.status == B.EINVAL
+        assert B.halos_lps_get_counters(c.lps[0])["queued"] == 0
+    finally:
+        c.close()
+
+
+# ---------------------------------------------------------------- momentum-free global server (Sec. 5.4)
+@pytest.mark.parametrize("recipe", ["70m", "160m"])
+def test_global_server_without_momentum_every_element(recipe):
+    """HALOS_FLAG_GPS_NO_MOMENTUM: no M exists; everything else equals the general rule at beta_g = 0 (the oracle),
+    compared numerically exactly (an exact zero may differ in sign)."""
+    from paper_2506_04531_amd import binding as B
+    base = synth.get_workload(recipe)
+    lay = RAGGED if recipe == "70m" else synth.gpt_layout(96, 2, vocab=1031)
+    w = replace(base.scaled(lay, n_updates=120, name=recipe + "-nomom"), beta_g=0.0)
+    trace = synth.make_trace(w)
+    hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, 0.0, w.alpha, w.k_range[0], flags=B.FLAG_GPS_NO_MOMENTUM)
+    c = _cluster(w, trace, hp=hp)
+    try:
+        assert c.M is None
+        gpu_log, _ = c.replay(trace.events, fuse_pull=True)
+        torch.cuda.synchronize()
+        gpu = {k: c.flat(k) for k in c.state_lists()}
+    finally:
+        c.close()
+    assert "M" not in gpu
+    o32, log32 = oracle_run(w, trace, None, 32, FORM_ACCUMULATOR)
+    check_step_logs(trace, gpu_log, log32)
+    ref = oracle_state(o32, w.n_lps, with_scale=False)
+    for k, v in gpu.items():
+        r = ref[k][0].astype(np.float32)
+        assert np.array_equal(v, r), k                       # numeric equality: +0 == -0, no NaN anywhere
+    o64, _ = oracle_run(w, trace, None, 64, FORM_LITERAL)
+    ref64 = {k: v for k, v in oracle_state(o64, w.n_lps).items() if k != "M"}
+    worst, _, name = compare_state(gpu, ref64, bitwise=False)
+    assert worst <= REL_TOL, (worst, name)
+
+
+def test_momentum_free_server_refuses_what_needs_momentum():
+    from paper_2506_04531_amd import binding as B
+    dev = torch.device("cuda:0")
+    n = 5000
+    Theta, buf, g = (torch.zeros(n, device=dev) for _ in range(3))
+    with pytest.raises(B.HalosError) as e:                   # the flag with beta_g != 0
+        B.halos_gps_create([n], B.paper_hparams(0.2, 0.9, 0.15, 0.5, 0.25, 4, flags=B.FLAG_GPS_NO_MOMENTUM), [Theta], None)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.HalosError) as e:                   # deferring the clear makes no sense with a snapshot
+        B.halos_gps_create([n], B.paper_hparams(0.2, 0.9, 0.15, 0.5, 0.25, 4, flags=B.FLAG_SNAPSHOT | B.FLAG_DEFER_CLEAR), [Theta], [buf])
+    assert e.value.status == B.EINVAL
+    gps = B.halos_gps_create([n], B.paper_hparams(0.2, 0.9, 0.15, 0.0, 0.25, 4, flags=B.FLAG_GPS_NO_MOMENTUM), [Theta], None)
+    try:
+        with pytest.raises(B.HalosError) as e:
+            B.halos_gps_push_update(gps, [g], B.F32)
+        assert e.value.status == B.ESTATE
+        with pytest.raises(B.HalosError) as e:
+            B.halos_gps_set_momentum_delay(gps, 2, [buf])
+        assert e.value.status == B.ESTATE
+        with pytest.raises(B.HalosError) as e:
+            B.halos_set_hparams(gps, True, B.paper_hparams(0.2, 0.9, 0.15, 0.5, 0.25, 4))
+        assert e.value.status == B.EINVAL
+        B.halos_set_hparams(gps, True, B.paper_hparams(0.2, 0.9, 0.3, 0.0, 0.25, 4))       # the rate may change
+    finally:
+        B.halos_gps_destroy(gps)
+
+
+# ---------------------------------------------------------------- merges that leave the third buffer alone
+@pytest.mark.parametrize("recipe,dtype,d_l", [("410m", "f32", 1), ("160m", "bf16", 1), ("70m", "f32", 3)])
+def test_deferred_clear_changes_no_result(recipe, dtype, d_l):
+    """HALOS_FLAG_DEFER_CLEAR: the merge writes theta only and the next accumulating update stores 0 + its step.  Every
+    array equals the oracle's bit for bit; the third buffer of a server that has merged and not updated since is
+    unspecified and left out."""
+    from paper_2506_04531_amd import binding as B
+    base = synth.get_workload(recipe).scaled(RAGGED, n_updates=120, name=f"defer-{recipe}")
+    w = replace(base, delta_dtype=dtype, d_l=d_l, eta_l=0.2 * d_l, max_link_delay=2, k_range=(2, 5))
+    trace = synth.make_trace(w, seed=91)
+    hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0], flags=B.FLAG_DEFER_CLEAR)
+    n_merges = int((trace.events["kind"] == synth.EV_ARRIVE_GLOBAL).sum())
+    assert n_merges >= 4
+    # stop right after a merge as well as at the end, so that both kinds of final state are seen
+    ev = trace.events
+    last_merge = max(i for i in range(len(ev)) if ev[i]["kind"] == synth.EV_LPS_STEP and ev[i]["exp_kind"] == 2)
+    for cut in (last_merge + 1, len(ev)):
+        c = _cluster(w, trace, hp=hp)
+        try:
+            gpu_log, _ = c.replay(ev[:cut], fuse_pull=True)
+            torch.cuda.synchronize()
+            gpu = {k: c.flat(k) for k in c.state_lists()}
+            fresh = [B.halos_lps_get_counters(h) for h in c.lps]
+        finally:
+            c.close()
+        o32, log32 = oracle_run(w, replace(trace, events=ev[:cut]), None, 32, FORM_ACCUMULATOR)
+        assert gpu_log == log32
+        ref = oracle_state(o32, w.n_lps)
+        skipped = 0
+        for l, cnt in enumerate(fresh):
+            if cnt["phase"] == B.PHASE_ACCUMULATING and cnt["t"] == cnt["t_last"] and cnt["t"] > 0:
+                ref.pop(f"aux{l}"); skipped += 1
+        if cut == last_merge + 1:
+            assert skipped >= 1
+        worst, n_diff, name = compare_state(gpu, ref, bitwise=True)
+        assert n_diff == 0, (cut, n_diff, worst, name)
+
+
+# ---------------------------------------------------------------- single tier
+@pytest.mark.parametrize("dtype,d_g", [("f32", 1), ("bf16", 1), ("f16", 1), ("f32", 3)])
+def test_single_tier_server_every_element(dtype, d_g):
+    """halos_gps_push_update: the global server applies worker deltas itself (weights included), against the oracle's
+    gps_apply_delta, model and momentum (and the open gradient buffer) bit for bit."""
+    from paper_2506_04531_amd import binding as B
+    from paper_2506_04531_amd.harness import alloc_tensor_list, fill_delta_slot, fill_initial_model
+    dev = torch.device("cuda:0")
+    w = replace(synth.get_workload("70m").scaled(RAGGED, n_updates=1, name="single-tier"), delta_dtype=dtype, d_g=d_g,
+                eta_g=0.05 * d_g, beta_g=0.9)
+    numel = [int(x) for x in w.layout.numel]
+    f32 = torch.float32
+    Theta, M, Bf = (alloc_tensor_list(numel, f32, dev) for _ in range(3))
+    fill_initial_model(w, Theta)
+    ddt = {"f32": f32, "bf16": torch.bfloat16, "f16": torch.float16}[dtype]
+    code = {"f32": B.F32, "bf16": B.BF16, "f16": B.F16}[dtype]
+    pool = []
+    for s in range(4):
+        ts = alloc_tensor_list(numel, ddt, dev)
+        fill_delta_slot(w, s, ts)
+        pool.append(ts)
+    hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, 8)
+    gps = B.halos_gps_create(numel, hp, Theta, M)
+    weights = [1.0, 0.5, float(np.float32(2 ** -0.5)), 1.0, 0.25, 1.0, 1.0, float(np.float32(3 ** -0.5))]
+    try:
+        if d_g > 1:
+            B.halos_gps_set_momentum_delay(gps, d_g, Bf)
+        for k, wt in enumerate(weights):
+            B.halos_gps_push_update(gps, pool[k % 4], code, wt)
+        torch.cuda.synchronize()
+        assert B.halos_gps_get_counters(gps)["updates"] == len(weights)
+        flat = lambda ts: torch.cat([t.reshape(-1) for t in ts]).cpu().numpy()
+        gpu = {"Theta": flat(Theta), "M": flat(M), "B": flat(Bf)}
+    finally:
+        B.halos_gps_destroy(gps)
+    idx = torch.arange(w.layout.total, dtype=torch.int64)
+    theta0 = synth.normal_at(w.seed, 0, idx, synth.tensors.scale_f32(w.init_sigma)).numpy()
+    scale = torch.from_numpy(synth.delta_scales(w)[w.layout.tensor_of(idx.numpy())])
+    o = HalosOracle(theta0, 1, eta_l=w.eta_l, beta_l=w.beta_l, eta_g=w.eta_g, beta_g=w.beta_g, alpha=w.alpha, K=8,
+                    precision=32, form=FORM_ACCUMULATOR)
+    if d_g > 1:
+        o.set_delay(-1, d_g)
+    for k, wt in enumerate(weights):
+        g = synth.normal_at(w.seed, 1 + k % 4, idx, scale)
+        g = g.to(ddt).to(torch.float32).numpy()                     # what the 16-bit buffer holds, upcast (exact)
+        o.gps_apply_delta(g, wt)
+    for name, what in (("Theta", O.GPS_THETA), ("M", O.GPS_MOM)):
+        ref = o.get(what).astype(np.float32)
+        assert np.array_equal(gpu[name].view(np.uint32), ref.view(np.uint32)), name
+    if o.delay_seen(-1) > 0:
+        ref = o.get(O.GPS_BUFFER).astype(np.float32)
+        assert np.array_equal(gpu["B"].view(np.uint32), ref.view(np.uint32))
