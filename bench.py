@@ -42,10 +42,17 @@ def bytes_per_param(label: str, delta_dtype: str, delayed: bool) -> int:
                     (+8), "_refresh" reads it and reads and writes the momentum (+12).
       gps_update*   read G, Theta; write Theta and the returned model (16), plus the momentum (+8) or, delayed, the
                     same buffer / momentum terms as above.
-      lps_merge     read theta and the returned model, write theta and the cleared third buffer (16).
+      lps_merge     read theta and the returned model, write theta and the cleared third buffer (16);
+                    "lps_merge_leave" does not clear (12), and the "restart" update after it writes the third buffer
+                    without reading it (4 less than "acc").
+      gps_update_nomom  no momentum array at all: read G, Theta; write Theta and the returned model (16).
       pull          read and write a model (8).
     """
     if label == "lps_merge":
+        return 16
+    if label == "lps_merge_leave":
+        return 12
+    if label == "gps_update_nomom":
         return 16
     if label == "pull":
         return 8
@@ -58,7 +65,7 @@ def bytes_per_param(label: str, delta_dtype: str, delayed: bool) -> int:
         return 16 + rule
     assert label.startswith("lps_update"), label
     g = 2 if delta_dtype == "bf16" else 4
-    third = 0 if "noacc" in parts else 8
+    third = 0 if "noacc" in parts else (4 if "restart" in parts else 8)
     return g + 8 + third + rule + (4 if "pull" in parts else 0)
 
 
@@ -101,7 +108,7 @@ def split_steps(events, n_updates_per_step: int, n_steps: int):
 
 
 def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: str = "regions", fuse_pull: bool = True,
-                 snapshot: bool = False):
+                 snapshot: bool = False, defer_clear: bool = False, gps_no_momentum: bool = False):
     import numpy as np
     import torch
     import synth
@@ -114,10 +121,12 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
     N = w.layout.total
     t0 = time.time()
     hp = None
-    if snapshot:
+    if snapshot or defer_clear or gps_no_momentum:
         from paper_2506_04531_amd import binding as B
-        hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0], cg_l=w.cg_l, cg_g=w.cg_g,
-                             flags=B.FLAG_SNAPSHOT)
+        flags = (B.FLAG_SNAPSHOT if snapshot else 0) | (B.FLAG_DEFER_CLEAR if defer_clear else 0) | \
+                (B.FLAG_GPS_NO_MOMENTUM if gps_no_momentum else 0)
+        hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, 0.0 if gps_no_momentum else w.beta_g, w.alpha, w.k_range[0],
+                             cg_l=w.cg_l, cg_g=w.cg_g, flags=flags)
     c = Cluster(w, "cuda:0", k_initial=trace.k_initial, placement=placement, verbose=verbose, hp=hp)
     n_regions = c.region_arena.n_regions if c.region_arena is not None else 0
     if verbose:
@@ -187,6 +196,7 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
         "whole_path_frac_of_peak": total_bytes / elapsed / 1e9 / HBM_PEAK_GBS,
         "kernels": kernels, "roofline": roofline, "placement": placement, "hbm_regions_found": n_regions,
         "fuse_pull": fuse_pull, "delta_form": "snapshot" if snapshot else "accumulator",
+        "defer_clear": defer_clear, "gps_no_momentum": gps_no_momentum,
         "momentum_delay": {"d_l": w.d_l, "d_g": w.d_g},
     }
 
@@ -527,6 +537,10 @@ def main():
     ap.add_argument("--snapshot", action="store_true",
                     help="form the accumulated update by subtracting the snapshot theta_{t_last} (the Delta of Alg. 1's LPS block as "
                          "written) instead of keeping a running sum: fewer bytes per update, larger rounding error")
+    ap.add_argument("--defer-clear", action="store_true",
+                    help="merges leave the third buffer (12 B/parameter instead of 16); the next update restarts it")
+    ap.add_argument("--gps-no-momentum", action="store_true",
+                    help="the global server keeps no momentum (beta_g = 0, Sec. 5.4): 16 B/parameter per GPS update instead of 24")
     ap.add_argument("--no-end-model-ab", action="store_true",
                     help="skip the A/B of the update pass fed a delta vs fed the worker's end model")
     ap.add_argument("--no-graph-ab", action="store_true",
@@ -561,10 +575,11 @@ def main():
     if args.placement_search:
         return placement_search_mode(args.search_elements, args.search_dtype)
 
-    head = run_workload(args.workload, args.steps, args.warmup, not args.quiet, args.placement, not args.no_fuse_pull, args.snapshot)
+    variant = dict(snapshot=args.snapshot, defer_clear=args.defer_clear, gps_no_momentum=args.gps_no_momentum)
+    head = run_workload(args.workload, args.steps, args.warmup, not args.quiet, args.placement, not args.no_fuse_pull, **variant)
     others = []
     for name in [x for x in args.also.split(",") if x and x != args.workload]:
-        others.append(run_workload(name, args.steps, args.warmup, not args.quiet, args.placement, not args.no_fuse_pull, args.snapshot))
+        others.append(run_workload(name, args.steps, args.warmup, not args.quiet, args.placement, not args.no_fuse_pull, **variant))
     ab = None if args.no_end_model_ab else end_model_ab(args.workload, verbose=not args.quiet)
     gab = None if args.no_graph_ab else graph_ab()
     cpu = None if args.no_cpu_baseline else cpu_baseline(args.workload)
@@ -582,6 +597,7 @@ def main():
                    "delta_dtype": head["delta_dtype"], "events_per_step": head["events_per_step"],
                    "placement": head["placement"], "hbm_regions_found": head["hbm_regions_found"],
                    "fuse_pull": head["fuse_pull"], "delta_form": head["delta_form"],
+                   "defer_clear": head["defer_clear"], "gps_no_momentum": head["gps_no_momentum"],
                    "momentum_delay": head["momentum_delay"]},
         "roofline": head["roofline"],
         "cpu_baseline": cpu,

@@ -251,6 +251,36 @@ halos_status halos_lps_set_worker_model(halos_lps *lps, int32_t worker, void *co
 halos_status halos_lps_step_pull(halos_lps *lps, void *stream, halos_step_info *info);
 
 /*
+ * Averaged step: the `count` (1..4) worker deltas at the head of the queue are averaged -- (w_1 g_1 + ... + w_n g_n) / n,
+ * added in arrival order, the 1/n formed in fp32 -- and applied as ONE update of Algorithm 1's LPS block (t advances by
+ * one; the accumulated update and the send test see one update).  This is the synchronous outer step of the
+ * Local-SGD methods the paper compares with (Sec. 2: average the workers' deltas, then one momentum step), in one pass:
+ * n deltas are read, the server's state is read and written once.  count = 1 is halos_lps_step.
+ * ESTATE (nothing modified) unless the first `count` items are worker deltas of one element type, none of them an end
+ * model; also under a momentum delay or HALOS_FLAG_NORMS.  Workers read the new model with halos_pull_model.
+ * info->worker is the last of the averaged senders.
+ */
+halos_status halos_lps_step_average(halos_lps *lps, int32_t count, void *stream, halos_step_info *info);
+
+/*
+ * Batched steps: if several worker deltas wait at the head of the queue, apply up to max_items (1..4) of them in ONE
+ * pass, one after the other in arrival order while each element is in registers.  Results -- state, counters, the
+ * accumulated update, the send test, the models handed back -- are those of that many single steps, bit for bit; only
+ * m, theta and the third buffer are read and written once instead of once per delta (k deltas: 2k + 28 + 4k bytes per
+ * parameter instead of 30k, bf16 deltas with the model handed back).  The queue sentence of Sec. 4.1 is respected: a
+ * batch never reaches past a queued global model.
+ *   pull      non-zero: each update also writes the model right after it to its sender's registered buffer
+ *             (halos_lps_step_pull for every item)
+ *   infos     host array of max_items entries; entry i describes the i-th step taken
+ *   n_done    number of queue items handled: 0 (empty queue), 1 (a merge, or a single update: whenever fewer than two
+ *             deltas of one element type wait, or the server runs a momentum delay or the norm monitors, the call is
+ *             exactly halos_lps_step / halos_lps_step_pull), or the size of the batch
+ * Errors as for halos_lps_step_pull; nothing is modified on error.
+ */
+halos_status halos_lps_step_batch(halos_lps *lps, int32_t max_items, int32_t pull, void *stream, halos_step_info *infos,
+                                  int32_t *n_done);
+
+/*
  * The accumulated update of LPS `from` reaches the GPS (Algorithm 1, GPS block): one fused pass applies
  * ModelUpdate(Theta, G, eta_g, beta_g) and writes the new global model Theta_i over `from`'s third buffer,
  * where it stays frozen until `from` merges it -- later GPS updates do not change it.

@@ -87,6 +87,8 @@ def load_library():
         "halos_lps_step": [vp, vp, P(StepInfo)],
         "halos_lps_step_pull": [vp, vp, P(StepInfo)],
         "halos_lps_step_norms": [vp, vp, P(StepInfo), vp],
+        "halos_lps_step_average": [vp, i32, vp, P(StepInfo)],
+        "halos_lps_step_batch": [vp, i32, i32, vp, P(StepInfo), P(i32)],
         "halos_lps_set_worker_model": [vp, i32, P(vp), vp],
         "halos_gps_merge": [vp, vp, vp],
         "halos_pull_model": [vp, i32, P(vp), vp],
@@ -206,6 +208,25 @@ def halos_lps_step_pull(lps: int, stream=None) -> StepInfo:
     info = StepInfo()
     _check(load_library().halos_lps_step_pull(lps, _stream(stream), ctypes.byref(info)))
     return info
+
+
+def halos_lps_step_average(lps: int, count: int, stream=None) -> StepInfo:
+    info = StepInfo()
+    _check(load_library().halos_lps_step_average(lps, count, _stream(stream), ctypes.byref(info)))
+    return info
+
+
+def halos_lps_step_batch(lps: int, max_items: int, pull: bool = False, stream=None) -> list:
+    """The StepInfo of every step taken (possibly none)."""
+    infos = (StepInfo * 4)()
+    n = ctypes.c_int32()
+    _check(load_library().halos_lps_step_batch(lps, max_items, 1 if pull else 0, _stream(stream), infos, ctypes.byref(n)))
+    out = []
+    for i in range(n.value):
+        c = StepInfo()
+        ctypes.memmove(ctypes.byref(c), ctypes.byref(infos[i]), ctypes.sizeof(StepInfo))
+        out.append(c)
+    return out
 
 
 def halos_lps_step_norms(lps: int, norms_out, stream=None) -> StepInfo:

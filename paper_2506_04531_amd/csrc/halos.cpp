@@ -6,6 +6,7 @@
 
 #include <hip/hip_runtime_api.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdarg>
@@ -126,7 +127,9 @@ struct halos_lps {
     void *d_tables = nullptr;          // one allocation: [theta | m | acc] pointer tables
     float **d_theta = nullptr, **d_m = nullptr, **d_acc = nullptr;
     float **d_worker_model = nullptr;  // n_workers tables of n_tensors pointers, appended to d_tables
-    float **d_buffer = nullptr;        // gradient buffer of the delayed momentum (last table of d_tables; null until set)
+    float **d_buffer = nullptr;        // gradient buffer of the delayed momentum (a table of d_tables; null until set)
+    float **d_delta = nullptr;         // n_workers tables of delta pointers, for the passes that take several deltas
+    std::vector<std::vector<const void *>> delta_in_table;   // per worker: the pointer set its device table holds now
     MomentumCycle cycle;
     std::vector<char> worker_has_model;
     // update-norm monitors (HALOS_FLAG_NORMS): per-workgroup partial sums, then [ |g|^2 of the last update,
@@ -493,13 +496,15 @@ halos_status halos_lps_create(halos_gps *g, int32_t lps_id, int32_t n_workers, v
     l->validated_dtype.assign(n_workers, HALOS_F32);
     const size_t nt = g->numel.size();
     st = upload_tables(&l->d_tables, {(const void *const *)theta, (const void *const *)m, (const void *const *)acc}, nt,
-                       (size_t)n_workers + 1);
+                       2 * (size_t)n_workers + 1);
     if (st != HALOS_OK) { delete l; return st; }
     l->d_theta = (float **)l->d_tables;
     l->d_m = l->d_theta + nt;
     l->d_acc = l->d_m + nt;
     l->d_worker_model = l->d_acc + nt;
     l->d_buffer = l->d_worker_model + (size_t)n_workers * nt;
+    l->d_delta = l->d_buffer + nt;
+    l->delta_in_table.resize(n_workers);
     l->worker_has_model.assign(n_workers, 0);
     if (g->hp.flags & HALOS_FLAG_NORMS) {
         l->norm_partial_cap = (uint32_t)(g->ranges.size() ? g->ranges.size() : 1) * 64u * (uint32_t)g->n_cu;
@@ -729,6 +734,152 @@ halos_status halos_lps_step(halos_lps *l, void *stream, halos_step_info *info) {
 
 halos_status halos_lps_step_pull(halos_lps *l, void *stream, halos_step_info *info) {
     return lps_step_impl(l, stream, info, true);
+}
+
+namespace {
+
+// Can the first `count` queue items go through one multi-delta pass?  All must be plain deltas of one element type.
+bool multi_eligible(const halos_lps *l, int32_t count, bool pull) {
+    if (!l->proto.head_is_deltas(count)) return false;
+    const PendingDelta &first = l->pending[l->proto.item(0).worker];
+    for (int32_t i = 0; i < count; ++i) {
+        const int32_t w = l->proto.item(i).worker;
+        const PendingDelta &p = l->pending[w];
+        if (p.end_model || p.dtype != first.dtype) return false;
+        if (pull && !l->worker_has_model[w]) return false;
+    }
+    return true;
+}
+
+// Make worker w's device table of delta pointers hold the pointer set it has queued (rewritten in stream order if it
+// holds another), and return the table.
+halos_status delta_table(halos_lps *l, int32_t w, hipStream_t stream, const float *const **out) {
+    const size_t nt = l->gps->numel.size();
+    float **tab = l->d_delta + (size_t)w * nt;
+    const PendingDelta &p = l->pending[w];
+    std::vector<const void *> &held = l->delta_in_table[w];
+    if (held.size() != nt || std::memcmp(held.data(), p.ptrs.data(), nt * sizeof(void *)) != 0) {
+        halos_status st = store_table(stream, tab, p.ptrs.data(), nt);
+        if (st != HALOS_OK) return st;
+        held = p.ptrs;
+    }
+    *out = tab;
+    return HALOS_OK;
+}
+
+int grad_kind(halos_dtype d) { return d == HALOS_BF16 ? GRAD_BF16 : (d == HALOS_F16 ? GRAD_F16 : GRAD_F32); }
+
+}  // namespace
+
+halos_status halos_lps_step_average(halos_lps *l, int32_t count, void *stream, halos_step_info *info) {
+    if (!live_lps(l)) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    if (count < 1 || count > MAX_MULTI) return fail(HALOS_EINVAL, "count = %d outside 1..%d", count, MAX_MULTI);
+    halos_gps *g = l->gps;
+    if (l->cycle.d() > 1) return fail(HALOS_ESTATE, "lps %d: the averaged step is not available under a momentum delay", l->id);
+    if (l->d_norm_partials) return fail(HALOS_ESTATE, "lps %d: the averaged step does not feed the norm monitors", l->id);
+    if (!multi_eligible(l, count, false))
+        return fail(HALOS_ESTATE, "lps %d: the first %d queue items are not %d worker deltas of one element type", l->id, count, count);
+    halos_status st = check_device(g);
+    if (st != HALOS_OK) return st;
+    const UpdateOutcome oc = l->proto.preview_update();
+    MultiArgs a{};
+    a.n_in = count;
+    a.n_acc = oc.accumulate ? 1 : 0;
+    halos_dtype dtype = HALOS_F32;
+    int32_t last_worker = -1;
+    for (int32_t i = 0; i < count; ++i) {
+        const int32_t w = l->proto.item(i).worker;
+        st = delta_table(l, w, (hipStream_t)stream, &a.delta[i]);
+        if (st != HALOS_OK) return st;
+        a.w[i] = l->pending[w].weight;
+        dtype = l->pending[w].dtype;
+        last_worker = w;
+    }
+    const int third_mode = l->snapshot ? (oc.freezes ? THIRD_FREEZE_SNAPSHOT : THIRD_NONE)
+                         : (oc.accumulate ? (l->third_stale ? THIRD_RESTART : THIRD_ADD) : THIRD_NONE);
+    const LaunchShape shape = current_shape(g);
+    const float inv_n = 1.0f / (float)count;
+    for (const TileRange &r : g->ranges) {
+        hipError_t e = launch_lps_update_multi((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_acc, a, true,
+                                               grad_kind(dtype), third_mode, l->rule.eta, l->rule.beta, l->rule.cg, inv_n, shape);
+        if (e != hipSuccess) return fail_hip(e, "launching the averaged update");
+    }
+    l->proto.commit_average(count);
+    if (third_mode == THIRD_RESTART) l->third_stale = false;
+    if (info) {
+        halos_step_info out{};
+        out.kind = 1;
+        out.worker = last_worker;
+        out.accumulated = oc.accumulate ? 1 : 0;
+        out.delta_ready = oc.freezes ? 1 : 0;
+        out.t = l->proto.t();
+        out.t_last = l->proto.t_last();
+        *info = out;
+    }
+    return HALOS_OK;
+}
+
+halos_status halos_lps_step_batch(halos_lps *l, int32_t max_items, int32_t pull, void *stream, halos_step_info *infos,
+                                  int32_t *n_done) {
+    if (!live_lps(l)) return fail(HALOS_EINVAL, "lps is not a valid handle");
+    if (max_items < 1 || max_items > MAX_MULTI) return fail(HALOS_EINVAL, "max_items = %d outside 1..%d", max_items, MAX_MULTI);
+    if (!infos || !n_done) return fail(HALOS_EINVAL, "infos / n_done is NULL");
+    *n_done = 0;
+    halos_gps *g = l->gps;
+    // the longest run of plain deltas of one element type at the head of the queue
+    int32_t count = 0;
+    if (l->cycle.d() == 1 && !l->d_norm_partials)
+        for (int32_t c = std::min<int32_t>(max_items, l->proto.queued()); c >= 2 && count == 0; --c)
+            if (multi_eligible(l, c, pull != 0)) count = c;
+    if (count < 2) {                    // nothing to batch: one ordinary step
+        const QueueItem head = l->proto.head();
+        halos_status st = lps_step_impl(l, stream, &infos[0], pull != 0 && head.kind == ITEM_DELTA);
+        if (st == HALOS_OK && infos[0].kind != 0) *n_done = 1;
+        return st;
+    }
+    halos_status st = check_device(g);
+    if (st != HALOS_OK) return st;
+    // what each of the updates will mean for the accumulated update, on a copy of the protocol state
+    LpsProtocol sim = l->proto;
+    MultiArgs a{};
+    a.n_in = count;
+    halos_step_info out[MAX_MULTI];
+    int32_t n_acc = 0, freeze_at = 0;
+    halos_dtype dtype = HALOS_F32;
+    const size_t nt = g->numel.size();
+    for (int32_t i = 0; i < count; ++i) {
+        const int32_t w = sim.head().worker;
+        const UpdateOutcome oc = sim.preview_update();
+        sim.commit_update();
+        if (oc.accumulate) n_acc = i + 1;
+        if (oc.freezes) freeze_at = i + 1;
+        st = delta_table(l, w, (hipStream_t)stream, &a.delta[i]);
+        if (st != HALOS_OK) return st;
+        a.pull[i] = pull ? l->d_worker_model + (size_t)w * nt : nullptr;
+        a.w[i] = l->pending[w].weight;
+        dtype = l->pending[w].dtype;
+        out[i] = halos_step_info{};
+        out[i].kind = 1;
+        out[i].worker = w;
+        out[i].accumulated = oc.accumulate ? 1 : 0;
+        out[i].delta_ready = oc.freezes ? 1 : 0;
+        out[i].t = sim.t();
+        out[i].t_last = sim.t_last();
+    }
+    int third_mode;
+    if (l->snapshot) { third_mode = freeze_at ? THIRD_FREEZE_SNAPSHOT : THIRD_NONE; a.n_acc = freeze_at; }
+    else { third_mode = n_acc ? (l->third_stale ? THIRD_RESTART : THIRD_ADD) : THIRD_NONE; a.n_acc = n_acc; }
+    const LaunchShape shape = current_shape(g);
+    for (const TileRange &r : g->ranges) {
+        hipError_t e = launch_lps_update_multi((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_acc, a, false,
+                                               grad_kind(dtype), third_mode, l->rule.eta, l->rule.beta, l->rule.cg, 1.0f, shape);
+        if (e != hipSuccess) return fail_hip(e, "launching the batched update");
+    }
+    l->proto = sim;
+    if (third_mode == THIRD_RESTART) l->third_stale = false;
+    for (int32_t i = 0; i < count; ++i) infos[i] = out[i];
+    *n_done = count;
+    return HALOS_OK;
 }
 
 halos_status halos_lps_step_norms(halos_lps *l, void *stream, halos_step_info *info, double *norms_out) {

@@ -62,6 +62,28 @@ hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r,
                              float *const *acc, float *const *pull, const PtrArgs &g, int g_kind, int third_mode,
                              float eta, float beta, float cg, float gw, double *norm_partials, LaunchShape shape);
 
+// Several worker deltas in ONE pass over the server's state.  The deltas are found through device pointer tables (one per
+// delta: table[tensor] is that delta's tensor), because several lists of pointers do not fit a kernel-argument block.
+//   sequential (average = false): the n_in deltas are applied one after the other, in order, to each element while it
+//       is in registers -- the same operations in the same order as n_in single passes, but m, theta and the third
+//       buffer are read and written once.  The first n_acc of them count towards the accumulated update (n_acc = 0:
+//       none; under third_mode THIRD_FREEZE_SNAPSHOT the n_acc-th completes it).  pull[i], if not null, receives the
+//       model right after delta i was applied (that worker's next start model).
+//   average (average = true): ONE ModelUpdate with (w_0 g_0 + ... + w_{n-1} g_{n-1}) * inv_n, added in that order;
+//       n_acc is 1 if the update counts, 0 if not; pull tables are ignored.
+// dtype of all deltas: GRAD_F32, GRAD_BF16 or GRAD_F16.  Always non-temporal; no norm monitors.
+constexpr int MAX_MULTI = 4;
+struct MultiArgs {
+    const float *const *delta[MAX_MULTI];    // device tables of n_tensors pointers each (element type per g_kind)
+    float *const *pull[MAX_MULTI];           // device tables, or null
+    float w[MAX_MULTI];                      // the callers' scalars on the deltas
+    int32_t n_in;                            // 2..MAX_MULTI (1 is allowed)
+    int32_t n_acc;
+};
+hipError_t launch_lps_update_multi(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
+                                   float *const *acc, const MultiArgs &a, bool average, int g_kind, int third_mode,
+                                   float eta, float beta, float cg, float inv_n, LaunchShape shape);
+
 // Number of workgroups a launch over range r uses (0 for an empty range).
 uint32_t launch_grid_size(TileRange r, LaunchShape shape);
 

@@ -4,6 +4,7 @@
 // item 2).  Pure C++, no device code: everything here is integers.
 #pragma once
 
+#include <cstddef>
 #include <cstdint>
 #include <deque>
 #include <vector>
@@ -85,6 +86,23 @@ public:
         QueueItem it = queue_.front();
         queue_.pop_front();
         worker_queued_[it.worker] = 0;
+        t_ += 1;
+        if (o.freezes) phase_ = PHASE_SENT;
+    }
+
+    // An averaged step: the first `count` items (all deltas) become ONE update with their mean.
+    bool head_is_deltas(int32_t count) const {
+        if (count < 1 || (std::size_t)count > queue_.size()) return false;
+        for (int32_t i = 0; i < count; ++i) if (queue_[i].kind != ITEM_DELTA) return false;
+        return true;
+    }
+    QueueItem item(int32_t i) const { return queue_[i]; }
+    void commit_average(int32_t count) {
+        UpdateOutcome o = preview_update();
+        for (int32_t i = 0; i < count; ++i) {
+            worker_queued_[queue_.front().worker] = 0;
+            queue_.pop_front();
+        }
         t_ += 1;
         if (o.freezes) phase_ = PHASE_SENT;
     }

@@ -160,6 +160,7 @@ class Cluster:
         self.hp = hp if hp is not None else B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0],
                                                                  cg_l=w.cg_l, cg_g=w.cg_g)
         self.snapshot = bool(self.hp.flags & B.FLAG_SNAPSHOT)
+        self.defer_clear = bool(self.hp.flags & B.FLAG_DEFER_CLEAR)
         self.Theta = mk(role="Theta")
         self.M = None if self.hp.flags & B.FLAG_GPS_NO_MOMENTUM else mk(role="M")      # a momentum-free GPS has no M at all
         fill_initial_model(w, self.Theta)
@@ -211,11 +212,14 @@ class Cluster:
             self.region_arena = None
 
     # ------------------------------------------------------------------ replay
-    def replay(self, events: np.ndarray, timed: bool = False, fuse_pull: bool = False):
+    def replay(self, events: np.ndarray, timed: bool = False, fuse_pull: bool = False, batch: int = 0):
         """Issue every record through the C ABI, in order, on the current stream.
 
         fuse_pull: an update step that is directly followed by the pull of the same worker is issued as one
         halos_lps_step_pull call (same results, one pass less).
+        batch (2..4, needs fuse_pull): update steps of one server that follow each other directly in the trace (each with
+        its pull; events of other servers in between do not touch this server's state) are issued as one
+        halos_lps_step_batch call (same results; the server's state is read and written once for all of them).
 
         Returns (step_log, timings): step_log has one tuple (record index, kind, t, t_last, delta_ready,
         accumulated) per LPS step; timings (only if timed) maps a kernel label to a list of
@@ -230,8 +234,18 @@ class Cluster:
         fuse_pull = fuse_pull and self._pull_ptrs is not None
         weighted = self.w.staleness_exponent > 0.0
         skip = -1
+        consumed = set()
+        batch = batch if (fuse_pull and self.w.d_l == 1 and batch >= 2) else 0
+        infos = (B.StepInfo * 4)()
+        n_done = ctypes.c_int32()
         info = B.StepInfo()
         k_now = [None] * len(self.lps)
+        # under deferred clearing: has this server merged and not accumulated since? (labels only; the library keeps its own state)
+        restart = [False] * len(self.lps)
+        if self.defer_clear:
+            for j, hh in enumerate(self.lps):
+                cnt = B.halos_lps_get_counters(hh)
+                restart[j] = cnt["phase"] == B.PHASE_ACCUMULATING and cnt["t"] == cnt["t_last"] and cnt["t"] > 0
         seen_l = [B.halos_lps_get_momentum_delay(h)["seen"] for h in self.lps]
         seen_g = B.halos_gps_get_momentum_delay(self.gps)["seen"]
 
@@ -246,8 +260,37 @@ class Cluster:
             return rc
 
         n_ev = len(events)
+
+        def following_steps(i, l, limit):
+            """Record indices of the update steps of server l that follow step i directly: l's own events after i must read
+            pull, step, pull, step, ... (each pull for the worker of the step before it)."""
+            group, want_pull, worker = [i], True, int(events[i]["worker"])
+            pulls = []
+            j = i + 1
+            while j < n_ev and len(group) <= limit:
+                e2 = events[j]
+                if int(e2["lps"]) != l:
+                    j += 1
+                    continue
+                k2 = int(e2["kind"])
+                if want_pull:
+                    if k2 != _PULL or int(e2["worker"]) != worker:
+                        return None if not pulls else (group[:len(pulls)], pulls)
+                    pulls.append(j)
+                    want_pull = False
+                    if len(group) == limit:
+                        break
+                else:
+                    if k2 != _LPS_STEP or int(e2["exp_kind"]) != 1 or int(e2["k_cur"]) != int(events[i]["k_cur"]):
+                        break
+                    group.append(j)
+                    worker = int(e2["worker"])
+                    want_pull = True
+                j += 1
+            return (group[:len(pulls)], pulls) if pulls else None
+
         for i in range(n_ev):
-            if i == skip:
+            if i == skip or i in consumed:
                 continue
             ev = events[i]
             kind, l = int(ev["kind"]), int(ev["lps"])
@@ -266,12 +309,15 @@ class Cluster:
                     k_now[l] = k
                 fused = False
                 if int(ev["exp_kind"]) == 2:
-                    label = "lps_merge"
+                    label = "lps_merge_leave" if self.defer_clear else "lps_merge"
+                    restart[l] = self.defer_clear
                 else:
                     if self.snapshot:      # third buffer untouched except by the update that completes the accumulation
                         label = "lps_update_freeze" if int(ev["exp_send"]) else "lps_update_noacc"
                     else:
                         label = "lps_update_acc" if int(ev["exp_accumulate"]) else "lps_update_noacc"
+                        if restart[l] and int(ev["exp_accumulate"]):
+                            label, restart[l] = "lps_update_restart", False      # stores 0 + step: the third buffer is not read
                     if self.w.d_l > 1:      # delayed momentum: an update that refreshes the momentum moves more bytes
                         seen = seen_l[l]
                         label += "_refresh" if seen + 1 == self.w.d_l else ("_first" if seen == 0 else "")
@@ -279,6 +325,20 @@ class Cluster:
                     if fuse_pull and i + 1 < n_ev:
                         nx = events[i + 1]
                         fused = (int(nx["kind"]) == _PULL and int(nx["lps"]) == l and int(nx["worker"]) == int(ev["worker"]))
+                    grp = following_steps(i, l, batch) if batch else None
+                    if grp is not None and len(grp[0]) >= 2:
+                        steps, pulls = grp
+                        any_acc = any(int(events[j]["exp_accumulate"]) for j in steps)
+                        blabel = f"lps_update_batch{len(steps)}_{'acc' if any_acc else 'noacc'}_pull"
+                        chk(bracket(blabel, lambda: lib.halos_lps_step_batch(h, len(steps), 1, sp, infos, ctypes.byref(n_done))))
+                        assert n_done.value == len(steps), (n_done.value, len(steps))
+                        for j, inf in zip(steps, infos):
+                            log.append((j, inf.kind, inf.t, inf.t_last, inf.delta_ready, inf.accumulated))
+                            if restart[l] and inf.accumulated:
+                                restart[l] = False
+                        consumed.update(steps[1:])
+                        consumed.update(pulls)
+                        continue
                 if fused:
                     skip = i + 1
                     chk(bracket(label + "_pull", lambda: lib.halos_lps_step_pull(h, sp, ctypes.byref(info))))
@@ -286,7 +346,7 @@ class Cluster:
                     chk(bracket(label, lambda: lib.halos_lps_step(h, sp, ctypes.byref(info))))
                 log.append((i, info.kind, info.t, info.t_last, info.delta_ready, info.accumulated))
             elif kind == _GPS_MERGE:
-                glabel = "gps_update"
+                glabel = "gps_update_nomom" if self.M is None else "gps_update"
                 if self.w.d_g > 1:
                     glabel += "_refresh" if seen_g + 1 == self.w.d_g else ("_first" if seen_g == 0 else "")
                     seen_g = (seen_g + 1) % self.w.d_g
@@ -298,6 +358,7 @@ class Cluster:
                     chk(bracket("pull", lambda: lib.halos_pull_model(h, 0, self._pull_ptrs[l], sp)))
             else:
                 raise ValueError(f"unknown event kind {kind}")
+        log.sort(key=lambda rec: rec[0])          # batched steps were logged ahead of other servers' steps
         return log, (dict(timings) if timed else None)
 
     # ------------------------------------------------------------------ inspection

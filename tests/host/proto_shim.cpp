@@ -35,6 +35,16 @@ int proto_step(void *p, long long *out) {
     out[4] = s->t(); out[5] = s->t_last();
     return 0;
 }
+// averaged step over the first `count` items: -1 if they are not all deltas; out as in proto_step (worker = the last sender)
+int proto_step_average(void *p, int count, long long *out) {
+    LpsProtocol *s = (LpsProtocol *)p;
+    if (!s->head_is_deltas(count)) return -1;
+    halos::UpdateOutcome o = s->preview_update();
+    out[0] = halos::ITEM_DELTA; out[1] = s->item(count - 1).worker; out[2] = o.accumulate; out[3] = o.freezes;
+    s->commit_average(count);
+    out[4] = s->t(); out[5] = s->t_last();
+    return 0;
+}
 int proto_consume(void *p) {
     LpsProtocol *s = (LpsProtocol *)p;
     int rc = s->can_consume();

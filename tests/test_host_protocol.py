@@ -22,6 +22,7 @@ def shim(tmp_path_factory):
               "proto_phase", "proto_queued"):
         getattr(lib, f).argtypes = [ctypes.c_void_p] + {"proto_set_K": [ctypes.c_int], "proto_push_delta": [ctypes.c_int],
                                                          "proto_step": [ctypes.POINTER(ctypes.c_longlong)]}.get(f, [])
+    lib.proto_step_average.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_longlong)]
     lib.cycle_new.restype = ctypes.c_void_p
     for f in ("cycle_free", "cycle_set_d", "cycle_next", "cycle_commit", "cycle_seen", "cycle_d"):
         getattr(lib, f).argtypes = [ctypes.c_void_p] + ([ctypes.c_int] if f == "cycle_set_d" else [])
@@ -112,3 +113,30 @@ def test_momentum_cycle_positions(shim):
         assert [shim.cycle_next(c), shim.cycle_commit(c), shim.cycle_next(c)][::2] == [FIRST, REFRESH]
     finally:
         shim.cycle_free(c)
+
+
+def test_averaged_step_counts_as_one_update(shim):
+    """n deltas averaged: t advances by one, every sender may send again, the send test sees one update, and a queued
+    global model is never stepped over."""
+    p = shim.proto_new(4, 2)
+    out = (ctypes.c_longlong * 6)()
+    assert shim.proto_step_average(p, 1, out) == -1                 # empty queue
+    for w in range(3):
+        assert shim.proto_push_delta(p, w) == OK
+    assert shim.proto_step_average(p, 4, out) == -1                 # only three queued
+    assert shim.proto_step_average(p, 3, out) == 0
+    assert list(out) == [1, 2, 1, 0, 1, 0]
+    assert shim.proto_queued(p) == 0
+    for w in range(4):
+        assert shim.proto_push_delta(p, w) == OK                    # all senders free again
+    assert shim.proto_step_average(p, 2, out) == 0
+    assert list(out) == [1, 1, 1, 1, 2, 0]                          # second UPDATE reaches K = 2 (five deltas so far)
+    assert shim.proto_phase(p) == 1
+    assert shim.proto_consume(p) == OK and shim.proto_push_global(p) == OK
+    assert shim.proto_push_delta(p, 0) == OK                        # queue: delta 2, delta 3, global, delta 0
+    assert shim.proto_step_average(p, 3, out) == -1                 # the global model is third in line
+    assert shim.proto_step_average(p, 2, out) == 0
+    assert list(out) == [1, 3, 0, 0, 3, 0]                          # in flight: applied, not accumulated
+    assert _step(shim, p) == [2, -1, 0, 0, 3, 3]
+    assert shim.proto_step_average(p, 1, out) == 0 and list(out) == [1, 0, 1, 0, 4, 3]
+    shim.proto_free(p)
