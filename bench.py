@@ -46,6 +46,8 @@ def bytes_per_param(label: str, delta_dtype: str, delayed: bool) -> int:
                     "lps_merge_leave" does not clear (12), and the "restart" update after it writes the third buffer
                     without reading it (4 less than "acc").
       gps_update_nomom  no momentum array at all: read G, Theta; write Theta and the returned model (16).
+      lps_update_batchK_*  K queued deltas in one pass: K deltas read, K worker models written, momentum, model and
+                    (if any of them accumulates) the third buffer read and written once.
       pull          read and write a model (8).
     """
     if label == "lps_merge":
@@ -57,6 +59,10 @@ def bytes_per_param(label: str, delta_dtype: str, delayed: bool) -> int:
     if label == "pull":
         return 8
     parts = label.split("_")
+    if label.startswith("lps_update_batch"):
+        k = int(parts[2][len("batch"):])
+        g = 4 if delta_dtype == "f32" else 2
+        return k * g + 16 + (0 if "noacc" in parts else 8) + 4 * k
     if delayed:
         rule = 4 if "first" in parts else (12 if "refresh" in parts else 8)
     else:
@@ -64,7 +70,7 @@ def bytes_per_param(label: str, delta_dtype: str, delayed: bool) -> int:
     if label.startswith("gps_update"):
         return 16 + rule
     assert label.startswith("lps_update"), label
-    g = 2 if delta_dtype == "bf16" else 4
+    g = 4 if delta_dtype == "f32" else 2
     third = 0 if "noacc" in parts else (4 if "restart" in parts else 8)
     return g + 8 + third + rule + (4 if "pull" in parts else 0)
 
@@ -108,7 +114,7 @@ def split_steps(events, n_updates_per_step: int, n_steps: int):
 
 
 def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: str = "regions", fuse_pull: bool = True,
-                 snapshot: bool = False, defer_clear: bool = False, gps_no_momentum: bool = False):
+                 snapshot: bool = False, defer_clear: bool = False, gps_no_momentum: bool = False, batch: int = 0):
     import numpy as np
     import torch
     import synth
@@ -130,16 +136,17 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
     c = Cluster(w, "cuda:0", k_initial=trace.k_initial, placement=placement, verbose=verbose, hp=hp)
     n_regions = c.region_arena.n_regions if c.region_arena is not None else 0
     if verbose:
+        free_b, total_b = torch.cuda.mem_get_info()
         print(f"[bench] {name}: N={N} tensors={w.layout.n_tensors} state resident after {time.time() - t0:.1f}s, "
-              f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB", file=sys.stderr, flush=True)
+              f"{(total_b - free_b) / 2**30:.1f} GiB of device memory in use", file=sys.stderr, flush=True)
     try:
         for s in range(warmup):
-            c.replay(slices[s], fuse_pull=fuse_pull)
+            c.replay(slices[s], fuse_pull=fuse_pull, batch=batch)
         torch.cuda.synchronize()
         t_start = time.perf_counter()
         timings = {}
         for s in range(warmup, warmup + steps):
-            log, tm = c.replay(slices[s], timed=True, fuse_pull=fuse_pull)
+            log, tm = c.replay(slices[s], timed=True, fuse_pull=fuse_pull, batch=batch)
             for k, v in tm.items():
                 timings.setdefault(k, []).extend(v)
         torch.cuda.synchronize()
@@ -167,20 +174,24 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
             "total_ms": float(ms.sum()),
         }
     upd_labels = [k for k in kernels if k.startswith("lps_update")]
-    n_upd = sum(kernels[k]["launches"] for k in upd_labels)
+    per_launch = lambda k: int(k.split("_")[2][len("batch"):]) if k.startswith("lps_update_batch") else 1
+    n_upd = sum(kernels[k]["launches"] * per_launch(k) for k in upd_labels)
     n_pull_events = kernels.get("pull", {}).get("launches", 0) + sum(
-        kernels[k]["launches"] for k in upd_labels if k.endswith("_pull"))
+        kernels[k]["launches"] * per_launch(k) for k in upd_labels if k.endswith("_pull"))
     n_gps = sum(v["launches"] for k, v in kernels.items() if k.startswith("gps_update"))
-    n_mrg = kernels.get("lps_merge", {}).get("launches", 0)
+    n_mrg = sum(v["launches"] for k, v in kernels.items() if k.startswith("lps_merge"))
     updates = n_upd + n_gps + n_mrg
     value = N * updates / elapsed
     # dominant kernel: the LPS update variant that takes the most time
     dom = max(upd_labels, key=lambda k: kernels[k]["total_ms"])
     traffic = MEASURED_TRAFFIC.get(kernels_digest(), {}).get(f"{name}:{dom}")
+    traffic_source = ("stored: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/, valid for the "
+                      "kernel source with this sha256 only" if traffic is not None else
+                      "none: the kernel source has changed since the counters under profiles/ were taken")
     roofline = {
         "bound": "hbm", "kernel": dom, "achieved": kernels[dom]["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": kernels[dom]["achieved_GBps"] / HBM_PEAK_GBS,
-        "traffic": (traffic * N) if traffic is not None else None,
+        "traffic": (traffic * N) if traffic is not None else None, "traffic_source": traffic_source,
         "algorithmic_bytes_per_launch": N * kernels[dom]["bytes_per_param"],
         "avg_launch_ms": kernels[dom]["avg_ms"],
     }
@@ -196,7 +207,7 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
         "whole_path_frac_of_peak": total_bytes / elapsed / 1e9 / HBM_PEAK_GBS,
         "kernels": kernels, "roofline": roofline, "placement": placement, "hbm_regions_found": n_regions,
         "fuse_pull": fuse_pull, "delta_form": "snapshot" if snapshot else "accumulator",
-        "defer_clear": defer_clear, "gps_no_momentum": gps_no_momentum,
+        "defer_clear": defer_clear, "gps_no_momentum": gps_no_momentum, "batch": batch,
         "momentum_delay": {"d_l": w.d_l, "d_g": w.d_g},
     }
 
@@ -325,12 +336,15 @@ def graph_ab(reps: int = 300):
 
 
 def cpu_baseline(name: str, budget_elements: int = 1 << 22):
-    """Time the CPU oracle (fp64, literal form, single thread) on a bounded sample: every event of one
-    workload-sized trace, on `budget_elements` evenly spaced parameters of the workload."""
+    """Time the CPU oracle, as it stands, on a bounded sample: every event of one workload-sized trace, on
+    `budget_elements` evenly spaced parameters of the workload, single thread.  `value` is the canonical figure (fp64,
+    literal form: whole replay, wall clock around the replay loop, the Python-side hand-over of deltas included);
+    `per_event` is the time inside the oracle's own C++ handlers per event type (its stopwatch), in fp64 and in the fp32
+    same-order form, so that each GPU kernel has the oracle's figure for the same event beside it."""
     import numpy as np
     import torch
     import synth
-    from oracle import FORM_LITERAL, HalosOracle
+    from oracle import FORM_ACCUMULATOR, FORM_LITERAL, HalosOracle
     from oracle.replay import replay
     from synth.tensors import scale_f32
 
@@ -345,28 +359,44 @@ def cpu_baseline(name: str, budget_elements: int = 1 << 22):
     pool = {}
     for s in range(w.pool_slots):
         g = synth.normal_at(w.seed, 1 + s, tidx, scale)
-        pool[s] = synth.to_bf16_bits(g).numpy() if w.delta_dtype == "bf16" else g.numpy()
-    o = HalosOracle(theta0, w.n_lps, eta_l=w.eta_l, beta_l=w.beta_l, eta_g=w.eta_g, beta_g=w.beta_g, alpha=w.alpha,
-                    K=trace.k_initial, precision=64, form=FORM_LITERAL)
-    if w.d_l > 1:
-        for l in range(w.n_lps):
-            o.set_delay(l, w.d_l)
-    if w.d_g > 1:
-        o.set_delay(-1, w.d_g)
+        pool[s] = (synth.to_bf16_bits(g).numpy() if w.delta_dtype == "bf16" else
+                   synth.to_f16(g).numpy() if w.delta_dtype == "f16" else g.numpy())
     ev = trace.events
     ev = ev[ev["kind"] != synth.EV_PULL]          # the oracle's pull is a host copy for tests, not timed work
-    t0 = time.perf_counter()
-    log = replay(o, ev, lambda s: pool[s])
-    dt = time.perf_counter() - t0
-    updates = len(log) + trace.count(synth.EV_GPS_MERGE)
-    return {
-        "value": n_s * updates / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
-        "sample": f"{n_s} evenly spaced parameters of the {name} workload, all {updates} update/merge events of one "
-                  f"trace (fp64, single thread, {dt:.1f} s); host has {os.cpu_count()} logical cores",
-    }
+    g_bytes = 4 if w.delta_dtype == "f32" else 2
+    # algorithmic bytes per parameter of the same events in fp32 state (what the GPU kernels are charged); fp64 state doubles the state part
+    alg = {"lps_update": g_bytes + 24, "gps_update": 24, "lps_merge": 16}
+    out, per_event = None, {}
+    for precision, form, tag in ((64, FORM_LITERAL, "f64"), (32, FORM_ACCUMULATOR, "f32")):
+        o = HalosOracle(theta0, w.n_lps, eta_l=w.eta_l, beta_l=w.beta_l, eta_g=w.eta_g, beta_g=w.beta_g, alpha=w.alpha,
+                        K=trace.k_initial, precision=precision, form=form)
+        if w.d_l > 1:
+            for l in range(w.n_lps):
+                o.set_delay(l, w.d_l)
+        if w.d_g > 1:
+            o.set_delay(-1, w.d_g)
+        t0 = time.perf_counter()
+        log = replay(o, ev, lambda s: pool[s])
+        dt = time.perf_counter() - t0
+        updates = len(log) + trace.count(synth.EV_GPS_MERGE)
+        for kind, (sec, calls) in o.stopwatch().items():
+            if calls:
+                per_event.setdefault(kind, {})[tag] = {
+                    "events": calls, "params_per_s": n_s * calls / sec,
+                    "GBps_fp32_algorithmic": n_s * calls * alg[kind] / sec / 1e9}
+        if precision == 64:
+            out = {"value": n_s * updates / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
+                   "sample": f"{n_s} evenly spaced parameters of the {name} workload, all {updates} update/merge events of one "
+                             f"trace (fp64, literal form, single thread, {dt:.1f} s wall clock including the hand-over of every "
+                             f"delta); host has {os.cpu_count()} logical cores"}
+        o.close()
+    out["per_event"] = per_event
+    out["per_event_note"] = ("time inside the oracle's own loops per event type (stopwatch in the C++ handlers, no Python), fp64 literal "
+                             "form and fp32 same-order form; GB/s counts the fp32 algorithmic bytes of the event, as for the GPU kernels")
+    return out
 
 
-def ceilings_mode(gib: float, reps: int):
+def ceilings_mode(gib: float, reps: int, quick: bool = False):
     """`bench.py --ceilings`: what this device's memory system delivers to plain streaming kernels, by HBM region.
 
     Places buffers in each HBM region the library's arena finds, then times halos_probe_streams (read some buffers,
@@ -397,6 +427,15 @@ def ceilings_mode(gib: float, reps: int):
         bufs = list(reads) + list(writes)
         ptrs = [b.data_ptr() + (shift[i] if shift else 0) for i, b in enumerate(bufs)]
         return B.halos_probe_streams(ptrs[:len(reads)], ptrs[len(reads):], nbytes, reps, unroll)
+
+    if quick:       # three patterns only, one kernel each: for counter runs (rocprofv3 --pmc), where every dispatch is listed
+        for name, rd, wr in (("4 reads, one region", X[:4], []), ("4 writes over three regions", [], [X[4], Y[4], Z[4], X[5]]),
+                             ("4 reads + 4 writes, the benchmark's placement", [X[0], X[1], X[2], Y[0]], [X[4], X[5], Y[4], Z[4]])):
+            v = run(rd, wr)
+            print(f"{name:60s} {v:8.0f} GB/s {v / HBM_PEAK_GBS:7.1%}")
+        del X, Y, Z
+        arena.close()
+        return
 
     def table(title, rows):
         print(f"\n{title}")
@@ -541,6 +580,11 @@ def main():
                     help="merges leave the third buffer (12 B/parameter instead of 16); the next update restarts it")
     ap.add_argument("--gps-no-momentum", action="store_true",
                     help="the global server keeps no momentum (beta_g = 0, Sec. 5.4): 16 B/parameter per GPS update instead of 24")
+    ap.add_argument("--batch", type=int, default=4,
+                    help="2..4: update steps of one server that follow each other directly go through one pass "
+                         "(halos_lps_step_batch; same results bit for bit); 0 = every step its own pass")
+    ap.add_argument("--no-plain-placement", action="store_true",
+                    help="skip the second run of the headline workload with ordinary allocations instead of the region-sorted arena")
     ap.add_argument("--no-end-model-ab", action="store_true",
                     help="skip the A/B of the update pass fed a delta vs fed the worker's end model")
     ap.add_argument("--no-graph-ab", action="store_true",
@@ -551,6 +595,7 @@ def main():
                          "(reads, writes, the update pass's mix; by region, tile size, grid size and start offsets)")
     ap.add_argument("--ceilings-gib", type=float, default=1.0, help="buffer size for --ceilings")
     ap.add_argument("--ceilings-reps", type=int, default=5)
+    ap.add_argument("--ceilings-quick", action="store_true", help="with --ceilings: only pure reads, pure writes and the update pass's mix")
     ap.add_argument("--placement-search", action="store_true",
                     help="instead of the benchmark: time the fused update pass for every assignment of its arrays to the HBM regions")
     ap.add_argument("--search-elements", type=int, default=1 << 29)
@@ -571,15 +616,21 @@ def main():
     if args.blocks_per_cu or args.nontemporal >= 0:
         halos.halos_set_launch_config(args.blocks_per_cu, args.nontemporal)
     if args.ceilings:
-        return ceilings_mode(args.ceilings_gib, args.ceilings_reps)
+        return ceilings_mode(args.ceilings_gib, args.ceilings_reps, args.ceilings_quick)
     if args.placement_search:
         return placement_search_mode(args.search_elements, args.search_dtype)
 
-    variant = dict(snapshot=args.snapshot, defer_clear=args.defer_clear, gps_no_momentum=args.gps_no_momentum)
+    variant = dict(snapshot=args.snapshot, defer_clear=args.defer_clear, gps_no_momentum=args.gps_no_momentum, batch=args.batch)
     head = run_workload(args.workload, args.steps, args.warmup, not args.quiet, args.placement, not args.no_fuse_pull, **variant)
     others = []
     for name in [x for x in args.also.split(",") if x and x != args.workload]:
         others.append(run_workload(name, args.steps, args.warmup, not args.quiet, args.placement, not args.no_fuse_pull, **variant))
+    plain = None
+    if args.placement == "regions" and not args.no_plain_placement:      # what a caller with ordinary allocations gets
+        r = run_workload(args.workload, args.steps, args.warmup, not args.quiet, "plain", not args.no_fuse_pull, **variant)
+        plain = {"placement": "plain", "value": r["params_updated_per_s"], "ms_per_step": r["ms_per_step"],
+                 "whole_path_GBps": r["whole_path_GBps"], "roofline": r["roofline"],
+                 "note": "same workload, every tensor an ordinary allocation of the framework's caching allocator"}
     ab = None if args.no_end_model_ab else end_model_ab(args.workload, verbose=not args.quiet)
     gab = None if args.no_graph_ab else graph_ab()
     cpu = None if args.no_cpu_baseline else cpu_baseline(args.workload)
@@ -597,9 +648,10 @@ def main():
                    "delta_dtype": head["delta_dtype"], "events_per_step": head["events_per_step"],
                    "placement": head["placement"], "hbm_regions_found": head["hbm_regions_found"],
                    "fuse_pull": head["fuse_pull"], "delta_form": head["delta_form"],
-                   "defer_clear": head["defer_clear"], "gps_no_momentum": head["gps_no_momentum"],
+                   "defer_clear": head["defer_clear"], "gps_no_momentum": head["gps_no_momentum"], "batch": head["batch"],
                    "momentum_delay": head["momentum_delay"]},
         "roofline": head["roofline"],
+        "plain_placement": plain,
         "cpu_baseline": cpu,
         "whole_path_GBps": head["whole_path_GBps"],
         "kernels": head["kernels"],

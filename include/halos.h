@@ -24,6 +24,11 @@
  *                its stream, a pull destination until that copy has finished.
  *                The library allocates only small tables and frees them in the
  *                destroy calls.  It never frees caller memory.
+ *                A set of delta / destination pointers is checked against its allocations
+ *                (device memory, alignment, room for every tensor) the first time a server
+ *                sees it and trusted while the same addresses keep coming; a caller that
+ *                frees such a buffer and later passes another allocation at the same
+ *                address calls halos_forget_buffers first.
  *   Streams      `stream` is a hipStream_t (NULL = the default stream).  Device
  *                work is enqueued there and the call returns; the caller
  *                synchronises.  All calls that touch the same server's state
@@ -208,7 +213,9 @@ halos_status halos_lps_push_update_weighted(halos_lps *lps, int32_t worker, cons
  * such an item is ESTATE.  The worker saves its subtraction pass and the delta buffer; the server reads 4 more
  * bytes per parameter than for an fp32 delta.
  *   end_model  device tensors of the layout, fp32, 16-byte aligned; borrowed like `g` above
- * ESTATE if the worker has no registered model buffer or already has an item queued; otherwise as halos_lps_push_update.
+ * ESTATE if the worker has no registered model buffer or already has an item queued; EINVAL if a tensor of `end_model`
+ * overlaps the worker's registered model buffer (the start model would be read from what the worker trained in);
+ * otherwise as halos_lps_push_update.
  * The |g|^2 monitor, where enabled, sees the g formed here.
  */
 halos_status halos_lps_push_end_model(halos_lps *lps, int32_t worker, const void *const *end_model, uint32_t staleness);
@@ -312,6 +319,11 @@ halos_status halos_pull_model(const void *server, int32_t is_gps, void *const *d
  * next step.  For the GPS: hp->global.  Other fields are validated but ignored.
  */
 halos_status halos_set_hparams(void *server, int32_t is_gps, const halos_hparams *hp);
+
+/* Drop what a server remembers about pointer sets it has already checked (deltas per worker, pull destinations, the
+ * norm output; for the GPS: deltas of halos_gps_push_update): the next use of any pointer set is checked again.
+ * For callers that free buffers and may get the same addresses back for smaller allocations. */
+halos_status halos_forget_buffers(void *server, int32_t is_gps);
 
 /* Change only the accumulation count K of one LPS (>= 1), effective from the next step. */
 halos_status halos_lps_set_threshold(halos_lps *lps, int32_t K);

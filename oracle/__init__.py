@@ -68,6 +68,7 @@ def _load():
         lib.ho_get.argtypes = [vp, i32, i32, vp]
         lib.ho_counters.argtypes = [vp, i32] + [vp] * 5
         lib.ho_norms.argtypes = [vp, i32, vp]
+        lib.ho_stopwatch.argtypes = [vp, vp, vp]
         lib.ho_bf16_to_f32.restype = f32
         lib.ho_bf16_to_f32.argtypes = [ctypes.c_uint16]
         _lib = lib
@@ -181,6 +182,12 @@ class HalosOracle:
         out = (ctypes.c_double * 2)()
         self._lib.ho_norms(self._h, l, out)
         return float(out[0]), float(out[1])
+
+    def stopwatch(self):
+        """Seconds spent inside, and calls of, the oracle's own handlers: {"lps_update": (s, n), "gps_update": ..., "lps_merge": ...}."""
+        sec, n = (ctypes.c_double * 3)(), (ctypes.c_int64 * 3)()
+        self._lib.ho_stopwatch(self._h, sec, n)
+        return {k: (float(sec[i]), int(n[i])) for i, k in enumerate(("lps_update", "gps_update", "lps_merge"))}
 
     def counters(self, l: int):
         t, tl, gu = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()

@@ -78,6 +78,7 @@
 // external reference: they are pinned only through the tiny cases above plus
 // elementwise independence -- otherwise parity unpinned.
 
+#include <chrono>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -216,6 +217,15 @@ struct Oracle {
     std::vector<R> gps_buffer, sc_gps_buffer;
     int64_t gps_updates = 0;
     std::vector<Lps<R>> lps;
+    // Stopwatch (not part of the algorithm): seconds spent inside, and calls of, the three event handlers, so that a
+    // benchmark can quote this code's own speed per event type without the cost of getting data to it.
+    double seconds[3] = {0.0, 0.0, 0.0};     // 0 worker update, 1 GPS update, 2 merge
+    int64_t calls[3] = {0, 0, 0};
+    struct Stopwatch {
+        double &acc; int64_t &n; std::chrono::steady_clock::time_point t0;
+        Stopwatch(double &a, int64_t &c) : acc(a), n(c), t0(std::chrono::steady_clock::now()) {}
+        ~Stopwatch() { acc += std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count(); n += 1; }
+    };
 
     static void grow(std::vector<R> &scale, const std::vector<R> &v) {
         for (size_t j = 0; j < v.size(); ++j) {
@@ -274,6 +284,7 @@ struct Oracle {
     // One worker update of server s with the pseudo-gradient gvec (already weighted or averaged): the counter, ModelUpdate,
     // the accumulation and the send test of the LPS block.
     void apply_update(Lps<R> &s, const std::vector<R> &gvec, StepInfo &out) {
+        Stopwatch watch(seconds[0], calls[0]);
         s.t += 1;                                                       // t <- t + 1
         const bool accumulate = (s.phase == ACCUMULATING);
         s.last_delta_sq = 0.0;
@@ -352,6 +363,7 @@ struct Oracle {
             out.worker = it.worker;
         } else {
             if (s.phase != QUEUED) return -3;
+            Stopwatch watch(seconds[2], calls[2]);
             s.t_last = s.t;                                             // t_last <- t
             const R keep = R(1) - alpha;
             s.last_merge_dist_sq = 0.0;
@@ -379,6 +391,7 @@ struct Oracle {
     int gps_receive(int l) {
         Lps<R> &s = lps[l];
         if (s.phase != SENT) return -2;
+        Stopwatch watch(seconds[1], calls[1]);
         gps_updates += 1;
         const bool first = gps_delay.seen == 0, refresh = gps_delay.seen + 1 == gps_delay.d;
         for (int64_t j = 0; j < n; ++j) {
@@ -638,6 +651,16 @@ int ho_counters(void *p, int32_t l, int64_t *t, int64_t *t_last, int32_t *phase,
     } else {
         auto &s = h->d->lps[l]; *t = s.t; *t_last = s.t_last; *phase = s.phase; *queued = (int32_t)s.queue.size();
         *gps_updates = h->d->gps_updates;
+    }
+    return 0;
+}
+
+// Stopwatch read-out: seconds[3] and calls[3] for worker updates, GPS updates, merges (see Oracle::Stopwatch).
+int ho_stopwatch(void *p, double *seconds, int64_t *calls) {
+    Handle *h = (Handle *)p;
+    for (int k = 0; k < 3; ++k) {
+        seconds[k] = h->precision == 32 ? h->f->seconds[k] : h->d->seconds[k];
+        calls[k] = h->precision == 32 ? h->f->calls[k] : h->d->calls[k];
     }
     return 0;
 }

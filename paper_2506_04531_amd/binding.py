@@ -94,6 +94,7 @@ def load_library():
         "halos_pull_model": [vp, i32, P(vp), vp],
         "halos_set_hparams": [vp, i32, P(HParams)],
         "halos_lps_set_threshold": [vp, i32],
+        "halos_forget_buffers": [vp, i32],
         "halos_lps_get_counters": [vp, P(i64), P(i64), P(i32), P(i32), P(u32)],
         "halos_gps_get_counters": [vp, P(i64)],
         "halos_lps_get_norms": [vp, vp, P(ctypes.c_double)],
@@ -251,6 +252,10 @@ def halos_pull_model(server: int, is_gps: bool, dst, stream=None) -> None:
 
 def halos_set_hparams(server: int, is_gps: bool, hp: HParams) -> None:
     _check(load_library().halos_set_hparams(server, 1 if is_gps else 0, ctypes.byref(hp)))
+
+
+def halos_forget_buffers(server: int, is_gps: bool) -> None:
+    _check(load_library().halos_forget_buffers(server, 1 if is_gps else 0))
 
 
 def halos_lps_set_threshold(lps: int, K: int) -> None:

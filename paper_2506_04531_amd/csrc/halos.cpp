@@ -132,6 +132,7 @@ struct halos_lps {
     std::vector<std::vector<const void *>> delta_in_table;   // per worker: the pointer set its device table holds now
     MomentumCycle cycle;
     std::vector<char> worker_has_model;
+    std::vector<std::vector<const void *>> worker_model_host;   // per worker: the registered model buffers (host copy)
     // update-norm monitors (HALOS_FLAG_NORMS): per-workgroup partial sums, then [ |g|^2 of the last update,
     // |theta - Theta_i|^2 before the last merge ]
     double *d_norm_partials = nullptr;
@@ -506,6 +507,7 @@ halos_status halos_lps_create(halos_gps *g, int32_t lps_id, int32_t n_workers, v
     l->d_delta = l->d_buffer + nt;
     l->delta_in_table.resize(n_workers);
     l->worker_has_model.assign(n_workers, 0);
+    l->worker_model_host.resize(n_workers);
     if (g->hp.flags & HALOS_FLAG_NORMS) {
         l->norm_partial_cap = (uint32_t)(g->ranges.size() ? g->ranges.size() : 1) * 64u * (uint32_t)g->n_cu;
         const size_t bytes = ((size_t)l->norm_partial_cap + 2) * sizeof(double);
@@ -563,6 +565,15 @@ static halos_status push_delta_impl(halos_lps *l, int32_t worker, const void *co
     if (!gptrs) return fail(HALOS_EINVAL, "%s: pointer array is NULL", what);
     const halos_gps *g = l->gps;
     const size_t nt = g->numel.size();
+    if (end_model) {        // the end model must not be (or overlap) the buffer that holds the start model: g would be 0 or garbage
+        const std::vector<const void *> &start = l->worker_model_host[worker];
+        for (size_t i = 0; i < nt && i < start.size(); ++i) {
+            const uintptr_t a = reinterpret_cast<uintptr_t>(gptrs[i]), b = reinterpret_cast<uintptr_t>(start[i]);
+            const uintptr_t len = (uintptr_t)g->numel[i] * sizeof(float);
+            if (len && a < b + len && b < a + len)
+                return fail(HALOS_EINVAL, "end_model: tensor %zu overlaps the worker's registered model buffer (its start model)", i);
+        }
+    }
     std::vector<const void *> &seen = l->validated[worker];
     const bool same = seen.size() == nt && l->validated_dtype[worker] == dtype &&
                       std::memcmp(seen.data(), gptrs, nt * sizeof(void *)) == 0;
@@ -631,6 +642,7 @@ halos_status halos_lps_set_worker_model(halos_lps *l, int32_t worker, void *cons
     st = store_table((hipStream_t)stream, l->d_worker_model + (size_t)worker * nt, (const void *const *)model, nt);
     if (st != HALOS_OK) return st;
     l->worker_has_model[worker] = 1;
+    l->worker_model_host[worker].assign((const void *const *)model, (const void *const *)model + nt);
     return HALOS_OK;
 }
 
@@ -1041,6 +1053,22 @@ halos_status halos_set_hparams(void *server, int32_t is_gps, const halos_hparams
         l->rule = hp->local;
         l->alpha = hp->alpha;
         l->proto.set_K(hp->K);
+    }
+    return HALOS_OK;
+}
+
+halos_status halos_forget_buffers(void *server, int32_t is_gps) {
+    if (!server) return fail(HALOS_EINVAL, "server is NULL");
+    if (is_gps) {
+        halos_gps *g = static_cast<halos_gps *>(server);
+        if (!live_gps(g)) return fail(HALOS_EINVAL, "server is not a valid gps handle");
+        g->validated_delta.clear();
+    } else {
+        halos_lps *l = static_cast<halos_lps *>(server);
+        if (!live_lps(l)) return fail(HALOS_EINVAL, "server is not a valid lps handle");
+        for (auto &v : l->validated) v.clear();
+        l->validated_pull.clear();
+        l->validated_norm_out = nullptr;
     }
     return HALOS_OK;
 }

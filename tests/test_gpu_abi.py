@@ -255,3 +255,61 @@ def test_gps_may_be_destroyed_before_its_local_servers():
     torch.cuda.synchronize()
     assert torch.equal(dst[0], Theta[0] - 0.5)
     B.halos_lps_destroy(lps)                                              # releases the GPS's tables too
+
+
+def test_end_model_must_not_overlap_the_registered_start_model():
+    from paper_2506_04531_amd import binding as B
+    dev = torch.device("cuda:0")
+    n = 9000
+    Theta, M, th, m, acc, wm, end = (torch.zeros(n, device=dev) for _ in range(7))
+    gps = B.halos_gps_create([n], B.paper_hparams(0.2, 0.9, 0.15, 0.5, 0.25, 4), [Theta], [M])
+    lps = B.halos_lps_create(gps, 0, 1, [th], [m], [acc])
+    try:
+        B.halos_lps_set_worker_model(lps, 0, [wm])
+        for bad in ([wm], [wm.data_ptr() + 4096]):                 # the buffer itself, and a view into it
+            with pytest.raises(B.HalosError) as e:
+                B.halos_lps_push_end_model(lps, 0, bad)
+            assert e.value.status == B.EINVAL and "overlaps" in e.value.message
+        assert B.halos_lps_get_counters(lps)["queued"] == 0
+        B.halos_lps_push_end_model(lps, 0, [end])
+        assert B.halos_lps_step_pull(lps).kind == 1
+    finally:
+        B.halos_lps_destroy(lps)
+        B.halos_gps_destroy(gps)
+
+
+def test_forget_buffers_makes_the_next_pointer_set_be_checked_again():
+    """A pointer set is range-checked when a server first sees it.  After halos_forget_buffers the same addresses are
+    checked again: here the second time they belong to an allocation that is too small."""
+    from paper_2506_04531_amd import binding as B
+    dev = torch.device("cuda:0")
+    n = 1 << 20
+    Theta, M, th, m, acc = (torch.zeros(n, device=dev) for _ in range(5))
+    # an allocation of exactly known size: the arena gives a request above 2 GiB a device allocation of its own
+    big_bytes = (2 << 30) + (64 << 20)
+    arena = B.halos_arena_create([1 << 20], 4 << 30)
+    big = B.halos_arena_alloc(arena, 0, big_bytes)
+    gps = B.halos_gps_create([n], B.paper_hparams(0.2, 0.9, 0.15, 0.5, 0.25, 4), [Theta], [M])
+    lps = B.halos_lps_create(gps, 0, 1, [th], [m], [acc])
+    try:
+        tail = big + big_bytes - n * 4                               # the last n floats of the allocation: fits exactly
+        torch.cuda.synchronize()
+        B.halos_probe_streams([], [tail], n * 4, 1)                  # zero-fill them (the probe writes zeros)
+        B.halos_lps_push_update(lps, 0, [tail], B.F32)
+        assert B.halos_lps_step(lps).kind == 1
+        short = tail + (2 << 20)                                      # n floats from here run 2 MiB past the allocation
+        with pytest.raises(B.HalosError) as e:
+            B.halos_lps_push_update(lps, 0, [short], B.F32)
+        assert e.value.status == B.EINVAL
+        B.halos_lps_push_update(lps, 0, [tail], B.F32)               # remembered: accepted without a new check
+        assert B.halos_lps_step(lps).kind == 1
+        B.halos_forget_buffers(lps, False)
+        B.halos_forget_buffers(gps, True)
+        B.halos_lps_push_update(lps, 0, [tail], B.F32)               # checked again, still fine
+        assert B.halos_lps_step(lps).kind == 1
+        with pytest.raises(B.HalosError):
+            B.halos_forget_buffers(0, False)
+    finally:
+        B.halos_lps_destroy(lps)
+        B.halos_gps_destroy(gps)
+        B.halos_arena_destroy(arena)

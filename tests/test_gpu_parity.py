@@ -468,3 +468,56 @@ def test_many_schedules_on_a_ragged_list(seed):
     base = synth.get_workload("160m" if seed % 2 else "410m")
     w = replace(base.scaled(RAGGED, n_updates=64, name=f"seed{seed}"), seed=seed)
     _full_parity(w, synth.make_trace(w, seed=seed))
+
+
+def test_full_size_70m_every_element(tmp_path):
+    """All 70,426,624 parameters of the 70M workload, every state array, in the configuration the benchmark times: the
+    fp32 same-order oracle replays the whole trace chunk by chunk (elements are independent) in worker processes and each
+    chunk is compared bit for bit with the GPU's state."""
+    import os
+    import subprocess
+    import sys
+    from concurrent.futures import ThreadPoolExecutor
+    name = "70m"
+    w = synth.get_workload(name)
+    trace = synth.make_trace(w)
+    N = w.layout.total
+    state_dir = "/dev/shm/halos_full_70m" if os.path.isdir("/dev/shm") else str(tmp_path)
+    os.makedirs(state_dir, exist_ok=True)
+    print(f"[parity] workload={name} every element n={N} events={len(trace.events)} state_dir={state_dir}", flush=True)
+    c = _cluster(w, trace, placement="regions")
+    try:
+        gpu_log, _ = c.replay(trace.events, fuse_pull=True)
+        torch.cuda.synchronize()
+        names = list(c.state_lists())
+        for k in names:
+            np.save(os.path.join(state_dir, k + ".npy"), c.flat(k))
+    finally:
+        c.close()
+        del c
+        torch.cuda.empty_cache()
+    try:
+        chunk = 1 << 22
+        bounds = [(lo, min(N, lo + chunk)) for lo in range(0, N, chunk)]
+        worker = os.path.join(os.path.dirname(os.path.abspath(__file__)), "chunk_oracle_check.py")
+        n_proc = max(2, min(12, (os.cpu_count() or 4) - 2))
+
+        def run(b):
+            res = subprocess.run([sys.executable, worker, name, state_dir, str(b[0]), str(b[1])], capture_output=True, text=True,
+                                 timeout=600, env=dict(os.environ, OMP_NUM_THREADS="1"))
+            assert res.returncode == 0, res.stderr[-2000:]
+            line = [ln for ln in res.stdout.splitlines() if ln.startswith("CHUNK")][-1].split()
+            print(f"[parity] chunk {line[1]}..{line[2]}: {line[3]} differing of {line[4]}", flush=True)
+            return int(line[3]), int(line[4])
+
+        with ThreadPoolExecutor(n_proc) as pool:
+            results = list(pool.map(run, bounds))
+        n_diff = sum(r[0] for r in results)
+        n_cmp = sum(r[1] for r in results)
+        assert n_cmp == N * len(names), (n_cmp, N, names)
+        assert n_diff == 0, f"{n_diff} of {n_cmp} elements differ from the fp32 same-order oracle"
+        print(f"[parity] {name}: all {n_cmp} state elements ({len(names)} arrays x {N}) bit-identical to the oracle", flush=True)
+    finally:
+        for k in os.listdir(state_dir):
+            os.remove(os.path.join(state_dir, k))
+        os.rmdir(state_dir)
