@@ -79,15 +79,15 @@ def bytes_per_param(label: str, delta_dtype: str, delayed: bool) -> int:
 # only for the kernel source it was measured on: {sha256 of kernels.hip: {kernel label: bytes/param}}.
 MEASURED_TRAFFIC: dict = {
     # profiles/lps_update_1b_hbm_traffic.md, profiles/lps_update_delayed_1b_dn.md
-    "a88c0a6aa60fccf3deb8590183df648b982b595eed0a0592632d53deaaeeeec9": {
+    "46e3011d3d83bda762faa9d97b9b02e75eb4f1cdfeff18a64c771cc4bd5a6de6": {
         "1b:lps_update_acc_pull": 30.033,
-        "1b:lps_update_noacc_pull": 22.034,
+        "1b:lps_update_noacc_pull": 22.031,
         "1b-dn:lps_update_acc_first_pull": 26.039,
-        "1b-dn:lps_update_acc_pull": 30.035,
+        "1b-dn:lps_update_acc_pull": 30.032,
         "1b-dn:lps_update_acc_refresh_pull": 34.031,
-        "1b-dn:lps_update_noacc_first_pull": 18.041,
-        "1b-dn:lps_update_noacc_pull": 22.037,
-        "1b-dn:lps_update_noacc_refresh_pull": 26.03,
+        "1b-dn:lps_update_noacc_first_pull": 18.031,
+        "1b-dn:lps_update_noacc_pull": 22.035,
+        "1b-dn:lps_update_noacc_refresh_pull": 26.031,
     },
 }
 
@@ -546,7 +546,8 @@ def placement_search_mode(elements: int, dtype_name: str):
             B.halos_gps_destroy(gps)
         rename, pat = {}, []
         for r in assign:
-            rename.setdefault(r, "XYZ"[len(rename)])
+            if r not in rename:
+                rename[r] = "XYZ"[len(rename)]
             pat.append(rename[r])
         groups["".join(pat)].append(n * bpp / ms / 1e6)
     print(f"update pass with fused pull, {n} elements per array, {dtype_name} delta, {bpp} B/parameter")
