@@ -586,6 +586,8 @@ def main():
                          "(halos_lps_step_batch; same results bit for bit); 0 = every step its own pass")
     ap.add_argument("--no-plain-placement", action="store_true",
                     help="skip the second run of the headline workload with ordinary allocations instead of the region-sorted arena")
+    ap.add_argument("--no-variants-ab", action="store_true",
+                    help="skip the runs of the headline workload with one option changed at a time")
     ap.add_argument("--no-end-model-ab", action="store_true",
                     help="skip the A/B of the update pass fed a delta vs fed the worker's end model")
     ap.add_argument("--no-graph-ab", action="store_true",
@@ -632,6 +634,18 @@ def main():
         plain = {"placement": "plain", "value": r["params_updated_per_s"], "ms_per_step": r["ms_per_step"],
                  "whole_path_GBps": r["whole_path_GBps"], "roofline": r["roofline"],
                  "note": "same workload, every tensor an ordinary allocation of the framework's caching allocator"}
+    vab = None
+    if not args.no_variants_ab:         # the same workload with one option changed at a time (one warm-up + one timed step each)
+        vab = {}
+        for tag, kw in (("single_steps", dict(variant, batch=0)), ("defer_clear", dict(variant, defer_clear=True)),
+                        ("gps_no_momentum", dict(variant, gps_no_momentum=True)), ("snapshot_form", dict(variant, snapshot=True))):
+            r = run_workload(args.workload, 1, 1, False, args.placement, not args.no_fuse_pull, **kw)
+            vab[tag] = {"value": r["params_updated_per_s"], "ms_per_step": r["ms_per_step"], "whole_path_GBps": r["whole_path_GBps"],
+                        "kernels": {k: {"launches": v["launches"], "avg_ms": v["avg_ms"], "bytes_per_param": v["bytes_per_param"],
+                                        "achieved_GBps": v["achieved_GBps"]} for k, v in r["kernels"].items()}}
+        vab["note"] = ("single_steps: every update its own pass (no halos_lps_step_batch); defer_clear: merges leave the third buffer "
+                       "(HALOS_FLAG_DEFER_CLEAR, same results); gps_no_momentum: beta_g = 0 without a momentum array (Sec. 5.4; "
+                       "another optimizer setting); snapshot_form: Delta by subtraction (HALOS_FLAG_SNAPSHOT; rounds differently)")
     ab = None if args.no_end_model_ab else end_model_ab(args.workload, verbose=not args.quiet)
     gab = None if args.no_graph_ab else graph_ab()
     cpu = None if args.no_cpu_baseline else cpu_baseline(args.workload)
@@ -657,6 +671,7 @@ def main():
         "whole_path_GBps": head["whole_path_GBps"],
         "kernels": head["kernels"],
         "workloads": [brief(r) for r in others],
+        "variants_ab": vab,
         "end_model_ab": ab,
         "tiny_graph_ab": gab,
     }

@@ -377,3 +377,53 @@ def test_batch_call_on_a_single_item_is_the_ordinary_step():
         assert e.value.status == B.EINVAL
     finally:
         c.close()
+
+
+# ---------------------------------------------------------------- the variants at full benchmark size
+@pytest.mark.parametrize("name,variant", [("160m", "batch+defer"), ("70m", "nomom+f16"), ("410m", "weighted+snapshot")])
+def test_variants_at_full_size_on_sampled_elements(name, variant):
+    """Full benchmark sizes, arena placement, fused pulls, the variants switched on; the oracle replays the sampled
+    elements (random ones plus every tensor and tile boundary)."""
+    from paper_2506_04531_amd import binding as B
+    from parity_util import sample_indices
+    w = synth.get_workload(name)
+    flags, batch, form = 0, 0, FORM_ACCUMULATOR
+    if variant == "batch+defer":
+        flags, batch = B.FLAG_DEFER_CLEAR, 4
+    elif variant == "nomom+f16":
+        w = replace(w, delta_dtype="f16", beta_g=0.0)
+        flags = B.FLAG_GPS_NO_MOMENTUM
+    else:
+        w = replace(w, staleness_exponent=0.5)
+        flags, form = B.FLAG_SNAPSHOT, FORM_LITERAL
+    trace = synth.make_trace(w)
+    idx = sample_indices(w.layout, 1 << 16, seed=7)
+    print(f"[parity] workload={name} variant={variant} n={w.layout.total} sample={idx.size} events={len(trace.events)}", flush=True)
+    hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0], flags=flags)
+    c = _cluster(w, trace, placement="regions", hp=hp)
+    try:
+        gpu_log, tm = c.replay(trace.events, fuse_pull=True, batch=batch, timed=True)
+        torch.cuda.synchronize()
+        gpu = {k: c.gather(k, torch.from_numpy(idx)) for k in c.state_lists()}
+        fresh = [B.halos_lps_get_counters(h) for h in c.lps]
+    finally:
+        c.close()
+        del c
+        torch.cuda.empty_cache()
+    if batch:
+        assert any(k.startswith("lps_update_batch") for k in tm), "the full-size schedule must contain bursts"
+    o32, log32 = oracle_run(w, trace, idx, 32, form)
+    check_step_logs(trace, gpu_log, log32)
+    ref = oracle_state(o32, w.n_lps, snapshot_form=(form == FORM_LITERAL))
+    if flags & B.FLAG_GPS_NO_MOMENTUM:
+        ref.pop("M")
+    if flags & B.FLAG_DEFER_CLEAR:
+        for l, cnt in enumerate(fresh):
+            if cnt["phase"] == B.PHASE_ACCUMULATING and cnt["t"] == cnt["t_last"] and cnt["t"] > 0:
+                ref.pop(f"aux{l}")
+    if flags & B.FLAG_GPS_NO_MOMENTUM:
+        for k, v in gpu.items():
+            assert np.array_equal(v, ref[k][0].astype(np.float32)), k          # numerically exact (sign of zero aside)
+    else:
+        worst, n_diff, wname = compare_state(gpu, ref, bitwise=True)
+        assert n_diff == 0, (n_diff, worst, wname)
