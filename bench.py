@@ -82,7 +82,7 @@ MEASURED_TRAFFIC: dict = {
     "46e3011d3d83bda762faa9d97b9b02e75eb4f1cdfeff18a64c771cc4bd5a6de6": {
         "1b:lps_update_acc_pull": 30.033,
         "1b:lps_update_noacc_pull": 22.031,
-        "1b-dn:lps_update_acc_first_pull": 26.039,
+        "1b-dn:lps_update_acc_first_pull": 26.038,
         "1b-dn:lps_update_acc_pull": 30.032,
         "1b-dn:lps_update_acc_refresh_pull": 34.031,
         "1b-dn:lps_update_noacc_first_pull": 18.031,

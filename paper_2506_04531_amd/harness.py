@@ -328,7 +328,8 @@ class Cluster:
                     grp = following_steps(i, l, batch) if batch else None
                     if grp is not None and len(grp[0]) >= 2:
                         steps, pulls = grp
-                        any_acc = any(int(events[j]["exp_accumulate"]) for j in steps)
+                        # does the pass touch the third buffer? (snapshot form: only the update that completes the accumulation does)
+                        any_acc = any(int(events[j]["exp_send" if self.snapshot else "exp_accumulate"]) for j in steps)
                         blabel = f"lps_update_batch{len(steps)}_{'acc' if any_acc else 'noacc'}_pull"
                         chk(bracket(blabel, lambda: lib.halos_lps_step_batch(h, len(steps), 1, sp, infos, ctypes.byref(n_done))))
                         assert n_done.value == len(steps), (n_done.value, len(steps))

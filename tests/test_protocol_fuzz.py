@@ -26,6 +26,7 @@ def shim(tmp_path_factory):
     lib.proto_push_delta.argtypes = [ctypes.c_void_p, ctypes.c_int]
     lib.proto_push_global.argtypes = [ctypes.c_void_p]
     lib.proto_step.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_longlong)]
+    lib.proto_step_average.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_longlong)]
     lib.proto_consume.argtypes = [ctypes.c_void_p]
     lib.proto_phase.argtypes = [ctypes.c_void_p]
     lib.proto_queued.argtypes = [ctypes.c_void_p]
@@ -46,7 +47,7 @@ def test_random_sequences_agree_with_the_oracle(shim, seed):
     g = np.ones(3, dtype=np.float32)
     out = (ctypes.c_longlong * 6)()
     for _ in range(400):
-        op = rng.choice(["delta", "delta", "delta", "step", "step", "step", "global", "consume", "setK", "setD"])
+        op = rng.choice(["delta", "delta", "delta", "step", "step", "step", "average", "global", "consume", "setK", "setD"])
         if op == "delta":
             w = rng.randint(0, n_workers - 1)
             rc = shim.proto_push_delta(p, w)
@@ -81,6 +82,20 @@ def test_random_sequences_agree_with_the_oracle(shim, seed):
             except O.OracleError:
                 ok = False
             assert (rc == 0) == ok
+        elif op == "average":          # the first n queue items as one update with their mean: allowed only if all are deltas
+            n = rng.randint(1, 4)
+            rc = shim.proto_step_average(p, n, out)
+            try:
+                info = o.lps_step_average(0, n)
+                ok = True
+            except O.OracleError:
+                ok = False
+            assert (rc == 0) == ok
+            if ok:
+                kind, worker, acc, freezes, t, t_last = list(out)
+                assert (kind, worker, acc, freezes, t, t_last) == (info.kind, info.worker, info.accumulated, info.sent, info.t, info.t_last)
+                shim.cycle_commit(cyc)
+                assert shim.cycle_seen(cyc) == o.delay_seen(0)
         elif op == "setK":
             k = rng.randint(1, 5)
             assert shim.proto_set_K(p, k) == 0
