@@ -313,3 +313,49 @@ def test_forget_buffers_makes_the_next_pointer_set_be_checked_again():
         B.halos_lps_destroy(lps)
         B.halos_gps_destroy(gps)
         B.halos_arena_destroy(arena)
+
+
+def test_many_tensors_through_the_multi_delta_passes():
+    """More tensors than one launch range, zero-sized tensors among them, through halos_lps_step_batch and
+    halos_lps_step_average: the per-worker device tables of delta pointers span all ranges.  beta = 0, eta = 1 and
+    dyadic values make every expected number exact."""
+    from paper_2506_04531_amd import binding as B
+    n_t = 800
+    numel = [0 if i % 97 == 5 else 9 + (i % 7) * 2051 for i in range(n_t)]
+    dev = "cuda:0"
+    mk = lambda fill=None: [torch.zeros(n, device=dev) if fill is None else torch.full((n,), fill(i), device=dev)
+                            for i, n in enumerate(numel)]
+    Theta, M, th, m, acc = mk(lambda i: float(i)), mk(), mk(), mk(), mk()
+    g = [mk(lambda i, k=k: (k + 1) * 0.25 + i / 256.0) for k in range(3)]
+    wm = [mk() for _ in range(3)]
+    hp = B.paper_hparams(1.0, 0.0, 1.0, 0.0, 0.5, 1 << 30)
+    gps = B.halos_gps_create(numel, hp, Theta, M)
+    lps = B.halos_lps_create(gps, 0, 3, th, m, acc)
+    try:
+        for k in range(3):
+            B.halos_lps_set_worker_model(lps, k, wm[k])
+            B.halos_lps_push_update(lps, k, g[k], B.F32)
+        infos = B.halos_lps_step_batch(lps, 4, True)
+        assert [i.t for i in infos] == [1, 2, 3] and [i.worker for i in infos] == [0, 1, 2]
+        torch.cuda.synchronize()
+        for i in range(n_t):
+            if numel[i] == 0:
+                continue
+            run = float(i)
+            for k in range(3):
+                run -= (k + 1) * 0.25 + i / 256.0
+                assert torch.all(wm[k][i] == run), (i, k)            # each worker got the model right after ITS update
+            assert torch.all(th[i] == run) and torch.all(acc[i] == float(i) - run), i
+        # averaged step over the first two deltas: one update with their mean (0.375 + i/256; the factor 1/2 is exact)
+        for k in range(2):
+            B.halos_lps_push_update(lps, k, g[k], B.F32)
+        info = B.halos_lps_step_average(lps, 2)
+        assert (info.t, info.worker) == (4, 1)
+        torch.cuda.synchronize()
+        for i in range(n_t):
+            if numel[i]:
+                want = float(i) - 1.5 - 3 * (i / 256.0) - 0.375 - i / 256.0
+                assert torch.all(th[i] == want), (i, float(th[i][0]), want)
+    finally:
+        B.halos_lps_destroy(lps)
+        B.halos_gps_destroy(gps)
