@@ -88,6 +88,31 @@ __device__ __forceinline__ float ldg1(const gf32 *p) { return *p; }
 __device__ __forceinline__ float ldg1(const gu16 *p) { return bf16_up(*p); }
 __device__ __forceinline__ float ldg1(const gf16 *p) { return static_cast<float>(*p); }
 
+// The same four delta elements as they lie in memory, and their upcast as a separate step: a pass that loads several
+// deltas under (uniform) branches issues all its loads first and converts afterwards, instead of waiting per delta.
+template <bool NT> __device__ __forceinline__ f32x4 ldraw4(const gf32 *p) { return ld4<NT>(p); }
+template <bool NT> __device__ __forceinline__ u16x4 ldraw4(const gu16 *p) {
+    const gu16x4 *q = (const gu16x4 *)p;
+    if constexpr (NT) return __builtin_nontemporal_load(q);
+    else return *q;
+}
+template <bool NT> __device__ __forceinline__ f16x4 ldraw4(const gf16 *p) {
+    const gf16x4 *q = (const gf16x4 *)p;
+    if constexpr (NT) return __builtin_nontemporal_load(q);
+    else return *q;
+}
+__device__ __forceinline__ f32x4 up4(f32x4 v) { return v; }
+__device__ __forceinline__ f32x4 up4(u16x4 b) {
+    f32x4 r;
+    r[0] = bf16_up(b[0]); r[1] = bf16_up(b[1]); r[2] = bf16_up(b[2]); r[3] = bf16_up(b[3]);
+    return r;
+}
+__device__ __forceinline__ f32x4 up4(f16x4 h) {
+    f32x4 r;
+    r[0] = static_cast<float>(h[0]); r[1] = static_cast<float>(h[1]); r[2] = static_cast<float>(h[2]); r[3] = static_cast<float>(h[3]);
+    return r;
+}
+
 __device__ __forceinline__ f32x4 sub4(f32x4 a, f32x4 b);
 
 // The pseudo-gradient of four consecutive elements: read from the worker's delta tensor, or (FROM_END) formed here
@@ -304,12 +329,13 @@ lps_update_multi_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32
             pd[i] = (PULL && i < n_in && a.pull[i]) ? to_global(a.pull[i][tensor]) + tl.start : nullptr;
         }
         if (tl.len == TILE_ELEMS) {
-            f32x4 gv[MAX_MULTI][UNROLL], mv[UNROLL], tv[UNROLL], av[UNROLL];
+            decltype(ldraw4<NT>(g[0])) gv[MAX_MULTI][UNROLL];      // as loaded; upcast and weighted where they are used
+            f32x4 mv[UNROLL], tv[UNROLL], av[UNROLL];
 #pragma unroll
             for (int i = 0; i < MAX_MULTI; ++i)
                 if (i < n_in) {
 #pragma unroll
-                    for (int u = 0; u < UNROLL; ++u) gv[i][u] = scale4(a.w[i], ldg4<NT>(g[i] + (u * BLOCK_THREADS + tid) * VEC));
+                    for (int u = 0; u < UNROLL; ++u) gv[i][u] = ldraw4<NT>(g[i] + (u * BLOCK_THREADS + tid) * VEC);
                 }
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
@@ -325,16 +351,16 @@ lps_update_multi_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32
 #pragma unroll
                     for (int i = 0; i < MAX_MULTI; ++i)
                         if (i < n_in) {
-                            const f32x4 s = model_update4(tv[u], mv[u], gv[i][u], eta, beta, cg);
+                            const f32x4 s = model_update4(tv[u], mv[u], scale4(a.w[i], up4(gv[i][u])), eta, beta, cg);
                             if constexpr (THIRD == 1 || THIRD == 3) { if (i < n_acc) av[u] = add4(av[u], s); }
                             if constexpr (THIRD == 2) { if (i + 1 == n_acc) av[u] = sub4(av[u], tv[u]); }
                             if constexpr (PULL) { if (pd[i]) st4<NT>(pd[i] + off, tv[u]); }
                         }
                 } else {
-                    f32x4 sum = gv[0][u];
+                    f32x4 sum = scale4(a.w[0], up4(gv[0][u]));
 #pragma unroll
                     for (int i = 1; i < MAX_MULTI; ++i)
-                        if (i < n_in) sum = add4(sum, gv[i][u]);
+                        if (i < n_in) sum = add4(sum, scale4(a.w[i], up4(gv[i][u])));
                     const f32x4 s = model_update4(tv[u], mv[u], scale4(inv_n, sum), eta, beta, cg);
                     if constexpr (THIRD == 1 || THIRD == 3) av[u] = add4(av[u], s);
                     if constexpr (THIRD == 2) av[u] = sub4(av[u], tv[u]);
