@@ -79,10 +79,10 @@ def bytes_per_param(label: str, delta_dtype: str, delayed: bool) -> int:
 # only for the kernel source it was measured on: {sha256 of kernels.hip: {kernel label: bytes/param}}.
 MEASURED_TRAFFIC: dict = {
     # profiles/lps_update_1b_hbm_traffic.md, profiles/lps_update_delayed_1b_dn.md
-    "46e3011d3d83bda762faa9d97b9b02e75eb4f1cdfeff18a64c771cc4bd5a6de6": {
-        "1b:lps_update_acc_pull": 30.033,
+    "c1b9946f3fba2558821a49c31bb47f3efd75b61366e99efe2968af30940c1a56": {
+        "1b:lps_update_acc_pull": 30.032,
         "1b:lps_update_noacc_pull": 22.031,
-        "1b-dn:lps_update_acc_first_pull": 26.038,
+        "1b-dn:lps_update_acc_first_pull": 26.039,
         "1b-dn:lps_update_acc_pull": 30.032,
         "1b-dn:lps_update_acc_refresh_pull": 34.031,
         "1b-dn:lps_update_noacc_first_pull": 18.031,
