@@ -184,10 +184,15 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
     value = N * updates / elapsed
     # dominant kernel: the LPS update variant that takes the most time
     dom = max(upd_labels, key=lambda k: kernels[k]["total_ms"])
-    traffic = MEASURED_TRAFFIC.get(kernels_digest(), {}).get(f"{name}:{dom}")
-    traffic_source = ("stored: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/, valid for the "
-                      "kernel source with this sha256 only" if traffic is not None else
-                      "none: the kernel source has changed since the counters under profiles/ were taken")
+    stored = MEASURED_TRAFFIC.get(kernels_digest())
+    traffic = (stored or {}).get(f"{name}:{dom}")
+    if traffic is not None:
+        traffic_source = ("stored: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/, valid for the "
+                          "kernel source with this sha256 only")
+    elif stored is None:
+        traffic_source = "none: the kernel source has changed since the counters under profiles/ were taken"
+    else:
+        traffic_source = "none: the counter runs under profiles/ cover the 1b and 1b-dn workloads only"
     roofline = {
         "bound": "hbm", "kernel": dom, "achieved": kernels[dom]["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": kernels[dom]["achieved_GBps"] / HBM_PEAK_GBS,
