@@ -48,3 +48,18 @@ def test_argument_errors_that_need_no_device():
     assert lib.halos_set_launch_config(0, -1) == B.OK
     lib.halos_lps_destroy(None)
     lib.halos_gps_destroy(None)
+
+
+def test_layout_limits_are_checked_before_the_device():
+    """A tensor may hold at most 2^32 - 1 elements, none a negative count, and a layout at least one tensor: refused
+    with EINVAL and a message, without a device."""
+    from paper_2506_04531_amd import binding as B
+    lib = B.load_library()
+    hp = B.paper_hparams(0.2, 0.9, 0.15, 0.5, 0.25, 8)
+    out = ctypes.c_void_p()
+    for numel, word in (([1 << 32], "2^32"), ([5, -1], "negative"), ([], "n_tensors")):
+        arr = (ctypes.c_int64 * max(1, len(numel)))(*numel)
+        lay = B._Layout(len(numel), arr)
+        rc = lib.halos_gps_create(ctypes.byref(lay), ctypes.byref(hp), None, None, None, ctypes.byref(out))
+        assert rc == B.EINVAL and word in B.halos_last_error(), (numel, rc, B.halos_last_error())
+        assert not out.value

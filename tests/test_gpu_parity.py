@@ -375,16 +375,18 @@ def test_hyper_parameters_changed_between_events():
     assert n_diff == 0, (n_diff, worst, name)
 
 
-def test_one_tensor_larger_than_2_to_31_elements():
-    """64-bit element offsets: a single tensor of 2^31 + 5003 elements, checked on sampled elements."""
+@pytest.mark.parametrize("n", [(1 << 31) + 5003, (1 << 32) - 1], ids=["2^31+5003", "2^32-1"])
+def test_one_tensor_larger_than_2_to_31_elements(n):
+    """64-bit element offsets: a single tensor of 2^31 + 5003 elements, and one of 2^32 - 1, the most a tensor may have
+    (ragged last tile of 4095), checked on sampled elements, around 2^31 and at the very end."""
     from dataclasses import replace
-    n = (1 << 31) + 5003
     lay = synth.Layout(("huge",), ((n,),), (1,))
     w = replace(synth.get_workload("tiny").scaled(lay, n_updates=5, name="huge"), pool_slots=2, scale_by_fan_in=False,
                 n_lps=1, workers_per_lps=2, k_range=(2, 2))
     trace = synth.make_trace(w, seed=51)
     idx = np.unique(np.concatenate([sample_indices(lay, 1 << 15, seed=2),
-                                    np.arange((1 << 31) - 4100, (1 << 31) + 4100, dtype=np.int64)]))
+                                    np.arange((1 << 31) - 4100, (1 << 31) + 4100, dtype=np.int64),
+                                    np.arange(n - 8200, n, dtype=np.int64)]))
     print(f"[parity] workload=huge n={n} sample={idx.size} events={len(trace.events)}", flush=True)
     c = _cluster(w, trace)
     try:
