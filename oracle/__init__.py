@@ -71,6 +71,10 @@ def _load():
         lib.ho_stopwatch.argtypes = [vp, vp, vp]
         lib.ho_bf16_to_f32.restype = f32
         lib.ho_bf16_to_f32.argtypes = [ctypes.c_uint16]
+        lib.ho_f32_to_bf16.restype = ctypes.c_uint16
+        lib.ho_f32_to_bf16.argtypes = [f32]
+        lib.ho_set_momentum_bf16.argtypes = [vp, i32]
+        lib.ho_f32_to_bf16_array.argtypes = [vp, i64, vp]
         _lib = lib
     return _lib
 
@@ -89,7 +93,7 @@ class HalosOracle:
 
     def __init__(self, theta0: np.ndarray, n_lps: int, *, eta_l: float, beta_l: float, eta_g: float, beta_g: float,
                  alpha: float, K: Sequence[int] | int, cg_l: float | None = None, cg_g: float | None = None,
-                 precision: int = 64, form: int = FORM_LITERAL):
+                 precision: int = 64, form: int = FORM_LITERAL, momentum_bf16: bool = False):
         lib = _load()
         theta0 = np.ascontiguousarray(theta0, dtype=np.float32)
         self.n = int(theta0.size)
@@ -106,6 +110,8 @@ class HalosOracle:
                                 f(cg_g), f(alpha), Ks.ctypes.data, theta0.ctypes.data)
         if not self._h:
             raise OracleError("ho_create failed")
+        if momentum_bf16:
+            self.set_momentum_bf16(True)
 
     def close(self):
         if getattr(self, "_h", None):
@@ -165,6 +171,11 @@ class HalosOracle:
         to the plain rule.  Only between cycles."""
         self._chk(self._lib.ho_set_delay(self._h, which, d), "set_delay")
 
+    def set_momentum_bf16(self, on: bool):
+        """Keep every server's momentum in bfloat16 (rounded to nearest even whenever it is updated); an option of this
+        repository, not of the paper.  Refused once a momentum holds a value bfloat16 cannot, or under the delayed rule."""
+        self._chk(self._lib.ho_set_momentum_bf16(self._h, 1 if on else 0), "set_momentum_bf16")
+
     def delay_seen(self, which: int) -> int:
         return int(self._lib.ho_delay_seen(self._h, which))
 
@@ -199,6 +210,17 @@ class HalosOracle:
 
 def bf16_to_f32(bits: int) -> float:
     return float(_load().ho_bf16_to_f32(bits & 0xFFFF))
+
+
+def f32_to_bf16(value: float) -> int:
+    return int(_load().ho_f32_to_bf16(ctypes.c_float(value)))
+
+
+def f32_to_bf16_array(values: np.ndarray) -> np.ndarray:
+    v = np.ascontiguousarray(values, dtype=np.float32)
+    out = np.empty(v.shape, dtype=np.uint16)
+    _load().ho_f32_to_bf16_array(v.ctypes.data, v.size, out.ctypes.data)
+    return out
 
 
 def f16_to_f32(bits: int) -> float:

@@ -56,6 +56,13 @@
 //     App. D lists this baseline's hyper-parameters), gps_apply_delta below.
 // Deltas may also arrive as IEEE half precision (the workers of Sec. 5.1 train in fp16): upcast exactly.
 //
+// Momentum kept in bfloat16 (an option of this repository, not of the paper, which does not state the servers'
+// precision): after  m <- beta * m + grad  the new momentum is rounded to bfloat16 (round to nearest, ties to
+// even, decided on the binary32 value) and it is that rounded value which enters the step and is carried over.
+// Model, accumulated update and returned global model stay in full precision.  Not combined with the delayed rule.
+// Pins (tests/test_oracle_variants.py): the rounding against torch's conversion, hand-computed ties, equality
+// with full-precision momentum whenever nothing needs rounding.
+//
 // Two numerical forms are provided and selected at creation:
 //   form 0 (literal)      keeps the snapshot theta_{t_last} and forms Delta by
 //                         subtraction exactly as Algorithm 1's LPS block writes it;
@@ -109,9 +116,26 @@ struct Rule { R eta, beta, cg; };
 
 // ModelUpdate (Appendix E): momentum first, then the step.  Returns the step
 // that was subtracted so that callers can accumulate it.
+// binary32 -> bfloat16 bit pattern: round to nearest, ties to even; any NaN becomes the quiet NaN 0x7FC0.
+inline uint16_t f32_to_bf16(float f) {
+    uint32_t u;
+    std::memcpy(&u, &f, sizeof u);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;
+    u += 0x7FFFu + ((u >> 16) & 1u);                     // half an ulp, less one bit when the kept part is even
+    return (uint16_t)(u >> 16);
+}
+
+inline float bf16_value(uint16_t bits) {                 // bfloat16 is the upper half of a binary32
+    uint32_t u = (uint32_t)bits << 16;
+    float f;
+    std::memcpy(&f, &u, sizeof f);
+    return f;
+}
+
 template <class R>
-inline R model_update(R &x, R &m, R grad, const Rule<R> &r) {
+inline R model_update(R &x, R &m, R grad, const Rule<R> &r, bool m_bf16 = false) {
     m = std::fma(r.beta, m, grad);                       // m <- beta m + grad
+    if (m_bf16) m = R(bf16_value(f32_to_bf16((float)m)));   // momentum kept in bfloat16: the rounded value is the state
     R direction = std::fma(r.beta, m, r.cg * grad);      // (1-beta) grad + beta m   (cg = 1-beta)
     R step = r.eta * direction;
     x = x - step;
@@ -213,6 +237,7 @@ struct Oracle {
     Rule<R> local, global;
     R alpha;
     std::vector<R> Theta, M, sc_Theta, sc_M;
+    bool momentum_bf16 = false;     // every server's momentum is rounded to bfloat16 whenever it is updated
     Delay<R> gps_delay;
     std::vector<R> gps_buffer, sc_gps_buffer;
     int64_t gps_updates = 0;
@@ -297,7 +322,7 @@ struct Oracle {
                 step = delayed_update<R>(s.theta[j], s.m[j], s.buffer[j], grad, local, s.delay.inv_d, first, refresh);
                 terms = delayed_scales<R>(s.sc_m[j], s.sc_buffer[j], s.m[j], grad, local, s.delay.inv_d, first, refresh);
             } else {
-                step = model_update<R>(s.theta[j], s.m[j], grad, local);
+                step = model_update<R>(s.theta[j], s.m[j], grad, local, momentum_bf16);
                 raise_to(s.sc_m[j], std::fabs(grad));
                 raise_to(s.sc_m[j], std::fabs(s.m[j]));
                 terms = step_scale<R>(s.sc_m[j], std::fabs(grad), local);
@@ -402,7 +427,7 @@ struct Oracle {
                 raise_to(sc_Theta[j], std::fabs(Theta[j]));
                 continue;
             }
-            model_update<R>(Theta[j], M[j], s.frozen[j], global);       // ModelUpdate
+            model_update<R>(Theta[j], M[j], s.frozen[j], global, momentum_bf16);   // ModelUpdate
             raise_to(sc_M[j], s.sc_aux[j]);                             // the scale of G travels with it
             raise_to(sc_M[j], std::fabs(M[j]));
             raise_to(sc_Theta[j], step_scale<R>(sc_M[j], s.sc_aux[j], global));
@@ -428,7 +453,7 @@ struct Oracle {
                 delayed_update<R>(Theta[j], M[j], gps_buffer[j], grad, global, gps_delay.inv_d, first, refresh);
                 terms = delayed_scales<R>(sc_M[j], sc_gps_buffer[j], M[j], std::fabs(grad), global, gps_delay.inv_d, first, refresh);
             } else {
-                model_update<R>(Theta[j], M[j], grad, global);
+                model_update<R>(Theta[j], M[j], grad, global, momentum_bf16);
                 raise_to(sc_M[j], std::fabs(grad));
                 raise_to(sc_M[j], std::fabs(M[j]));
                 terms = step_scale<R>(sc_M[j], std::fabs(grad), global);
@@ -493,12 +518,7 @@ int get_impl(Oracle<R> *o, int what, int l, double *out) {
     return -1;
 }
 
-inline float bf16_to_f32(uint16_t bits) {       // bfloat16 is the upper half of a binary32
-    uint32_t u = (uint32_t)bits << 16;
-    float f;
-    std::memcpy(&f, &u, sizeof f);
-    return f;
-}
+inline float bf16_to_f32(uint16_t bits) { return bf16_value(bits); }
 
 }  // namespace
 
@@ -605,6 +625,7 @@ int ho_set_K(void *p, int32_t l, int32_t K) {
 int ho_set_delay(void *p, int32_t which, int32_t d) {
     Handle *h = (Handle *)p;
     if (d < 0) return -1;
+    if (d > 0 && (h->precision == 32 ? h->f->momentum_bf16 : h->d->momentum_bf16)) return -2;
     if (h->precision == 32) {
         auto &dl = which < 0 ? h->f->gps_delay : h->f->lps[which].delay;
         if (dl.seen != 0) return -2;
@@ -673,5 +694,30 @@ int ho_norms(void *p, int32_t l, double *out) {
 }
 
 float ho_bf16_to_f32(uint16_t bits) { return bf16_to_f32(bits); }
+
+uint16_t ho_f32_to_bf16(float v) { return f32_to_bf16(v); }
+
+void ho_f32_to_bf16_array(const float *v, int64_t n, uint16_t *out) { for (int64_t j = 0; j < n; ++j) out[j] = f32_to_bf16(v[j]); }
+
+// Keep every server's momentum in bfloat16 from now on (on = 1) or in full precision (0).  Refused (-2) once a momentum
+// holds a value that bfloat16 cannot, or while a server runs the delayed rule.
+int ho_set_momentum_bf16(void *p, int32_t on) {
+    Handle *h = (Handle *)p;
+    auto apply = [&](auto *o) -> int {
+        if (on) {
+            if (o->gps_delay.enabled) return -2;
+            for (auto &s : o->lps) if (s.delay.enabled) return -2;
+            auto fits = [](const auto &v) {
+                for (auto x : v) if ((double)bf16_value(f32_to_bf16((float)x)) != (double)x) return false;
+                return true;
+            };
+            if (!fits(o->M)) return -2;
+            for (auto &s : o->lps) if (!fits(s.m)) return -2;
+        }
+        o->momentum_bf16 = on != 0;
+        return 0;
+    };
+    return h->precision == 32 ? apply(h->f) : apply(h->d);
+}
 
 }  // extern "C"

@@ -36,7 +36,8 @@ MUTANTS = [
     ("Delta sign flipped", "s.frozen[j] = (form == 1) ? s.acc[j] : (s.snap[j] - s.theta[j]);",
      "s.frozen[j] = (form == 1) ? -s.acc[j] : (s.theta[j] - s.snap[j]);"),
     ("threshold off by one", "if (accumulate && s.t - s.t_last >= s.K) {", "if (accumulate && s.t - s.t_last > s.K) {"),
-    ("GPS uses the local rule", "model_update<R>(Theta[j], M[j], s.frozen[j], global);", "model_update<R>(Theta[j], M[j], s.frozen[j], local);"),
+    ("GPS uses the local rule", "model_update<R>(Theta[j], M[j], s.frozen[j], global, momentum_bf16);",
+     "model_update<R>(Theta[j], M[j], s.frozen[j], local, momentum_bf16);"),
     ("LPS merges the live global model, not the frozen one", "s.theta[j] = std::fma(alpha, s.inbox[j], keep * s.theta[j]);",
      "s.theta[j] = std::fma(alpha, gps_Theta_live[j], keep * s.theta[j]);"),
     ("queue handled last-in first-out", "QueueItem<R> it = std::move(s.queue.front());\n        s.queue.pop_front();",
@@ -81,7 +82,8 @@ MUTANTS = [
     ("variants: average ignores the weights", "const R term = w * R(it.grad[j]);", "const R term = R(it.grad[j]);"),
     ("variants: average leaves the senders marked busy", "            s.worker_queued[it.worker] = 0;\n            out.worker = it.worker;\n        }\n        const R inv_n",
      "            out.worker = it.worker;\n        }\n        const R inv_n"),
-    ("variants: single tier uses the local rule", "model_update<R>(Theta[j], M[j], grad, global);", "model_update<R>(Theta[j], M[j], grad, local);"),
+    ("variants: single tier uses the local rule", "model_update<R>(Theta[j], M[j], grad, global, momentum_bf16);",
+     "model_update<R>(Theta[j], M[j], grad, local, momentum_bf16);"),
     ("variants: single tier forgets the weight", "const R grad = w * R(g[j]);", "const R grad = R(g[j]);"),
     ("variants: single tier never closes its momentum cycle", "if (gps_delay.enabled) { gps_delay.seen = refresh ? 0 : gps_delay.seen + 1; }",
      "if (gps_delay.enabled) { gps_delay.seen = gps_delay.seen + 1; }"),
@@ -91,6 +93,18 @@ MUTANTS = [
      "else if (exp != 0) u = sign | ((exp + 112u) << 23) | (frac << 12);"),
     ("scales: everything doubled at the end", "        case 10: copy_out(o->lps[l].sc_theta, out); return 0;",
      "        case 10: { std::vector<R> v = o->lps[l].sc_theta; for (auto &x : v) x *= R(2); copy_out(v, out); return 0; }"),
+    # momentum kept in bfloat16
+    ("bf16 momentum: truncated instead of rounded", "    u += 0x7FFFu + ((u >> 16) & 1u);", "    u += 0u;"),
+    ("bf16 momentum: ties rounded away from zero", "    u += 0x7FFFu + ((u >> 16) & 1u);", "    u += 0x8000u;"),
+    ("bf16 momentum: the step uses the momentum before rounding",
+     "    if (m_bf16) m = R(bf16_value(f32_to_bf16((float)m)));   // momentum kept in bfloat16: the rounded value is the state\n"
+     "    R direction = std::fma(r.beta, m, r.cg * grad);",
+     "    const R m_exact = m;\n    if (m_bf16) m = R(bf16_value(f32_to_bf16((float)m)));\n"
+     "    R direction = std::fma(r.beta, m_exact, r.cg * grad);"),
+    ("bf16 momentum: the global server's momentum stays unrounded", "model_update<R>(Theta[j], M[j], s.frozen[j], global, momentum_bf16);",
+     "model_update<R>(Theta[j], M[j], s.frozen[j], global);"),
+    ("bf16 momentum: the single-tier server's momentum stays unrounded", "model_update<R>(Theta[j], M[j], grad, global, momentum_bf16);",
+     "model_update<R>(Theta[j], M[j], grad, global);"),
 ]
 
 PIN_TESTS = [
@@ -126,6 +140,9 @@ PIN_TESTS = [
     vpins.test_average_adds_in_arrival_order_and_uses_the_weights,
     lambda: [vpins.test_single_tier_server_is_the_same_rule_one_level_up(64, d) for d in (1, 3)],
     vpins.test_single_tier_server_matches_the_filter_closed_form,
+    vpins.test_bf16_rounding_matches_torch,
+    lambda: [vpins.test_bf16_momentum_hand_example(p) for p in (32, 64)],
+    vpins.test_bf16_momentum_is_rounded_on_both_tiers_and_only_the_momentum,
 ]
 
 

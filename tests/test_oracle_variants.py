@@ -1,7 +1,8 @@
 """Pins for the comparison rules the oracle states next to Alg. 1: weighted arrivals (a caller-side staleness
 scaling, Sec. 5.2), the averaged step over several deltas (the synchronous outer step of the Local-SGD methods of
 Sec. 2), the single-tier server (the global server applying worker deltas itself, App. D's baseline column), and
-half-precision deltas (the workers of Sec. 5.1 train in fp16).  Each is checked against a closed form, a library
+half-precision deltas (the workers of Sec. 5.1 train in fp16); and this repository's own option of keeping the servers'
+momentum in bfloat16.  Each is checked against a closed form, a library
 routine, or a reduction to a rule that is pinned elsewhere; nothing re-types the oracle's loops."""
 import numpy as np
 import pytest
@@ -249,3 +250,107 @@ def test_without_global_momentum_the_global_model_never_needs_M():
         run = run + G[k]                       # eta_l = 1, beta_l = 0: each accumulated update is the delta itself
         assert np.array_equal(o.get(O.GPS_THETA), theta0 - eta_g * 1.0 * run)
         assert np.array_equal(o.get(O.GPS_MOM), G[k].astype(np.float64))       # what M would hold: just the last update
+
+
+# ---------------------------------------------------------------- momentum kept in bfloat16
+def test_bf16_rounding_matches_torch():
+    """binary32 -> bfloat16, nearest with ties to even: every upper half with the lower halves that decide a rounding
+    (exact, just above, just below and at the tie, all ones), plus random patterns, against torch's conversion."""
+    hi = np.arange(65536, dtype=np.uint32) << 16
+    lows = np.array([0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0xFFFF], dtype=np.uint32)
+    pats = (hi[:, None] | lows[None, :]).ravel()
+    pats = np.concatenate([pats, np.random.default_rng(31).integers(0, 1 << 32, size=1 << 20, dtype=np.uint64).astype(np.uint32)])
+    vals = pats.view(F32)
+    want = torch.from_numpy(vals.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = O.f32_to_bf16_array(vals)
+    nan = np.isnan(vals)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.all((got[nan] & 0x7F80) == 0x7F80) and np.all((got[nan] & 0x007F) != 0)       # a NaN stays a NaN
+    # hand-checked ties at 1.0 (spacing 2^-7): 1 + 2^-8 lies between 0x3F80 (even) and 0x3F81 -> down;
+    # 1 + 3 * 2^-8 between 0x3F81 and 0x3F82 (even) -> up; just above a tie always up; infinity by overflow
+    assert O.f32_to_bf16(1.0 + 2.0 ** -8) == 0x3F80
+    assert O.f32_to_bf16(1.0 + 3 * 2.0 ** -8) == 0x3F82
+    assert O.f32_to_bf16(float(F32(1.0 + 2.0 ** -8 + 2.0 ** -23))) == 0x3F81
+    assert O.f32_to_bf16(-(1.0 + 3 * 2.0 ** -8)) == 0xBF82
+    assert O.f32_to_bf16(float(np.finfo(F32).max)) == 0x7F80
+
+
+@pytest.mark.parametrize("precision", [32, 64])
+def test_bf16_momentum_hand_example(precision):
+    """One element, beta = 1, eta = 1, cg = 1, three deltas 1, 2^-8, 3 * 2^-8.  Momentum before rounding: 1, 1 + 2^-8,
+    then (from the ROUNDED 1) 1 + 3 * 2^-8; in bfloat16: 1, 1 (tie to even), 1 + 2^-6 (tie to even, upwards).  Each step
+    subtracts g + m with the rounded m: 2, then 1 + 2^-8, then 3 * 2^-8 + 1 + 2^-6."""
+    o = single([8.0], eta_l=1.0, beta_l=1.0, cg_l=1.0, precision=precision, form=FORM_ACCUMULATOR, momentum_bf16=True)
+    expect_m = [1.0, 1.0, 1.0 + 2.0 ** -6]
+    steps = [2.0, 1.0 + 2.0 ** -8, 3 * 2.0 ** -8 + 1.0 + 2.0 ** -6]
+    theta = 8.0
+    for k, g in enumerate([1.0, 2.0 ** -8, 3 * 2.0 ** -8]):
+        o.arrive_delta(0, 0, np.array([g], dtype=F32)); o.lps_step(0)
+        theta -= steps[k]
+        assert o.get(O.MOM)[0] == expect_m[k], k
+        assert o.get(O.THETA)[0] == theta, k
+    assert o.get(O.AUX)[0] == sum(steps)
+
+
+@pytest.mark.parametrize("precision", [32, 64])
+def test_bf16_momentum_changes_nothing_when_nothing_needs_rounding(precision):
+    """With beta = 1/2 and deltas that are small multiples of 2^-6, four updates keep every momentum within bfloat16's
+    eight significant bits: the option must then give the full-precision run bit for bit, on both tiers."""
+    rng = np.random.default_rng(33)
+    theta0 = rng.normal(0, 0.02, 64).astype(F32)
+    G = (rng.integers(-3, 4, size=(4, 64)) * 2.0 ** -6).astype(F32)
+    out = []
+    for flag in (False, True):
+        o = HalosOracle(theta0, 1, eta_l=0.25, beta_l=0.5, eta_g=0.5, beta_g=0.5, alpha=0.5, K=2, precision=precision,
+                        form=FORM_ACCUMULATOR, momentum_bf16=flag)
+        for k in range(4):
+            o.arrive_delta(0, 0, G[k])
+            if o.lps_step(0).sent:
+                o.gps_receive(0); o.arrive_global(0); o.lps_step(0)
+        out.append([o.get(w) for w in (O.THETA, O.MOM, O.AUX, O.GPS_THETA, O.GPS_MOM)])
+    for a, b in zip(*out):
+        assert np.array_equal(a, b)
+    assert np.any(out[0][4] != 0)           # the global server did update
+
+
+def test_bf16_momentum_is_rounded_on_both_tiers_and_only_the_momentum():
+    """Random run: every momentum value (local and global, single tier too) is a bfloat16 value afterwards; models and
+    accumulated updates are not confined to it; the run differs from the full-precision one."""
+    rng = np.random.default_rng(34)
+    theta0 = rng.normal(0, 0.02, 500).astype(F32)
+    G = rng.normal(0, 1e-3, (12, 500)).astype(F32)
+    runs = {}
+    for flag in (False, True):
+        o = HalosOracle(theta0, 1, eta_l=0.2, beta_l=0.9, eta_g=0.15, beta_g=0.5, alpha=0.25, K=3, precision=32,
+                        form=FORM_ACCUMULATOR, momentum_bf16=flag)
+        for k in range(13):                 # K = 3: the last update leaves an accumulation of one step open
+            o.arrive_delta(0, 0, G[k % 12])
+            if o.lps_step(0).sent:
+                o.gps_receive(0); o.arrive_global(0); o.lps_step(0)
+        two_tier_M = o.get(O.GPS_MOM).astype(F32)          # after updates that came through the local server only
+        o.gps_apply_delta(G[0])
+        runs[flag] = {w: o.get(w).astype(F32) for w in (O.THETA, O.MOM, O.AUX, O.GPS_THETA, O.GPS_MOM)}
+        runs[flag]["two_tier_M"] = two_tier_M
+    is_bf16 = lambda v: np.all((v.view(np.uint32) & 0xFFFF) == 0)
+    r = runs[True]
+    assert is_bf16(r[O.MOM]) and is_bf16(r["two_tier_M"]) and np.any(r["two_tier_M"] != 0) and is_bf16(r[O.GPS_MOM])
+    assert not is_bf16(runs[False][O.MOM]) and not is_bf16(runs[False]["two_tier_M"]) and not is_bf16(runs[False][O.GPS_MOM])
+    assert not is_bf16(r[O.THETA]) and not is_bf16(r[O.GPS_THETA]) and not is_bf16(r[O.AUX])
+    assert not np.array_equal(r[O.THETA], runs[False][O.THETA])
+    # the rounded momentum stays within half a bfloat16 spacing (2^-9 relative) of what one more exact update of the
+    # previous rounded value would give; against the full-precision run it drifts by far less than its own size
+    assert np.abs(r[O.MOM] - runs[False][O.MOM]).max() < 0.05 * np.abs(runs[False][O.MOM]).max()
+
+
+def test_bf16_momentum_refuses_the_delayed_rule_and_unrepresentable_state():
+    o = single([1.0], eta_l=0.2, beta_l=0.9)
+    o.set_delay(0, 4)
+    with pytest.raises(O.OracleError):
+        o.set_momentum_bf16(True)
+    o = single([1.0], eta_l=0.2, beta_l=0.9, momentum_bf16=True)
+    with pytest.raises(O.OracleError):
+        o.set_delay(0, 4)
+    o = single([1.0], eta_l=0.2, beta_l=0.9)
+    o.arrive_delta(0, 0, np.array([1.0 + 2.0 ** -20], dtype=F32)); o.lps_step(0)
+    with pytest.raises(O.OracleError):
+        o.set_momentum_bf16(True)            # the momentum now holds a value bfloat16 cannot
