@@ -30,7 +30,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 # Algorithmic bytes per parameter per launch (fp32 state; delta fp32 or bf16).
-def bytes_per_param(label: str, delta_dtype: str, delayed: bool) -> int:
+def bytes_per_param(label: str, delta_dtype: str, delayed: bool, momentum_bytes: int = 4) -> int:
     """Algorithmic bytes per parameter of one launch, from the kernel label the harness gave it.
 
     Every array the event needs is read once and written once (fp32 = 4 bytes, a bf16 delta 2):
@@ -49,6 +49,7 @@ def bytes_per_param(label: str, delta_dtype: str, delayed: bool) -> int:
       lps_update_batchK_*  K queued deltas in one pass: K deltas read, K worker models written, momentum, model and
                     (if any of them accumulates) the third buffer read and written once.
       pull          read and write a model (8).
+    momentum_bytes = 2 (HALOS_FLAG_BF16_MOMENTUM): the momentum's read and write cost 4 instead of 8.
     """
     if label == "lps_merge":
         return 16
@@ -62,11 +63,11 @@ def bytes_per_param(label: str, delta_dtype: str, delayed: bool) -> int:
     if label.startswith("lps_update_batch"):
         k = int(parts[2][len("batch"):])
         g = 4 if delta_dtype == "f32" else 2
-        return k * g + 16 + (0 if "noacc" in parts else 8) + 4 * k
+        return k * g + 8 + 2 * momentum_bytes + (0 if "noacc" in parts else 8) + 4 * k
     if delayed:
         rule = 4 if "first" in parts else (12 if "refresh" in parts else 8)
     else:
-        rule = 8
+        rule = 2 * momentum_bytes
     if label.startswith("gps_update"):
         return 16 + rule
     assert label.startswith("lps_update"), label
@@ -114,7 +115,8 @@ def split_steps(events, n_updates_per_step: int, n_steps: int):
 
 
 def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: str = "regions", fuse_pull: bool = True,
-                 snapshot: bool = False, defer_clear: bool = False, gps_no_momentum: bool = False, batch: int = 0):
+                 snapshot: bool = False, defer_clear: bool = False, gps_no_momentum: bool = False, batch: int = 0,
+                 bf16_momentum: bool = False):
     import numpy as np
     import torch
     import synth
@@ -127,10 +129,12 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
     N = w.layout.total
     t0 = time.time()
     hp = None
-    if snapshot or defer_clear or gps_no_momentum:
+    if bf16_momentum and (w.d_l > 1 or w.d_g > 1):
+        raise SystemExit(f"bench.py: workload {name} uses a momentum delay; 16-bit momentum is not built for the delayed rule")
+    if snapshot or defer_clear or gps_no_momentum or bf16_momentum:
         from paper_2506_04531_amd import binding as B
         flags = (B.FLAG_SNAPSHOT if snapshot else 0) | (B.FLAG_DEFER_CLEAR if defer_clear else 0) | \
-                (B.FLAG_GPS_NO_MOMENTUM if gps_no_momentum else 0)
+                (B.FLAG_GPS_NO_MOMENTUM if gps_no_momentum else 0) | (B.FLAG_BF16_MOMENTUM if bf16_momentum else 0)
         hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, 0.0 if gps_no_momentum else w.beta_g, w.alpha, w.k_range[0],
                              cg_l=w.cg_l, cg_g=w.cg_g, flags=flags)
     c = Cluster(w, "cuda:0", k_initial=trace.k_initial, placement=placement, verbose=verbose, hp=hp)
@@ -161,7 +165,7 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
         if not pairs:
             continue
         ms = np.array([a.elapsed_time(b) for a, b in pairs], dtype=np.float64)
-        bpp = bytes_per_param(label, w.delta_dtype, (w.d_g if label.startswith("gps") else w.d_l) > 1)
+        bpp = bytes_per_param(label, w.delta_dtype, (w.d_g if label.startswith("gps") else w.d_l) > 1, 2 if bf16_momentum else 4)
         kernels[label] = {
             "launches": int(ms.size),
             "avg_ms": float(ms.mean()),
@@ -185,7 +189,7 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
     # dominant kernel: the LPS update variant that takes the most time
     dom = max(upd_labels, key=lambda k: kernels[k]["total_ms"])
     stored = MEASURED_TRAFFIC.get(kernels_digest())
-    traffic = (stored or {}).get(f"{name}:{dom}")
+    traffic = None if bf16_momentum else (stored or {}).get(f"{name}:{dom}")     # the counter runs were taken with fp32 momentum
     if traffic is not None:
         traffic_source = ("stored: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/, valid for the "
                           "kernel source with this sha256 only")
@@ -213,6 +217,7 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
         "kernels": kernels, "roofline": roofline, "placement": placement, "hbm_regions_found": n_regions,
         "fuse_pull": fuse_pull, "delta_form": "snapshot" if snapshot else "accumulator",
         "defer_clear": defer_clear, "gps_no_momentum": gps_no_momentum, "batch": batch,
+        "momentum_dtype": "bf16" if bf16_momentum else "f32",
         "momentum_delay": {"d_l": w.d_l, "d_g": w.d_g},
     }
 
@@ -586,6 +591,9 @@ def main():
                     help="merges leave the third buffer (12 B/parameter instead of 16); the next update restarts it")
     ap.add_argument("--gps-no-momentum", action="store_true",
                     help="the global server keeps no momentum (beta_g = 0, Sec. 5.4): 16 B/parameter per GPS update instead of 24")
+    ap.add_argument("--bf16-momentum", action="store_true",
+                    help="both tiers keep their momentum in bfloat16, rounded at every update (HALOS_FLAG_BF16_MOMENTUM: 4 B/parameter "
+                         "less per update, results differ by the rounding); workloads with a momentum delay are left out")
     ap.add_argument("--batch", type=int, default=4,
                     help="2..4: update steps of one server that follow each other directly go through one pass "
                          "(halos_lps_step_batch; same results bit for bit); 0 = every step its own pass")
@@ -628,10 +636,13 @@ def main():
     if args.placement_search:
         return placement_search_mode(args.search_elements, args.search_dtype)
 
-    variant = dict(snapshot=args.snapshot, defer_clear=args.defer_clear, gps_no_momentum=args.gps_no_momentum, batch=args.batch)
+    variant = dict(snapshot=args.snapshot, defer_clear=args.defer_clear, gps_no_momentum=args.gps_no_momentum, batch=args.batch,
+                   bf16_momentum=args.bf16_momentum)
     head = run_workload(args.workload, args.steps, args.warmup, not args.quiet, args.placement, not args.no_fuse_pull, **variant)
     others = []
     for name in [x for x in args.also.split(",") if x and x != args.workload]:
+        if args.bf16_momentum and name.endswith("-dn"):
+            continue
         others.append(run_workload(name, args.steps, args.warmup, not args.quiet, args.placement, not args.no_fuse_pull, **variant))
     plain = None
     if args.placement == "regions" and not args.no_plain_placement:      # what a caller with ordinary allocations gets
@@ -643,14 +654,19 @@ def main():
     if not args.no_variants_ab:         # the same workload with one option changed at a time (one warm-up + one timed step each)
         vab = {}
         for tag, kw in (("single_steps", dict(variant, batch=0)), ("defer_clear", dict(variant, defer_clear=True)),
-                        ("gps_no_momentum", dict(variant, gps_no_momentum=True)), ("snapshot_form", dict(variant, snapshot=True))):
+                        ("gps_no_momentum", dict(variant, gps_no_momentum=True)), ("snapshot_form", dict(variant, snapshot=True)),
+                        ("bf16_momentum", dict(variant, bf16_momentum=True))):
+            if tag == "bf16_momentum" and args.workload.endswith("-dn"):
+                continue
             r = run_workload(args.workload, 1, 1, False, args.placement, not args.no_fuse_pull, **kw)
             vab[tag] = {"value": r["params_updated_per_s"], "ms_per_step": r["ms_per_step"], "whole_path_GBps": r["whole_path_GBps"],
                         "kernels": {k: {"launches": v["launches"], "avg_ms": v["avg_ms"], "bytes_per_param": v["bytes_per_param"],
                                         "achieved_GBps": v["achieved_GBps"]} for k, v in r["kernels"].items()}}
         vab["note"] = ("single_steps: every update its own pass (no halos_lps_step_batch); defer_clear: merges leave the third buffer "
                        "(HALOS_FLAG_DEFER_CLEAR, same results); gps_no_momentum: beta_g = 0 without a momentum array (Sec. 5.4; "
-                       "another optimizer setting); snapshot_form: Delta by subtraction (HALOS_FLAG_SNAPSHOT; rounds differently)")
+                       "another optimizer setting); snapshot_form: Delta by subtraction (HALOS_FLAG_SNAPSHOT; rounds differently); "
+                       "bf16_momentum: both tiers' momentum in bfloat16 (HALOS_FLAG_BF16_MOMENTUM; an option of this library that "
+                       "changes results by the rounding; every update its own pass)")
     ab = None if args.no_end_model_ab else end_model_ab(args.workload, verbose=not args.quiet)
     gab = None if args.no_graph_ab else graph_ab()
     cpu = None if args.no_cpu_baseline else cpu_baseline(args.workload)
@@ -669,7 +685,7 @@ def main():
                    "placement": head["placement"], "hbm_regions_found": head["hbm_regions_found"],
                    "fuse_pull": head["fuse_pull"], "delta_form": head["delta_form"],
                    "defer_clear": head["defer_clear"], "gps_no_momentum": head["gps_no_momentum"], "batch": head["batch"],
-                   "momentum_delay": head["momentum_delay"]},
+                   "momentum_dtype": head["momentum_dtype"], "momentum_delay": head["momentum_delay"]},
         "roofline": head["roofline"],
         "plain_placement": plain,
         "cpu_baseline": cpu,

@@ -135,6 +135,17 @@ typedef struct {
  * and the next update are unspecified (logically zero).  Not with HALOS_FLAG_SNAPSHOT.  Honoured at halos_gps_create. */
 #define HALOS_FLAG_DEFER_CLEAR 8u
 
+/* Momentum kept in bfloat16, at both tiers: the M tensors of halos_gps_create and the m tensors of every
+ * halos_lps_create are arrays of numel 16-bit elements (half the bytes; same 16-byte alignment).  After
+ * m <- beta m + g the new momentum is rounded to bfloat16 (round to nearest, ties to even, decided on the fp32 value;
+ * a NaN becomes 0x7FC0), and it is the rounded value that enters the step and is stored; models, accumulated updates
+ * and returned global models stay fp32.  An option of this library, not of the paper (which does not state the
+ * servers' precision; its workers train in fp16, Sec. 5.1): 4 bytes per parameter less on every update (LPS and GPS),
+ * results that differ from the fp32-momentum run by the rounding.  Not available with a momentum delay above 1
+ * (ESTATE); halos_lps_step_average refuses, halos_lps_step_batch falls back to single steps.  Honoured at
+ * halos_gps_create. */
+#define HALOS_FLAG_BF16_MOMENTUM 16u
+
 /* What one halos_lps_step did. */
 typedef struct {
     int32_t kind;         /* 0 queue was empty, 1 applied a worker delta, 2 merged a global model */
@@ -159,7 +170,8 @@ enum {
  *   layout   tensor list (copied).  Tensors with numel 0 are allowed and skipped.
  *   hp       hyper-parameters (copied); hp->global is the GPS rule.
  *   Theta    device tensors holding the initial model Theta_0 (read and later updated in place).
- *   M        device tensors for the GPS momentum; zero-filled on `stream` by this call (NULL under HALOS_FLAG_GPS_NO_MOMENTUM).
+ *   M        device tensors for the GPS momentum; zero-filled on `stream` by this call (NULL under HALOS_FLAG_GPS_NO_MOMENTUM;
+ *            16-bit elements under HALOS_FLAG_BF16_MOMENTUM).
  * Errors: EINVAL (null/misaligned pointers, n_tensors < 1, negative numel, more than 2^32-1 elements
  * in one tensor, non-finite or out-of-range hyper-parameters), ENOMEM, EHIP.
  */
@@ -171,7 +183,8 @@ halos_status halos_gps_create(const halos_layout *layout, const halos_hparams *h
  *   lps_id      caller's label for this server, >= 0 (reported in error strings only)
  *   n_workers   number of workers that may push to it, >= 1
  *   theta,m,acc device tensors of the layout.  On `stream` this call copies the GPS's CURRENT model into
- *               theta and zero-fills m and acc (under HALOS_FLAG_SNAPSHOT acc receives the model too).  `acc` is the server's third buffer: it holds the
+ *               theta and zero-fills m and acc (under HALOS_FLAG_SNAPSHOT acc receives the model too; under
+ *               HALOS_FLAG_BF16_MOMENTUM m has 16-bit elements).  `acc` is the server's third buffer: it holds the
  *               accumulated update G = theta_{t_last} - theta_t while collecting, stays frozen while that
  *               update is in flight, is overwritten with the returned global model by halos_gps_merge,
  *               and is zeroed again by the merge step.

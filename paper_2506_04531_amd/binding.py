@@ -19,6 +19,7 @@ FLAG_NORMS = 1
 FLAG_SNAPSHOT = 2
 FLAG_GPS_NO_MOMENTUM = 4
 FLAG_DEFER_CLEAR = 8
+FLAG_BF16_MOMENTUM = 16
 PHASE_ACCUMULATING, PHASE_SENT, PHASE_RETURNING, PHASE_QUEUED = 0, 1, 2, 3
 
 

@@ -78,7 +78,8 @@ halos_status check_hparams(const halos_hparams *hp) {
     if (!rule_ok(hp->local) || !rule_ok(hp->global)) return fail(HALOS_EINVAL, "non-finite eta/beta/cg");
     if (!(hp->alpha >= 0.0f && hp->alpha <= 1.0f)) return fail(HALOS_EINVAL, "alpha %g outside [0,1]", (double)hp->alpha);
     if (hp->K < 1) return fail(HALOS_EINVAL, "K = %d, must be >= 1", hp->K);
-    if ((hp->flags & ~(uint32_t)(HALOS_FLAG_NORMS | HALOS_FLAG_SNAPSHOT | HALOS_FLAG_GPS_NO_MOMENTUM | HALOS_FLAG_DEFER_CLEAR)) != 0)
+    if ((hp->flags & ~(uint32_t)(HALOS_FLAG_NORMS | HALOS_FLAG_SNAPSHOT | HALOS_FLAG_GPS_NO_MOMENTUM | HALOS_FLAG_DEFER_CLEAR |
+                                 HALOS_FLAG_BF16_MOMENTUM)) != 0)
         return fail(HALOS_EINVAL, "unknown bits in flags");
     if ((hp->flags & HALOS_FLAG_SNAPSHOT) && (hp->flags & HALOS_FLAG_DEFER_CLEAR))
         return fail(HALOS_EINVAL, "HALOS_FLAG_DEFER_CLEAR has no meaning under HALOS_FLAG_SNAPSHOT (the merge writes the snapshot)");
@@ -107,6 +108,7 @@ struct halos_gps {
     int64_t updates = 0;
     int n_lps_attached = 0;
     bool no_momentum = false;          // HALOS_FLAG_GPS_NO_MOMENTUM: there is no M; beta stays 0
+    bool momentum_bf16 = false;        // HALOS_FLAG_BF16_MOMENTUM: M and every local server's m hold bfloat16
     std::vector<const void *> validated_delta;   // last pointer set accepted by halos_gps_push_update
     halos_dtype validated_delta_dtype = HALOS_F32;
     bool retired = false;              // halos_gps_destroy was called while local servers were still attached
@@ -406,8 +408,9 @@ halos_status halos_gps_create(const halos_layout *layout, const halos_hparams *h
     g->rule = hp->global;
 
     g->no_momentum = (hp->flags & HALOS_FLAG_GPS_NO_MOMENTUM) != 0;
+    g->momentum_bf16 = (hp->flags & HALOS_FLAG_BF16_MOMENTUM) != 0;
     st = check_tensors(g, Theta, sizeof(float), "Theta");
-    if (st == HALOS_OK && !g->no_momentum) st = check_tensors(g, M, sizeof(float), "M");
+    if (st == HALOS_OK && !g->no_momentum) st = check_tensors(g, M, g->momentum_bf16 ? 2 : sizeof(float), "M");
     if (st != HALOS_OK) { delete g; return st; }
 
     // tile table and launch ranges
@@ -444,7 +447,8 @@ halos_status halos_gps_create(const halos_layout *layout, const halos_hparams *h
 
     for (const TileRange &r : g->ranges) {       // M <- 0
         if (g->no_momentum) break;
-        e = launch_init((hipStream_t)stream, g->d_tiles, r, nullptr, nullptr, g->d_M, nullptr, false, current_shape(g));
+        e = launch_init((hipStream_t)stream, g->d_tiles, r, nullptr, nullptr, g->d_M, nullptr, false, current_shape(g),
+                        g->momentum_bf16);
         if (e != hipSuccess) {
             (void)hipFree(g->d_tables); (void)hipFree(g->d_tiles); delete g;
             return fail_hip(e, "zero-filling M");
@@ -481,7 +485,7 @@ halos_status halos_lps_create(halos_gps *g, int32_t lps_id, int32_t n_workers, v
     if (n_workers < 1) return fail(HALOS_EINVAL, "n_workers = %d, must be >= 1", n_workers);
     halos_status st = check_device(g);
     if (st == HALOS_OK) st = check_tensors(g, theta, sizeof(float), "theta");
-    if (st == HALOS_OK) st = check_tensors(g, m, sizeof(float), "m");
+    if (st == HALOS_OK) st = check_tensors(g, m, g->momentum_bf16 ? 2 : sizeof(float), "m");
     if (st == HALOS_OK) st = check_tensors(g, acc, sizeof(float), "acc");
     if (st != HALOS_OK) return st;
     halos_lps *l = new (std::nothrow) halos_lps(n_workers, g->hp.K);
@@ -524,7 +528,7 @@ halos_status halos_lps_create(halos_gps *g, int32_t lps_id, int32_t n_workers, v
     }
     for (const TileRange &r : g->ranges) {       // theta <- Theta, m <- 0, acc <- 0
         hipError_t e = launch_init((hipStream_t)stream, g->d_tiles, r, g->d_Theta, l->d_theta, l->d_m, l->d_acc,
-                                   l->snapshot, current_shape(g));
+                                   l->snapshot, current_shape(g), g->momentum_bf16);
         if (e != hipSuccess) {
             if (l->d_norm_partials) (void)hipFree(l->d_norm_partials);
             (void)hipFree(l->d_tables);
@@ -699,7 +703,8 @@ static halos_status lps_step_impl(halos_lps *l, void *stream, halos_step_info *i
                                               l->rule.eta, l->rule.beta, l->rule.cg * inv_d, inv_d, p.weight, partials, shape);
             } else {
                 e = launch_lps_update((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_acc, pull_tab, args,
-                                      g_kind, third_mode, l->rule.eta, l->rule.beta, l->rule.cg, p.weight, partials, shape);
+                                      g_kind, third_mode, l->rule.eta, l->rule.beta, l->rule.cg, p.weight, partials, shape,
+                                      g->momentum_bf16);
             }
             if (e != hipSuccess) return fail_hip(e, "launching the local update");
             n_partials += launch_grid_size(r, shape);
@@ -752,6 +757,7 @@ namespace {
 
 // Can the first `count` queue items go through one multi-delta pass?  All must be plain deltas of one element type.
 bool multi_eligible(const halos_lps *l, int32_t count, bool pull) {
+    if (l->gps->momentum_bf16) return false;           // the multi-delta passes keep the momentum in fp32 only
     if (!l->proto.head_is_deltas(count)) return false;
     const PendingDelta &first = l->pending[l->proto.item(0).worker];
     for (int32_t i = 0; i < count; ++i) {
@@ -789,6 +795,7 @@ halos_status halos_lps_step_average(halos_lps *l, int32_t count, void *stream, h
     halos_gps *g = l->gps;
     if (l->cycle.d() > 1) return fail(HALOS_ESTATE, "lps %d: the averaged step is not available under a momentum delay", l->id);
     if (l->d_norm_partials) return fail(HALOS_ESTATE, "lps %d: the averaged step does not feed the norm monitors", l->id);
+    if (g->momentum_bf16) return fail(HALOS_ESTATE, "lps %d: the averaged step is not available with bfloat16 momentum", l->id);
     if (!multi_eligible(l, count, false))
         return fail(HALOS_ESTATE, "lps %d: the first %d queue items are not %d worker deltas of one element type", l->id, count, count);
     halos_status st = check_device(g);
@@ -951,7 +958,7 @@ halos_status halos_gps_merge(halos_gps *g, halos_lps *from, void *stream) {
                                         g->rule.eta, g->rule.cg, shape);
         } else {
             e = launch_gps_update((hipStream_t)stream, g->d_tiles, r, g->d_Theta, g->d_M, from->d_acc, from->d_acc,
-                                  g->rule.eta, g->rule.beta, g->rule.cg, shape);
+                                  g->rule.eta, g->rule.beta, g->rule.cg, shape, g->momentum_bf16);
         }
         if (e != hipSuccess) return fail_hip(e, "launching the global update");
     }
@@ -992,7 +999,7 @@ halos_status halos_gps_push_update(halos_gps *g, const void *const *gptrs, halos
                                           g->rule.cg * inv_d, inv_d, weight, nullptr, shape);
         } else {
             e = launch_lps_update((hipStream_t)stream, g->d_tiles, r, g->d_Theta, g->d_M, nullptr, nullptr, args, g_kind,
-                                  THIRD_NONE, g->rule.eta, g->rule.beta, g->rule.cg, weight, nullptr, shape);
+                                  THIRD_NONE, g->rule.eta, g->rule.beta, g->rule.cg, weight, nullptr, shape, g->momentum_bf16);
         }
         if (e != hipSuccess) return fail_hip(e, "launching the global server's update");
     }
@@ -1104,6 +1111,8 @@ halos_status halos_lps_get_norms(const halos_lps *l, void *stream, double *out) 
 static halos_status set_momentum_delay(const halos_gps *g, MomentumCycle &cycle, float **d_slot, int32_t d,
                                        void *const *buffer, void *stream, const char *who) {
     if (d < 1) return fail(HALOS_EINVAL, "d = %d, must be >= 1", d);
+    if (d > 1 && g->momentum_bf16)
+        return fail(HALOS_ESTATE, "%s keeps its momentum in bfloat16 (HALOS_FLAG_BF16_MOMENTUM): the delayed rule is not built for that", who);
     if (cycle.seen() != 0)
         return fail(HALOS_ESTATE, "%s is %d updates into a cycle of %d: the delay can change only between cycles", who,
                     cycle.seen(), cycle.d());

@@ -88,6 +88,36 @@ __device__ __forceinline__ float ldg1(const gf32 *p) { return *p; }
 __device__ __forceinline__ float ldg1(const gu16 *p) { return bf16_up(*p); }
 __device__ __forceinline__ float ldg1(const gf16 *p) { return static_cast<float>(*p); }
 
+// Momentum kept in bfloat16 (MB): the array holds 16-bit patterns; a new momentum is rounded to bfloat16 (nearest,
+// ties to even, decided on the binary32 value; a NaN becomes the quiet NaN 0x7FC0) BEFORE it enters the step, so the
+// value that is used is the value that is stored.  bf16_round returns that value as a float (low half zero).
+__device__ __forceinline__ float bf16_round(float v) {
+    const uint32_t u = __float_as_uint(v);
+    const uint32_t r = (u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u;
+    return __uint_as_float((u & 0x7FFFFFFFu) > 0x7F800000u ? 0x7FC00000u : r);
+}
+
+template <bool MB> struct MomentumElem { typedef gf32 type; };
+template <> struct MomentumElem<true> { typedef gu16 type; };
+template <bool MB>
+__device__ __forceinline__ typename MomentumElem<MB>::type *momentum_ptr(float *p) {
+    return (typename MomentumElem<MB>::type *)p;
+}
+
+template <bool NT>
+__device__ __forceinline__ void stm4(gf32 *p, f32x4 v) { st4<NT>(p, v); }
+template <bool NT>
+__device__ __forceinline__ void stm4(gu16 *p, f32x4 v) {          // v holds bfloat16 values: keep the upper halves
+    u16x4 b;
+    b[0] = static_cast<unsigned short>(__float_as_uint(v[0]) >> 16); b[1] = static_cast<unsigned short>(__float_as_uint(v[1]) >> 16);
+    b[2] = static_cast<unsigned short>(__float_as_uint(v[2]) >> 16); b[3] = static_cast<unsigned short>(__float_as_uint(v[3]) >> 16);
+    gu16x4 *q = (gu16x4 *)p;
+    if constexpr (NT) __builtin_nontemporal_store(b, q);
+    else *q = b;
+}
+__device__ __forceinline__ void stm1(gf32 *p, float v) { *p = v; }
+__device__ __forceinline__ void stm1(gu16 *p, float v) { *p = static_cast<unsigned short>(__float_as_uint(v) >> 16); }
+
 // The same four delta elements as they lie in memory, and their upcast as a separate step: a pass that loads several
 // deltas under (uniform) branches issues all its loads first and converts afterwards, instead of waiting per delta.
 template <bool NT> __device__ __forceinline__ f32x4 ldraw4(const gf32 *p) { return ld4<NT>(p); }
@@ -134,8 +164,10 @@ __device__ __forceinline__ float grad1(const GP *g, const gf32 *start, uint32_t 
 }
 
 // ModelUpdate (App. E) on one element; returns the step that was subtracted from x.
+template <bool MB = false>
 __device__ __forceinline__ float model_update(float &x, float &m, float g, float eta, float beta, float cg) {
     m = __fmaf_rn(beta, m, g);
+    if constexpr (MB) m = bf16_round(m);
     const float u = __fmaf_rn(beta, m, __fmul_rn(cg, g));
     const float s = __fmul_rn(eta, u);
     x = __fsub_rn(x, s);
@@ -144,12 +176,13 @@ __device__ __forceinline__ float model_update(float &x, float &m, float g, float
 
 
 // The same on four lanes of a 128-bit access (vector elements cannot be bound to references).
+template <bool MB = false>
 __device__ __forceinline__ f32x4 model_update4(f32x4 &x, f32x4 &m, f32x4 g, float eta, float beta, float cg) {
     f32x4 s;
 #pragma unroll
     for (int i = 0; i < VEC; ++i) {
         float xi = x[i], mi = m[i];
-        s[i] = model_update(xi, mi, g[i], eta, beta, cg);
+        s[i] = model_update<MB>(xi, mi, g[i], eta, beta, cg);
         x[i] = xi;
         m[i] = mi;
     }
@@ -223,7 +256,8 @@ __device__ __forceinline__ void block_sum_store(double v, double *dst) {
 // its next round from: ModelUpdate and "schedule the worker" of Alg. 1 in one pass instead of an update pass plus a copy pass).
 // With NORM every workgroup also leaves the sum of g^2 over its tiles in partials[blockIdx.x].
 // With FROM_END (needs PULL) the delta tensors hold the worker's end model and pull_tab its start model.
-template <typename GT, int THIRD, bool NT, bool PULL, bool NORM, bool FROM_END = false>
+// With MB the momentum tensors hold bfloat16 (see bf16_round).
+template <typename GT, int THIRD, bool NT, bool PULL, bool NORM, bool FROM_END = false, bool MB = false>
 __global__ void __launch_bounds__(BLOCK_THREADS)
 lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, uint32_t tensor_base,
                   float *const *__restrict__ theta_tab, float *const *__restrict__ m_tab,
@@ -238,7 +272,7 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
         const Tile tl = tiles[t];
         const uint32_t tensor = tl.tensor;
         gf32 *th = to_global(theta_tab[tensor]) + tl.start;
-        gf32 *mm = to_global(m_tab[tensor]) + tl.start;
+        auto *mm = momentum_ptr<MB>(m_tab[tensor]) + tl.start;
         gf32 *ac = THIRD != 0 ? to_global(acc_tab[tensor]) + tl.start : nullptr;
         gf32 *pd = PULL ? to_global(pull_tab[tensor]) + tl.start : nullptr;
         const auto *g = to_global(static_cast<const GT *>(gargs.p[tensor - tensor_base])) + tl.start;
@@ -248,7 +282,7 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
                 gv[u] = grad4<FROM_END, NT>(g, pd, off, gw);
-                mv[u] = ld4<NT>(mm + off);
+                mv[u] = ldg4<NT>(mm + off);
                 tv[u] = ld4<NT>(th + off);
                 if constexpr (LOAD_THIRD) av[u] = ld4<NT>(ac + off);
             }
@@ -261,8 +295,8 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
-                const f32x4 s = model_update4(tv[u], mv[u], gv[u], eta, beta, cg);
-                st4<NT>(mm + off, mv[u]);
+                const f32x4 s = model_update4<MB>(tv[u], mv[u], gv[u], eta, beta, cg);
+                stm4<NT>(mm + off, mv[u]);
                 st4<NT>(th + off, tv[u]);
                 if constexpr (PULL) st4<NT>(pd + off, tv[u]);
                 if constexpr (THIRD == 1) st4<NT>(ac + off, add4(av[u], s));
@@ -273,10 +307,10 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
             const uint32_t len = tl.len;
             for (uint32_t off = tid * VEC; off < len; off += BLOCK_THREADS * VEC) {
                 if (off + VEC <= len) {
-                    f32x4 gv = grad4<FROM_END, NT>(g, pd, off, gw), mv = ld4<NT>(mm + off), tv = ld4<NT>(th + off);
+                    f32x4 gv = grad4<FROM_END, NT>(g, pd, off, gw), mv = ldg4<NT>(mm + off), tv = ld4<NT>(th + off);
                     if constexpr (NORM) norm_acc += static_cast<double>(sumsq4(gv, 0.f));
-                    const f32x4 s = model_update4(tv, mv, gv, eta, beta, cg);
-                    st4<NT>(mm + off, mv);
+                    const f32x4 s = model_update4<MB>(tv, mv, gv, eta, beta, cg);
+                    stm4<NT>(mm + off, mv);
                     st4<NT>(th + off, tv);
                     if constexpr (PULL) st4<NT>(pd + off, tv);
                     if constexpr (THIRD == 1) st4<NT>(ac + off, add4(ld4<NT>(ac + off), s));
@@ -284,11 +318,11 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
                     if constexpr (THIRD == 3) st4<NT>(ac + off, add4(zero, s));
                 } else {
                     for (uint32_t k = off; k < len; ++k) {      // ragged tail: fewer than 4 elements
-                        float mv = mm[k], tv = th[k];
+                        float mv = ldg1(mm + k), tv = th[k];
                         const float gk = grad1<FROM_END>(g, pd, k, gw);
                         if constexpr (NORM) norm_acc += static_cast<double>(__fmul_rn(gk, gk));
-                        const float s = model_update(tv, mv, gk, eta, beta, cg);
-                        mm[k] = mv; th[k] = tv;
+                        const float s = model_update<MB>(tv, mv, gk, eta, beta, cg);
+                        stm1(mm + k, mv); th[k] = tv;
                         if constexpr (PULL) pd[k] = tv;
                         if constexpr (THIRD == 1) ac[k] = __fadd_rn(ac[k], s);
                         if constexpr (THIRD == 2) ac[k] = __fsub_rn(ac[k], tv);
@@ -395,8 +429,8 @@ lps_update_multi_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32
 }
 
 // ---------------------------------------------------------------------------------------------
-// S3: global-server step.  G and out may alias.
-template <bool NT>
+// S3: global-server step.  G and out may alias.  With MB the momentum tensors hold bfloat16 (see bf16_round).
+template <bool NT, bool MB = false>
 __global__ void __launch_bounds__(BLOCK_THREADS)
 gps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi,
                   float *const *__restrict__ Theta_tab, float *const *__restrict__ M_tab,
@@ -406,7 +440,7 @@ gps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
         const Tile tl = tiles[t];
         const uint32_t tensor = tl.tensor;
         gf32 *Th = to_global(Theta_tab[tensor]) + tl.start;
-        gf32 *Mm = to_global(M_tab[tensor]) + tl.start;
+        auto *Mm = momentum_ptr<MB>(M_tab[tensor]) + tl.start;
         const gf32 *G = to_global(G_tab[tensor]) + tl.start;
         gf32 *out = to_global(out_tab[tensor]) + tl.start;
         if (tl.len == TILE_ELEMS) {
@@ -415,14 +449,14 @@ gps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
                 gv[u] = ld4<NT>(G + off);
-                mv[u] = ld4<NT>(Mm + off);
+                mv[u] = ldg4<NT>(Mm + off);
                 tv[u] = ld4<NT>(Th + off);
             }
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
-                model_update4(tv[u], mv[u], gv[u], eta, beta, cg);
-                st4<NT>(Mm + off, mv[u]);
+                model_update4<MB>(tv[u], mv[u], gv[u], eta, beta, cg);
+                stm4<NT>(Mm + off, mv[u]);
                 st4<NT>(Th + off, tv[u]);
                 st4<NT>(out + off, tv[u]);
             }
@@ -430,16 +464,16 @@ gps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
             const uint32_t len = tl.len;
             for (uint32_t off = tid * VEC; off < len; off += BLOCK_THREADS * VEC) {
                 if (off + VEC <= len) {
-                    f32x4 gv = ld4<NT>(G + off), mv = ld4<NT>(Mm + off), tv = ld4<NT>(Th + off);
-                    model_update4(tv, mv, gv, eta, beta, cg);
-                    st4<NT>(Mm + off, mv);
+                    f32x4 gv = ld4<NT>(G + off), mv = ldg4<NT>(Mm + off), tv = ld4<NT>(Th + off);
+                    model_update4<MB>(tv, mv, gv, eta, beta, cg);
+                    stm4<NT>(Mm + off, mv);
                     st4<NT>(Th + off, tv);
                     st4<NT>(out + off, tv);
                 } else {
                     for (uint32_t k = off; k < len; ++k) {
-                        float mv = Mm[k], tv = Th[k];
-                        model_update(tv, mv, G[k], eta, beta, cg);
-                        Mm[k] = mv; Th[k] = tv; out[k] = tv;
+                        float mv = ldg1(Mm + k), tv = Th[k];
+                        model_update<MB>(tv, mv, G[k], eta, beta, cg);
+                        stm1(Mm + k, mv); Th[k] = tv; out[k] = tv;
                     }
                 }
             }
@@ -790,7 +824,8 @@ pull_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, 
 
 // ---------------------------------------------------------------------------------------------
 // Alg. 1, LPS initialisation: theta <- Theta_0, m <- 0, third buffer <- 0 (or <- Theta_0 if it is to hold the snapshot
-// theta_{t_last}).  With src_tab == nullptr only m is zero-filled.
+// theta_{t_last}).  With src_tab == nullptr only m is zero-filled.  MB: the momentum tensors hold bfloat16.
+template <bool MB>
 __global__ void __launch_bounds__(BLOCK_THREADS)
 init_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, float *const *src_tab,
             float *const *theta_tab, float *const *m_tab, float *const *acc_tab, bool snapshot) {
@@ -800,13 +835,13 @@ init_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, 
         const Tile tl = tiles[t];
         const uint32_t tensor = tl.tensor;
         const uint32_t len = tl.len;
-        gf32 *mm = to_global(m_tab[tensor]) + tl.start;
+        auto *mm = momentum_ptr<MB>(m_tab[tensor]) + tl.start;
         const gf32 *src = src_tab ? to_global(src_tab[tensor]) + tl.start : nullptr;
         gf32 *th = src_tab ? to_global(theta_tab[tensor]) + tl.start : nullptr;
         gf32 *ac = src_tab ? to_global(acc_tab[tensor]) + tl.start : nullptr;
         for (uint32_t off = tid * VEC; off < len; off += BLOCK_THREADS * VEC) {
             if (off + VEC <= len) {
-                st4<false>(mm + off, zero);
+                stm4<false>(mm + off, zero);
                 if (src_tab) {
                     const f32x4 v = ld4<false>(src + off);
                     st4<false>(th + off, v);
@@ -814,7 +849,7 @@ init_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, 
                 }
             } else {
                 for (uint32_t k = off; k < len; ++k) {
-                    mm[k] = 0.f;
+                    stm1(mm + k, 0.f);
                     if (src_tab) { th[k] = src[k]; ac[k] = snapshot ? src[k] : 0.f; }
                 }
             }
@@ -923,21 +958,24 @@ uint32_t launch_grid_size(TileRange r, LaunchShape shape) { return r.hi > r.lo ?
 
 hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
                              float *const *acc, float *const *pull, const PtrArgs &g, int g_kind, int third_mode,
-                             float eta, float beta, float cg, float gw, double *norm_partials, LaunchShape shape) {
+                             float eta, float beta, float cg, float gw, double *norm_partials, LaunchShape shape,
+                             bool m_bf16) {
     if (r.hi <= r.lo) return hipSuccess;
     if (g_kind < GRAD_F32 || g_kind > GRAD_F16 || third_mode < THIRD_NONE || third_mode > THIRD_RESTART ||
         (g_kind == GRAD_END_MODEL && !pull))
         return hipErrorInvalidValue;
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
-#define HALOS_LAUNCH_UPD(GT, THIRD, NT, PULL, END)                                                                         \
+#define HALOS_LAUNCH_UPD_MB(GT, THIRD, NT, PULL, END, MB)                                                                 \
     do {                                                                                                                 \
         if (norm_partials)                                                                                               \
-            lps_update_kernel<GT, THIRD, NT, PULL, true, END><<<grid, block, 0, stream>>>(                               \
+            lps_update_kernel<GT, THIRD, NT, PULL, true, END, MB><<<grid, block, 0, stream>>>(                           \
                 tiles, r.lo, r.hi, r.tensor_base, theta, m, acc, pull, g, eta, beta, cg, gw, norm_partials);             \
         else                                                                                                             \
-            lps_update_kernel<GT, THIRD, NT, PULL, false, END><<<grid, block, 0, stream>>>(                              \
+            lps_update_kernel<GT, THIRD, NT, PULL, false, END, MB><<<grid, block, 0, stream>>>(                          \
                 tiles, r.lo, r.hi, r.tensor_base, theta, m, acc, pull, g, eta, beta, cg, gw, nullptr);                   \
     } while (0)
+#define HALOS_LAUNCH_UPD(GT, THIRD, NT, PULL, END) \
+    do { if (m_bf16) HALOS_LAUNCH_UPD_MB(GT, THIRD, NT, PULL, END, true); else HALOS_LAUNCH_UPD_MB(GT, THIRD, NT, PULL, END, false); } while (0)
 #define HALOS_LAUNCH_UPD_NT(GT, THIRD, PULL, END) \
     do { if (shape.nontemporal) HALOS_LAUNCH_UPD(GT, THIRD, true, PULL, END); else HALOS_LAUNCH_UPD(GT, THIRD, false, PULL, END); } while (0)
 #define HALOS_LAUNCH_UPD_THIRD(GT, PULL, END)                                  \
@@ -957,6 +995,7 @@ hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r,
 #undef HALOS_LAUNCH_UPD_THIRD
 #undef HALOS_LAUNCH_UPD_NT
 #undef HALOS_LAUNCH_UPD
+#undef HALOS_LAUNCH_UPD_MB
     return hipGetLastError();
 }
 
@@ -998,13 +1037,17 @@ hipError_t launch_lps_update_multi(hipStream_t stream, const Tile *tiles, TileRa
 }
 
 hipError_t launch_gps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *Theta, float *const *M,
-                             float *const *G, float *const *out, float eta, float beta, float cg, LaunchShape shape) {
+                             float *const *G, float *const *out, float eta, float beta, float cg, LaunchShape shape,
+                             bool m_bf16) {
     if (r.hi <= r.lo) return hipSuccess;
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
-    if (shape.nontemporal)
-        gps_update_kernel<true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, Theta, M, G, out, eta, beta, cg);
-    else
-        gps_update_kernel<false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, Theta, M, G, out, eta, beta, cg);
+    if (shape.nontemporal) {
+        if (m_bf16) gps_update_kernel<true, true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, Theta, M, G, out, eta, beta, cg);
+        else gps_update_kernel<true, false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, Theta, M, G, out, eta, beta, cg);
+    } else {
+        if (m_bf16) gps_update_kernel<false, true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, Theta, M, G, out, eta, beta, cg);
+        else gps_update_kernel<false, false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, Theta, M, G, out, eta, beta, cg);
+    }
     return hipGetLastError();
 }
 
@@ -1123,10 +1166,11 @@ hipError_t launch_store_pointers(hipStream_t stream, float **table, const PtrArg
 }
 
 hipError_t launch_init(hipStream_t stream, const Tile *tiles, TileRange r, float *const *src, float *const *theta,
-                       float *const *m, float *const *acc, bool snapshot, LaunchShape shape) {
+                       float *const *m, float *const *acc, bool snapshot, LaunchShape shape, bool m_bf16) {
     if (r.hi <= r.lo) return hipSuccess;
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
-    init_kernel<<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, src, theta, m, acc, snapshot);
+    if (m_bf16) init_kernel<true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, src, theta, m, acc, snapshot);
+    else init_kernel<false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, src, theta, m, acc, snapshot);
     return hipGetLastError();
 }
 

@@ -58,9 +58,12 @@ struct TileRange {      // tiles [lo, hi) all belong to tensors [tensor_base, te
 // GRAD_F16: the tensors in `g` hold IEEE half values (upcast exactly).
 constexpr int GRAD_F32 = 0, GRAD_BF16 = 1, GRAD_END_MODEL = 2, GRAD_F16 = 3;
 constexpr int THIRD_NONE = 0, THIRD_ADD = 1, THIRD_FREEZE_SNAPSHOT = 2, THIRD_RESTART = 3;
+// m_bf16: the momentum tensors hold bfloat16; every new momentum is rounded to bfloat16 (nearest even) before it enters
+// the step and is stored as 16 bits.
 hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
                              float *const *acc, float *const *pull, const PtrArgs &g, int g_kind, int third_mode,
-                             float eta, float beta, float cg, float gw, double *norm_partials, LaunchShape shape);
+                             float eta, float beta, float cg, float gw, double *norm_partials, LaunchShape shape,
+                             bool m_bf16 = false);
 
 // Several worker deltas in ONE pass over the server's state.  The deltas are found through device pointer tables (one per
 // delta: table[tensor] is that delta's tensor), because several lists of pointers do not fit a kernel-argument block.
@@ -93,7 +96,8 @@ hipError_t launch_norm_finalize(hipStream_t stream, const double *partials, uint
 // Global-server step: M <- beta M + G; Theta <- Theta - eta (cg G + beta M); out <- Theta.
 // `G` and `out` may be the same table (each element is read before it is overwritten by the same thread).
 hipError_t launch_gps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *Theta, float *const *M,
-                             float *const *G, float *const *out, float eta, float beta, float cg, LaunchShape shape);
+                             float *const *G, float *const *out, float eta, float beta, float cg, LaunchShape shape,
+                             bool m_bf16 = false);
 
 // The global-server step without momentum (beta_g = 0, Sec. 5.4): Theta <- Theta - eta (cg G); out <- Theta.  No
 // momentum array is touched.
@@ -140,7 +144,7 @@ hipError_t launch_pull(hipStream_t stream, const Tile *tiles, TileRange r, float
 // theta <- src; m <- 0; acc <- 0   (Alg. 1, LPS initialisation).  src == nullptr: only zero-fill `m` (used for the GPS momentum).
 // `snapshot`: acc <- src instead of 0.
 hipError_t launch_init(hipStream_t stream, const Tile *tiles, TileRange r, float *const *src, float *const *theta,
-                       float *const *m, float *const *acc, bool snapshot, LaunchShape shape);
+                       float *const *m, float *const *acc, bool snapshot, LaunchShape shape, bool m_bf16 = false);
 
 // Sweep the first n_tiles * TILE_ELEMS floats of two buffers (read both, write both back unchanged).
 hipError_t launch_probe_pair(hipStream_t stream, float *a, float *b, uint32_t n_tiles, LaunchShape shape);

@@ -130,14 +130,20 @@ class Cluster:
         self.n = lay.total
         f32 = torch.float32
         self.region_arena = None
+        self.hp = hp if hp is not None else B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0],
+                                                                 cg_l=w.cg_l, cg_g=w.cg_g)
+        self.snapshot = bool(self.hp.flags & B.FLAG_SNAPSHOT)
+        self.defer_clear = bool(self.hp.flags & B.FLAG_DEFER_CLEAR)
+        self.momentum_bf16 = bool(self.hp.flags & B.FLAG_BF16_MOMENTUM)
+        mdt = torch.bfloat16 if self.momentum_bf16 else f32        # element type of the momentum arrays
         if placement == "regions":
             ddt_size = 4 if w.delta_dtype == "f32" else 2
             S = sum((n * 4 + 255) // 256 * 256 for n in self.numel)
             L = w.n_lps
             pool_bytes = w.pool_slots * S * ddt_size // 4
             # Measured on MI355X (all 243 assignments of m, theta, third buffer, delta, worker model to three regions,
-            # python -m paper_2506_04531_amd.placement_search): everything in one region 5.0 TB/s, an even spread 6.2,
-            # best (6.35) with the worker's model copy in a region of its own, momentum and third buffer in a second,
+            # bench.py --placement-search): everything in one region 5.4 TB/s, an even spread 6.2-6.4,
+            # best (6.5) with the worker's model copy in a region of its own, momentum and third buffer in a second,
             # model and delta in the third.  That pattern also spreads the three written arrays of an update that leaves
             # the third buffer alone over three regions (6.3 instead of 6.0 TB/s for those).
             #   class 0: momenta m_l and third buffers acc_l (delayed momentum: the gradient buffer b_l takes m_l's
@@ -147,7 +153,8 @@ class Cluster:
             # so that the GPS update (reads G = acc_l, M, Theta; writes M, Theta, acc_l) touches all three as well.
             cls_of = {"m": 2 if w.d_l > 1 else 0, "b": 0, "acc": 0, "theta": 1, "pool": 1, "M": 1, "B": 1,
                       "wm": 2, "Theta": 2}
-            size_of = {"Theta": S, "M": S, "B": S if w.d_g > 1 else 0, "theta": L * S, "m": L * S,
+            Sm = sum((n * 2 + 255) // 256 * 256 for n in self.numel) if self.momentum_bf16 else S
+            size_of = {"Theta": S, "M": Sm, "B": S if w.d_g > 1 else 0, "theta": L * S, "m": L * Sm,
                        "b": L * S if w.d_l > 1 else 0, "acc": L * S, "pool": pool_bytes, "wm": L * S if pull_buffers else 0}
             need = [0, 0, 0]
             for role, c in cls_of.items():
@@ -157,12 +164,8 @@ class Cluster:
             mk = lambda dt=f32, role="theta": ra.alloc_list(cls_of[role], self.numel, dt)
         else:
             mk = lambda dt=f32, role="theta": alloc_tensor_list(self.numel, dt, self.device, arena)
-        self.hp = hp if hp is not None else B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0],
-                                                                 cg_l=w.cg_l, cg_g=w.cg_g)
-        self.snapshot = bool(self.hp.flags & B.FLAG_SNAPSHOT)
-        self.defer_clear = bool(self.hp.flags & B.FLAG_DEFER_CLEAR)
         self.Theta = mk(role="Theta")
-        self.M = None if self.hp.flags & B.FLAG_GPS_NO_MOMENTUM else mk(role="M")      # a momentum-free GPS has no M at all
+        self.M = None if self.hp.flags & B.FLAG_GPS_NO_MOMENTUM else mk(mdt, role="M")      # a momentum-free GPS has no M at all
         fill_initial_model(w, self.Theta)
         self.gps = B.halos_gps_create(self.numel, self.hp, self.Theta, self.M)
         self.gps_buffer = None
@@ -171,7 +174,7 @@ class Cluster:
             B.halos_gps_set_momentum_delay(self.gps, w.d_g, self.gps_buffer)
         self.theta, self.m, self.acc, self.buffer, self.lps = [], [], [], [], []
         for l in range(w.n_lps):
-            th, m, acc = mk(role="theta"), mk(role="m"), mk(role="acc")
+            th, m, acc = mk(role="theta"), mk(mdt, role="m"), mk(role="acc")
             self.theta.append(th); self.m.append(m); self.acc.append(acc)
             h = B.halos_lps_create(self.gps, l, w.workers_per_lps, th, m, acc)
             if w.d_l > 1:
@@ -235,7 +238,8 @@ class Cluster:
         weighted = self.w.staleness_exponent > 0.0
         skip = -1
         consumed = set()
-        batch = batch if (fuse_pull and self.w.d_l == 1 and batch >= 2) else 0
+        # (with 16-bit momentum the library's batch call falls back to single steps: issue them as such)
+        batch = batch if (fuse_pull and self.w.d_l == 1 and batch >= 2 and not self.momentum_bf16) else 0
         infos = (B.StepInfo * 4)()
         n_done = ctypes.c_int32()
         info = B.StepInfo()
@@ -378,7 +382,7 @@ class Cluster:
         return out
 
     def gather(self, name: str, flat_idx: torch.Tensor) -> np.ndarray:
-        return gather_flat(self.state_lists()[name], self.offsets, flat_idx).cpu().numpy()
+        return gather_flat(self.state_lists()[name], self.offsets, flat_idx).float().cpu().numpy()     # bfloat16 -> float is exact
 
     def flat(self, name: str) -> np.ndarray:
-        return torch.cat([t.reshape(-1) for t in self.state_lists()[name]]).cpu().numpy()
+        return torch.cat([t.reshape(-1) for t in self.state_lists()[name]]).float().cpu().numpy()

@@ -45,7 +45,8 @@ def sample_indices(lay: synth.Layout, n_random: int, seed: int = 0, tile: int = 
     return np.unique(np.concatenate(picks))
 
 
-def oracle_run(w: synth.Workload, trace: synth.Trace, idx: Optional[np.ndarray], precision: int, form: int):
+def oracle_run(w: synth.Workload, trace: synth.Trace, idx: Optional[np.ndarray], precision: int, form: int,
+               momentum_bf16: bool = False):
     """Replay `trace` through the oracle on the packed flat indices `idx` (None = every element)."""
     lay = w.layout
     if idx is None:
@@ -63,7 +64,8 @@ def oracle_run(w: synth.Workload, trace: synth.Trace, idx: Optional[np.ndarray],
         return cache[slot]
 
     o = HalosOracle(theta0, w.n_lps, eta_l=w.eta_l, beta_l=w.beta_l, eta_g=w.eta_g, beta_g=w.beta_g,
-                    alpha=w.alpha, K=trace.k_initial, cg_l=w.cg_l, cg_g=w.cg_g, precision=precision, form=form)
+                    alpha=w.alpha, K=trace.k_initial, cg_l=w.cg_l, cg_g=w.cg_g, precision=precision, form=form,
+                    momentum_bf16=momentum_bf16)
     if w.d_l > 1:
         for l in range(w.n_lps):
             o.set_delay(l, w.d_l)

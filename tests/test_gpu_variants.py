@@ -1,6 +1,6 @@
 """GPU parity of the variants next to the base path: IEEE-half deltas, weighted arrivals, the momentum-free global
-server, merges that do not clear the third buffer, and the single-tier server -- each through the C ABI against the
-CPU oracle on the same seeded inputs."""
+server, merges that do not clear the third buffer, the single-tier server, and momentum kept in bfloat16 -- each
+through the C ABI against the CPU oracle on the same seeded inputs."""
 from dataclasses import replace
 
 import numpy as np
@@ -380,7 +380,8 @@ def test_batch_call_on_a_single_item_is_the_ordinary_step():
 
 
 # ---------------------------------------------------------------- the variants at full benchmark size
-@pytest.mark.parametrize("name,variant", [("160m", "batch+defer"), ("70m", "nomom+f16"), ("410m", "weighted+snapshot")])
+@pytest.mark.parametrize("name,variant", [("160m", "batch+defer"), ("70m", "nomom+f16"), ("410m", "weighted+snapshot"),
+                                          ("1b", "bf16-momentum")])
 def test_variants_at_full_size_on_sampled_elements(name, variant):
     """Full benchmark sizes, arena placement, fused pulls, the variants switched on; the oracle replays the sampled
     elements (random ones plus every tensor and tile boundary)."""
@@ -388,7 +389,9 @@ def test_variants_at_full_size_on_sampled_elements(name, variant):
     from parity_util import sample_indices
     w = synth.get_workload(name)
     flags, batch, form = 0, 0, FORM_ACCUMULATOR
-    if variant == "batch+defer":
+    if variant == "bf16-momentum":
+        flags = B.FLAG_BF16_MOMENTUM
+    elif variant == "batch+defer":
         flags, batch = B.FLAG_DEFER_CLEAR, 4
     elif variant == "nomom+f16":
         w = replace(w, delta_dtype="f16", beta_g=0.0)
@@ -412,7 +415,7 @@ def test_variants_at_full_size_on_sampled_elements(name, variant):
         torch.cuda.empty_cache()
     if batch:
         assert any(k.startswith("lps_update_batch") for k in tm), "the full-size schedule must contain bursts"
-    o32, log32 = oracle_run(w, trace, idx, 32, form)
+    o32, log32 = oracle_run(w, trace, idx, 32, form, momentum_bf16=bool(flags & B.FLAG_BF16_MOMENTUM))
     check_step_logs(trace, gpu_log, log32)
     ref = oracle_state(o32, w.n_lps, snapshot_form=(form == FORM_LITERAL))
     if flags & B.FLAG_GPS_NO_MOMENTUM:
@@ -427,3 +430,120 @@ def test_variants_at_full_size_on_sampled_elements(name, variant):
     else:
         worst, n_diff, wname = compare_state(gpu, ref, bitwise=True)
         assert n_diff == 0, (n_diff, worst, wname)
+
+
+# ---------------------------------------------------------------- momentum kept in bfloat16
+@pytest.mark.parametrize("recipe,dtype,mode", [("70m", "f32", "plain"), ("160m", "bf16", "pull"), ("410m", "f32", "pull+batch"),
+                                               ("160m", "f16", "snapshot"), ("70m", "f32", "norms")])
+def test_bf16_momentum_every_element(recipe, dtype, mode):
+    """HALOS_FLAG_BF16_MOMENTUM: the momentum arrays of both tiers hold bfloat16 and every new momentum is rounded (nearest
+    even) before it enters the step.  The rounding is decided on the fp32 value, so the reference is the fp32
+    same-order oracle with the same option: every array bit for bit (the 16-bit momentum upcast exactly)."""
+    from paper_2506_04531_amd import binding as B
+    lay = RAGGED if recipe != "160m" else synth.gpt_layout(96, 2, vocab=1031)
+    w = replace(synth.get_workload(recipe).scaled(lay, n_updates=120, name=f"{recipe}-bf16m-{mode}"), delta_dtype=dtype)
+    trace = synth.make_trace(w, seed=91)
+    flags = B.FLAG_BF16_MOMENTUM | (B.FLAG_SNAPSHOT if mode == "snapshot" else 0) | (B.FLAG_NORMS if mode == "norms" else 0)
+    form = FORM_LITERAL if mode == "snapshot" else FORM_ACCUMULATOR
+    hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0], flags=flags)
+    print(f"[parity] workload={w.name} n={w.layout.total} dtype={dtype} mode={mode} events={len(trace.events)}", flush=True)
+    c = _cluster(w, trace, hp=hp)
+    try:
+        assert all(t.dtype == torch.bfloat16 for t in c.M) and all(t.dtype == torch.bfloat16 for ts in c.m for t in ts)
+        gpu_log, _ = c.replay(trace.events, fuse_pull=(mode != "plain"), batch=4 if mode == "pull+batch" else 0)
+        torch.cuda.synchronize()
+        gpu = {k: c.flat(k) for k in c.state_lists()}
+        norms = B.halos_lps_get_norms(c.lps[0]) if mode == "norms" else None
+    finally:
+        c.close()
+    o32, log32 = oracle_run(w, trace, None, 32, form, momentum_bf16=True)
+    check_step_logs(trace, gpu_log, log32)
+    worst, n_diff, name = compare_state(gpu, oracle_state(o32, w.n_lps, snapshot_form=(mode == "snapshot")), bitwise=True)
+    assert n_diff == 0, (n_diff, worst, name)
+    assert np.any(gpu["M"] != 0) and np.any(gpu["m0"] != 0)
+    if norms is not None:
+        ref = o32.norms(0)
+        assert abs(norms[0] - ref[0]) <= 1e-4 * ref[0] and abs(norms[1] - ref[1]) <= 1e-4 * max(ref[1], 1e-30)
+    # for the record: how far the rounding moves the models from the full-precision fp64 reference
+    o64, _ = oracle_run(w, trace, None, 64, FORM_LITERAL)
+    ref64 = o64.get(O.GPS_THETA)
+    dev_rel = float(np.sqrt(np.mean((gpu["Theta"] - ref64) ** 2)) / np.sqrt(np.mean(ref64 ** 2)))
+    print(f"[parity] {w.name}: bit-exact vs the fp32 oracle with bfloat16 momentum; rms deviation of Theta from the "
+          f"full-precision fp64 reference {dev_rel:.3g} of its rms", flush=True)
+    assert dev_rel < 1e-3
+
+
+def test_bf16_momentum_on_the_single_tier_server_and_with_end_models():
+    """The global server applying worker deltas itself, and a local server forming the delta from the worker's end model,
+    both with 16-bit momentum."""
+    from paper_2506_04531_amd import binding as B
+    from paper_2506_04531_amd.harness import alloc_tensor_list, fill_delta_slot, fill_initial_model
+    dev = torch.device("cuda:0")
+    w = replace(synth.get_workload("70m").scaled(RAGGED, n_updates=1, name="bf16m-single"), eta_g=0.05, beta_g=0.9)
+    numel = [int(x) for x in w.layout.numel]
+    f32, bf16 = torch.float32, torch.bfloat16
+    Theta, th, acc, wm, end = (alloc_tensor_list(numel, f32, dev) for _ in range(5))
+    M, m = alloc_tensor_list(numel, bf16, dev), alloc_tensor_list(numel, bf16, dev)
+    fill_initial_model(w, Theta)
+    pool = []
+    for s in range(3):
+        ts = alloc_tensor_list(numel, f32, dev)
+        fill_delta_slot(w, s, ts)
+        pool.append(ts)
+    hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, 8, flags=B.FLAG_BF16_MOMENTUM)
+    gps = B.halos_gps_create(numel, hp, Theta, M)
+    lps = B.halos_lps_create(gps, 0, 1, th, m, acc)
+    flat = lambda ts: torch.cat([t.reshape(-1) for t in ts]).float().cpu().numpy()
+    try:
+        B.halos_lps_set_worker_model(lps, 0, wm)
+        B.halos_pull_model(lps, False, wm)                                  # the worker's start model
+        for a, b, d in zip(end, wm, pool[2]):                               # its end model: start minus some progress
+            a.copy_(b - d)
+        B.halos_lps_push_end_model(lps, 0, end)
+        B.halos_lps_step_pull(lps)
+        for k in range(5):
+            B.halos_gps_push_update(gps, pool[k % 3], B.F32, 1.0 if k != 2 else 0.5)
+        torch.cuda.synchronize()
+        gpu = {"Theta": flat(Theta), "M": flat(M), "theta0": flat(th), "m0": flat(m), "aux0": flat(acc), "wm": flat(wm)}
+        end_host = flat(end)
+    finally:
+        B.halos_lps_destroy(lps)
+        B.halos_gps_destroy(gps)
+    idx = torch.arange(w.layout.total, dtype=torch.int64)
+    theta0 = synth.normal_at(w.seed, 0, idx, synth.tensors.scale_f32(w.init_sigma)).numpy()
+    scale = torch.from_numpy(synth.delta_scales(w)[w.layout.tensor_of(idx.numpy())])
+    deltas = [synth.normal_at(w.seed, 1 + s, idx, scale).numpy() for s in range(3)]
+    o = HalosOracle(theta0, 1, eta_l=w.eta_l, beta_l=w.beta_l, eta_g=w.eta_g, beta_g=w.beta_g, alpha=w.alpha, K=8,
+                    precision=32, form=FORM_ACCUMULATOR, momentum_bf16=True)
+    g = theta0 - end_host                                                   # start - end, in fp32 like a worker would
+    o.arrive_delta(0, 0, g); o.lps_step(0)
+    for k in range(5):
+        o.gps_apply_delta(deltas[k % 3], 1.0 if k != 2 else 0.5)
+    for name, what in (("Theta", O.GPS_THETA), ("M", O.GPS_MOM), ("theta0", O.THETA), ("m0", O.MOM), ("aux0", O.AUX)):
+        ref = o.get(what).astype(np.float32)
+        assert np.array_equal(gpu[name].view(np.uint32), ref.view(np.uint32)), name
+    assert np.array_equal(gpu["wm"].view(np.uint32), gpu["theta0"].view(np.uint32))     # the worker got the updated model back
+
+
+def test_bf16_momentum_refuses_what_is_not_built_for_it():
+    from paper_2506_04531_amd import binding as B
+    w = synth.get_workload("tiny").scaled(synth.flat_layout(5000), n_updates=4, name="bf16m-refuse")
+    trace = synth.make_trace(w)
+    hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, 4, flags=B.FLAG_BF16_MOMENTUM)
+    c = _cluster(w, trace, hp=hp)
+    try:
+        buf = [torch.zeros(5000, device="cuda:0")]
+        for call in (lambda: B.halos_lps_set_momentum_delay(c.lps[0], 4, buf), lambda: B.halos_gps_set_momentum_delay(c.gps, 2, buf)):
+            with pytest.raises(B.HalosError) as e:
+                call()
+            assert e.value.status == B.ESTATE and "bfloat16" in str(e.value)
+        B.halos_lps_set_momentum_delay(c.lps[0], 1, None)                   # delay 1 is the plain rule: fine
+        B.halos_lps_push_update(c.lps[0], 0, c.pool[0], c.delta_dtype)
+        B.halos_lps_push_update(c.lps[0], 1, c.pool[1], c.delta_dtype)
+        with pytest.raises(B.HalosError) as e:
+            B.halos_lps_step_average(c.lps[0], 2)
+        assert e.value.status == B.ESTATE
+        done = B.halos_lps_step_batch(c.lps[0], 4)                          # falls back to one ordinary step
+        assert len(done) == 1 and done[0].kind == 1 and B.halos_lps_get_counters(c.lps[0])["queued"] == 1
+    finally:
+        c.close()
