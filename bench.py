@@ -666,7 +666,7 @@ def main():
                        "(HALOS_FLAG_DEFER_CLEAR, same results); gps_no_momentum: beta_g = 0 without a momentum array (Sec. 5.4; "
                        "another optimizer setting); snapshot_form: Delta by subtraction (HALOS_FLAG_SNAPSHOT; rounds differently); "
                        "bf16_momentum: both tiers' momentum in bfloat16 (HALOS_FLAG_BF16_MOMENTUM; an option of this library that "
-                       "changes results by the rounding; every update its own pass)")
+                       "changes results by the rounding)")
     ab = None if args.no_end_model_ab else end_model_ab(args.workload, verbose=not args.quiet)
     gab = None if args.no_graph_ab else graph_ab()
     cpu = None if args.no_cpu_baseline else cpu_baseline(args.workload)

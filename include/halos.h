@@ -142,8 +142,7 @@ typedef struct {
  * and returned global models stay fp32.  An option of this library, not of the paper (which does not state the
  * servers' precision; its workers train in fp16, Sec. 5.1): 4 bytes per parameter less on every update (LPS and GPS),
  * results that differ from the fp32-momentum run by the rounding.  Not available with a momentum delay above 1
- * (ESTATE); halos_lps_step_average refuses, halos_lps_step_batch falls back to single steps.  Honoured at
- * halos_gps_create. */
+ * (ESTATE).  Honoured at halos_gps_create. */
 #define HALOS_FLAG_BF16_MOMENTUM 16u
 
 /* What one halos_lps_step did. */

@@ -757,7 +757,6 @@ namespace {
 
 // Can the first `count` queue items go through one multi-delta pass?  All must be plain deltas of one element type.
 bool multi_eligible(const halos_lps *l, int32_t count, bool pull) {
-    if (l->gps->momentum_bf16) return false;           // the multi-delta passes keep the momentum in fp32 only
     if (!l->proto.head_is_deltas(count)) return false;
     const PendingDelta &first = l->pending[l->proto.item(0).worker];
     for (int32_t i = 0; i < count; ++i) {
@@ -795,7 +794,6 @@ halos_status halos_lps_step_average(halos_lps *l, int32_t count, void *stream, h
     halos_gps *g = l->gps;
     if (l->cycle.d() > 1) return fail(HALOS_ESTATE, "lps %d: the averaged step is not available under a momentum delay", l->id);
     if (l->d_norm_partials) return fail(HALOS_ESTATE, "lps %d: the averaged step does not feed the norm monitors", l->id);
-    if (g->momentum_bf16) return fail(HALOS_ESTATE, "lps %d: the averaged step is not available with bfloat16 momentum", l->id);
     if (!multi_eligible(l, count, false))
         return fail(HALOS_ESTATE, "lps %d: the first %d queue items are not %d worker deltas of one element type", l->id, count, count);
     halos_status st = check_device(g);
@@ -820,7 +818,8 @@ halos_status halos_lps_step_average(halos_lps *l, int32_t count, void *stream, h
     const float inv_n = 1.0f / (float)count;
     for (const TileRange &r : g->ranges) {
         hipError_t e = launch_lps_update_multi((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_acc, a, true,
-                                               grad_kind(dtype), third_mode, l->rule.eta, l->rule.beta, l->rule.cg, inv_n, shape);
+                                               grad_kind(dtype), third_mode, l->rule.eta, l->rule.beta, l->rule.cg, inv_n, shape,
+                                               g->momentum_bf16);
         if (e != hipSuccess) return fail_hip(e, "launching the averaged update");
     }
     l->proto.commit_average(count);
@@ -891,7 +890,8 @@ halos_status halos_lps_step_batch(halos_lps *l, int32_t max_items, int32_t pull,
     const LaunchShape shape = current_shape(g);
     for (const TileRange &r : g->ranges) {
         hipError_t e = launch_lps_update_multi((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_acc, a, false,
-                                               grad_kind(dtype), third_mode, l->rule.eta, l->rule.beta, l->rule.cg, 1.0f, shape);
+                                               grad_kind(dtype), third_mode, l->rule.eta, l->rule.beta, l->rule.cg, 1.0f, shape,
+                                               g->momentum_bf16);
         if (e != hipSuccess) return fail_hip(e, "launching the batched update");
     }
     l->proto = sim;

@@ -339,7 +339,8 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
 // S1 over several deltas in one pass (see kernels.hpp, launch_lps_update_multi).  SEQ: apply them one after the other;
 // otherwise average them and apply the mean once.  THIRD as in lps_update_kernel; under SEQ the first n_acc deltas
 // count towards the accumulated update, and with THIRD = 2 the n_acc-th turns the snapshot into theta_{t_last} - theta_t.
-template <typename GT, bool SEQ, int THIRD, bool PULL>
+// With MB the momentum tensors hold bfloat16 and the momentum is rounded after every one of the updates, as in single steps.
+template <typename GT, bool SEQ, int THIRD, bool PULL, bool MB = false>
 __global__ void __launch_bounds__(BLOCK_THREADS)
 lps_update_multi_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi,
                         float *const *__restrict__ theta_tab, float *const *__restrict__ m_tab,
@@ -353,7 +354,7 @@ lps_update_multi_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32
         const Tile tl = tiles[t];
         const uint32_t tensor = tl.tensor;
         gf32 *th = to_global(theta_tab[tensor]) + tl.start;
-        gf32 *mm = to_global(m_tab[tensor]) + tl.start;
+        auto *mm = momentum_ptr<MB>(m_tab[tensor]) + tl.start;
         gf32 *ac = THIRD != 0 ? to_global(acc_tab[tensor]) + tl.start : nullptr;
         decltype(to_global(static_cast<const GT *>(nullptr))) g[MAX_MULTI];
         gf32 *pd[MAX_MULTI];
@@ -374,7 +375,7 @@ lps_update_multi_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
-                mv[u] = ld4<NT>(mm + off);
+                mv[u] = ldg4<NT>(mm + off);
                 tv[u] = ld4<NT>(th + off);
                 av[u] = LOAD_THIRD ? ld4<NT>(ac + off) : zero;
             }
@@ -385,7 +386,7 @@ lps_update_multi_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32
 #pragma unroll
                     for (int i = 0; i < MAX_MULTI; ++i)
                         if (i < n_in) {
-                            const f32x4 s = model_update4(tv[u], mv[u], scale4(a.w[i], up4(gv[i][u])), eta, beta, cg);
+                            const f32x4 s = model_update4<MB>(tv[u], mv[u], scale4(a.w[i], up4(gv[i][u])), eta, beta, cg);
                             if constexpr (THIRD == 1 || THIRD == 3) { if (i < n_acc) av[u] = add4(av[u], s); }
                             if constexpr (THIRD == 2) { if (i + 1 == n_acc) av[u] = sub4(av[u], tv[u]); }
                             if constexpr (PULL) { if (pd[i]) st4<NT>(pd[i] + off, tv[u]); }
@@ -395,21 +396,21 @@ lps_update_multi_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32
 #pragma unroll
                     for (int i = 1; i < MAX_MULTI; ++i)
                         if (i < n_in) sum = add4(sum, scale4(a.w[i], up4(gv[i][u])));
-                    const f32x4 s = model_update4(tv[u], mv[u], scale4(inv_n, sum), eta, beta, cg);
+                    const f32x4 s = model_update4<MB>(tv[u], mv[u], scale4(inv_n, sum), eta, beta, cg);
                     if constexpr (THIRD == 1 || THIRD == 3) av[u] = add4(av[u], s);
                     if constexpr (THIRD == 2) av[u] = sub4(av[u], tv[u]);
                 }
-                st4<NT>(mm + off, mv[u]);
+                stm4<NT>(mm + off, mv[u]);
                 st4<NT>(th + off, tv[u]);
                 if constexpr (THIRD != 0) st4<NT>(ac + off, av[u]);
             }
         } else {                                    // a ragged tile: element by element
             const uint32_t len = tl.len;
             for (uint32_t k = tid; k < len; k += BLOCK_THREADS) {
-                float mk = mm[k], tk = th[k], ak = LOAD_THIRD ? ac[k] : 0.f;
+                float mk = ldg1(mm + k), tk = th[k], ak = LOAD_THIRD ? ac[k] : 0.f;
                 if constexpr (SEQ) {
                     for (int i = 0; i < n_in; ++i) {
-                        const float s = model_update(tk, mk, __fmul_rn(a.w[i], ldg1(g[i] + k)), eta, beta, cg);
+                        const float s = model_update<MB>(tk, mk, __fmul_rn(a.w[i], ldg1(g[i] + k)), eta, beta, cg);
                         if constexpr (THIRD == 1 || THIRD == 3) { if (i < n_acc) ak = __fadd_rn(ak, s); }
                         if constexpr (THIRD == 2) { if (i + 1 == n_acc) ak = __fsub_rn(ak, tk); }
                         if constexpr (PULL) { if (pd[i]) pd[i][k] = tk; }
@@ -417,11 +418,11 @@ lps_update_multi_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32
                 } else {
                     float sum = __fmul_rn(a.w[0], ldg1(g[0] + k));
                     for (int i = 1; i < n_in; ++i) sum = __fadd_rn(sum, __fmul_rn(a.w[i], ldg1(g[i] + k)));
-                    const float s = model_update(tk, mk, __fmul_rn(inv_n, sum), eta, beta, cg);
+                    const float s = model_update<MB>(tk, mk, __fmul_rn(inv_n, sum), eta, beta, cg);
                     if constexpr (THIRD == 1 || THIRD == 3) ak = __fadd_rn(ak, s);
                     if constexpr (THIRD == 2) ak = __fsub_rn(ak, tk);
                 }
-                mm[k] = mk; th[k] = tk;
+                stm1(mm + k, mk); th[k] = tk;
                 if constexpr (THIRD != 0) ac[k] = ak;
             }
         }
@@ -1001,7 +1002,7 @@ hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r,
 
 hipError_t launch_lps_update_multi(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
                                    float *const *acc, const MultiArgs &a, bool average, int g_kind, int third_mode,
-                                   float eta, float beta, float cg, float inv_n, LaunchShape shape) {
+                                   float eta, float beta, float cg, float inv_n, LaunchShape shape, bool m_bf16) {
     if (r.hi <= r.lo) return hipSuccess;
     if (a.n_in < 1 || a.n_in > MAX_MULTI || a.n_acc < 0 || a.n_acc > a.n_in || third_mode < THIRD_NONE ||
         third_mode > THIRD_RESTART || (g_kind != GRAD_F32 && g_kind != GRAD_BF16 && g_kind != GRAD_F16))
@@ -1012,8 +1013,13 @@ hipError_t launch_lps_update_multi(hipStream_t stream, const Tile *tiles, TileRa
         pull = pull || a.pull[i] != nullptr;
     }
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
-#define HALOS_LAUNCH_MULTI(GT, SEQ, THIRD, PULL) \
-    lps_update_multi_kernel<GT, SEQ, THIRD, PULL><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, m, acc, a, eta, beta, cg, inv_n)
+#define HALOS_LAUNCH_MULTI(GT, SEQ, THIRD, PULL)                                                                                      \
+    do {                                                                                                                             \
+        if (m_bf16)                                                                                                                  \
+            lps_update_multi_kernel<GT, SEQ, THIRD, PULL, true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, m, acc, a, eta, beta, cg, inv_n); \
+        else                                                                                                                         \
+            lps_update_multi_kernel<GT, SEQ, THIRD, PULL, false><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, m, acc, a, eta, beta, cg, inv_n); \
+    } while (0)
 #define HALOS_LAUNCH_MULTI_THIRD(GT, SEQ, PULL)                                    \
     do {                                                                           \
         if (third_mode == THIRD_NONE) HALOS_LAUNCH_MULTI(GT, SEQ, 0, PULL);        \

@@ -85,7 +85,7 @@ struct MultiArgs {
 };
 hipError_t launch_lps_update_multi(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
                                    float *const *acc, const MultiArgs &a, bool average, int g_kind, int third_mode,
-                                   float eta, float beta, float cg, float inv_n, LaunchShape shape);
+                                   float eta, float beta, float cg, float inv_n, LaunchShape shape, bool m_bf16 = false);
 
 // Number of workgroups a launch over range r uses (0 for an empty range).
 uint32_t launch_grid_size(TileRange r, LaunchShape shape);

@@ -238,8 +238,7 @@ class Cluster:
         weighted = self.w.staleness_exponent > 0.0
         skip = -1
         consumed = set()
-        # (with 16-bit momentum the library's batch call falls back to single steps: issue them as such)
-        batch = batch if (fuse_pull and self.w.d_l == 1 and batch >= 2 and not self.momentum_bf16) else 0
+        batch = batch if (fuse_pull and self.w.d_l == 1 and batch >= 2) else 0
         infos = (B.StepInfo * 4)()
         n_done = ctypes.c_int32()
         info = B.StepInfo()

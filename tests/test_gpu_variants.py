@@ -239,7 +239,7 @@ def test_single_tier_server_every_element(dtype, d_g):
 
 
 # ---------------------------------------------------------------- several deltas in one pass
-@pytest.mark.parametrize("dtype,flags", [("f32", 0), ("bf16", 0), ("f16", 0), ("f32", "snapshot"), ("bf16", "defer")])
+@pytest.mark.parametrize("dtype,flags", [("f32", 0), ("bf16", 0), ("f16", 0), ("f32", "snapshot"), ("bf16", "defer"), ("bf16", "bf16m")])
 def test_averaged_step_every_element(dtype, flags):
     """halos_lps_step_average: n queued deltas (with weights) become one update with their mean, against the oracle's
     lps_step_average; rounds of 1..4 deltas, accumulation, GPS updates and merges in between."""
@@ -249,7 +249,8 @@ def test_averaged_step_every_element(dtype, flags):
     w = replace(synth.get_workload("70m").scaled(RAGGED, n_updates=1, name="avg"), delta_dtype=dtype)
     numel = [int(x) for x in w.layout.numel]
     f32 = torch.float32
-    Theta, M, th, m, acc = (alloc_tensor_list(numel, f32, dev) for _ in range(5))
+    Theta, th, acc = (alloc_tensor_list(numel, f32, dev) for _ in range(3))
+    M, m = (alloc_tensor_list(numel, torch.bfloat16 if flags == "bf16m" else f32, dev) for _ in range(2))
     fill_initial_model(w, Theta)
     ddt = {"f32": f32, "bf16": torch.bfloat16, "f16": torch.float16}[dtype]
     code = {"f32": B.F32, "bf16": B.BF16, "f16": B.F16}[dtype]
@@ -258,7 +259,7 @@ def test_averaged_step_every_element(dtype, flags):
         ts = alloc_tensor_list(numel, ddt, dev)
         fill_delta_slot(w, s, ts)
         pool.append(ts)
-    fl = {0: 0, "snapshot": B.FLAG_SNAPSHOT, "defer": B.FLAG_DEFER_CLEAR}[flags]
+    fl = {0: 0, "snapshot": B.FLAG_SNAPSHOT, "defer": B.FLAG_DEFER_CLEAR, "bf16m": B.FLAG_BF16_MOMENTUM}[flags]
     K = 2
     hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, K, flags=fl)
     gps = B.halos_gps_create(numel, hp, Theta, M)
@@ -271,8 +272,8 @@ def test_averaged_step_every_element(dtype, flags):
         g = synth.normal_at(w.seed, 1 + s, idx, scale)
         host.append(synth.to_bf16_bits(g).numpy() if dtype == "bf16" else synth.to_f16(g).numpy() if dtype == "f16" else g.numpy())
     o = HalosOracle(theta0, 1, eta_l=w.eta_l, beta_l=w.beta_l, eta_g=w.eta_g, beta_g=w.beta_g, alpha=w.alpha, K=K,
-                    precision=32, form=FORM_LITERAL if flags == "snapshot" else FORM_ACCUMULATOR)
-    flat = lambda ts: torch.cat([t.reshape(-1) for t in ts]).cpu().numpy()
+                    precision=32, form=FORM_LITERAL if flags == "snapshot" else FORM_ACCUMULATOR, momentum_bf16=(flags == "bf16m"))
+    flat = lambda ts: torch.cat([t.reshape(-1) for t in ts]).float().cpu().numpy()
     rounds = [(4, [1.0, 1.0, 1.0, 1.0]), (2, [0.5, 1.0]), (3, [1.0, 0.25, 0.70710677]), (1, [1.0]), (4, [1.0, 0.5, 1.0, 2.0]), (2, [1.0, 1.0])]
     try:
         for r, (n, ws) in enumerate(rounds):
@@ -312,7 +313,8 @@ def test_averaged_step_every_element(dtype, flags):
 
 
 @pytest.mark.parametrize("recipe,dtype,flags,weighted", [("160m", "bf16", 0, False), ("160m", "f32", "defer", True),
-                                                         ("70m", "f16", 0, False), ("160m", "f32", "snapshot", False)])
+                                                         ("70m", "f16", 0, False), ("160m", "f32", "snapshot", False),
+                                                         ("160m", "bf16", "bf16m", True)])
 def test_batched_steps_equal_single_steps(recipe, dtype, flags, weighted):
     """halos_lps_step_batch on a bursty schedule (8 workers per server at uneven rates): wherever several deltas of one
     server wait, they go through one pass.  State, step log and every model handed back equal the step-by-step run's
@@ -321,7 +323,7 @@ def test_batched_steps_equal_single_steps(recipe, dtype, flags, weighted):
     base = synth.get_workload(recipe).scaled(RAGGED, n_updates=200, name=f"batch-{recipe}")
     w = replace(base, delta_dtype=dtype, n_lps=2, workers_per_lps=8, hetero_rates=True, staleness_exponent=0.5 if weighted else 0.0)
     trace = synth.make_trace(w, seed=97)
-    fl = {0: 0, "snapshot": B.FLAG_SNAPSHOT, "defer": B.FLAG_DEFER_CLEAR}[flags]
+    fl = {0: 0, "snapshot": B.FLAG_SNAPSHOT, "defer": B.FLAG_DEFER_CLEAR, "bf16m": B.FLAG_BF16_MOMENTUM}[flags]
     hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0], flags=fl)
     runs = []
     for batch in (0, 4):
@@ -345,7 +347,8 @@ def test_batched_steps_equal_single_steps(recipe, dtype, flags, weighted):
     for k in runs[0][1]:
         if k not in skip:
             assert np.array_equal(runs[0][1][k].view(np.uint32), runs[1][1][k].view(np.uint32)), k
-    o32, log32 = oracle_run(w, trace, None, 32, FORM_LITERAL if flags == "snapshot" else FORM_ACCUMULATOR)
+    o32, log32 = oracle_run(w, trace, None, 32, FORM_LITERAL if flags == "snapshot" else FORM_ACCUMULATOR,
+                            momentum_bf16=(flags == "bf16m"))
     check_step_logs(trace, runs[1][0], log32)
     ref = oracle_state(o32, w.n_lps, snapshot_form=(flags == "snapshot"))
     for k in skip:
@@ -381,7 +384,7 @@ def test_batch_call_on_a_single_item_is_the_ordinary_step():
 
 # ---------------------------------------------------------------- the variants at full benchmark size
 @pytest.mark.parametrize("name,variant", [("160m", "batch+defer"), ("70m", "nomom+f16"), ("410m", "weighted+snapshot"),
-                                          ("1b", "bf16-momentum")])
+                                          ("160m", "bf16-momentum")])
 def test_variants_at_full_size_on_sampled_elements(name, variant):
     """Full benchmark sizes, arena placement, fused pulls, the variants switched on; the oracle replays the sampled
     elements (random ones plus every tensor and tile boundary)."""
@@ -390,7 +393,7 @@ def test_variants_at_full_size_on_sampled_elements(name, variant):
     w = synth.get_workload(name)
     flags, batch, form = 0, 0, FORM_ACCUMULATOR
     if variant == "bf16-momentum":
-        flags = B.FLAG_BF16_MOMENTUM
+        flags, batch = B.FLAG_BF16_MOMENTUM, 4
     elif variant == "batch+defer":
         flags, batch = B.FLAG_DEFER_CLEAR, 4
     elif variant == "nomom+f16":
@@ -538,12 +541,5 @@ def test_bf16_momentum_refuses_what_is_not_built_for_it():
                 call()
             assert e.value.status == B.ESTATE and "bfloat16" in str(e.value)
         B.halos_lps_set_momentum_delay(c.lps[0], 1, None)                   # delay 1 is the plain rule: fine
-        B.halos_lps_push_update(c.lps[0], 0, c.pool[0], c.delta_dtype)
-        B.halos_lps_push_update(c.lps[0], 1, c.pool[1], c.delta_dtype)
-        with pytest.raises(B.HalosError) as e:
-            B.halos_lps_step_average(c.lps[0], 2)
-        assert e.value.status == B.ESTATE
-        done = B.halos_lps_step_batch(c.lps[0], 4)                          # falls back to one ordinary step
-        assert len(done) == 1 and done[0].kind == 1 and B.halos_lps_get_counters(c.lps[0])["queued"] == 1
     finally:
         c.close()
