@@ -79,16 +79,18 @@ def bytes_per_param(label: str, delta_dtype: str, delayed: bool, momentum_bytes:
 # HBM traffic per parameter per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), valid
 # only for the kernel source it was measured on: {sha256 of kernels.hip: {kernel label: bytes/param}}.
 MEASURED_TRAFFIC: dict = {
-    # profiles/lps_update_1b_hbm_traffic.md, profiles/lps_update_delayed_1b_dn.md
-    "c1b9946f3fba2558821a49c31bb47f3efd75b61366e99efe2968af30940c1a56": {
-        "1b:lps_update_acc_pull": 30.032,
+    # profiles/lps_update_1b_hbm_traffic.md, profiles/lps_update_delayed_1b_dn.md, profiles/lps_update_1b_bf16_momentum.md
+    "3c5fade1b5d9f41545cd7e48a4a634b02e97be8a8640bd7814b8af2aa389b9be": {
+        "1b:lps_update_acc_pull": 30.033,
         "1b:lps_update_noacc_pull": 22.031,
-        "1b-dn:lps_update_acc_first_pull": 26.039,
+        "1b-dn:lps_update_acc_first_pull": 26.038,
         "1b-dn:lps_update_acc_pull": 30.032,
         "1b-dn:lps_update_acc_refresh_pull": 34.031,
         "1b-dn:lps_update_noacc_first_pull": 18.031,
         "1b-dn:lps_update_noacc_pull": 22.035,
         "1b-dn:lps_update_noacc_refresh_pull": 26.031,
+        "1b+bf16m:lps_update_acc_pull": 26.031,
+        "1b+bf16m:lps_update_noacc_pull": 18.031,
     },
 }
 
@@ -189,14 +191,14 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
     # dominant kernel: the LPS update variant that takes the most time
     dom = max(upd_labels, key=lambda k: kernels[k]["total_ms"])
     stored = MEASURED_TRAFFIC.get(kernels_digest())
-    traffic = None if bf16_momentum else (stored or {}).get(f"{name}:{dom}")     # the counter runs were taken with fp32 momentum
+    traffic = (stored or {}).get(f"{name}{'+bf16m' if bf16_momentum else ''}:{dom}")
     if traffic is not None:
         traffic_source = ("stored: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/, valid for the "
                           "kernel source with this sha256 only")
     elif stored is None:
         traffic_source = "none: the kernel source has changed since the counters under profiles/ were taken"
     else:
-        traffic_source = "none: the counter runs under profiles/ cover the 1b and 1b-dn workloads only"
+        traffic_source = "none: the counter runs under profiles/ cover the 1b workload (fp32 and bfloat16 momentum) and 1b-dn only"
     roofline = {
         "bound": "hbm", "kernel": dom, "achieved": kernels[dom]["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": kernels[dom]["achieved_GBps"] / HBM_PEAK_GBS,
