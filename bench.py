@@ -47,7 +47,9 @@ def bytes_per_param(label: str, delta_dtype: str, delayed: bool, momentum_bytes:
                     without reading it (4 less than "acc").
       gps_update_nomom  no momentum array at all: read G, Theta; write Theta and the returned model (16).
       lps_update_batchK_*  K queued deltas in one pass: K deltas read, K worker models written, momentum, model and
-                    (if any of them accumulates) the third buffer read and written once.
+                    (if any of them accumulates) the third buffer read and written once.  "_merge_": the pass opens with
+                    the merge of the returned global model (read from the third buffer, which then restarts: +8, and
+                    no separate 16-byte merge pass).
       pull          read and write a model (8).
     momentum_bytes = 2 (HALOS_FLAG_BF16_MOMENTUM): the momentum's read and write cost 4 instead of 8.
     """
@@ -185,7 +187,7 @@ def run_workload(name: str, steps: int, warmup: int, verbose: bool, placement: s
     n_pull_events = kernels.get("pull", {}).get("launches", 0) + sum(
         kernels[k]["launches"] * per_launch(k) for k in upd_labels if k.endswith("_pull"))
     n_gps = sum(v["launches"] for k, v in kernels.items() if k.startswith("gps_update"))
-    n_mrg = sum(v["launches"] for k, v in kernels.items() if k.startswith("lps_merge"))
+    n_mrg = sum(v["launches"] for k, v in kernels.items() if k.startswith("lps_merge") or "_merge_" in k)   # own pass, or opening a batch
     updates = n_upd + n_gps + n_mrg
     value = N * updates / elapsed
     # dominant kernel: the LPS update variant that takes the most time

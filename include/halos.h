@@ -287,13 +287,17 @@ halos_status halos_lps_step_average(halos_lps *lps, int32_t count, void *stream,
  * accumulated update, the send test, the models handed back -- are those of that many single steps, bit for bit; only
  * m, theta and the third buffer are read and written once instead of once per delta (k deltas: 2k + 28 + 4k bytes per
  * parameter instead of 30k, bf16 deltas with the model handed back).  The queue sentence of Sec. 4.1 is respected: a
- * batch never reaches past a queued global model.
+ * batch never reaches past a queued global model.  If a returned global model is AT the head and worker deltas wait
+ * right behind it, the pass opens with the merge (Algorithm 1's merge branch, then the updates, on each element while
+ * it is in registers): the same results as halos_lps_step followed by the updates, without the merge's own pass over
+ * the model and the third buffer (16 bytes per parameter less).  Such a batch is the merge plus up to max_items - 1
+ * deltas, and is taken already when one delta waits.
  *   pull      non-zero: each update also writes the model right after it to its sender's registered buffer
  *             (halos_lps_step_pull for every item)
  *   infos     host array of max_items entries; entry i describes the i-th step taken
- *   n_done    number of queue items handled: 0 (empty queue), 1 (a merge, or a single update: whenever fewer than two
- *             deltas of one element type wait, or the server runs a momentum delay or the norm monitors, the call is
- *             exactly halos_lps_step / halos_lps_step_pull), or the size of the batch
+ *   n_done    number of queue items handled: 0 (empty queue), 1 (a merge with no delta behind it, or a single update:
+ *             whenever fewer than two items can share a pass, or the server runs a momentum delay or the norm
+ *             monitors, the call is exactly halos_lps_step / halos_lps_step_pull), or the size of the batch
  * Errors as for halos_lps_step_pull; nothing is modified on error.
  */
 halos_status halos_lps_step_batch(halos_lps *lps, int32_t max_items, int32_t pull, void *stream, halos_step_info *infos,

@@ -755,11 +755,12 @@ halos_status halos_lps_step_pull(halos_lps *l, void *stream, halos_step_info *in
 
 namespace {
 
-// Can the first `count` queue items go through one multi-delta pass?  All must be plain deltas of one element type.
-bool multi_eligible(const halos_lps *l, int32_t count, bool pull) {
-    if (!l->proto.head_is_deltas(count)) return false;
-    const PendingDelta &first = l->pending[l->proto.item(0).worker];
-    for (int32_t i = 0; i < count; ++i) {
+// Can the `count` queue items from position `first_item` on go through one multi-delta pass?  All must be plain deltas
+// of one element type.
+bool multi_eligible(const halos_lps *l, int32_t count, bool pull, int32_t first_item = 0) {
+    if (!l->proto.are_deltas(first_item, count)) return false;
+    const PendingDelta &first = l->pending[l->proto.item(first_item).worker];
+    for (int32_t i = first_item; i < first_item + count; ++i) {
         const int32_t w = l->proto.item(i).worker;
         const PendingDelta &p = l->pending[w];
         if (p.end_model || p.dtype != first.dtype) return false;
@@ -844,12 +845,14 @@ halos_status halos_lps_step_batch(halos_lps *l, int32_t max_items, int32_t pull,
     if (!infos || !n_done) return fail(HALOS_EINVAL, "infos / n_done is NULL");
     *n_done = 0;
     halos_gps *g = l->gps;
-    // the longest run of plain deltas of one element type at the head of the queue
+    // the longest run of plain deltas of one element type at the head of the queue, or right behind a returned global
+    // model at the head (then the merge opens the pass)
+    const int32_t lead = l->proto.head().kind == ITEM_GLOBAL ? 1 : 0;
     int32_t count = 0;
     if (l->cycle.d() == 1 && !l->d_norm_partials)
-        for (int32_t c = std::min<int32_t>(max_items, l->proto.queued()); c >= 2 && count == 0; --c)
-            if (multi_eligible(l, c, pull != 0)) count = c;
-    if (count < 2) {                    // nothing to batch: one ordinary step
+        for (int32_t c = std::min<int32_t>(max_items, l->proto.queued()) - lead; c >= 2 - lead && c >= 1 && count == 0; --c)
+            if (multi_eligible(l, c, pull != 0, lead)) count = c;
+    if (count < 2 - lead) {             // nothing to batch: one ordinary step
         const QueueItem head = l->proto.head();
         halos_status st = lps_step_impl(l, stream, &infos[0], pull != 0 && head.kind == ITEM_DELTA);
         if (st == HALOS_OK && infos[0].kind != 0) *n_done = 1;
@@ -857,11 +860,22 @@ halos_status halos_lps_step_batch(halos_lps *l, int32_t max_items, int32_t pull,
     }
     halos_status st = check_device(g);
     if (st != HALOS_OK) return st;
-    // what each of the updates will mean for the accumulated update, on a copy of the protocol state
+    // what each of the items will mean for the accumulated update, on a copy of the protocol state
     LpsProtocol sim = l->proto;
     MultiArgs a{};
     a.n_in = count;
-    halos_step_info out[MAX_MULTI];
+    halos_step_info out[MAX_MULTI + 1];
+    if (lead) {                         // the merge branch of the LPS block, on the copy
+        sim.commit_merge();
+        out[0] = halos_step_info{};
+        out[0].kind = 2;
+        out[0].worker = -1;
+        out[0].t = sim.t();
+        out[0].t_last = sim.t_last();
+        a.merge = 1;
+        a.alpha = l->alpha;
+        a.keep = 1.0f - l->alpha;
+    }
     int32_t n_acc = 0, freeze_at = 0;
     halos_dtype dtype = HALOS_F32;
     const size_t nt = g->numel.size();
@@ -876,16 +890,18 @@ halos_status halos_lps_step_batch(halos_lps *l, int32_t max_items, int32_t pull,
         a.pull[i] = pull ? l->d_worker_model + (size_t)w * nt : nullptr;
         a.w[i] = l->pending[w].weight;
         dtype = l->pending[w].dtype;
-        out[i] = halos_step_info{};
-        out[i].kind = 1;
-        out[i].worker = w;
-        out[i].accumulated = oc.accumulate ? 1 : 0;
-        out[i].delta_ready = oc.freezes ? 1 : 0;
-        out[i].t = sim.t();
-        out[i].t_last = sim.t_last();
+        halos_step_info &o = out[lead + i];
+        o = halos_step_info{};
+        o.kind = 1;
+        o.worker = w;
+        o.accumulated = oc.accumulate ? 1 : 0;
+        o.delta_ready = oc.freezes ? 1 : 0;
+        o.t = sim.t();
+        o.t_last = sim.t_last();
     }
     int third_mode;
-    if (l->snapshot) { third_mode = freeze_at ? THIRD_FREEZE_SNAPSHOT : THIRD_NONE; a.n_acc = freeze_at; }
+    if (l->snapshot) { third_mode = (freeze_at || lead) ? THIRD_FREEZE_SNAPSHOT : THIRD_NONE; a.n_acc = freeze_at; }
+    else if (lead) { third_mode = THIRD_ADD; a.n_acc = n_acc; }       // the pass itself restarts the accumulation from zero
     else { third_mode = n_acc ? (l->third_stale ? THIRD_RESTART : THIRD_ADD) : THIRD_NONE; a.n_acc = n_acc; }
     const LaunchShape shape = current_shape(g);
     for (const TileRange &r : g->ranges) {
@@ -895,9 +911,9 @@ halos_status halos_lps_step_batch(halos_lps *l, int32_t max_items, int32_t pull,
         if (e != hipSuccess) return fail_hip(e, "launching the batched update");
     }
     l->proto = sim;
-    if (third_mode == THIRD_RESTART) l->third_stale = false;
-    for (int32_t i = 0; i < count; ++i) infos[i] = out[i];
-    *n_done = count;
+    if (third_mode == THIRD_RESTART || lead) l->third_stale = false;
+    for (int32_t i = 0; i < lead + count; ++i) infos[i] = out[i];
+    *n_done = lead + count;
     return HALOS_OK;
 }
 

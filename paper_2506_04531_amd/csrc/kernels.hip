@@ -340,11 +340,14 @@ lps_update_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t til
 // otherwise average them and apply the mean once.  THIRD as in lps_update_kernel; under SEQ the first n_acc deltas
 // count towards the accumulated update, and with THIRD = 2 the n_acc-th turns the snapshot into theta_{t_last} - theta_t.
 // With MB the momentum tensors hold bfloat16 and the momentum is rounded after every one of the updates, as in single steps.
-template <typename GT, bool SEQ, int THIRD, bool PULL, bool MB = false>
+// With MERGE (SEQ, THIRD 1 or 2) the third buffer arrives holding the returned global model: merge it into theta first,
+// then restart the accumulation (THIRD 1: from zero; THIRD 2: the merged model is the new snapshot).
+template <typename GT, bool SEQ, int THIRD, bool PULL, bool MB = false, bool MERGE = false>
 __global__ void __launch_bounds__(BLOCK_THREADS)
 lps_update_multi_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi,
                         float *const *__restrict__ theta_tab, float *const *__restrict__ m_tab,
                         float *const *__restrict__ acc_tab, MultiArgs a, float eta, float beta, float cg, float inv_n) {
+    static_assert(!MERGE || (SEQ && (THIRD == 1 || THIRD == 2)), "a merge-first pass is sequential and rewrites the third buffer");
     constexpr bool NT = true;
     constexpr bool LOAD_THIRD = THIRD == 1 || THIRD == 2;
     const uint32_t tid = threadIdx.x;
@@ -382,6 +385,10 @@ lps_update_multi_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
+                if constexpr (MERGE) {
+                    tv[u] = merge4(tv[u], av[u], a.alpha, a.keep);
+                    av[u] = THIRD == 2 ? tv[u] : zero;
+                }
                 if constexpr (SEQ) {
 #pragma unroll
                     for (int i = 0; i < MAX_MULTI; ++i)
@@ -408,6 +415,10 @@ lps_update_multi_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32
             const uint32_t len = tl.len;
             for (uint32_t k = tid; k < len; k += BLOCK_THREADS) {
                 float mk = ldg1(mm + k), tk = th[k], ak = LOAD_THIRD ? ac[k] : 0.f;
+                if constexpr (MERGE) {
+                    tk = merge1(tk, ak, a.alpha, a.keep);
+                    ak = THIRD == 2 ? tk : 0.f;
+                }
                 if constexpr (SEQ) {
                     for (int i = 0; i < n_in; ++i) {
                         const float s = model_update<MB>(tk, mk, __fmul_rn(a.w[i], ldg1(g[i] + k)), eta, beta, cg);
@@ -1007,6 +1018,7 @@ hipError_t launch_lps_update_multi(hipStream_t stream, const Tile *tiles, TileRa
     if (a.n_in < 1 || a.n_in > MAX_MULTI || a.n_acc < 0 || a.n_acc > a.n_in || third_mode < THIRD_NONE ||
         third_mode > THIRD_RESTART || (g_kind != GRAD_F32 && g_kind != GRAD_BF16 && g_kind != GRAD_F16))
         return hipErrorInvalidValue;
+    if (a.merge && (average || (third_mode != THIRD_ADD && third_mode != THIRD_FREEZE_SNAPSHOT))) return hipErrorInvalidValue;
     bool pull = false;
     for (int i = 0; i < a.n_in; ++i) {
         if (!a.delta[i]) return hipErrorInvalidValue;
@@ -1027,9 +1039,20 @@ hipError_t launch_lps_update_multi(hipStream_t stream, const Tile *tiles, TileRa
         else if (third_mode == THIRD_FREEZE_SNAPSHOT) HALOS_LAUNCH_MULTI(GT, SEQ, 2, PULL); \
         else HALOS_LAUNCH_MULTI(GT, SEQ, 3, PULL);                                 \
     } while (0)
+#define HALOS_LAUNCH_MULTI_MERGE(GT, THIRD, PULL)                                                                                     \
+    do {                                                                                                                             \
+        if (m_bf16)                                                                                                                  \
+            lps_update_multi_kernel<GT, true, THIRD, PULL, true, true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, m, acc, a, eta, beta, cg, inv_n); \
+        else                                                                                                                         \
+            lps_update_multi_kernel<GT, true, THIRD, PULL, false, true><<<grid, block, 0, stream>>>(tiles, r.lo, r.hi, theta, m, acc, a, eta, beta, cg, inv_n); \
+    } while (0)
 #define HALOS_LAUNCH_MULTI_KIND(GT)                                                \
     do {                                                                           \
-        if (average) HALOS_LAUNCH_MULTI_THIRD(GT, false, false);                   \
+        if (a.merge) {                                                             \
+            if (third_mode == THIRD_ADD) { if (pull) HALOS_LAUNCH_MULTI_MERGE(GT, 1, true); else HALOS_LAUNCH_MULTI_MERGE(GT, 1, false); } \
+            else { if (pull) HALOS_LAUNCH_MULTI_MERGE(GT, 2, true); else HALOS_LAUNCH_MULTI_MERGE(GT, 2, false); } \
+        }                                                                          \
+        else if (average) HALOS_LAUNCH_MULTI_THIRD(GT, false, false);              \
         else if (pull) HALOS_LAUNCH_MULTI_THIRD(GT, true, true);                   \
         else HALOS_LAUNCH_MULTI_THIRD(GT, true, false);                            \
     } while (0)
@@ -1037,6 +1060,7 @@ hipError_t launch_lps_update_multi(hipStream_t stream, const Tile *tiles, TileRa
     else if (g_kind == GRAD_F16) HALOS_LAUNCH_MULTI_KIND(_Float16);
     else HALOS_LAUNCH_MULTI_KIND(float);
 #undef HALOS_LAUNCH_MULTI_KIND
+#undef HALOS_LAUNCH_MULTI_MERGE
 #undef HALOS_LAUNCH_MULTI_THIRD
 #undef HALOS_LAUNCH_MULTI
     return hipGetLastError();

@@ -74,6 +74,12 @@ hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r,
 //       model right after delta i was applied (that worker's next start model).
 //   average (average = true): ONE ModelUpdate with (w_0 g_0 + ... + w_{n-1} g_{n-1}) * inv_n, added in that order;
 //       n_acc is 1 if the update counts, 0 if not; pull tables are ignored.
+//   merge first (a.merge != 0, sequential only): the third buffer holds the returned global model Theta_i; before
+//       the first delta each element is merged, theta <- alpha Theta_i + keep theta (the merge of Alg. 1's LPS block),
+//       and the accumulation restarts: the third buffer leaves the pass as the sum of the first n_acc steps
+//       (third_mode THIRD_ADD), or, in the snapshot form (THIRD_FREEZE_SNAPSHOT), as the merged model -- turned into
+//       theta_{t_last} - theta_t by the n_acc-th update if n_acc > 0.  Same operations in the same order as a merge
+//       pass followed by the update passes; the merge pass's 16 bytes per parameter are not moved.
 // dtype of all deltas: GRAD_F32, GRAD_BF16 or GRAD_F16.  Always non-temporal; no norm monitors.
 constexpr int MAX_MULTI = 4;
 struct MultiArgs {
@@ -82,6 +88,8 @@ struct MultiArgs {
     float w[MAX_MULTI];                      // the callers' scalars on the deltas
     int32_t n_in;                            // 2..MAX_MULTI (1 is allowed)
     int32_t n_acc;
+    int32_t merge;                           // 1: merge the returned global model first (see above)
+    float alpha, keep;                       // merge weights (used if merge)
 };
 hipError_t launch_lps_update_multi(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
                                    float *const *acc, const MultiArgs &a, bool average, int g_kind, int third_mode,

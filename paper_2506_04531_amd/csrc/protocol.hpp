@@ -91,9 +91,11 @@ public:
     }
 
     // An averaged step: the first `count` items (all deltas) become ONE update with their mean.
-    bool head_is_deltas(int32_t count) const {
-        if (count < 1 || (std::size_t)count > queue_.size()) return false;
-        for (int32_t i = 0; i < count; ++i) if (queue_[i].kind != ITEM_DELTA) return false;
+    bool head_is_deltas(int32_t count) const { return are_deltas(0, count); }
+    // Are the `count` items from position `first` on all worker deltas?
+    bool are_deltas(int32_t first, int32_t count) const {
+        if (first < 0 || count < 1 || (std::size_t)first + (std::size_t)count > queue_.size()) return false;
+        for (int32_t i = first; i < first + count; ++i) if (queue_[i].kind != ITEM_DELTA) return false;
         return true;
     }
     QueueItem item(int32_t i) const { return queue_[i]; }

@@ -222,7 +222,9 @@ class Cluster:
         halos_lps_step_pull call (same results, one pass less).
         batch (2..4, needs fuse_pull): update steps of one server that follow each other directly in the trace (each with
         its pull; events of other servers in between do not touch this server's state) are issued as one
-        halos_lps_step_batch call (same results; the server's state is read and written once for all of them).
+        halos_lps_step_batch call (same results; the server's state is read and written once for all of them).  A merge
+        step whose server does nothing else until its next update step is held back and opens that update's pass (the
+        returned model waits in the queue meanwhile; same results, the merge's own pass is saved).
 
         Returns (step_log, timings): step_log has one tuple (record index, kind, t, t_last, delta_ready,
         accumulated) per LPS step; timings (only if timed) maps a kernel label to a list of
@@ -249,6 +251,7 @@ class Cluster:
             for j, hh in enumerate(self.lps):
                 cnt = B.halos_lps_get_counters(hh)
                 restart[j] = cnt["phase"] == B.PHASE_ACCUMULATING and cnt["t"] == cnt["t_last"] and cnt["t"] > 0
+        held_merge = [None] * len(self.lps)      # record index of a merge step that waits to open the server's next pass
         seen_l = [B.halos_lps_get_momentum_delay(h)["seen"] for h in self.lps]
         seen_g = B.halos_gps_get_momentum_delay(self.gps)["seen"]
 
@@ -292,6 +295,15 @@ class Cluster:
                 j += 1
             return (group[:len(pulls)], pulls) if pulls else None
 
+        def merge_can_wait(i, l):
+            """Is the server's next event after merge step i (arrivals of deltas aside) an update step?"""
+            for j in range(i + 1, n_ev):
+                e2 = events[j]
+                if int(e2["lps"]) != l or int(e2["kind"]) == _ARRIVE_DELTA:
+                    continue
+                return int(e2["kind"]) == _LPS_STEP and int(e2["exp_kind"]) == 1
+            return False
+
         for i in range(n_ev):
             if i == skip or i in consumed:
                 continue
@@ -311,10 +323,21 @@ class Cluster:
                     chk(lib.halos_lps_set_threshold(h, k))
                     k_now[l] = k
                 fused = False
+                merge_label = "lps_merge_leave" if self.defer_clear else "lps_merge"
+                lead, grp = 0, None
                 if int(ev["exp_kind"]) == 2:
-                    label = "lps_merge_leave" if self.defer_clear else "lps_merge"
+                    if batch and merge_can_wait(i, l):
+                        held_merge[l] = i
+                        continue
+                    label = merge_label
                     restart[l] = self.defer_clear
                 else:
+                    lead = 1 if held_merge[l] is not None else 0
+                    grp = following_steps(i, l, batch - lead) if batch else None
+                    if lead and grp is None:        # this update shares no pass: the merge that waited goes first, on its own
+                        chk(bracket(merge_label, lambda: lib.halos_lps_step(h, sp, ctypes.byref(info))))
+                        log.append((held_merge[l], info.kind, info.t, info.t_last, info.delta_ready, info.accumulated))
+                        held_merge[l], restart[l], lead = None, self.defer_clear, 0
                     if self.snapshot:      # third buffer untouched except by the update that completes the accumulation
                         label = "lps_update_freeze" if int(ev["exp_send"]) else "lps_update_noacc"
                     else:
@@ -328,15 +351,19 @@ class Cluster:
                     if fuse_pull and i + 1 < n_ev:
                         nx = events[i + 1]
                         fused = (int(nx["kind"]) == _PULL and int(nx["lps"]) == l and int(nx["worker"]) == int(ev["worker"]))
-                    grp = following_steps(i, l, batch) if batch else None
-                    if grp is not None and len(grp[0]) >= 2:
+                    if grp is not None and len(grp[0]) >= 2 - lead:
                         steps, pulls = grp
                         # does the pass touch the third buffer? (snapshot form: only the update that completes the accumulation does)
                         any_acc = any(int(events[j]["exp_send" if self.snapshot else "exp_accumulate"]) for j in steps)
-                        blabel = f"lps_update_batch{len(steps)}_{'acc' if any_acc else 'noacc'}_pull"
-                        chk(bracket(blabel, lambda: lib.halos_lps_step_batch(h, len(steps), 1, sp, infos, ctypes.byref(n_done))))
-                        assert n_done.value == len(steps), (n_done.value, len(steps))
-                        for j, inf in zip(steps, infos):
+                        third = "merge" if lead else ("acc" if any_acc else "noacc")
+                        blabel = f"lps_update_batch{len(steps)}_{third}_pull"
+                        chk(bracket(blabel, lambda: lib.halos_lps_step_batch(h, lead + len(steps), 1, sp, infos, ctypes.byref(n_done))))
+                        assert n_done.value == lead + len(steps), (n_done.value, lead, len(steps))
+                        if lead:
+                            inf = infos[0]
+                            log.append((held_merge[l], inf.kind, inf.t, inf.t_last, inf.delta_ready, inf.accumulated))
+                            held_merge[l], restart[l] = None, False
+                        for j, inf in zip(steps, list(infos)[lead:]):
                             log.append((j, inf.kind, inf.t, inf.t_last, inf.delta_ready, inf.accumulated))
                             if restart[l] and inf.accumulated:
                                 restart[l] = False

@@ -341,6 +341,7 @@ def test_batched_steps_equal_single_steps(recipe, dtype, flags, weighted):
     batched = {k: len(v) for k, v in runs[1][2].items() if k.startswith("lps_update_batch")}
     print(f"[parity] {w.name}: batched launches {batched}", flush=True)
     assert sum(batched.values()) >= 5, "the schedule must produce bursts for this test to mean anything"
+    assert sum(n for k, n in batched.items() if "_merge_" in k) >= 3, "some passes must open with a merge"
     assert runs[0][0] == runs[1][0]
     skip = {f"aux{l}" for l, cnt in enumerate(fresh)
             if flags == "defer" and cnt["phase"] == B.PHASE_ACCUMULATING and cnt["t"] == cnt["t_last"] and cnt["t"] > 0}
@@ -380,6 +381,62 @@ def test_batch_call_on_a_single_item_is_the_ordinary_step():
         assert e.value.status == B.EINVAL
     finally:
         c.close()
+
+
+@pytest.mark.parametrize("flags", [0, "snapshot", "defer", "bf16m"])
+def test_batch_that_opens_with_the_merge_equals_the_steps_one_by_one(flags):
+    """A returned global model at the head of the queue with deltas behind it: halos_lps_step_batch merges and updates in
+    one pass.  Two identical clusters take the same items, one through the batch call and one step by step; state, counters
+    and the models handed back must agree bit for bit, for K reached inside the batch and not."""
+    from paper_2506_04531_amd import binding as B
+    fl = {0: 0, "snapshot": B.FLAG_SNAPSHOT, "defer": B.FLAG_DEFER_CLEAR, "bf16m": B.FLAG_BF16_MOMENTUM}[flags]
+    w = replace(synth.get_workload("160m").scaled(RAGGED, n_updates=8, name=f"mergebatch-{flags}"), n_lps=1, workers_per_lps=4,
+                pool_slots=4)
+    trace = synth.make_trace(w)
+    out = []
+    for batched in (False, True):
+        hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, 2, flags=fl)
+        c = _cluster(w, trace, hp=hp)
+        try:
+            h = c.lps[0]
+            log = []
+            for rnd, (K, n_behind) in enumerate([(2, 3), (5, 2), (1, 1), (2, 3)]):
+                B.halos_lps_set_threshold(h, 2)
+                for k in range(2):                                              # two updates complete an accumulation
+                    B.halos_lps_push_update(h, k, c.pool[(rnd + k) % 4], c.delta_dtype)
+                    B.halos_lps_step_pull(h)
+                B.halos_gps_merge(c.gps, h)
+                B.halos_lps_push_global(h)
+                for k in range(n_behind):                                       # deltas arrive behind the returned model
+                    B.halos_lps_push_update(h, k, c.pool[(rnd + k + 1) % 4], c.delta_dtype)
+                B.halos_lps_set_threshold(h, K)
+                if batched:
+                    infos = B.halos_lps_step_batch(h, 4, True)
+                    assert [i.kind for i in infos] == [2] + [1] * n_behind, (rnd, [i.kind for i in infos])
+                else:
+                    infos = [B.halos_lps_step(h)] + [B.halos_lps_step_pull(h) for _ in range(n_behind)]
+                log.append([(i.kind, i.worker, i.t, i.t_last, i.delta_ready, i.accumulated) for i in infos])
+                cnt = B.halos_lps_get_counters(h)
+                if cnt["phase"] == B.PHASE_SENT:                                # K was reached inside the batch: send it on
+                    B.halos_gps_merge(c.gps, h); B.halos_lps_push_global(h); B.halos_lps_step(h)
+                else:                                                           # finish the accumulation for the next round
+                    while B.halos_lps_get_counters(h)["phase"] != B.PHASE_SENT:
+                        B.halos_lps_set_threshold(h, 1)
+                        B.halos_lps_push_update(h, 3, c.pool[rnd % 4], c.delta_dtype); B.halos_lps_step_pull(h)
+                    B.halos_gps_merge(c.gps, h); B.halos_lps_push_global(h); B.halos_lps_step(h)
+            torch.cuda.synchronize()
+            state = {k: c.flat(k) for k in c.state_lists()}
+            state["pull"] = torch.cat([t.reshape(-1) for t in c.pull_dst[0]]).cpu().numpy()
+            fresh = B.halos_lps_get_counters(h)
+            out.append((log, state, fresh))
+        finally:
+            c.close()
+    assert out[0][0] == out[1][0]
+    assert out[0][2] == out[1][2]
+    for k in out[0][1]:
+        if flags == "defer" and k == "aux0":
+            continue                                                            # ends right after a merge: unspecified there
+        assert np.array_equal(out[0][1][k].view(np.uint32), out[1][1][k].view(np.uint32)), k
 
 
 # ---------------------------------------------------------------- the variants at full benchmark size
