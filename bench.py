@@ -82,10 +82,10 @@ def bytes_per_param(label: str, delta_dtype: str, delayed: bool, momentum_bytes:
 # only for the kernel source it was measured on: {sha256 of kernels.hip: {kernel label: bytes/param}}.
 MEASURED_TRAFFIC: dict = {
     # profiles/lps_update_1b_hbm_traffic.md, profiles/lps_update_delayed_1b_dn.md, profiles/lps_update_1b_bf16_momentum.md
-    "3c5fade1b5d9f41545cd7e48a4a634b02e97be8a8640bd7814b8af2aa389b9be": {
-        "1b:lps_update_acc_pull": 30.033,
+    "e1be1d88caa8397ba67de6a039538e7e21a53c1fd0240a2950103cfd68ada506": {
+        "1b:lps_update_acc_pull": 30.032,
         "1b:lps_update_noacc_pull": 22.031,
-        "1b-dn:lps_update_acc_first_pull": 26.038,
+        "1b-dn:lps_update_acc_first_pull": 26.039,
         "1b-dn:lps_update_acc_pull": 30.032,
         "1b-dn:lps_update_acc_refresh_pull": 34.031,
         "1b-dn:lps_update_noacc_first_pull": 18.031,
