@@ -316,8 +316,8 @@ def test_forget_buffers_makes_the_next_pointer_set_be_checked_again():
 
 
 def test_many_tensors_through_the_multi_delta_passes():
-    """More tensors than one launch range, zero-sized tensors among them, through halos_lps_step_batch and
-    halos_lps_step_average: the per-worker device tables of delta pointers span all ranges.  beta = 0, eta = 1 and
+    """More tensors than one launch range, zero-sized tensors among them, through halos_lps_step_batch (deltas only, and
+    opening with a merge) and halos_lps_step_average: the per-worker device tables of delta pointers span all ranges.  beta = 0, eta = 1 and
     dyadic values make every expected number exact."""
     from paper_2506_04531_amd import binding as B
     n_t = 800
@@ -356,6 +356,31 @@ def test_many_tensors_through_the_multi_delta_passes():
             if numel[i]:
                 want = float(i) - 1.5 - 3 * (i / 256.0) - 0.375 - i / 256.0
                 assert torch.all(th[i] == want), (i, float(th[i][0]), want)
+        # a batch that opens with the merge: complete the accumulation, add one update while it is in flight, let the
+        # global server answer, then take [returned model, delta, delta] in one call
+        B.halos_lps_set_threshold(lps, 1)
+        B.halos_lps_push_update(lps, 0, g[0], B.F32)
+        assert B.halos_lps_step_batch(lps, 4, True)[0].delta_ready == 1
+        B.halos_lps_push_update(lps, 2, g[2], B.F32)
+        assert B.halos_lps_step_pull(lps).accumulated == 0
+        B.halos_gps_merge(gps, lps)                                  # Theta <- Theta - G = the local model at the send
+        B.halos_lps_push_global(lps)
+        B.halos_lps_push_update(lps, 1, g[1], B.F32)
+        B.halos_lps_push_update(lps, 2, g[2], B.F32)
+        B.halos_lps_set_threshold(lps, 1 << 30)
+        infos = B.halos_lps_step_batch(lps, 4, True)
+        assert [i.kind for i in infos] == [2, 1, 1] and [i.worker for i in infos] == [-1, 1, 2]
+        assert [i.t_last for i in infos] == [6, 6, 6] and [i.t for i in infos] == [6, 7, 8]
+        torch.cuda.synchronize()
+        for i in range(n_t):
+            if numel[i]:
+                sent = float(i) - 1.5 - 3 * (i / 256.0) - 0.375 - i / 256.0 - (0.25 + i / 256.0)      # model at the send = Theta_i
+                merged = 0.5 * sent + 0.5 * (sent - (0.75 + i / 256.0))                                # alpha = 1/2
+                after1 = merged - (0.5 + i / 256.0)
+                after2 = after1 - (0.75 + i / 256.0)
+                assert torch.all(Theta[i] == sent), i
+                assert torch.all(wm[1][i] == after1) and torch.all(wm[2][i] == after2) and torch.all(th[i] == after2), i
+                assert torch.all(acc[i] == 1.25 + 2 * (i / 256.0)), i                                  # restarted by the merge
     finally:
         B.halos_lps_destroy(lps)
         B.halos_gps_destroy(gps)
