@@ -65,7 +65,8 @@ def bytes_per_param(label: str, delta_dtype: str, delayed: bool, momentum_bytes:
     if label.startswith("lps_update_batch"):
         k = int(parts[2][len("batch"):])
         g = 4 if delta_dtype == "f32" else 2
-        return k * g + 8 + 2 * momentum_bytes + (0 if "noacc" in parts else 8) + 4 * k
+        rule = (4 if "first" in parts else (12 if "refresh" in parts else 8)) if delayed else 2 * momentum_bytes
+        return k * g + 8 + rule + (0 if "noacc" in parts else 8) + 4 * k
     if delayed:
         rule = 4 if "first" in parts else (12 if "refresh" in parts else 8)
     else:

@@ -291,7 +291,8 @@ halos_status halos_lps_step_average(halos_lps *lps, int32_t count, void *stream,
  * right behind it, the pass opens with the merge (Algorithm 1's merge branch, then the updates, on each element while
  * it is in registers): the same results as halos_lps_step followed by the updates, without the merge's own pass over
  * the model and the third buffer (16 bytes per parameter less).  Such a batch is the merge plus up to max_items - 1
- * deltas, and is taken already when one delta waits.
+ * deltas, and is taken already when one delta waits.  Under a momentum delay the merge and ONE delta behind it share a
+ * pass (with pull non-zero); more deltas do not.
  *   pull      non-zero: each update also writes the model right after it to its sender's registered buffer
  *             (halos_lps_step_pull for every item)
  *   infos     host array of max_items entries; entry i describes the i-th step taken

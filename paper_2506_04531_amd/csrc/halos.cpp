@@ -787,6 +787,54 @@ halos_status delta_table(halos_lps *l, int32_t w, hipStream_t stream, const floa
 
 int grad_kind(halos_dtype d) { return d == HALOS_BF16 ? GRAD_BF16 : (d == HALOS_F16 ? GRAD_F16 : GRAD_F32); }
 
+// Under a momentum delay: the returned global model at the head of the queue and the ONE plain delta behind it, merged
+// and applied in one pass (the caller has checked that this is what the queue holds and that the sender has a model
+// buffer).  Same results as halos_lps_step followed by halos_lps_step_pull.
+halos_status merge_then_delayed_update(halos_lps *l, void *stream, halos_step_info *infos, int32_t *n_done) {
+    halos_gps *g = l->gps;
+    halos_status st = check_device(g);
+    if (st != HALOS_OK) return st;
+    LpsProtocol sim = l->proto;
+    sim.commit_merge();
+    halos_step_info out[2];
+    out[0] = halos_step_info{};
+    out[0].kind = 2;
+    out[0].worker = -1;
+    out[0].t = sim.t();
+    out[0].t_last = sim.t_last();
+    const int32_t w = sim.head().worker;
+    const UpdateOutcome oc = sim.preview_update();          // right after a merge every update accumulates
+    sim.commit_update();
+    const PendingDelta &p = l->pending[w];
+    const int third_mode = l->snapshot ? (oc.freezes ? THIRD_FREEZE_SNAPSHOT : THIRD_MERGED_SNAPSHOT) : THIRD_ADD;
+    const float inv_d = 1.0f / (float)l->cycle.d();
+    const LaunchShape shape = current_shape(g);
+    const size_t nt = g->numel.size();
+    for (const TileRange &r : g->ranges) {
+        PtrArgs args;
+        fill_args(args, p.ptrs.data(), r, nt);
+        hipError_t e = launch_lps_update_delayed((hipStream_t)stream, g->d_tiles, r, l->d_theta, l->d_m, l->d_buffer, l->d_acc,
+                                                 l->d_worker_model + (size_t)w * nt, args, grad_kind(p.dtype), third_mode,
+                                                 (int)l->cycle.next(), l->rule.eta, l->rule.beta, l->rule.cg * inv_d, inv_d,
+                                                 p.weight, nullptr, shape, true, l->alpha, 1.0f - l->alpha);
+        if (e != hipSuccess) return fail_hip(e, "launching the merge and delayed update");
+    }
+    l->proto = sim;
+    l->cycle.commit();
+    l->third_stale = false;
+    out[1] = halos_step_info{};
+    out[1].kind = 1;
+    out[1].worker = w;
+    out[1].accumulated = oc.accumulate ? 1 : 0;
+    out[1].delta_ready = oc.freezes ? 1 : 0;
+    out[1].t = l->proto.t();
+    out[1].t_last = l->proto.t_last();
+    infos[0] = out[0];
+    infos[1] = out[1];
+    *n_done = 2;
+    return HALOS_OK;
+}
+
 }  // namespace
 
 halos_status halos_lps_step_average(halos_lps *l, int32_t count, void *stream, halos_step_info *info) {
@@ -848,6 +896,8 @@ halos_status halos_lps_step_batch(halos_lps *l, int32_t max_items, int32_t pull,
     // the longest run of plain deltas of one element type at the head of the queue, or right behind a returned global
     // model at the head (then the merge opens the pass)
     const int32_t lead = l->proto.head().kind == ITEM_GLOBAL ? 1 : 0;
+    if (lead && l->cycle.d() > 1 && !l->d_norm_partials && pull && max_items >= 2 && multi_eligible(l, 1, true, 1))
+        return merge_then_delayed_update(l, stream, infos, n_done);
     int32_t count = 0;
     if (l->cycle.d() == 1 && !l->d_norm_partials)
         for (int32_t c = std::min<int32_t>(max_items, l->proto.queued()) - lead; c >= 2 - lead && c >= 1 && count == 0; --c)

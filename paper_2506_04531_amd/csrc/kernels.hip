@@ -581,16 +581,21 @@ __device__ __forceinline__ f32x4 delayed_update4(f32x4 &x, f32x4 &m, f32x4 &b, f
 }
 
 // S1 under the delayed rule.  THIRD and PULL as in lps_update_kernel; accesses are non-temporal.
-template <typename GT, int THIRD, bool PULL, int RULE, bool FROM_END, bool NORM>
+// MERGE: the third buffer arrives holding the returned global model Theta_i; each element is merged first
+// (theta <- alpha Theta_i + keep theta, the merge of Alg. 1's LPS block) and the accumulation restarts with this update:
+// THIRD 1 the third buffer leaves as 0 + s; THIRD 2 (snapshot form, this update completes the accumulation) as
+// merged - updated; THIRD 4 (snapshot form, it does not) as the merged model, the new snapshot.
+template <typename GT, int THIRD, bool PULL, int RULE, bool FROM_END, bool NORM, bool MERGE = false>
 __global__ void __launch_bounds__(BLOCK_THREADS)
 lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint32_t tile_hi, uint32_t tensor_base,
                           float *const *__restrict__ theta_tab, float *const *__restrict__ m_tab,
                           float *const *__restrict__ buf_tab, float *const *__restrict__ acc_tab,
                           float *const *__restrict__ pull_tab, PtrArgs gargs, float eta, float beta, float cgd,
-                          float inv_d, float gw, double *__restrict__ partials) {
+                          float inv_d, float gw, double *__restrict__ partials, float alpha, float keep) {
     static_assert(!FROM_END || (PULL && sizeof(GT) == 4), "an end model is fp32 and needs the worker's start model");
+    static_assert(MERGE ? (THIRD == 1 || THIRD == 2 || THIRD == 4) : THIRD != 4, "THIRD 4 exists only for a merge-first pass");
     constexpr bool NT = true;
-    constexpr bool LOAD_THIRD = THIRD == 1 || THIRD == 2;
+    constexpr bool LOAD_THIRD = THIRD == 1 || THIRD == 2 || THIRD == 4;
     constexpr bool LOAD_B = RULE != CYCLE_FIRST, STORE_B = RULE != CYCLE_REFRESH, USE_M = RULE == CYCLE_REFRESH;
     const uint32_t tid = threadIdx.x;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
@@ -624,6 +629,10 @@ lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t off = (u * BLOCK_THREADS + tid) * VEC;
+                if constexpr (MERGE) {
+                    tv[u] = merge4(tv[u], av[u], alpha, keep);
+                    av[u] = THIRD == 1 ? zero : tv[u];
+                }
                 const f32x4 s = delayed_update4<RULE>(tv[u], mv[u], bv[u], gv[u], eta, beta, cgd, inv_d);
                 if constexpr (STORE_B) st4<NT>(bb + off, bv[u]);
                 if constexpr (USE_M) st4<NT>(mm + off, mv[u]);
@@ -632,6 +641,7 @@ lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint
                 if constexpr (THIRD == 1) st4<NT>(ac + off, add4(av[u], s));
                 if constexpr (THIRD == 2) st4<NT>(ac + off, sub4(av[u], tv[u]));
                 if constexpr (THIRD == 3) st4<NT>(ac + off, add4(zero, s));
+                if constexpr (THIRD == 4) st4<NT>(ac + off, av[u]);
             }
         } else {
             const uint32_t len = tl.len;
@@ -639,28 +649,42 @@ lps_update_delayed_kernel(const Tile *__restrict__ tiles, uint32_t tile_lo, uint
                 if (off + VEC <= len) {
                     f32x4 gv = grad4<FROM_END, NT>(g, pd, off, gw), tv = ld4<NT>(th + off);
                     f32x4 bv = LOAD_B ? ld4<NT>(bb + off) : zero, mv = USE_M ? ld4<NT>(mm + off) : zero;
+                    f32x4 av = zero;
+                    if constexpr (LOAD_THIRD) av = ld4<NT>(ac + off);
                     if constexpr (NORM) norm_acc += static_cast<double>(sumsq4(gv, 0.f));
+                    if constexpr (MERGE) {
+                        tv = merge4(tv, av, alpha, keep);
+                        av = THIRD == 1 ? zero : tv;
+                    }
                     const f32x4 s = delayed_update4<RULE>(tv, mv, bv, gv, eta, beta, cgd, inv_d);
                     if constexpr (STORE_B) st4<NT>(bb + off, bv);
                     if constexpr (USE_M) st4<NT>(mm + off, mv);
                     st4<NT>(th + off, tv);
                     if constexpr (PULL) st4<NT>(pd + off, tv);
-                    if constexpr (THIRD == 1) st4<NT>(ac + off, add4(ld4<NT>(ac + off), s));
-                    if constexpr (THIRD == 2) st4<NT>(ac + off, sub4(ld4<NT>(ac + off), tv));
+                    if constexpr (THIRD == 1) st4<NT>(ac + off, add4(av, s));
+                    if constexpr (THIRD == 2) st4<NT>(ac + off, sub4(av, tv));
                     if constexpr (THIRD == 3) st4<NT>(ac + off, add4(zero, s));
+                    if constexpr (THIRD == 4) st4<NT>(ac + off, av);
                 } else {
                     for (uint32_t k = off; k < len; ++k) {      // ragged tail: fewer than 4 elements
                         float tv = th[k], bv = LOAD_B ? bb[k] : 0.f, mv = USE_M ? mm[k] : 0.f;
+                        float av = 0.f;
+                        if constexpr (LOAD_THIRD) av = ac[k];
                         const float gk = grad1<FROM_END>(g, pd, k, gw);
                         if constexpr (NORM) norm_acc += static_cast<double>(__fmul_rn(gk, gk));
+                        if constexpr (MERGE) {
+                            tv = merge1(tv, av, alpha, keep);
+                            av = THIRD == 1 ? 0.f : tv;
+                        }
                         const float s = delayed_update<RULE>(tv, mv, bv, gk, eta, beta, cgd, inv_d);
                         if constexpr (STORE_B) bb[k] = bv;
                         if constexpr (USE_M) mm[k] = mv;
                         th[k] = tv;
                         if constexpr (PULL) pd[k] = tv;
-                        if constexpr (THIRD == 1) ac[k] = __fadd_rn(ac[k], s);
-                        if constexpr (THIRD == 2) ac[k] = __fsub_rn(ac[k], tv);
+                        if constexpr (THIRD == 1) ac[k] = __fadd_rn(av, s);
+                        if constexpr (THIRD == 2) ac[k] = __fsub_rn(av, tv);
                         if constexpr (THIRD == 3) ac[k] = __fadd_rn(0.f, s);
+                        if constexpr (THIRD == 4) ac[k] = av;
                     }
                 }
             }
@@ -1095,20 +1119,49 @@ hipError_t launch_gps_update_nomom(hipStream_t stream, const Tile *tiles, TileRa
 hipError_t launch_lps_update_delayed(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
                                      float *const *m, float *const *buffer, float *const *acc, float *const *pull,
                                      const PtrArgs &g, int g_kind, int third_mode, int cycle_pos, float eta,
-                                     float beta, float cgd, float inv_d, float gw, double *norm_partials, LaunchShape shape) {
+                                     float beta, float cgd, float inv_d, float gw, double *norm_partials, LaunchShape shape,
+                                     bool merge, float alpha, float keep) {
     if (r.hi <= r.lo) return hipSuccess;
-    if (cycle_pos < CYCLE_FIRST || cycle_pos > CYCLE_REFRESH || third_mode < THIRD_NONE || third_mode > THIRD_RESTART ||
+    if (cycle_pos < CYCLE_FIRST || cycle_pos > CYCLE_REFRESH || third_mode < THIRD_NONE ||
+        third_mode > (merge ? THIRD_MERGED_SNAPSHOT : THIRD_RESTART) ||
         g_kind < GRAD_F32 || g_kind > GRAD_F16 || (g_kind == GRAD_END_MODEL && !pull))
         return hipErrorInvalidValue;
     const dim3 grid = grid_for(r, shape), block(BLOCK_THREADS);
+    if (merge) {        // merge-first pass: plain deltas with the model handed back, no monitors
+        if (!pull || norm_partials || g_kind == GRAD_END_MODEL ||
+            (third_mode != THIRD_ADD && third_mode != THIRD_FREEZE_SNAPSHOT && third_mode != THIRD_MERGED_SNAPSHOT))
+            return hipErrorInvalidValue;
+#define HALOS_LAUNCH_DNM(GT, THIRD, RULE)                                                                               \
+    lps_update_delayed_kernel<GT, THIRD, true, RULE, false, false, true><<<grid, block, 0, stream>>>(                   \
+        tiles, r.lo, r.hi, r.tensor_base, theta, m, buffer, acc, pull, g, eta, beta, cgd, inv_d, gw, nullptr, alpha, keep)
+#define HALOS_LAUNCH_DNM_RULE(GT, THIRD)                                                 \
+    do {                                                                                 \
+        if (cycle_pos == CYCLE_FIRST) HALOS_LAUNCH_DNM(GT, THIRD, CYCLE_FIRST);          \
+        else if (cycle_pos == CYCLE_INNER) HALOS_LAUNCH_DNM(GT, THIRD, CYCLE_INNER);     \
+        else HALOS_LAUNCH_DNM(GT, THIRD, CYCLE_REFRESH);                                 \
+    } while (0)
+#define HALOS_LAUNCH_DNM_THIRD(GT)                                                       \
+    do {                                                                                 \
+        if (third_mode == THIRD_ADD) HALOS_LAUNCH_DNM_RULE(GT, 1);                       \
+        else if (third_mode == THIRD_FREEZE_SNAPSHOT) HALOS_LAUNCH_DNM_RULE(GT, 2);      \
+        else HALOS_LAUNCH_DNM_RULE(GT, 4);                                               \
+    } while (0)
+        if (g_kind == GRAD_BF16) HALOS_LAUNCH_DNM_THIRD(unsigned short);
+        else if (g_kind == GRAD_F16) HALOS_LAUNCH_DNM_THIRD(_Float16);
+        else HALOS_LAUNCH_DNM_THIRD(float);
+#undef HALOS_LAUNCH_DNM_THIRD
+#undef HALOS_LAUNCH_DNM_RULE
+#undef HALOS_LAUNCH_DNM
+        return hipGetLastError();
+    }
 #define HALOS_LAUNCH_DN(GT, THIRD, PULL, RULE, END)                                                                     \
     do {                                                                                                                \
         if (norm_partials)                                                                                              \
             lps_update_delayed_kernel<GT, THIRD, PULL, RULE, END, true><<<grid, block, 0, stream>>>(                    \
-                tiles, r.lo, r.hi, r.tensor_base, theta, m, buffer, acc, pull, g, eta, beta, cgd, inv_d, gw, norm_partials); \
+                tiles, r.lo, r.hi, r.tensor_base, theta, m, buffer, acc, pull, g, eta, beta, cgd, inv_d, gw, norm_partials, 0.f, 0.f); \
         else                                                                                                            \
             lps_update_delayed_kernel<GT, THIRD, PULL, RULE, END, false><<<grid, block, 0, stream>>>(                   \
-                tiles, r.lo, r.hi, r.tensor_base, theta, m, buffer, acc, pull, g, eta, beta, cgd, inv_d, gw, nullptr);  \
+                tiles, r.lo, r.hi, r.tensor_base, theta, m, buffer, acc, pull, g, eta, beta, cgd, inv_d, gw, nullptr, 0.f, 0.f); \
     } while (0)
 #define HALOS_LAUNCH_DN_RULE(GT, THIRD, PULL, END)                                       \
     do {                                                                                 \

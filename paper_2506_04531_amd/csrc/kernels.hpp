@@ -58,6 +58,7 @@ struct TileRange {      // tiles [lo, hi) all belong to tensors [tensor_base, te
 // GRAD_F16: the tensors in `g` hold IEEE half values (upcast exactly).
 constexpr int GRAD_F32 = 0, GRAD_BF16 = 1, GRAD_END_MODEL = 2, GRAD_F16 = 3;
 constexpr int THIRD_NONE = 0, THIRD_ADD = 1, THIRD_FREEZE_SNAPSHOT = 2, THIRD_RESTART = 3;
+constexpr int THIRD_MERGED_SNAPSHOT = 4;      // merge-first pass in the snapshot form: the third buffer receives the merged model
 // m_bf16: the momentum tensors hold bfloat16; every new momentum is rounded to bfloat16 (nearest even) before it enters
 // the step and is stored as 16 bits.
 hipError_t launch_lps_update(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta, float *const *m,
@@ -117,11 +118,16 @@ hipError_t launch_gps_update_nomom(hipStream_t stream, const Tile *tiles, TileRa
 // CYCLE_REFRESH (m <- beta m + (buffer + g) * inv_d, then applied; the buffer is left as it is).  Every update
 // steps the model by eta * cgd * g (cgd = cg / d); only a refresh reads or writes m.  Always non-temporal.
 // norm_partials as in launch_lps_update.
+// merge (local server only; needs pull, no monitors, no end model): the third buffer holds the returned global model;
+// every element is merged first, theta <- alpha Theta_i + keep theta, and the accumulation restarts with this update
+// (third_mode THIRD_ADD: third <- 0 + step; THIRD_FREEZE_SNAPSHOT: third <- merged - updated; THIRD_MERGED_SNAPSHOT:
+// third <- merged).  Same operations in the same order as a merge pass followed by the update pass.
 constexpr int CYCLE_FIRST = 1, CYCLE_INNER = 2, CYCLE_REFRESH = 3;
 hipError_t launch_lps_update_delayed(hipStream_t stream, const Tile *tiles, TileRange r, float *const *theta,
                                      float *const *m, float *const *buffer, float *const *acc, float *const *pull,
                                      const PtrArgs &g, int g_kind, int third_mode, int cycle_pos, float eta,
-                                     float beta, float cgd, float inv_d, float gw, double *norm_partials, LaunchShape shape);
+                                     float beta, float cgd, float inv_d, float gw, double *norm_partials, LaunchShape shape,
+                                     bool merge = false, float alpha = 0.f, float keep = 0.f);
 hipError_t launch_gps_update_delayed(hipStream_t stream, const Tile *tiles, TileRange r, float *const *Theta,
                                      float *const *M, float *const *buffer, float *const *G, float *const *out,
                                      int cycle_pos, float eta, float beta, float cgd, float inv_d, LaunchShape shape);

@@ -240,7 +240,8 @@ class Cluster:
         weighted = self.w.staleness_exponent > 0.0
         skip = -1
         consumed = set()
-        batch = batch if (fuse_pull and self.w.d_l == 1 and batch >= 2) else 0
+        batch = batch if (fuse_pull and batch >= 2) else 0
+        delayed = self.w.d_l > 1          # under a momentum delay only a merge and the one update behind it share a pass
         infos = (B.StepInfo * 4)()
         n_done = ctypes.c_int32()
         info = B.StepInfo()
@@ -333,7 +334,7 @@ class Cluster:
                     restart[l] = self.defer_clear
                 else:
                     lead = 1 if held_merge[l] is not None else 0
-                    grp = following_steps(i, l, batch - lead) if batch else None
+                    grp = following_steps(i, l, 1 if delayed else batch - lead) if batch and (lead or not delayed) else None
                     if lead and grp is None:        # this update shares no pass: the merge that waited goes first, on its own
                         chk(bracket(merge_label, lambda: lib.halos_lps_step(h, sp, ctypes.byref(info))))
                         log.append((held_merge[l], info.kind, info.t, info.t_last, info.delta_ready, info.accumulated))
@@ -356,7 +357,8 @@ class Cluster:
                         # does the pass touch the third buffer? (snapshot form: only the update that completes the accumulation does)
                         any_acc = any(int(events[j]["exp_send" if self.snapshot else "exp_accumulate"]) for j in steps)
                         third = "merge" if lead else ("acc" if any_acc else "noacc")
-                        blabel = f"lps_update_batch{len(steps)}_{third}_pull"
+                        cyc = "_refresh" if label.endswith("_refresh") else ("_first" if label.endswith("_first") else "")
+                        blabel = f"lps_update_batch{len(steps)}_{third}{cyc}_pull"
                         chk(bracket(blabel, lambda: lib.halos_lps_step_batch(h, lead + len(steps), 1, sp, infos, ctypes.byref(n_done))))
                         assert n_done.value == lead + len(steps), (n_done.value, lead, len(steps))
                         if lead:

@@ -197,3 +197,41 @@ def test_buffer_needs_no_initialisation():
     check_step_logs(trace, gpu_log, log32)
     worst, n_diff, name = compare_state(gpu, oracle_state(o32, w.n_lps), bitwise=True)
     assert n_diff == 0, (n_diff, worst, name)
+
+
+@pytest.mark.parametrize("snapshot", [False, True])
+def test_merges_ride_in_the_next_update_pass_under_a_momentum_delay(snapshot):
+    """With a momentum delay, a replay that asks for batching holds each merge back and issues it with the update step
+    that follows (halos_lps_step_batch: merge and one delayed update in one pass).  State, step log and handed-back models
+    equal the step-by-step replay's and the oracle's, bit for bit."""
+    from dataclasses import replace
+    from paper_2506_04531_amd import binding as B
+    from paper_2506_04531_amd.harness import Cluster
+    from parity_util import check_step_logs, compare_state, oracle_run, oracle_state
+    from test_gpu_parity import RAGGED
+    w = replace(synth.get_workload("160m").scaled(RAGGED, n_updates=160, name="dn-mergebatch"), d_l=4, d_g=2, eta_l=0.8, eta_g=0.3)
+    trace = synth.make_trace(w, seed=123)
+    hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0], flags=B.FLAG_SNAPSHOT if snapshot else 0)
+    runs = []
+    for batch in (0, 4):
+        c = Cluster(w, "cuda:0", k_initial=trace.k_initial, hp=hp)
+        try:
+            log, tm = c.replay(trace.events, fuse_pull=True, batch=batch, timed=True)
+            torch.cuda.synchronize()
+            state = {k: c.flat(k) for k in c.state_lists()}
+            for l, dst in enumerate(c.pull_dst):
+                state[f"pull{l}"] = torch.cat([t.reshape(-1) for t in dst]).cpu().numpy()
+            runs.append((log, state, tm))
+        finally:
+            c.close()
+    merged = {k: len(v) for k, v in runs[1][2].items() if "_merge_" in k}
+    print(f"[parity] {w.name} snapshot={snapshot}: passes that open with the merge {merged}", flush=True)
+    assert sum(merged.values()) >= 5 and len(merged) >= 2         # at more than one position of the momentum cycle
+    assert runs[0][0] == runs[1][0]
+    for k in runs[0][1]:
+        assert np.array_equal(runs[0][1][k].view(np.uint32), runs[1][1][k].view(np.uint32)), k
+    o32, log32 = oracle_run(w, trace, None, 32, FORM_LITERAL if snapshot else FORM_ACCUMULATOR)
+    check_step_logs(trace, runs[1][0], log32)
+    gpu = {k: v for k, v in runs[1][1].items() if not k.startswith("pull")}
+    worst, n_diff, name = compare_state(gpu, oracle_state(o32, w.n_lps, snapshot_form=snapshot), bitwise=True)
+    assert n_diff == 0, (n_diff, worst, name)
