@@ -83,10 +83,10 @@ def bytes_per_param(label: str, delta_dtype: str, delayed: bool, momentum_bytes:
 # only for the kernel source it was measured on: {sha256 of kernels.hip: {kernel label: bytes/param}}.
 MEASURED_TRAFFIC: dict = {
     # profiles/lps_update_1b_hbm_traffic.md, profiles/lps_update_delayed_1b_dn.md, profiles/lps_update_1b_bf16_momentum.md
-    "e1be1d88caa8397ba67de6a039538e7e21a53c1fd0240a2950103cfd68ada506": {
-        "1b:lps_update_acc_pull": 30.032,
+    "71e43cab53cd9043d20d729908c04d42e74f8a0f58ccdc5014d471e14fa755b4": {
+        "1b:lps_update_acc_pull": 30.033,
         "1b:lps_update_noacc_pull": 22.031,
-        "1b-dn:lps_update_acc_first_pull": 26.039,
+        "1b-dn:lps_update_acc_first_pull": 26.038,
         "1b-dn:lps_update_acc_pull": 30.032,
         "1b-dn:lps_update_acc_refresh_pull": 34.031,
         "1b-dn:lps_update_noacc_first_pull": 18.031,
