@@ -383,14 +383,15 @@ def test_batch_call_on_a_single_item_is_the_ordinary_step():
         c.close()
 
 
-@pytest.mark.parametrize("flags", [0, "snapshot", "defer", "bf16m", "delayed", "delayed+snapshot"])
+@pytest.mark.parametrize("flags", [0, "snapshot", "defer", "bf16m", "delayed", "delayed+snapshot", "nopull"])
 def test_batch_that_opens_with_the_merge_equals_the_steps_one_by_one(flags):
     """A returned global model at the head of the queue with deltas behind it: halos_lps_step_batch merges and updates in
     one pass.  Two identical clusters take the same items, one through the batch call and one step by step; state, counters
     and the models handed back must agree bit for bit, for K reached inside the batch and not."""
     from paper_2506_04531_amd import binding as B
     fl = {0: 0, "snapshot": B.FLAG_SNAPSHOT, "defer": B.FLAG_DEFER_CLEAR, "bf16m": B.FLAG_BF16_MOMENTUM, "delayed": 0,
-          "delayed+snapshot": B.FLAG_SNAPSHOT}[flags]
+          "delayed+snapshot": B.FLAG_SNAPSHOT, "nopull": 0}[flags]
+    pull = flags != "nopull"                         # without the hand-back the batch still opens with the merge (plain rule only)
     delayed = str(flags).startswith("delayed")       # momentum delay 3: the merge shares a pass with ONE delta, the rest follow singly
     w = replace(synth.get_workload("160m").scaled(RAGGED, n_updates=8, name=f"mergebatch-{flags}"), n_lps=1, workers_per_lps=4,
                 pool_slots=4, d_l=3 if delayed else 1, eta_l=0.6 if delayed else 0.2)
@@ -413,12 +414,12 @@ def test_batch_that_opens_with_the_merge_equals_the_steps_one_by_one(flags):
                     B.halos_lps_push_update(h, k, c.pool[(rnd + k + 1) % 4], c.delta_dtype)
                 B.halos_lps_set_threshold(h, K)
                 if batched:
-                    infos = B.halos_lps_step_batch(h, 4, True)
+                    infos = B.halos_lps_step_batch(h, 4, pull)
                     assert [i.kind for i in infos] == [2] + [1] * (1 if delayed else n_behind), (rnd, [i.kind for i in infos])
                     while B.halos_lps_get_counters(h)["queued"]:
-                        infos += B.halos_lps_step_batch(h, 4, True)
+                        infos += B.halos_lps_step_batch(h, 4, pull)
                 else:
-                    infos = [B.halos_lps_step(h)] + [B.halos_lps_step_pull(h) for _ in range(n_behind)]
+                    infos = [B.halos_lps_step(h)] + [(B.halos_lps_step_pull if pull else B.halos_lps_step)(h) for _ in range(n_behind)]
                 log.append([(i.kind, i.worker, i.t, i.t_last, i.delta_ready, i.accumulated) for i in infos])
                 cnt = B.halos_lps_get_counters(h)
                 if cnt["phase"] == B.PHASE_SENT:                                # K was reached inside the batch: send it on
