@@ -16,8 +16,9 @@
  *                n_tensors device pointers, one per tensor of the layout.
  *   Layout       tensor i is a contiguous array of numel[i] elements; every
  *                non-empty tensor's base address must be 16-byte aligned.
- *                Server state is fp32.  Worker deltas are fp32, bfloat16 or IEEE half (or
- *                arrive as the worker's fp32 end model, halos_lps_push_end_model).
+ *                Server state is fp32 (the momentum arrays optionally bfloat16, HALOS_FLAG_BF16_MOMENTUM).
+ *                Worker deltas are fp32, bfloat16 or IEEE half (or arrive as the worker's fp32 end model,
+ *                halos_lps_push_end_model).
  *   Ownership    all parameter-sized buffers are allocated by the caller and
  *                only BORROWED: state buffers for the life of the handle, a
  *                pushed delta until the step that consumes it has finished on
@@ -34,8 +35,8 @@
  *                synchronises.  All calls that touch the same server's state
  *                must be issued on streams that are ordered with each other.
  *   Graphs       the event-loop calls (push_update / push_end_model with a pointer
- *                set the worker has used before, push_global, step, step_pull,
- *                gps_merge, pull_model with a destination used before) only launch
+ *                set the worker has used before, push_global, step, step_pull, step_batch,
+ *                step_average, gps_merge, pull_model with a destination used before) only launch
  *                kernels on `stream`: no allocation, no synchronisation, no memset.
  *                They may therefore be issued on a capturing stream.  Host-side
  *                protocol state advances when a call is made, not when a graph is
