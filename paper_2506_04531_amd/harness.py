@@ -240,7 +240,8 @@ class Cluster:
         weighted = self.w.staleness_exponent > 0.0
         skip = -1
         consumed = set()
-        batch = batch if (fuse_pull and batch >= 2) else 0
+        # (with the norm monitors on, the library's batch call takes one item at a time: issue the steps as such)
+        batch = batch if (fuse_pull and batch >= 2 and not (self.hp.flags & B.FLAG_NORMS)) else 0
         delayed = self.w.d_l > 1          # under a momentum delay only a merge and the one update behind it share a pass
         infos = (B.StepInfo * 4)()
         n_done = ctypes.c_int32()
