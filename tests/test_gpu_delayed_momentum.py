@@ -19,12 +19,12 @@ def _delayed(base, d_l, d_g, **kw):
     return replace(base, d_l=d_l, d_g=d_g, eta_l=0.2 * d_l, eta_g=0.15 * d_g, **kw)
 
 
-def _parity(w, trace, fuse_pull=False, placement="plain", idx=None):
+def _parity(w, trace, fuse_pull=False, placement="plain", idx=None, batch=0):
     print(f"[parity] workload={w.name} n={w.layout.total} dtype={w.delta_dtype} d_l={w.d_l} d_g={w.d_g} "
           f"events={len(trace.events)} fuse_pull={fuse_pull} placement={placement}", flush=True)
     c = _cluster(w, trace, placement=placement)
     try:
-        gpu_log, _ = c.replay(trace.events, fuse_pull=fuse_pull)
+        gpu_log, _ = c.replay(trace.events, fuse_pull=fuse_pull, batch=batch)
         torch.cuda.synchronize()
         if idx is None:
             gpu = {k: c.flat(k) for k in c.state_lists()}
@@ -89,7 +89,7 @@ def test_snapshot_form_with_delayed_momentum():
     hp = B.paper_hparams(w.eta_l, w.beta_l, w.eta_g, w.beta_g, w.alpha, w.k_range[0], flags=B.FLAG_SNAPSHOT)
     c = _cluster(w, trace, hp=hp)
     try:
-        gpu_log, _ = c.replay(trace.events, fuse_pull=True)
+        gpu_log, _ = c.replay(trace.events, fuse_pull=True, batch=4)
         torch.cuda.synchronize()
         gpu = {k: c.flat(k) for k in c.state_lists()}
     finally:
@@ -102,11 +102,12 @@ def test_snapshot_form_with_delayed_momentum():
 
 @pytest.mark.parametrize("name", ["1b-dn", "paper-410m-dn"])
 def test_full_size_workloads_on_sampled_elements(name):
-    """Full benchmark sizes in the configuration bench.py times (state placed by HBM region, fused pulls)."""
+    """Full benchmark sizes in the configuration bench.py times (state placed by HBM region, fused pulls, every merge
+    in the pass of the update behind it)."""
     w = synth.get_workload(name)
     trace = synth.make_trace(w)
     idx = sample_indices(w.layout, 1 << 17, seed=6)
-    _parity(w, trace, fuse_pull=True, placement="regions", idx=idx)
+    _parity(w, trace, fuse_pull=True, placement="regions", idx=idx, batch=4)
 
 
 def test_delay_one_is_the_plain_rule_and_errors():

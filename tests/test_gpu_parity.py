@@ -75,7 +75,7 @@ def test_scaled_down_workloads_every_element(recipe):
 @pytest.mark.parametrize("name", ["70m", "160m", "410m", "1b", "paper-410m"])
 def test_full_size_workloads_on_sampled_elements(name):
     """Full benchmark sizes in the configuration bench.py times (state placed by HBM region, worker pulls fused into
-    the update pass, default launch shape).  Every step is elementwise, so the oracle replays exactly the sampled
+    the update pass, queued deltas and a merge with the update behind it sharing one pass, default launch shape).  Every step is elementwise, so the oracle replays exactly the sampled
     elements (random ones plus every tensor and tile boundary)."""
     w = synth.get_workload(name)
     trace = synth.make_trace(w)
@@ -84,7 +84,7 @@ def test_full_size_workloads_on_sampled_elements(name):
     tidx = torch.from_numpy(idx)
     c = _cluster(w, trace, placement="regions")
     try:
-        gpu_log, _ = c.replay(trace.events, fuse_pull=True)
+        gpu_log, _ = c.replay(trace.events, fuse_pull=True, batch=4)
         torch.cuda.synchronize()
         gpu = {k: c.gather(k, tidx) for k in c.state_lists()}
         # the last pull of every LPS copied the model it had at that moment; the final pull target of the
@@ -489,7 +489,7 @@ def test_full_size_70m_every_element(tmp_path):
     print(f"[parity] workload={name} every element n={N} events={len(trace.events)} state_dir={state_dir}", flush=True)
     c = _cluster(w, trace, placement="regions")
     try:
-        gpu_log, _ = c.replay(trace.events, fuse_pull=True)
+        gpu_log, _ = c.replay(trace.events, fuse_pull=True, batch=4)
         torch.cuda.synchronize()
         names = list(c.state_lists())
         for k in names:
