@@ -384,3 +384,44 @@ def test_many_tensors_through_the_multi_delta_passes():
     finally:
         B.halos_lps_destroy(lps)
         B.halos_gps_destroy(gps)
+
+
+def test_create_and_destroy_give_back_what_they_took():
+    """The library's own device allocations (tile table, pointer tables, norm scratch, arena slabs) are released by the
+    destroy calls: after many create / use / destroy rounds the device has as much free memory as before."""
+    from paper_2506_04531_amd import binding as B
+    dev = "cuda:0"
+    numel = [5000, 0, 12345, 4096]
+    mk = lambda: [torch.zeros(n, device=dev) for n in numel]
+    Theta, M, th, m, acc, g, wm = (mk() for _ in range(7))
+    norms_out = torch.zeros(2, dtype=torch.float64, device=dev)
+
+    def one_round(flags):
+        hp = B.paper_hparams(0.2, 0.9, 0.15, 0.5, 0.25, 2, flags=flags)
+        gps = B.halos_gps_create(numel, hp, Theta, M)
+        lps = B.halos_lps_create(gps, 0, 2, th, m, acc)
+        B.halos_lps_set_worker_model(lps, 0, wm)
+        B.halos_lps_set_worker_model(lps, 1, wm)
+        for k in range(2):
+            B.halos_lps_push_update(lps, k, g, B.F32)
+        assert len(B.halos_lps_step_batch(lps, 4, True)) == (1 if flags & B.FLAG_NORMS else 2)
+        while B.halos_lps_get_counters(lps)["queued"]:
+            B.halos_lps_step_pull(lps)
+        B.halos_gps_merge(gps, lps)
+        B.halos_lps_push_global(lps)
+        B.halos_lps_step(lps)
+        B.halos_gps_destroy(gps)            # retired first, released with its last local server
+        B.halos_lps_destroy(lps)
+
+    torch.cuda.synchronize()
+    one_round(0)                             # warm: the runtime's own pools settle
+    one_round(B.FLAG_NORMS)
+    torch.cuda.synchronize()
+    free_before, _ = torch.cuda.mem_get_info()
+    for r in range(150):
+        one_round(B.FLAG_NORMS if r % 2 else 0)
+    arena = B.halos_arena_create([1 << 28, 1 << 28], max_walk_bytes=8 << 30)
+    B.halos_arena_destroy(arena)
+    torch.cuda.synchronize()
+    free_after, _ = torch.cuda.mem_get_info()
+    assert free_after >= free_before - (8 << 20), (free_before, free_after)
