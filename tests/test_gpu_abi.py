@@ -425,3 +425,33 @@ def test_create_and_destroy_give_back_what_they_took():
     torch.cuda.synchronize()
     free_after, _ = torch.cuda.mem_get_info()
     assert free_after >= free_before - (8 << 20), (free_before, free_after)
+
+
+def test_a_layout_of_empty_tensors_runs_the_protocol_and_launches_nothing():
+    """Degenerate input: every tensor of the layout has zero elements.  The protocol (queue, counters, send test, merge)
+    still runs; there is nothing to compute."""
+    from paper_2506_04531_amd import binding as B
+    numel = [0, 0, 0]
+    none = [None, None, None]
+    hp = B.paper_hparams(0.2, 0.9, 0.15, 0.5, 0.25, 2)
+    gps = B.halos_gps_create(numel, hp, none, none)
+    lps = B.halos_lps_create(gps, 0, 2, none, none, none)
+    try:
+        B.halos_lps_set_worker_model(lps, 0, none)
+        B.halos_lps_set_worker_model(lps, 1, none)
+        B.halos_lps_push_update(lps, 0, none, B.BF16)
+        B.halos_lps_push_update(lps, 1, none, B.BF16)
+        infos = B.halos_lps_step_batch(lps, 4, True)
+        assert [(i.kind, i.t, i.delta_ready) for i in infos] == [(1, 1, 0), (1, 2, 1)]
+        B.halos_gps_merge(gps, lps)
+        B.halos_lps_push_global(lps)
+        B.halos_lps_push_update(lps, 0, none, B.BF16)
+        infos = B.halos_lps_step_batch(lps, 4, True)
+        assert [(i.kind, i.t, i.t_last) for i in infos] == [(2, 2, 2), (1, 3, 2)]
+        B.halos_pull_model(lps, False, none)
+        B.halos_pull_model(gps, True, none)
+        torch.cuda.synchronize()
+        assert B.halos_gps_get_counters(gps)["updates"] == 1
+    finally:
+        B.halos_lps_destroy(lps)
+        B.halos_gps_destroy(gps)
