@@ -16,13 +16,13 @@ def _cluster(w, trace, **kw):
     return Cluster(w, "cuda:0", k_initial=trace.k_initial, **kw)
 
 
-def _full_parity(w, trace, arena=False):
+def _full_parity(w, trace, arena=False, **replay_kw):
     """Element-by-element comparison of every state array after the whole trace."""
     print(f"[parity] workload={w.name} n={w.layout.total} tensors={w.layout.n_tensors} dtype={w.delta_dtype} "
-          f"events={len(trace.events)} arena={arena}", flush=True)
+          f"events={len(trace.events)} arena={arena} replay={replay_kw}", flush=True)
     c = _cluster(w, trace, arena=arena)
     try:
-        gpu_log, _ = c.replay(trace.events)
+        gpu_log, _ = c.replay(trace.events, **replay_kw)
         torch.cuda.synchronize()
         gpu = {k: c.flat(k) for k in c.state_lists()}
     finally:
@@ -464,12 +464,18 @@ def test_snapshot_form_every_element(recipe):
 
 
 @pytest.mark.parametrize("seed", [101, 102, 103, 104, 105, 106])
-def test_many_schedules_on_a_ragged_list(seed):
-    """Different arrival orders, queue depths and accumulation counts (the seed changes the whole schedule)."""
+@pytest.mark.parametrize("grouped", [False, True])
+def test_many_schedules_on_a_ragged_list(seed, grouped):
+    """Different arrival orders, queue depths and accumulation counts (the seed changes the whole schedule), step by step
+    and the way the benchmark replays (pulls fused, queued deltas and merges sharing passes; bursty senders)."""
     from dataclasses import replace
     base = synth.get_workload("160m" if seed % 2 else "410m")
-    w = replace(base.scaled(RAGGED, n_updates=64, name=f"seed{seed}"), seed=seed)
-    _full_parity(w, synth.make_trace(w, seed=seed))
+    w = replace(base.scaled(RAGGED, n_updates=64 if not grouped else 96, name=f"seed{seed}"), seed=seed)
+    if grouped:
+        w = replace(w, n_lps=2, workers_per_lps=6, hetero_rates=True)
+        _full_parity(w, synth.make_trace(w, seed=seed), fuse_pull=True, batch=2 + seed % 3)
+    else:
+        _full_parity(w, synth.make_trace(w, seed=seed))
 
 
 def test_full_size_70m_every_element(tmp_path):
