@@ -41,7 +41,12 @@
  *                They may therefore be issued on a capturing stream.  Host-side
  *                protocol state advances when a call is made, not when a graph is
  *                replayed, so only a sequence that brings the protocol back to its
- *                starting state (a whole accumulation cycle) can be replayed as is.
+ *                starting state (a whole accumulation cycle) can be replayed as is.  step_batch
+ *                and step_average keep, per worker, a device table of its delta pointers and
+ *                rewrite it (a small kernel on `stream`) only when the worker shows another
+ *                buffer: a graph holding them is replayed from the table state it was captured
+ *                in (capture after one warm-up cycle; no batch calls with other buffers between
+ *                replays).
  *   Threads      a handle may be used by one host thread at a time; creating or
  *                destroying an LPS, and halos_gps_merge, also count as a use of its GPS.
  *   Errors       every call returns a halos_status; on anything but HALOS_OK no

@@ -82,3 +82,75 @@ def test_captured_cycle_replays_like_eager_calls(flags_name, delay):
         for s in (a, b):
             B.halos_lps_destroy(s["lps"])
             B.halos_gps_destroy(s["gps"])
+
+
+def _batched_cycle(B, s, deltas):
+    """K = 2: two queued deltas in one pass (the second completes the accumulation), GPS update, the returned model
+    merged in the pass of the next delta, one more update to complete the next accumulation, GPS update, merge."""
+    lps, gps = s["lps"], s["gps"]
+    B.halos_lps_push_update(lps, 0, deltas[0], B.F32)
+    B.halos_lps_push_update(lps, 1, deltas[1], B.F32)
+    infos = B.halos_lps_step_batch(lps, 4, True)
+    assert [i.kind for i in infos] == [1, 1] and infos[1].delta_ready == 1
+    B.halos_gps_merge(gps, lps)
+    B.halos_lps_push_global(lps)
+    B.halos_lps_push_update(lps, 0, deltas[2], B.F32)
+    infos = B.halos_lps_step_batch(lps, 4, True)
+    assert [i.kind for i in infos] == [2, 1]
+    B.halos_lps_push_update(lps, 1, deltas[0], B.F32)
+    assert B.halos_lps_step_pull(lps).delta_ready == 1
+    B.halos_gps_merge(gps, lps)
+    B.halos_lps_push_global(lps)
+    assert B.halos_lps_step(lps).kind == 2
+
+
+@pytest.mark.parametrize("flags_name", ["none", "bf16m"])
+def test_captured_batched_cycle_replays_like_eager_calls(flags_name):
+    """The batch call (queued deltas in one pass; a merge opening the pass of the delta behind it) rewrites its per-worker
+    tables of delta pointers with a small kernel in stream order, so it can be captured too."""
+    from paper_2506_04531_amd import binding as B
+    from paper_2506_04531_amd.harness import alloc_tensor_list
+    numel = [int(x) for x in RAGGED.numel]
+    gen = torch.Generator().manual_seed(6)
+    theta0 = [torch.randn(n, generator=gen) * 0.02 for n in numel]
+    deltas = [[(torch.randn(n, generator=gen) * 1e-3).to("cuda:0") for n in numel] for _ in range(3)]
+    flags = B.FLAG_BF16_MOMENTUM if flags_name == "bf16m" else 0
+
+    def make():
+        s = _make(B, numel, theta0, 2, 2, 0) if not flags else None
+        if s is None:           # the same with 16-bit momentum arrays
+            mk = lambda dt=torch.float32: alloc_tensor_list(numel, dt, "cuda:0")
+            s = dict(Theta=mk(), M=mk(torch.bfloat16), th=mk(), m=mk(torch.bfloat16), acc=mk(), wm=[mk(), mk()], extra=[])
+            for t, v in zip(s["Theta"], theta0):
+                t.copy_(v)
+            hp = B.paper_hparams(0.2, 0.9, 0.15, 0.5, 0.25, 2, flags=flags)
+            s["gps"] = B.halos_gps_create(numel, hp, s["Theta"], s["M"])
+            s["lps"] = B.halos_lps_create(s["gps"], 0, 2, s["th"], s["m"], s["acc"])
+            for k in range(2):
+                B.halos_lps_set_worker_model(s["lps"], k, s["wm"][k])
+        return s
+
+    a, b = make(), make()
+    state = lambda s: [torch.cat([t.reshape(-1) for t in ts]).float().clone()
+                       for ts in [s["Theta"], s["M"], s["th"], s["m"], s["acc"]] + s["wm"]]
+    try:
+        _batched_cycle(B, a, deltas)      # warm-up: pointer checks cached, delta tables in the state every cycle leaves them in
+        _batched_cycle(B, b, deltas)
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            _batched_cycle(B, a, deltas)
+        torch.cuda.synchronize()
+        for sa, sb in zip(state(a), state(b)):
+            assert torch.equal(sa, sb)
+        for rep in range(3):
+            graph.replay()
+            _batched_cycle(B, b, deltas)
+            torch.cuda.synchronize()
+            for i, (sa, sb) in enumerate(zip(state(a), state(b))):
+                assert np.array_equal(sa.cpu().numpy().view(np.uint32), sb.cpu().numpy().view(np.uint32)), (rep, i)
+    finally:
+        for s in (a, b):
+            B.halos_lps_destroy(s["lps"])
+            B.halos_gps_destroy(s["gps"])
