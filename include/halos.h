@@ -82,7 +82,11 @@ typedef enum {
 
 /* Element type of a worker delta.  bfloat16 and IEEE half (the paper's workers train in fp16, Sec. 5.1) are upcast
  * exactly inside the update pass. */
+#ifdef __cplusplus     /* a C++ caller or the library itself: every int32 value may arrive, an unknown one is answered with EINVAL */
+typedef enum halos_dtype : int32_t { HALOS_F32 = 0, HALOS_BF16 = 1, HALOS_F16 = 2 } halos_dtype;
+#else
 typedef enum { HALOS_F32 = 0, HALOS_BF16 = 1, HALOS_F16 = 2 } halos_dtype;
+#endif
 
 /* Tensor list.  numel is a host array, copied by the create call. */
 typedef struct {
