@@ -86,7 +86,8 @@ MEASURED_TRAFFIC: dict = {
     "71e43cab53cd9043d20d729908c04d42e74f8a0f58ccdc5014d471e14fa755b4": {
         "1b:lps_update_acc_pull": 30.033,
         "1b:lps_update_noacc_pull": 22.031,
-        "1b-dn:lps_update_acc_first_pull": 26.038,
+        "1b:lps_update_batch1_merge_pull": 30.031,
+        "1b-dn:lps_update_acc_first_pull": 26.039,
         "1b-dn:lps_update_acc_pull": 30.032,
         "1b-dn:lps_update_acc_refresh_pull": 34.031,
         "1b-dn:lps_update_noacc_first_pull": 18.031,
