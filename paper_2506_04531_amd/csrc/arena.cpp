@@ -20,6 +20,9 @@
 
 namespace halos {
 halos_status set_error(halos_status code, const char *fmt, ...);     // halos.cpp: fills the thread's error string
+void register_handle(const void *h);                                 // halos.cpp: the registry of live handles
+void unregister_handle(const void *h);
+bool is_registered(const void *h);
 }
 using halos::set_error;
 
@@ -155,6 +158,7 @@ halos_status halos_arena_create(int32_t n_classes, const uint64_t *bytes_per_cla
         a->cls[c].slabs.assign(src.begin(), src.begin() + take);
         src.erase(src.begin(), src.begin() + take);
     }
+    halos::register_handle(a);
     *out = a;
     return HALOS_OK;                               // ~Walk releases the slabs nobody took and the ballast
 }
@@ -162,7 +166,7 @@ halos_status halos_arena_create(int32_t n_classes, const uint64_t *bytes_per_cla
 halos_status halos_arena_alloc(halos_arena *a, int32_t cls, uint64_t bytes, void **ptr) {
     if (!ptr) return set_error(HALOS_EINVAL, "ptr is NULL");
     *ptr = nullptr;
-    if (!a || a->magic != ARENA_MAGIC) return set_error(HALOS_EINVAL, "arena is not a valid handle");
+    if (!halos::is_registered(a) || a->magic != ARENA_MAGIC) return set_error(HALOS_EINVAL, "arena is not a valid handle");
     if (cls < 0 || cls >= (int)a->cls.size()) return set_error(HALOS_EINVAL, "class %d outside 0..%d", cls, (int)a->cls.size() - 1);
     if (bytes == 0) return set_error(HALOS_EINVAL, "bytes is 0");
     const uint64_t need = (bytes + ALIGN - 1) / ALIGN * ALIGN;
@@ -191,7 +195,7 @@ halos_status halos_arena_alloc(halos_arena *a, int32_t cls, uint64_t bytes, void
 
 halos_status halos_arena_info(const halos_arena *a, int32_t *n_regions, uint64_t *walked_bytes, double *same_region_gbps,
                               int32_t *region_of_class, int32_t *slabs_of_class) {
-    if (!a || a->magic != ARENA_MAGIC) return set_error(HALOS_EINVAL, "arena is not a valid handle");
+    if (!halos::is_registered(a) || a->magic != ARENA_MAGIC) return set_error(HALOS_EINVAL, "arena is not a valid handle");
     if (n_regions) *n_regions = a->n_regions;
     if (walked_bytes) *walked_bytes = a->walked;
     if (same_region_gbps) *same_region_gbps = a->same_region_gbps;
@@ -203,7 +207,8 @@ halos_status halos_arena_info(const halos_arena *a, int32_t *n_regions, uint64_t
 }
 
 void halos_arena_destroy(halos_arena *a) {
-    if (!a || a->magic != ARENA_MAGIC) return;
+    if (!halos::is_registered(a) || a->magic != ARENA_MAGIC) return;
+    halos::unregister_handle(a);
     (void)hipDeviceSynchronize();                  // nothing may still be running on memory that is about to go
     for (ClassState &c : a->cls) for (void *p : c.slabs) (void)hipFree(p);
     for (void *p : a->big) (void)hipFree(p);

@@ -38,6 +38,20 @@ halos_status set_error(halos_status code, const char *fmt, ...) {
     g_last_error = buf;
     return code;
 }
+
+// Handles (servers and arenas) are validated against a registry of live ones, so that a stale or foreign pointer is
+// rejected without being dereferenced.  Shared with the other translation units of the library.
+namespace {
+std::mutex g_registry_mutex;
+std::unordered_set<const void *> g_live_handles;
+}
+void register_handle(const void *h) { std::lock_guard<std::mutex> lk(g_registry_mutex); g_live_handles.insert(h); }
+void unregister_handle(const void *h) { std::lock_guard<std::mutex> lk(g_registry_mutex); g_live_handles.erase(h); }
+bool is_registered(const void *h) {
+    if (!h) return false;
+    std::lock_guard<std::mutex> lk(g_registry_mutex);
+    return g_live_handles.count(h) != 0;
+}
 }  // namespace halos
 
 namespace {
@@ -56,18 +70,6 @@ std::atomic<int> g_nontemporal{1};
 constexpr uint32_t GPS_MAGIC = 0x48475053u;   // "HGPS"
 constexpr uint32_t LPS_MAGIC = 0x484c5053u;   // "HLPS"
 
-// Handles are validated against a registry of live ones, so that a stale or foreign pointer is rejected without
-// being dereferenced.
-std::mutex g_registry_mutex;
-std::unordered_set<const void *> g_live_handles;
-
-void register_handle(const void *h) { std::lock_guard<std::mutex> lk(g_registry_mutex); g_live_handles.insert(h); }
-void unregister_handle(const void *h) { std::lock_guard<std::mutex> lk(g_registry_mutex); g_live_handles.erase(h); }
-bool is_registered(const void *h) {
-    if (!h) return false;
-    std::lock_guard<std::mutex> lk(g_registry_mutex);
-    return g_live_handles.count(h) != 0;
-}
 
 bool rule_ok(const halos_rule &r) {
     return std::isfinite(r.eta) && std::isfinite(r.beta) && std::isfinite(r.cg);
@@ -547,6 +549,7 @@ void halos_lps_destroy(halos_lps *l) {
     (void)hipFree(l->d_tables);
     if (l->d_norm_partials) (void)hipFree(l->d_norm_partials);
     halos_gps *g = l->gps;
+    unregister_handle(l);
     l->magic = 0;
     delete l;
     if (is_registered(g) && g->magic == GPS_MAGIC) {

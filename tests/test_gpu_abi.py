@@ -255,6 +255,17 @@ def test_gps_may_be_destroyed_before_its_local_servers():
     torch.cuda.synchronize()
     assert torch.equal(dst[0], Theta[0] - 0.5)
     B.halos_lps_destroy(lps)                                              # releases the GPS's tables too
+    # destroyed handles are refused by every call (they are looked up in the registry of live handles, never dereferenced)
+    assert _status(B.halos_lps_step, lps) == B.EINVAL
+    assert _status(B.halos_lps_push_global, lps) == B.EINVAL
+    assert _status(B.halos_lps_get_counters, lps) == B.EINVAL
+    assert _status(B.halos_pull_model, gps, True, dst) == B.EINVAL
+    B.halos_lps_destroy(lps)                                              # destroying twice is harmless
+    B.halos_gps_destroy(gps)
+    arena = B.halos_arena_create([1 << 20], max_walk_bytes=4 << 30)
+    B.halos_arena_destroy(arena)
+    assert _status(B.halos_arena_alloc, arena, 0, 256) == B.EINVAL
+    B.halos_arena_destroy(arena)
 
 
 def test_end_model_must_not_overlap_the_registered_start_model():
